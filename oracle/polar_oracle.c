@@ -1,0 +1,296 @@
+/*
+ * polar_oracle.c — CPU oracle for batched decode-step Selective Head Attention.
+ *
+ * TEST INFRASTRUCTURE, NOT PRODUCT.  Only the tests, the smoke check and the
+ * bench's cpu_baseline leg may call this.  It shares no code with the HIP
+ * library: no common header, helper, table or conversion routine.
+ *
+ * Everything is the plain definition written out in double precision, reading
+ * the same 16-bit (fp16 / bf16) input bits the GPU reads, widened exactly:
+ *
+ *   router      logit[b,h] = sum_i hidden[b,i] * Wr[i,h]              (Section 4.2: the
+ *               attention router is one fully connected layer that emits a scalar per head)
+ *   top-k       per request keep the k heads with the largest logits   (Section 4.2)
+ *   attention   softmax(q K^T / sqrt(d_h)) V per (request, head)       (Section 3.2, the
+ *               per-head attention equation), evaluated two-pass: all scores, their
+ *               maximum, the exponentials, the weighted mean of V.  No tiling, no
+ *               online update, no blocking.
+ *   masking     heads that are not selected produce exactly +0.0       (Section 3.2, the
+ *               head-sparsity study masks non-activated heads to zero; Algorithm 1 writes
+ *               only the activated heads)
+ *   GQA         the selection unit is a KV group; every query head of a selected group
+ *               is computed against that group's K/V                   (Section 4.2, last
+ *               sentence: group sparsity for grouped-query attention)
+ *
+ * A second routine, oracle_alg1_tiled, follows Algorithm 1 (Selective Head
+ * FlashAttention, decode) step by step — tiles of B_c rows, running maximum and
+ * sum, output renormalised every tile — so a test can show that the tiled
+ * recurrence and the two-pass definition agree.
+ *
+ * Readings where the paper is silent (kept in step with the design notes):
+ *   - head ids come out ordered by descending logit; equal logits (-0.0 == +0.0)
+ *     are ordered by ascending head id; NaN logits rank after every number and
+ *     among themselves by id.
+ *   - no bias and no sigmoid in the router (monotone, cannot change the top-k).
+ *   - seqlens[b] is clamped to [0, S]; a request of length 0 yields zeros.
+ *   - head_idx entries outside [0, Hkv) are ignored; duplicates are harmless.
+ *   - the current token is already in the cache; one query row attends all
+ *     n_b rows; no causal mask.
+ *   - scale = 1/sqrt(d) when the caller passes 0.
+ *
+ * OpenMP, when compiled in, only spreads independent (request, slot) units
+ * over threads; each unit's arithmetic is the same scalar loop.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F16 = 0, ORACLE_BF16 = 1 };
+
+/* IEEE binary16 bit pattern -> double, exact. */
+static double widen_f16(uint16_t bits)
+{
+    int sign = bits >> 15;
+    int expo = (bits >> 10) & 0x1f;
+    int frac = bits & 0x3ff;
+    double v;
+    if (expo == 0)
+        v = ldexp((double)frac, -24);              /* zero and subnormals */
+    else if (expo == 31)
+        v = frac ? NAN : INFINITY;
+    else
+        v = ldexp((double)(frac + 1024), expo - 25);
+    return sign ? -v : v;
+}
+
+/* bfloat16 bit pattern -> double, exact: it is the top half of a binary32. */
+static double widen_bf16(uint16_t bits)
+{
+    uint32_t u = (uint32_t)bits << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static double widen(uint16_t bits, int dt)
+{
+    return dt == ORACLE_BF16 ? widen_bf16(bits) : widen_f16(bits);
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* Widen n 16-bit values; lets a test check the decoders against numpy. */
+int oracle_widen16(const uint16_t *in, long n, int dt, double *out)
+{
+    if (!in || !out || n < 0 || (dt != ORACLE_F16 && dt != ORACLE_BF16)) return -1;
+    for (long i = 0; i < n; ++i) out[i] = widen(in[i], dt);
+    return 0;
+}
+
+/* Router (Section 4.2): logits[b,h] = sum_{i<D} hidden[b,i] * Wr[i,h], i ascending.
+ * hidden is [B,D] row-major, Wr is [D,H] row-major (H innermost). */
+int oracle_router_logits(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H,
+                         int dt, double *logits)
+{
+    if (!hidden || !Wr || !logits || B < 0 || D < 1 || H < 1) return -1;
+    if (dt != ORACLE_F16 && dt != ORACLE_BF16) return -1;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            double acc = 0.0;
+            for (int i = 0; i < D; ++i)
+                acc += widen(hidden[(size_t)b * D + i], dt) * widen(Wr[(size_t)i * H + h], dt);
+            logits[(size_t)b * H + h] = acc;
+        }
+    return 0;
+}
+
+struct scored { double v; int id; };
+
+/* Total order "a ranks before b": larger logit first, equal logits by lower id,
+ * NaN after every number. */
+static int rank_cmp(const void *pa, const void *pb)
+{
+    const struct scored *a = pa, *b = pb;
+    int an = isnan(a->v), bn = isnan(b->v);
+    if (an != bn) return an ? 1 : -1;
+    if (!an) {
+        if (a->v > b->v) return -1;
+        if (a->v < b->v) return 1;
+    }
+    return (a->id > b->id) - (a->id < b->id);
+}
+
+/* Top-k (Section 4.2): sort each row's heads by (logit descending, id ascending)
+ * and keep the first k ids, in that order. */
+int oracle_topk(const double *logits, int B, int H, int k, int32_t *head_idx)
+{
+    if (!logits || !head_idx || B < 0 || H < 1 || k < 1 || k > H) return -1;
+    struct scored *row = malloc(sizeof *row * (size_t)H);
+    if (!row) return -2;
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            row[h].v = logits[(size_t)b * H + h];
+            row[h].id = h;
+        }
+        qsort(row, (size_t)H, sizeof *row, rank_cmp);
+        for (int t = 0; t < k; ++t) head_idx[(size_t)b * k + t] = row[t].id;
+    }
+    free(row);
+    return 0;
+}
+
+/* One query row against n cached rows (the per-head attention equation of
+ * Section 3.2): two passes over the scores, then the weighted mean of V. */
+static void attend_one(const uint16_t *q, const uint16_t *K, const uint16_t *V, int n, int d,
+                       int dt, double scale, double *score, double *out)
+{
+    double M = -INFINITY;
+    for (int j = 0; j < n; ++j) {
+        double s = 0.0;
+        for (int e = 0; e < d; ++e)
+            s += widen(q[e], dt) * widen(K[(size_t)j * d + e], dt);
+        s *= scale;
+        score[j] = s;
+        if (s > M) M = s;
+    }
+    double denom = 0.0;
+    for (int j = 0; j < n; ++j) {
+        score[j] = exp(score[j] - M);
+        denom += score[j];
+    }
+    for (int e = 0; e < d; ++e) {
+        double acc = 0.0;
+        for (int j = 0; j < n; ++j)
+            acc += score[j] * widen(V[(size_t)j * d + e], dt);
+        out[e] = acc / denom;
+    }
+}
+
+/* Selective head attention for a batch (Sections 3.2 and 4.2).
+ *   q [B,Hq,d], K and V [B,Hkv,S,d] 16-bit; seqlens [B]; head_idx [B,k] KV-head
+ *   (group) ids, or NULL for dense attention with k == Hkv; out [B,Hq,d] double.
+ * Every element of out is written: selected heads get attention, the rest +0.0. */
+int oracle_sha_decode(const uint16_t *q, const uint16_t *K, const uint16_t *V,
+                      const int32_t *seqlens, const int32_t *head_idx, double *out,
+                      int B, int Hq, int Hkv, int S, int d, int k, int dt, double scale)
+{
+    if (!q || !K || !V || !seqlens || !out) return -1;
+    if (B < 0 || Hq < 1 || Hkv < 1 || S < 1 || d < 1 || k < 1 || k > Hkv) return -1;
+    if (Hq % Hkv != 0) return -1;
+    if (!head_idx && k != Hkv) return -1;
+    if (dt != ORACLE_F16 && dt != ORACLE_BF16) return -1;
+    const int G = Hq / Hkv;
+    if (scale == 0.0) scale = 1.0 / sqrt((double)d);
+    for (size_t i = 0; i < (size_t)B * Hq * d; ++i) out[i] = 0.0;
+
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel
+#endif
+    {
+        double *score = malloc(sizeof *score * (size_t)S);
+        if (!score) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp for collapse(2) schedule(dynamic, 1)
+#endif
+        for (int b = 0; b < B; ++b)
+            for (int t = 0; t < k; ++t) {
+                if (!score) continue;
+                int n = seqlens[b];
+                if (n < 0) n = 0;
+                if (n > S) n = S;
+                if (n == 0) continue;
+                int g = head_idx ? head_idx[(size_t)b * k + t] : t;
+                if (g < 0 || g >= Hkv) continue;
+                /* A duplicate id recomputes the same values; skip all but its first slot
+                 * so two threads never write one output row. */
+                int first = 1;
+                if (head_idx)
+                    for (int u = 0; u < t; ++u)
+                        if (head_idx[(size_t)b * k + u] == g) first = 0;
+                if (!first) continue;
+                const uint16_t *Kg = K + ((size_t)b * Hkv + g) * (size_t)S * d;
+                const uint16_t *Vg = V + ((size_t)b * Hkv + g) * (size_t)S * d;
+                for (int r = 0; r < G; ++r) {
+                    int h = g * G + r;   /* query heads of group g are contiguous */
+                    attend_one(q + ((size_t)b * Hq + h) * d, Kg, Vg, n, d, dt, scale, score,
+                               out + ((size_t)b * Hq + h) * d);
+                }
+            }
+        free(score);
+    }
+    return failed ? -2 : 0;
+}
+
+/* Algorithm 1 (Selective Head FlashAttention, decode) for ONE already-gathered
+ * head, followed in its own order: the cache is visited in tiles of Bc rows;
+ * each tile yields its scores, their maximum, the shifted exponentials and
+ * their sum; the running maximum and sum are updated with the two rescale
+ * factors; the accumulated output is renormalised by the new sum every tile.
+ * Inputs are doubles so a test can feed any values. */
+int oracle_alg1_tiled(const double *q, const double *K, const double *V, int n, int d, int Bc,
+                      double scale, double *out)
+{
+    if (!q || !K || !V || !out || n < 1 || d < 1 || Bc < 1) return -1;
+    double m_acc = -INFINITY, l_acc = 0.0;
+    double *p = malloc(sizeof *p * (size_t)Bc);
+    double *pv = malloc(sizeof *pv * (size_t)d);
+    if (!p || !pv) { free(p); free(pv); return -2; }
+    for (int e = 0; e < d; ++e) out[e] = 0.0;
+    int tiles = (n + Bc - 1) / Bc;
+    for (int j = 1; j <= tiles; ++j) {
+        int lo = (j - 1) * Bc, hi = j * Bc < n ? j * Bc : n;
+        double m_tile = -INFINITY;
+        for (int r = lo; r < hi; ++r) {
+            double s = 0.0;
+            for (int e = 0; e < d; ++e) s += q[e] * K[(size_t)r * d + e];
+            p[r - lo] = scale * s;
+            if (p[r - lo] > m_tile) m_tile = p[r - lo];
+        }
+        double l_tile = 0.0;
+        for (int r = lo; r < hi; ++r) {
+            p[r - lo] = exp(p[r - lo] - m_tile);
+            l_tile += p[r - lo];
+        }
+        for (int e = 0; e < d; ++e) {
+            pv[e] = 0.0;
+            for (int r = lo; r < hi; ++r) pv[e] += p[r - lo] * V[(size_t)r * d + e];
+        }
+        double m_new = m_acc > m_tile ? m_acc : m_tile;
+        double alpha = exp(m_acc - m_new);   /* exp(-inf) = 0 on the first tile */
+        double beta = exp(m_tile - m_new);
+        double l_new = alpha * l_acc + beta * l_tile;
+        for (int e = 0; e < d; ++e)
+            out[e] = (alpha * l_acc * out[e] + beta * pv[e]) / l_new;
+        l_acc = l_new;
+        m_acc = m_new;
+    }
+    free(p);
+    free(pv);
+    return 0;
+}
