@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the Selective Head Attention decode path on one MI355X.
+
+A step is one pass of the whole hot path over one batch: router GEMV + per-request top-k,
+then selective decode attention (KV streaming + split merge + zero fill) for the heads the
+router just chose.  Inputs are seeded synthetic tensors already resident in HBM.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+Prints ONE JSON line.  `value` is the effective KV bandwidth of the whole step: bytes of
+K and V the selected heads oblige a kernel to read, divided by the wall time of a step
+(router included).  `roofline` is for the dominant kernel alone (the KV-streaming kernel),
+timed with events on the launch stream.  `cpu_baseline` is the fp64 oracle on the host
+cores over a bounded sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+DEFAULT_WORKLOAD = "C4_opt66b"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--k", type=int, default=0, help="override the number of selected units")
+    ap.add_argument("--B", type=int, default=0, help="override the batch size")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=32, help="requests the oracle is timed on")
+    ap.add_argument("--phase", choices=["all", "partial"], default="all",
+                    help="'partial' launches only the KV-streaming kernel (for counter runs)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported, use --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2505_14884_amd as polar
+    from paper_2505_14884_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    w = wl.CONFIGS[args.workload]
+    if args.k:
+        w = w.scaled(k=args.k)
+    if args.B:
+        w = w.scaled(B=args.B)
+
+    hidden, Wr = wl.make_router_inputs(w, dev)
+    q, K, V, seqlens = wl.make_attention_inputs(w, dev)
+    bytes_sel = wl.selected_kv_bytes(w, seqlens)
+    bytes_dense = wl.selected_kv_bytes(w, seqlens, k=w.Hkv)
+
+    # Small workloads: rotate over R copies of the KV cache so the footprint of consecutive
+    # steps exceeds the 256 MB memory-side cache and repeats cannot be served from it.
+    R = 1 if bytes_dense >= (2 << 30) else int(math.ceil((2 << 30) / max(bytes_dense, 1)))
+    R = min(R, 64)
+    caches = [(K, V)] + [(K.clone(), V.clone()) for _ in range(R - 1)]
+
+    head_idx = torch.empty((w.B, w.k), dtype=torch.int32, device=dev)
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    ws = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.Hkv, dev)   # sized for dense too
+    chunk = polar.sha_chunk_rows(w.B, w.Hq, w.Hkv, w.S, w.d, w.k)
+
+    def step(i):
+        Ki, Vi = caches[i % R]
+        polar.router_topk(hidden, Wr, w.k, head_idx=head_idx)
+        polar.sha_decode(q, Ki, Vi, seqlens, head_idx, w.k, out=out, workspace=ws)
+
+    def partial_only(i):
+        Ki, Vi = caches[i % R]
+        polar.sha_partial(q, Ki, Vi, seqlens, head_idx, w.k, ws)
+
+    def dense_step(i):
+        Ki, Vi = caches[i % R]
+        polar.sha_decode(q, Ki, Vi, seqlens, None, w.Hkv, out=out, workspace=ws)
+
+    polar.router_topk(hidden, Wr, w.k, head_idx=head_idx)
+    torch.cuda.synchronize()
+
+    if args.phase == "partial":
+        for i in range(args.warmup + args.steps):
+            partial_only(i)
+        torch.cuda.synchronize()
+        print(json.dumps({"phase": "partial", "workload": w.name, "launches": args.warmup + args.steps,
+                          "algorithmic_bytes_per_launch": bytes_sel}))
+        return
+
+    # ---- whole-step wall time: W untimed, then exactly K timed steps
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = bytes_sel / (ms_per_step * 1e-3) / 1e9
+
+    def event_time(fn, n):
+        """Average duration of n launches of fn, each bracketed by events on the launch stream."""
+        pairs = []
+        for i in range(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn(i)
+            b.record()
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in pairs)
+        return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+    n_ev = max(10, min(args.steps, 100))
+    part_avg, part_med, part_min = event_time(partial_only, n_ev)
+    router_avg, _, _ = event_time(lambda i: polar.router_topk(hidden, Wr, w.k, head_idx=head_idx), n_ev)
+    sha_avg, _, _ = event_time(
+        lambda i: polar.sha_decode(q, caches[i % R][0], caches[i % R][1], seqlens, head_idx, w.k,
+                                   out=out, workspace=ws), n_ev)
+    for i in range(3):
+        dense_step(i)
+    dense_avg, _, _ = event_time(dense_step, max(5, n_ev // 4))
+    achieved = bytes_sel / (part_avg * 1e-3) / 1e9
+
+    result = {
+        "metric": "selective-head decode attention effective KV HBM GB/s "
+                  "(selected-head K+V bytes / step time; us per layer = 1000*ms_per_step)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: B=%d Hq=%d Hkv=%d d=%d S=%d k=%d %s KV, router D=%d"
+                        % (w.name, w.B, w.Hq, w.Hkv, w.d, w.S, w.k, w.dtype, w.D),
+            "seqlens": "all %d" % w.S if w.seq_lo <= 0 else "uniform integers in [%d, %d]" % (w.seq_lo, w.S),
+            "selected_kv_bytes": bytes_sel,
+            "dense_kv_bytes": bytes_dense,
+            "chunk_rows": chunk,
+            "kv_copies_rotated": R,
+        },
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "us_per_layer": round(ms_per_step * 1e3, 2),
+        "breakdown_us": {
+            "router_topk": round(router_avg * 1e3, 2),
+            "sha_decode(partial+merge)": round(sha_avg * 1e3, 2),
+            "sha_partial": round(part_avg * 1e3, 2),
+            "dense_k_eq_H": round(dense_avg * 1e3, 2),
+        },
+        "dense_over_selective": round(dense_avg / sha_avg, 3),
+        "ideal_H_over_k": round(w.Hkv / w.k, 3),
+        "roofline": {
+            "kernel": "sha_partial_kernel",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "avg_us": round(part_avg * 1e3, 2),
+            "median_us": round(part_med * 1e3, 2),
+            "min_us": round(part_min * 1e3, 2),
+            "traffic": None,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import polar_oracle as orc
+
+        nb = max(1, min(args.cpu_sample, w.B))
+        hb, Wb = wl.bits_u16(hidden[:nb]), wl.bits_u16(Wr)
+        qb, Kb, Vb = wl.bits_u16(q[:nb]), wl.bits_u16(K[:nb]), wl.bits_u16(V[:nb])
+        nh = seqlens[:nb].cpu().numpy()
+        step(0)                       # leave the selective result of copy 0 in `out`
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        idx = orc.router_topk(hb, Wb, w.k, w.dtype)
+        ref = orc.sha_decode(qb, Kb, Vb, nh, idx, w.k, w.dtype)
+        c1 = time.perf_counter()
+        sample_bytes = int(np.clip(nh, 0, w.S).astype(np.int64).sum()) * w.k * 2 * w.d * 2
+        gpu_idx = head_idx[:nb].cpu().numpy()
+        err = float(np.abs(out[:nb].cpu().numpy() - ref).max())
+        result["cpu_baseline"] = {
+            "value": round(sample_bytes / (c1 - c0) / 1e9, 4),
+            "unit": "GB/s",
+            "cores": orc.num_threads(),
+            "kind": "oracle",
+            "sample": "first %d of %d requests of the same workload (router + top-k + selected "
+                      "heads' attention), %.2f s" % (nb, w.B, c1 - c0),
+            "seconds_per_layer_extrapolated": round((c1 - c0) * bytes_sel / max(sample_bytes, 1), 3),
+            "parity_on_sample": {"head_idx_equal": bool(np.array_equal(gpu_idx, idx)),
+                                 "out_max_abs_err": err},
+        }
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

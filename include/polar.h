@@ -1,0 +1,146 @@
+/*
+ * polar.h — C ABI of the MI355X (gfx950) Selective Head Attention decode path.
+ *
+ * The library implements the batched decode-step hot path of Polar Sparsity:
+ * a per-request attention-head router followed by attention over the selected
+ * heads only.  Conventions shared by every entry point:
+ *
+ *  - Every array pointer is a DEVICE pointer owned by the caller.  The library
+ *    never allocates, frees, copies to the host or synchronises; it validates
+ *    the scalar arguments on the host (before any HIP call) and enqueues kernels
+ *    on the caller's stream.  `stream` is a hipStream_t passed as void*; NULL is
+ *    the default stream.
+ *  - Return value: POLAR_OK (0) or a negative polar_status.  Nothing is printed,
+ *    no exception crosses the boundary.  B == 0 is a successful no-op.
+ *  - 16-bit storage: `dt` says whether hidden/Wr/q/K/V hold IEEE binary16
+ *    (POLAR_F16) or bfloat16 (POLAR_BF16).  Accumulation is wider (see each call).
+ *  - Device-side contents are not validated on the hot path; the behaviour for
+ *    out-of-range contents is defined below and never reads or writes out of
+ *    bounds.
+ *  - Calls that share a workspace, or the same output, must be ordered on one
+ *    stream (or by events); the library keeps no global mutable state besides
+ *    the last HIP error code.
+ */
+#ifndef POLAR_H
+#define POLAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { POLAR_F16 = 0, POLAR_BF16 = 1 } polar_dtype;
+
+typedef enum {
+    POLAR_OK = 0,
+    POLAR_EINVAL = -1,       /* NULL pointer, negative size, k outside [1,H], Hq % Hkv != 0 ... */
+    POLAR_EUNSUPPORTED = -2, /* a shape or dtype this build has no kernel for */
+    POLAR_EWORKSPACE = -3,   /* workspace NULL, misaligned or smaller than required */
+    POLAR_EHIP = -4          /* a HIP launch failed; see polar_last_hip_error() */
+} polar_status;
+
+/* Limits of this build (host-checked, POLAR_EUNSUPPORTED beyond them). */
+#define POLAR_MAX_ROUTER_H 256    /* selection units a router may score */
+#define POLAR_MAX_ROUTER_D 16384  /* router input width (the hidden row is staged in LDS) */
+#define POLAR_MAX_GROUP 8         /* query heads per KV head: 1, 2, 4 or 8 */
+
+/*
+ * Attention-head router and per-request top-k (Section 4.2: the router is one fully
+ * connected layer producing a scalar logit per head; the k highest-logit heads of each
+ * request form the batch head index).
+ *
+ *   logit[b,h]  = sum_{i<D} hidden[b,i] * Wr[i,h]          no bias, no activation
+ *   head_idx[b] = ids of the k largest logits of row b, best first; equal logits
+ *                 (-0.0 equals +0.0) are ordered by ascending id; NaN logits rank
+ *                 after every number and among themselves by id.
+ *
+ *   hidden     in   [B, D]  dt, row-major
+ *   Wr         in   [D, H]  dt, row-major (H innermost).  H is the number of
+ *                   selection units: heads for MHA, KV groups for GQA.
+ *   head_idx   out  [B, k]  int32
+ *   logits_out out  [B, H]  float, nullable: the logits rounded to float, for inspection.
+ *
+ * Products are exact and the sum over D is accumulated in double precision in a fixed,
+ * column-independent order, so identical columns of Wr give bit-identical logits and the
+ * result does not depend on launch timing.  1 <= k <= H <= POLAR_MAX_ROUTER_H,
+ * 1 <= D <= POLAR_MAX_ROUTER_D.
+ */
+int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, int k,
+                      polar_dtype dt, int32_t *head_idx, float *logits_out, void *stream);
+
+/*
+ * Bytes of device workspace polar_sha_decode needs for these sizes (split-KV partial
+ * results).  Returns 0 for invalid or unsupported sizes.  The workspace must be
+ * 256-byte aligned; its contents need no initialisation and are undefined afterwards.
+ */
+size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k);
+
+/*
+ * Selective Head Attention, decode step (Section 3.2, the per-head attention equation;
+ * Section 4.2 and Algorithm 1, Selective Head FlashAttention (decode); group sparsity
+ * for GQA as in the last sentence of Section 4.2).
+ *
+ * For every request b and every selected KV head g = head_idx[b,t], and every query
+ * head h of that group (h in [g*G, (g+1)*G), G = Hq/Hkv):
+ *
+ *   out[b,h,:] = softmax_j( scale * q[b,h,:] . K[b,g,j,:] ) @ V[b,g,j,:],   j in [0, n_b)
+ *
+ * with n_b = clamp(seqlens[b], 0, S).  Every other out[b,h',:] is written as +0.0
+ * (heads that are not activated are masked to zero).  Only rows j < n_b of the selected
+ * heads' K and V are read; no other K/V byte is touched.
+ *
+ *   q        in   [B, Hq, d]      dt
+ *   K, V     in   [B, Hkv, S, d]  dt, contiguous; S is the cache capacity in rows
+ *   seqlens  in   [B] int32       rows in use per request (the current token included)
+ *   head_idx in   [B, k] int32    KV-head (group) ids; entries outside [0,Hkv) are
+ *                                 skipped; duplicates are harmless.  NULL means dense
+ *                                 attention and requires k == Hkv.
+ *   out      out  [B, Hq, d] float; every element is written on every call.
+ *   scale         softmax scale; 0 selects 1/sqrt(d).
+ *   workspace     at least polar_sha_workspace_bytes(...) bytes, 256-byte aligned.
+ *
+ * Scores, softmax statistics and the output are accumulated in float.  A request with
+ * n_b == 0 gets zeros.  Supported: d in {64, 128}; G in {1, 2, 4, 8}; 1 <= k <= Hkv.
+ */
+int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                     const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
+                     int k, polar_dtype dt, float scale, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/*
+ * The two phases of polar_sha_decode as separate launches, with the same arguments and
+ * checks (polar_sha_decode is exactly partial followed by merge on one stream).  They
+ * exist so a harness can time the KV-streaming phase by itself.
+ *   polar_sha_partial: streams K/V of the selected heads in chunks of rows and leaves a
+ *     running (max, sum, unnormalised output) per chunk in the workspace (Algorithm 1's
+ *     recurrence applied per chunk).
+ *   polar_sha_merge: combines the chunks of each selected head with the same max/sum
+ *     rescale, normalises, and writes zeros for unselected heads.
+ */
+int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                      const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
+                      polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
+                      void *stream);
+int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out, int B, int Hq,
+                    int Hkv, int S, int d, int k, const void *workspace, size_t workspace_bytes,
+                    void *stream);
+
+/*
+ * Rows of the KV cache one workgroup of the streaming phase covers for these sizes
+ * (the split granularity the workspace size is computed from).  0 for invalid sizes.
+ */
+int polar_sha_chunk_rows(int B, int Hq, int Hkv, int S, int d, int k);
+
+/* Text for a polar_status value; never NULL. */
+const char *polar_strerror(int status);
+/* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */
+int polar_last_hip_error(void);
+/* ABI version: major * 1000 + minor. */
+int polar_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLAR_H */

@@ -1,0 +1,183 @@
+"""Thin ctypes binding of ``libpolar.so`` (see ``include/polar.h``).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch tensors are used as handles to device memory, and the current
+torch stream is the stream the kernels are enqueued on.  There is no CPU or
+PyTorch fallback: if the library cannot be loaded, or a tensor is not on the
+GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from .build import LIB_PATH, build_library
+
+F16, BF16 = 0, 1
+_STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
+           -4: "POLAR_EHIP"}
+EXPORTS = ("polar_router_topk", "polar_sha_workspace_bytes", "polar_sha_decode",
+           "polar_sha_partial", "polar_sha_merge", "polar_sha_chunk_rows", "polar_strerror",
+           "polar_last_hip_error", "polar_version")
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class PolarError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        text = lib().polar_strerror(status).decode()
+        extra = ""
+        if status == -4:
+            extra = " (hipError %d)" % lib().polar_last_hip_error()
+        super().__init__("%s: %s: %s%s" % (where, _STATUS.get(status, str(status)), text, extra))
+
+
+def lib() -> ctypes.CDLL:
+    """Load the shared library, compiling it first only when no built copy exists."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            build_library()
+        L = ctypes.CDLL(LIB_PATH)
+        i, vp, f, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
+        L.polar_router_topk.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp]
+        L.polar_router_topk.restype = i
+        L.polar_sha_workspace_bytes.argtypes = [i] * 6
+        L.polar_sha_workspace_bytes.restype = sz
+        L.polar_sha_chunk_rows.argtypes = [i] * 6
+        L.polar_sha_chunk_rows.restype = i
+        L.polar_sha_decode.argtypes = [vp] * 6 + [i] * 7 + [f, vp, sz, vp]
+        L.polar_sha_decode.restype = i
+        L.polar_sha_partial.argtypes = [vp] * 5 + [i] * 7 + [f, vp, sz, vp]
+        L.polar_sha_partial.restype = i
+        L.polar_sha_merge.argtypes = [vp] * 3 + [i] * 6 + [vp, sz, vp]
+        L.polar_sha_merge.restype = i
+        L.polar_strerror.argtypes = [i]
+        L.polar_strerror.restype = ctypes.c_char_p
+        L.polar_last_hip_error.restype = i
+        L.polar_version.restype = i
+        _lib = L
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return F16
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("expected a float16 or bfloat16 tensor, got %s" % t.dtype)
+
+
+def _dev(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU; this path has no CPU fallback" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise PolarError(rc, where)
+
+
+def router_topk(hidden: torch.Tensor, Wr: torch.Tensor, k: int,
+                head_idx: Optional[torch.Tensor] = None,
+                logits_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """hidden [B,D], Wr [D,H] (fp16/bf16, GPU) -> head_idx int32 [B,k]."""
+    B, D = hidden.shape
+    D2, H = Wr.shape
+    if D != D2 or hidden.dtype != Wr.dtype:
+        raise ValueError("hidden [B,D] and Wr [D,H] must agree in D and dtype")
+    if head_idx is None:
+        head_idx = torch.empty((B, max(k, 0)), dtype=torch.int32, device=hidden.device)
+    rc = lib().polar_router_topk(_dev(hidden, "hidden"), _dev(Wr, "Wr"), B, D, H, k,
+                                 _dtype_code(hidden), _dev(head_idx, "head_idx", torch.int32),
+                                 _dev(logits_out, "logits_out", torch.float32), _stream())
+    _check(rc, "polar_router_topk")
+    return head_idx
+
+
+def sha_workspace_bytes(B: int, Hq: int, Hkv: int, S: int, d: int, k: int) -> int:
+    return int(lib().polar_sha_workspace_bytes(B, Hq, Hkv, S, d, k))
+
+
+def sha_chunk_rows(B: int, Hq: int, Hkv: int, S: int, d: int, k: int) -> int:
+    return int(lib().polar_sha_chunk_rows(B, Hq, Hkv, S, d, k))
+
+
+def alloc_workspace(B: int, Hq: int, Hkv: int, S: int, d: int, k: int, device) -> torch.Tensor:
+    nbytes = sha_workspace_bytes(B, Hq, Hkv, S, d, k)
+    if nbytes == 0:
+        # sizes the library rejects: ask the size check itself for the status to report
+        rc = lib().polar_sha_merge(None, None, None, B, Hq, Hkv, S, d, k, None, 0, None)
+        raise PolarError(rc if rc != 0 else -1, "polar_sha_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def _sha_shapes(q, K, V, seqlens, head_idx, k):
+    B, Hq, d = q.shape
+    B2, Hkv, S, d2 = K.shape
+    if (B, d) != (B2, d2) or V.shape != K.shape or q.dtype != K.dtype or V.dtype != K.dtype:
+        raise ValueError("q [B,Hq,d], K/V [B,Hkv,S,d] must agree in B, d and dtype")
+    if tuple(seqlens.shape) != (B,):
+        raise ValueError("seqlens must be [B]")
+    if head_idx is not None and tuple(head_idx.shape) != (B, k):
+        raise ValueError("head_idx must be [B,k]")
+    return B, Hq, Hkv, S, d
+
+
+def sha_decode(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, seqlens: torch.Tensor,
+               head_idx: Optional[torch.Tensor], k: int, out: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None, scale: float = 0.0) -> torch.Tensor:
+    """Selective head attention, decode step -> out float32 [B,Hq,d] (unselected heads zero)."""
+    B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, head_idx, k)
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = alloc_workspace(B, Hq, Hkv, S, d, k, q.device)
+    rc = lib().polar_sha_decode(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"),
+                                _dev(seqlens, "seqlens", torch.int32),
+                                _dev(head_idx, "head_idx", torch.int32),
+                                _dev(out, "out", torch.float32), B, Hq, Hkv, S, d, k,
+                                _dtype_code(q), float(scale), _dev(workspace, "workspace"),
+                                workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "polar_sha_decode")
+    return out
+
+
+def sha_partial(q, K, V, seqlens, head_idx, k: int, workspace: torch.Tensor,
+                scale: float = 0.0) -> None:
+    """The KV-streaming phase of sha_decode alone (leaves per-chunk partials in workspace)."""
+    B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, head_idx, k)
+    rc = lib().polar_sha_partial(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"),
+                                 _dev(seqlens, "seqlens", torch.int32),
+                                 _dev(head_idx, "head_idx", torch.int32), B, Hq, Hkv, S, d, k,
+                                 _dtype_code(q), float(scale), _dev(workspace, "workspace"),
+                                 workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "polar_sha_partial")
+
+
+def sha_merge(seqlens, head_idx, out: torch.Tensor, Hkv: int, S: int, k: int,
+              workspace: torch.Tensor) -> torch.Tensor:
+    """The merge / zero-fill phase of sha_decode alone."""
+    B, Hq, d = out.shape
+    rc = lib().polar_sha_merge(_dev(seqlens, "seqlens", torch.int32),
+                               _dev(head_idx, "head_idx", torch.int32),
+                               _dev(out, "out", torch.float32), B, Hq, Hkv, S, d, k,
+                               _dev(workspace, "workspace"),
+                               workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "polar_sha_merge")
+    return out

@@ -1,0 +1,171 @@
+// extern "C" boundary: host-side argument validation, launch planning, error codes.
+// Every check below runs before the first HIP call, so invalid arguments are reported the
+// same way with or without a GPU in the machine.
+#include <math.h>
+#include <stdlib.h>
+
+#include "polar_internal.h"
+
+namespace polar {
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int record(hipError_t e)
+{
+    if (e == hipSuccess) return POLAR_OK;
+    g_last_hip_error = (int)e;
+    return POLAR_EHIP;
+}
+
+bool dtype_ok(polar_dtype dt) { return dt == POLAR_F16 || dt == POLAR_BF16; }
+
+// Rows per workgroup of the streaming kernel.  A multiple of 128 (the rows one workgroup
+// consumes per step at d = 64; 64 at d = 128) so only the last chunk of a request has a
+// ragged tail.  POLAR_SHA_CHUNK_ROWS overrides the default for tuning sweeps.
+int choose_chunk(int S)
+{
+    int chunk = 256;
+    if (const char *env = getenv("POLAR_SHA_CHUNK_ROWS")) {
+        const long v = strtol(env, nullptr, 10);
+        if (v >= 128 && v <= (1 << 20)) chunk = (int)((v + 127) / 128 * 128);
+    }
+    const int cap = (S + 127) / 128 * 128;
+    return chunk < cap ? chunk : cap;
+}
+
+int check_sha_sizes(int B, int Hq, int Hkv, int S, int d, int k)
+{
+    if (B < 0 || Hq < 1 || Hkv < 1 || S < 1 || d < 1 || k < 1) return POLAR_EINVAL;
+    if (k > Hkv || Hq % Hkv != 0) return POLAR_EINVAL;
+    if (d != 64 && d != 128) return POLAR_EUNSUPPORTED;
+    const int G = Hq / Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return POLAR_EUNSUPPORTED;
+    if (B > 65535 || k > 65535 || Hq > 65535) return POLAR_EUNSUPPORTED;   // grid y/z limits
+    return POLAR_OK;
+}
+
+}  // namespace
+
+int make_sha_plan(int B, int Hq, int Hkv, int S, int d, int k, ShaPlan *plan)
+{
+    const int rc = check_sha_sizes(B, Hq, Hkv, S, d, k);
+    if (rc != POLAR_OK) return rc;
+    plan->G = Hq / Hkv;
+    plan->chunk = choose_chunk(S);
+    plan->nsplit = (S + plan->chunk - 1) / plan->chunk;
+    const size_t units = (size_t)B * k * plan->G * plan->nsplit;
+    plan->o_floats = (units * d + 63) / 64 * 64;   // keeps the (max, sum) region 256-byte aligned
+    plan->ml_floats = units * 2;
+    plan->bytes = ((plan->o_floats + plan->ml_floats) * sizeof(float) + 255) / 256 * 256;
+    if (plan->bytes == 0) plan->bytes = 256;
+    return POLAR_OK;
+}
+
+}  // namespace polar
+
+using namespace polar;
+
+extern "C" {
+
+int polar_version(void) { return 1000; }
+
+int polar_last_hip_error(void) { return g_last_hip_error; }
+
+const char *polar_strerror(int status)
+{
+    switch (status) {
+    case POLAR_OK: return "ok";
+    case POLAR_EINVAL: return "invalid argument";
+    case POLAR_EUNSUPPORTED: return "unsupported shape or dtype";
+    case POLAR_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case POLAR_EHIP: return "HIP launch failed (see polar_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, int k,
+                      polar_dtype dt, int32_t *head_idx, float *logits_out, void *stream)
+{
+    if (B < 0 || D < 1 || H < 1 || k < 1 || k > H || !dtype_ok(dt)) return POLAR_EINVAL;
+    if (H > POLAR_MAX_ROUTER_H || D > POLAR_MAX_ROUTER_D || B > 0x7fffffff / 2)
+        return POLAR_EUNSUPPORTED;
+    if (B == 0) return POLAR_OK;
+    if (!hidden || !Wr || !head_idx) return POLAR_EINVAL;
+    return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k)
+{
+    ShaPlan plan;
+    if (make_sha_plan(B, Hq, Hkv, S, d, k, &plan) != POLAR_OK) return 0;
+    return plan.bytes;
+}
+
+int polar_sha_chunk_rows(int B, int Hq, int Hkv, int S, int d, int k)
+{
+    ShaPlan plan;
+    if (make_sha_plan(B, Hq, Hkv, S, d, k, &plan) != POLAR_OK) return 0;
+    return plan.chunk;
+}
+
+static int check_workspace(const ShaPlan &plan, const void *workspace, size_t workspace_bytes)
+{
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < plan.bytes)
+        return POLAR_EWORKSPACE;
+    return POLAR_OK;
+}
+
+int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                      const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
+                      polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
+                      void *stream)
+{
+    ShaPlan plan;
+    int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);
+    if (rc != POLAR_OK) return rc;
+    if (!dtype_ok(dt) || !(scale >= 0.0f) || isinf(scale)) return POLAR_EINVAL;
+    if (!head_idx && k != Hkv) return POLAR_EINVAL;
+    if (B == 0) return POLAR_OK;
+    if (!q || !K || !V || !seqlens) return POLAR_EINVAL;
+    if ((rc = check_workspace(plan, workspace, workspace_bytes)) != POLAR_OK) return rc;
+    const float s = scale == 0.0f ? 1.0f / sqrtf((float)d) : scale;
+    const float log2e = 1.4426950408889634f;
+    return record(launch_sha_partial(q, K, V, seqlens, head_idx, static_cast<float *>(workspace),
+                                     plan, B, Hq, Hkv, S, d, k, dt, s * log2e,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out, int B, int Hq,
+                    int Hkv, int S, int d, int k, const void *workspace, size_t workspace_bytes,
+                    void *stream)
+{
+    ShaPlan plan;
+    int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);
+    if (rc != POLAR_OK) return rc;
+    if (!head_idx && k != Hkv) return POLAR_EINVAL;
+    if (B == 0) return POLAR_OK;
+    if (!seqlens || !out) return POLAR_EINVAL;
+    if ((rc = check_workspace(plan, workspace, workspace_bytes)) != POLAR_OK) return rc;
+    return record(launch_sha_merge(seqlens, head_idx, out, static_cast<const float *>(workspace),
+                                   plan, B, Hq, Hkv, S, d, k, static_cast<hipStream_t>(stream)));
+}
+
+int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                     const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
+                     int k, polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
+                     void *stream)
+{
+    ShaPlan plan;
+    int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);   // size errors take precedence
+    if (rc != POLAR_OK) return rc;
+    if (B > 0 && !out) return POLAR_EINVAL;
+    rc = polar_sha_partial(q, K, V, seqlens, head_idx, B, Hq, Hkv, S, d, k, dt, scale,
+                               workspace, workspace_bytes, stream);
+    if (rc != POLAR_OK) return rc;
+    return polar_sha_merge(seqlens, head_idx, out, B, Hq, Hkv, S, d, k, workspace, workspace_bytes,
+                           stream);
+}
+
+}  // extern "C"

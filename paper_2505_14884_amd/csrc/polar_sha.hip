@@ -1,0 +1,371 @@
+// Selective Head Attention, decode step, for gfx950 (CDNA4): split-KV streaming kernel
+// and merge / zero-fill kernel.
+//
+// What is computed (Section 3.2, per-head attention equation; Algorithm 1, Selective Head
+// FlashAttention (decode)): for every request b and selected KV head g, one query row per
+// query head of the group attends rows [0, n_b) of K[b,g] and V[b,g].  The head is
+// gathered into the grid from the batch head index, so unselected K/V is never addressed.
+//
+// How it is laid out on the machine (differs from the paper's one-program-per-(b, slot)
+// Triton kernel, which was shaped for its GPUs' shared memory):
+//   * Decode attention is a memory-bound GEMV, so there is no MFMA and no LDS staging on
+//     the streaming path: K and V rows go global -> VGPR with 16-byte loads.  A row of d
+//     16-bit values is shared by d/8 adjacent lanes, so one wave-wide load covers 64*16
+//     contiguous bytes (4 rows at d = 128, 8 rows at d = 64).
+//   * Each lane holds its 8-element slice of q (per query head of the group) in registers;
+//     the row dot product is 4 packed dot2 instructions per lane followed by a DPP
+//     butterfly over the d/8 lanes of the row, which leaves the score in all of them.
+//   * Every (wave, row-slot) pair runs its own online softmax (running max, sum and an
+//     8-wide slice of the output per lane) over the rows it sees, in base-2 exponent space
+//     (scores are pre-multiplied by scale*log2 e).  At the end of a chunk the row-slots of
+//     a wave are merged with cross-lane shuffles, the waves through LDS, and one
+//     (max, sum, unnormalised output) record per query head goes to the workspace.
+//   * Long sequences are split across workgroups in chunks of rows (occupancy: the number
+//     of (request, head) units alone does not fill 256 compute units); the merge kernel
+//     applies the same max/sum rescale across chunks, normalises, and stores zeros for
+//     the heads that were not selected.
+#include "polar_internal.h"
+
+namespace polar {
+namespace {
+
+constexpr int kWaves = 4;                 // waves per workgroup of the streaming kernel
+constexpr int kThreads = kWaves * 64;
+constexpr int kLoads = 4;                 // 16-byte loads of K (and of V) per lane per step
+constexpr float kNegBig = -1.0e30f;       // "no row seen yet": finite, so exp2(x - max) never sees inf - inf
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+struct F16 {};
+struct BF16 {};
+
+template <class DT> __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc);
+template <> __device__ __forceinline__ float dot2<F16>(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b), acc,
+                                  false);
+}
+template <> __device__ __forceinline__ float dot2<BF16>(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a),
+                                           __builtin_bit_cast(bf16x2, b), acc, false);
+}
+
+// Two packed 16-bit values -> two floats (exact).
+template <class DT> __device__ __forceinline__ void widen2(uint32_t w, float &lo, float &hi);
+template <> __device__ __forceinline__ void widen2<F16>(uint32_t w, float &lo, float &hi)
+{
+    f16x2 h = __builtin_bit_cast(f16x2, w);
+    lo = (float)h.x;
+    hi = (float)h.y;
+}
+template <> __device__ __forceinline__ void widen2<BF16>(uint32_t w, float &lo, float &hi)
+{
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xffff0000u);
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp_add(float x)
+{
+    int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+    return x + __int_as_float(y);
+}
+
+// Sum over the LPR (8 or 16) adjacent lanes that share a row; result in every one of them.
+// quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror.
+template <int LPR> __device__ __forceinline__ float row_allreduce(float x)
+{
+    x = dpp_add<0xB1>(x);
+    x = dpp_add<0x4E>(x);
+    x = dpp_add<0x141>(x);
+    if (LPR == 16) x = dpp_add<0x140>(x);
+    return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// One step of a row-slot's online softmax: kLoads rows of K and V already in registers.
+template <class DT, int D, int G, bool MASKED>
+__device__ __forceinline__ void consume(const uint4 (&kr)[kLoads], const uint4 (&vr)[kLoads],
+                                        const bool (&ok)[kLoads], const uint4 (&qr)[G], float c,
+                                        float (&m)[G], float (&l)[G], float (&o)[G][8])
+{
+    constexpr int LPR = D / 8;
+    float p[G][kLoads];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        float s[kLoads];
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            float a = dot2<DT>(kr[u].x, qr[g].x, 0.0f);
+            a = dot2<DT>(kr[u].y, qr[g].y, a);
+            a = dot2<DT>(kr[u].z, qr[g].z, a);
+            a = dot2<DT>(kr[u].w, qr[g].w, a);
+            a = row_allreduce<LPR>(a) * c;
+            s[u] = (MASKED && !ok[u]) ? -INFINITY : a;
+        }
+        float mx = m[g];
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) mx = fmaxf(mx, s[u]);
+        const float alpha = fast_exp2(m[g] - mx);
+        float psum = 0.0f;
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            p[g][u] = fast_exp2(s[u] - mx);
+            psum += p[g][u];
+        }
+        l[g] = l[g] * alpha + psum;
+        m[g] = mx;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[g][e] *= alpha;
+    }
+#pragma unroll
+    for (int u = 0; u < kLoads; ++u) {
+        float v[8];
+        widen2<DT>(vr[u].x, v[0], v[1]);
+        widen2<DT>(vr[u].y, v[2], v[3]);
+        widen2<DT>(vr[u].z, v[4], v[5]);
+        widen2<DT>(vr[u].w, v[6], v[7]);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[g][e] = fmaf(p[g][u], v[e], o[g][e]);
+    }
+}
+
+// Streaming kernel.  grid = (nsplit, k, B); block = kThreads.
+// Workspace record of unit u = ((b*k + slot)*G + gi)*nsplit + split:
+//   ws_o[u*D .. u*D+D)   unnormalised output, ws_ml[2u] running max (base-2), ws_ml[2u+1] sum.
+// A workgroup whose chunk starts at or beyond n_b, or whose head id is out of range, writes
+// nothing; the merge kernel never reads those records.
+template <class DT, int D, int G>
+__global__ __launch_bounds__(kThreads) void sha_partial_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+    const int32_t *__restrict__ seqlens, const int32_t *__restrict__ head_idx,
+    float *__restrict__ ws_o, float *__restrict__ ws_ml, int Hq, int Hkv, int S, int k, int chunk,
+    int nsplit, float c)
+{
+    constexpr int LPR = D / 8;             // lanes per row
+    constexpr int RPL = 64 / LPR;          // rows per wave-wide load
+    constexpr int ROWS_WAVE = kLoads * RPL;
+    constexpr int ROWS_WG = kWaves * ROWS_WAVE;
+
+    const int split = blockIdx.x, slot = blockIdx.y, b = blockIdx.z;
+    int n = seqlens[b];
+    n = n < 0 ? 0 : (n > S ? S : n);
+    const int row_begin = split * chunk;
+    if (row_begin >= n) return;
+    const int g_kv = head_idx ? head_idx[(size_t)b * k + slot] : slot;
+    if ((unsigned)g_kv >= (unsigned)Hkv) return;
+    const int row_end = min(row_begin + chunk, n);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane / LPR, cl = lane % LPR;
+
+    const size_t slab = ((size_t)b * Hkv + g_kv) * (size_t)S * D;
+    const uint4 *__restrict__ Kp = reinterpret_cast<const uint4 *>(K + slab) + cl;
+    const uint4 *__restrict__ Vp = reinterpret_cast<const uint4 *>(V + slab) + cl;
+
+    uint4 qr[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        qr[g] = reinterpret_cast<const uint4 *>(q + ((size_t)b * Hq + (size_t)g_kv * G + g) * D)[cl];
+
+    float m[G], l[G], o[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = kNegBig;
+        l[g] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[g][e] = 0.0f;
+    }
+
+    for (int row0 = row_begin + wave * ROWS_WAVE; row0 < row_end; row0 += ROWS_WG) {
+        uint4 kr[kLoads], vr[kLoads];
+        bool ok[kLoads];
+        if (row0 + ROWS_WAVE <= row_end) {
+#pragma unroll
+            for (int u = 0; u < kLoads; ++u) {
+                kr[u] = Kp[(size_t)(row0 + u * RPL + r) * LPR];
+                ok[u] = true;
+            }
+#pragma unroll
+            for (int u = 0; u < kLoads; ++u) vr[u] = Vp[(size_t)(row0 + u * RPL + r) * LPR];
+            consume<DT, D, G, false>(kr, vr, ok, qr, c, m, l, o);
+        } else {
+#pragma unroll
+            for (int u = 0; u < kLoads; ++u) {
+                const int row = row0 + u * RPL + r;
+                ok[u] = row < row_end;
+                kr[u] = make_uint4(0u, 0u, 0u, 0u);
+                vr[u] = make_uint4(0u, 0u, 0u, 0u);
+                if (ok[u]) {
+                    kr[u] = Kp[(size_t)row * LPR];
+                    vr[u] = Vp[(size_t)row * LPR];
+                }
+            }
+            consume<DT, D, G, true>(kr, vr, ok, qr, c, m, l, o);
+        }
+    }
+
+    // Merge the RPL row-slots of this wave: butterfly over lane distances LPR, 2*LPR, ... 32.
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float m2 = __shfl_xor(m[g], off);
+            const float l2 = __shfl_xor(l[g], off);
+            const float mx = fmaxf(m[g], m2);
+            const float a1 = fast_exp2(m[g] - mx), a2 = fast_exp2(m2 - mx);
+            l[g] = l[g] * a1 + l2 * a2;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float o2 = __shfl_xor(o[g][e], off);
+                o[g][e] = o[g][e] * a1 + o2 * a2;
+            }
+            m[g] = mx;
+        }
+    }
+
+    __shared__ float sm_o[kWaves][G][D];
+    __shared__ float sm_ml[kWaves][G][2];
+    if (r == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float4 *dst = reinterpret_cast<float4 *>(&sm_o[wave][g][cl * 8]);
+            dst[0] = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
+            dst[1] = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
+            if (cl == 0) {
+                sm_ml[wave][g][0] = m[g];
+                sm_ml[wave][g][1] = l[g];
+            }
+        }
+    }
+    __syncthreads();
+
+    // Merge the waves: thread t owns output column t of every query head of the group.
+    const int t = threadIdx.x;
+    if (t < D) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float mx = sm_ml[0][g][0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm_ml[w][g][0]);
+            float acc = 0.0f, lsum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float a = fast_exp2(sm_ml[w][g][0] - mx);
+                acc = fmaf(a, sm_o[w][g][t], acc);
+                lsum = fmaf(a, sm_ml[w][g][1], lsum);
+            }
+            const size_t unit = (((size_t)b * k + slot) * G + g) * nsplit + split;
+            ws_o[unit * D + t] = acc;
+            if (t == 0) {
+                ws_ml[unit * 2 + 0] = mx;
+                ws_ml[unit * 2 + 1] = lsum;
+            }
+        }
+    }
+}
+
+// Merge / zero-fill kernel.  grid = (Hq, B); block = D threads; thread t owns out[b,h,t].
+// The query head's group is looked up in the request's row of the batch head index (first
+// match wins, so duplicate ids are harmless); heads with no match are stored as +0.0.
+template <int D>
+__global__ __launch_bounds__(D) void sha_merge_kernel(
+    const int32_t *__restrict__ seqlens, const int32_t *__restrict__ head_idx,
+    const float *__restrict__ ws_o, const float *__restrict__ ws_ml, float *__restrict__ out,
+    int Hq, int Hkv, int S, int k, int G, int chunk, int nsplit)
+{
+    const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
+    const int g_kv = h / G, gi = h % G;
+    int n = seqlens[b];
+    n = n < 0 ? 0 : (n > S ? S : n);
+    int slot = -1;
+    if (head_idx) {
+        for (int s = k - 1; s >= 0; --s)
+            if (head_idx[(size_t)b * k + s] == g_kv) slot = s;
+    } else {
+        slot = g_kv;
+    }
+    float result = 0.0f;
+    if (slot >= 0 && n > 0) {
+        const int used = (n + chunk - 1) / chunk;
+        const size_t unit0 = (((size_t)b * k + slot) * G + gi) * nsplit;
+        float mx = kNegBig;
+        for (int c = 0; c < used; ++c) mx = fmaxf(mx, ws_ml[(unit0 + c) * 2]);
+        float acc = 0.0f, lsum = 0.0f;
+        for (int c = 0; c < used; ++c) {
+            const float a = fast_exp2(ws_ml[(unit0 + c) * 2] - mx);
+            lsum = fmaf(a, ws_ml[(unit0 + c) * 2 + 1], lsum);
+            acc = fmaf(a, ws_o[(unit0 + c) * D + t], acc);
+        }
+        result = lsum > 0.0f ? acc / lsum : 0.0f;
+    }
+    out[((size_t)b * Hq + h) * D + t] = result;
+}
+
+template <class DT, int D>
+hipError_t launch_partial_g(int G, dim3 grid, hipStream_t st, const uint16_t *q, const uint16_t *K,
+                            const uint16_t *V, const int32_t *seqlens, const int32_t *head_idx,
+                            float *ws_o, float *ws_ml, int Hq, int Hkv, int S, int k, int chunk,
+                            int nsplit, float c)
+{
+#define POLAR_LAUNCH(GG)                                                                         \
+    hipLaunchKernelGGL((sha_partial_kernel<DT, D, GG>), grid, dim3(kThreads), 0, st, q, K, V,    \
+                       seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, chunk, nsplit, c)
+    switch (G) {
+    case 1: POLAR_LAUNCH(1); break;
+    case 2: POLAR_LAUNCH(2); break;
+    case 4: POLAR_LAUNCH(4); break;
+    case 8: POLAR_LAUNCH(8); break;
+    default: return hipErrorInvalidValue;
+    }
+#undef POLAR_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                              const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
+                              int Hq, int Hkv, int S, int d, int k, polar_dtype dt,
+                              float scale_log2e, hipStream_t stream)
+{
+    const dim3 grid((unsigned)plan.nsplit, (unsigned)k, (unsigned)B);
+    float *ws_o = ws, *ws_ml = ws + plan.o_floats;
+    const uint16_t *q16 = static_cast<const uint16_t *>(q);
+    const uint16_t *K16 = static_cast<const uint16_t *>(K);
+    const uint16_t *V16 = static_cast<const uint16_t *>(V);
+#define POLAR_ARGS plan.G, grid, stream, q16, K16, V16, seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, \
+                   plan.chunk, plan.nsplit, scale_log2e
+    if (dt == POLAR_F16) {
+        if (d == 128) return launch_partial_g<F16, 128>(POLAR_ARGS);
+        if (d == 64) return launch_partial_g<F16, 64>(POLAR_ARGS);
+    } else {
+        if (d == 128) return launch_partial_g<BF16, 128>(POLAR_ARGS);
+        if (d == 64) return launch_partial_g<BF16, 64>(POLAR_ARGS);
+    }
+#undef POLAR_ARGS
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
+                            const float *ws, const ShaPlan &plan, int B, int Hq, int Hkv, int S,
+                            int d, int k, hipStream_t stream)
+{
+    const dim3 grid((unsigned)Hq, (unsigned)B);
+    const float *ws_o = ws, *ws_ml = ws + plan.o_floats;
+    if (d == 128)
+        hipLaunchKernelGGL((sha_merge_kernel<128>), grid, dim3(128), 0, stream, seqlens, head_idx,
+                           ws_o, ws_ml, out, Hq, Hkv, S, k, plan.G, plan.chunk, plan.nsplit);
+    else if (d == 64)
+        hipLaunchKernelGGL((sha_merge_kernel<64>), grid, dim3(64), 0, stream, seqlens, head_idx,
+                           ws_o, ws_ml, out, Hq, Hkv, S, k, plan.G, plan.chunk, plan.nsplit);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace polar

@@ -1,0 +1,121 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments with the documented status before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_14884_amd as polar
+from paper_2505_14884_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE = 0, -1, -2, -3
+FAKE = ctypes.c_void_p(0x1000)          # a non-NULL pointer that is never dereferenced on the host
+ALIGNED = ctypes.c_void_p(0x10000)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "polar.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(polar_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(L, name) is not None
+    assert L.polar_version() >= 1000
+
+
+def test_strerror_covers_every_status():
+    L = binding.lib()
+    seen = {L.polar_strerror(s) for s in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and all(seen)
+    assert L.polar_strerror(-99)
+    assert L.polar_last_hip_error() == 0
+
+
+def router(L, hidden=FAKE, Wr=FAKE, B=4, D=512, H=8, k=4, dt=0, idx=FAKE):
+    return L.polar_router_topk(hidden, Wr, B, D, H, k, dt, idx, None, None)
+
+
+def test_router_argument_errors():
+    L = binding.lib()
+    assert router(L, k=0) == EINVAL
+    assert router(L, k=9) == EINVAL
+    assert router(L, D=0) == EINVAL
+    assert router(L, H=0) == EINVAL
+    assert router(L, B=-1) == EINVAL
+    assert router(L, dt=2) == EINVAL
+    assert router(L, hidden=None) == EINVAL
+    assert router(L, Wr=None) == EINVAL
+    assert router(L, idx=None) == EINVAL
+    assert router(L, H=257, k=4) == EUNSUPPORTED
+    assert router(L, D=16385) == EUNSUPPORTED
+    assert router(L, B=0, hidden=None, Wr=None, idx=None) == OK      # empty batch: no-op
+
+
+def decode(L, q=FAKE, K=FAKE, V=FAKE, n=FAKE, idx=FAKE, out=FAKE, B=4, Hq=8, Hkv=8, S=256, d=64,
+           k=4, dt=0, scale=0.0, ws=ALIGNED, ws_bytes=None):
+    if ws_bytes is None:
+        ws_bytes = L.polar_sha_workspace_bytes(B, Hq, Hkv, S, d, k)
+    return L.polar_sha_decode(q, K, V, n, idx, out, B, Hq, Hkv, S, d, k, dt, scale, ws, ws_bytes, None)
+
+
+def test_sha_argument_errors():
+    L = binding.lib()
+    assert decode(L, k=0) == EINVAL
+    assert decode(L, k=9) == EINVAL
+    assert decode(L, Hq=12, Hkv=8) == EINVAL                # Hq not a multiple of Hkv
+    assert decode(L, S=0) == EINVAL
+    assert decode(L, B=-2) == EINVAL
+    assert decode(L, dt=7) == EINVAL
+    assert decode(L, scale=-1.0) == EINVAL
+    assert decode(L, scale=float("nan")) == EINVAL
+    assert decode(L, scale=float("inf")) == EINVAL
+    assert decode(L, idx=None, k=4) == EINVAL               # dense needs k == Hkv
+    for name in ("q", "K", "V", "n", "out"):
+        assert decode(L, **{name: None}) == EINVAL
+    assert decode(L, d=96) == EUNSUPPORTED
+    assert decode(L, d=256) == EUNSUPPORTED
+    assert decode(L, Hq=24, Hkv=8) == EUNSUPPORTED          # G = 3
+    assert decode(L, Hq=128, Hkv=8) == EUNSUPPORTED         # G = 16
+    assert decode(L, ws=None) == EWORKSPACE
+    assert decode(L, ws=ctypes.c_void_p(0x10010)) == EWORKSPACE   # not 256-byte aligned
+    assert decode(L, ws_bytes=255) == EWORKSPACE
+    assert decode(L, B=0, q=None, K=None, V=None, n=None, out=None, ws=None) == OK   # empty batch
+
+
+def test_workspace_size_is_consistent_with_the_chunking():
+    L = binding.lib()
+    for (B, Hq, Hkv, S, d, k) in [(4, 8, 8, 256, 64, 4), (32, 32, 32, 1920, 128, 16),
+                                  (64, 32, 8, 4096, 128, 4), (128, 72, 72, 1920, 128, 36),
+                                  (256, 32, 32, 8192, 128, 8), (1, 8, 8, 1, 64, 8)]:
+        chunk = polar.sha_chunk_rows(B, Hq, Hkv, S, d, k)
+        assert chunk > 0 and chunk % 128 == 0
+        nsplit = -(-S // chunk)
+        need = B * k * (Hq // Hkv) * nsplit * (d + 2) * 4
+        got = polar.sha_workspace_bytes(B, Hq, Hkv, S, d, k)
+        assert need <= got <= need + 512 and got % 256 == 0
+    assert polar.sha_workspace_bytes(4, 8, 8, 256, 96, 4) == 0
+    assert polar.sha_chunk_rows(4, 12, 8, 256, 64, 4) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    q = torch.zeros((1, 8, 64), dtype=torch.float16)
+    K = torch.zeros((1, 8, 128, 64), dtype=torch.float16)
+    n = torch.ones(1, dtype=torch.int32)
+    ws = torch.zeros(1 << 16, dtype=torch.uint8)
+    out = torch.zeros((1, 8, 64))
+    with pytest.raises(ValueError, match="no CPU fallback"):
+        polar.sha_decode(q, K, K, n, None, 8, out=out, workspace=ws)
+    with pytest.raises(ValueError, match="no CPU fallback"):
+        polar.router_topk(torch.zeros((1, 16), dtype=torch.float16),
+                          torch.zeros((16, 4), dtype=torch.float16), 2,
+                          head_idx=torch.zeros((1, 2), dtype=torch.int32))
+    with pytest.raises(polar.PolarError):
+        polar.alloc_workspace(4, 8, 8, 256, 96, 4, "cpu")

@@ -1,0 +1,266 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle on the same bits.
+
+Bar: head_idx bit-exact; attention output max-abs error <= 2e-3 (16-bit inputs, float
+accumulation); skipped heads exactly +0.0.  Inputs are seeded and synthetic, shaped like the
+configurations the bench uses.  Every case prints its name before it touches the GPU.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_14884_amd as polar
+from oracle import polar_oracle as orc
+from paper_2505_14884_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def host_bits(t):
+    return wl.bits_u16(t)
+
+
+def check_against_oracle(w, q, K, V, seqlens, head_idx, out, rows=None):
+    """Compare `out` (GPU, float32 [B,Hq,d]) with the oracle for the requests in `rows`."""
+    rows = list(range(w.B)) if rows is None else list(rows)
+    sel = torch.tensor(rows, device=q.device)
+    idx_host = None if head_idx is None else head_idx[sel].cpu().numpy()
+    want = orc.sha_decode(host_bits(q[sel]), host_bits(K[sel]), host_bits(V[sel]),
+                          seqlens[sel].cpu().numpy(), idx_host, w.k, w.dtype)
+    got = out[sel].cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    err = np.abs(got - want).max() if got.size else 0.0
+    say("   max-abs error %.3e over %d requests" % (err, len(rows)))
+    assert err <= TOL
+    # heads the oracle leaves at zero must be +0.0 bit for bit
+    zero = (want == 0.0).all(axis=2)
+    assert (out[sel].cpu().numpy().view(np.uint32)[zero] == 0).all()
+    return err
+
+
+def poison_unselected(w, q, K, V, head_idx):
+    """NaN into q/K/V of every head a request did not select (nothing may read them)."""
+    keep = torch.zeros((w.B, w.Hkv), dtype=torch.bool, device=K.device)
+    valid = (head_idx >= 0) & (head_idx < w.Hkv)
+    b_ix = torch.arange(w.B, device=K.device)[:, None].expand_as(head_idx)
+    keep[b_ix[valid], head_idx[valid].long()] = True
+    K[~keep] = float("nan")
+    V[~keep] = float("nan")
+    q.view(w.B, w.Hkv, w.G, w.d)[~keep] = float("nan")
+
+
+def run_router(w):
+    hidden, Wr = wl.make_router_inputs(w, DEV)
+    logits = torch.empty((w.B, w.Hkv), dtype=torch.float32, device=DEV)
+    got = polar.router_topk(hidden, Wr, w.k, logits_out=logits)
+    torch.cuda.synchronize()
+    ref_logits = orc.router_logits(host_bits(hidden), host_bits(Wr), w.dtype)
+    want = orc.topk(ref_logits, w.k)
+    assert got.dtype == torch.int32 and tuple(got.shape) == (w.B, w.k)
+    assert np.array_equal(got.cpu().numpy(), want), "head_idx differs from the oracle"
+    np.testing.assert_allclose(logits.cpu().numpy(), ref_logits, rtol=2e-7, atol=1e-7)
+    srt = -np.sort(-ref_logits, axis=1)
+    say("   router ok; smallest gap among the top-(k+1) logits: %.3e"
+        % np.diff(-srt[:, : min(w.k + 1, w.Hkv)], axis=1).min(initial=np.inf))
+    return got
+
+
+def run_attention(w, head_idx, rows=None, poison=True, check_dense_rows=None):
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV, poison_padding=poison)
+    if poison and head_idx is not None:
+        poison_unselected(w, q, K, V, head_idx)
+    out = torch.full((w.B, w.Hq, w.d), float("nan"), dtype=torch.float32, device=DEV)
+    ws = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.k, DEV)
+    ws.fill_(0xFF)                                  # NaN bit patterns: stale partials would show
+    polar.sha_decode(q, K, V, seqlens, head_idx, w.k, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all(), "a NaN canary or an unwritten element reached the output"
+    check_against_oracle(w, q, K, V, seqlens, head_idx, out, rows)
+    # bit-reproducible: no atomics, fixed merge order
+    out2 = torch.empty_like(out)
+    polar.sha_decode(q, K, V, seqlens, head_idx, w.k, out=out2, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
+    return out
+
+
+# ----------------------------------------------------------------------------- the five configs
+@pytest.mark.parametrize("name", ["C1_tiny", "C2_llama2_7b", "C3_llama3_8b_gqa"])
+def test_config_full_parity(name):
+    w = wl.CONFIGS[name]
+    say("\ncase", name, w)
+    head_idx = run_router(w)
+    run_attention(w, head_idx)
+
+
+@pytest.mark.parametrize("name", ["C4_opt66b", "C5_ragged"])
+def test_config_full_size_sampled_parity(name):
+    """Full-size launch exactly as the bench times it; the oracle recomputes a sample of
+    requests (shortest, longest and a few others), every other request is checked for
+    finiteness and for exact zeros on skipped heads."""
+    w = wl.CONFIGS[name]
+    say("\ncase", name, w)
+    head_idx = run_router(w)
+    seqlens = wl.make_seqlens(w, "cpu")
+    rows = sorted({int(seqlens.argmin()), int(seqlens.argmax()), 0, w.B // 3, w.B - 1})
+    out = run_attention(w, head_idx, rows=rows, poison=True)
+    selected = torch.zeros((w.B, w.Hkv), dtype=torch.bool, device=DEV)
+    selected[torch.arange(w.B, device=DEV)[:, None], head_idx.long()] = True
+    skipped = ~selected.repeat_interleave(w.G, dim=1)
+    assert (out.view(torch.int32)[skipped] == 0).all()
+    assert (out[~skipped].abs().sum(dim=-1) > 0).all()
+
+
+# ----------------------------------------------------------------------------- dense path
+@pytest.mark.parametrize("dtype,d,G", [("f16", 128, 1), ("bf16", 64, 1), ("bf16", 128, 4),
+                                       ("f16", 64, 2), ("f16", 128, 8)])
+def test_dense_null_index_and_identity_index(dtype, d, G):
+    w = wl.ShaWorkload("dense", B=3, Hq=4 * G, Hkv=4, d=d, S=700, k=4, D=64, dtype=dtype,
+                       seq_lo=1, seed=7 + d + G)
+    say("\ncase dense", w)
+    out_null = run_attention(w, None)
+    ident = torch.arange(4, dtype=torch.int32, device=DEV).repeat(w.B, 1)
+    out_ident = run_attention(w, ident, poison=False)
+    assert torch.equal(out_null.view(torch.int32), out_ident.view(torch.int32))
+
+
+# ----------------------------------------------------------------------------- edge shapes
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("d,G", [(128, 1), (64, 1), (128, 4), (64, 8), (128, 2)])
+def test_ragged_lengths_and_tails(dtype, d, G):
+    """Lengths 0, 1, around every tile boundary (rows per load, per wave step, per workgroup
+    step, per chunk) and the full capacity."""
+    lens = [0, 1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 33, 63, 64, 65, 127, 128, 129, 255, 256,
+            257, 300, 511, 512, 513, 640, 1000, 1023]
+    w = wl.ShaWorkload("ragged", B=len(lens), Hq=6 * G, Hkv=6, d=d, S=1023, k=3, D=64,
+                       dtype=dtype, seed=11 * d + G)
+    say("\ncase ragged", w)
+    seqlens = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    q, K, V, _ = wl.make_attention_inputs(w, DEV, poison_padding=True, seqlens=seqlens)
+    head_idx = wl.random_head_idx(w, DEV)
+    poison_unselected(w, q, K, V, head_idx)
+    out = polar.sha_decode(q, K, V, seqlens, head_idx, w.k)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    check_against_oracle(w, q, K, V, seqlens, head_idx, out)
+    assert (out[0].view(torch.int32) == 0).all()          # length 0 -> zeros
+
+
+def test_invalid_and_duplicate_head_ids_and_clamped_lengths():
+    w = wl.ShaWorkload("ids", B=4, Hq=8, Hkv=8, d=128, S=300, k=4, D=64, dtype="f16", seed=5)
+    say("\ncase ids", w)
+    seqlens = torch.tensor([300, 9999, -7, 150], dtype=torch.int32, device=DEV)
+    q, K, V, _ = wl.make_attention_inputs(w, DEV, seqlens=seqlens.clamp(0, w.S))
+    head_idx = torch.tensor([[2, -1, 2, 8], [7, 7, 7, 7], [0, 1, 2, 3], [-5, 100, 3, 0]],
+                            dtype=torch.int32, device=DEV)
+    out = polar.sha_decode(q, K, V, seqlens, head_idx, w.k)
+    torch.cuda.synchronize()
+    check_against_oracle(w, q, K, V, seqlens, head_idx, out)
+    assert (out[2].view(torch.int32) == 0).all()
+
+
+def test_peaky_softmax_and_explicit_scale():
+    w = wl.ShaWorkload("peaky", B=2, Hq=4, Hkv=4, d=128, S=2048, k=2, D=64, dtype="bf16",
+                       peaky=0.05, seed=9)
+    say("\ncase peaky", w)
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV)
+    head_idx = wl.random_head_idx(w, DEV)
+    for scale in (0.0, 0.25, 0.01):
+        out = polar.sha_decode(q, K, V, seqlens, head_idx, w.k, scale=scale)
+        torch.cuda.synchronize()
+        want = orc.sha_decode(host_bits(q), host_bits(K), host_bits(V), seqlens.cpu().numpy(),
+                              head_idx.cpu().numpy(), w.k, w.dtype, scale=scale)
+        err = np.abs(out.cpu().numpy() - want).max()
+        say("   scale %.3g max-abs error %.3e" % (scale, err))
+        assert err <= TOL
+
+
+def test_empty_batch_is_a_noop():
+    e16 = torch.empty((0, 8, 64), dtype=torch.float16, device=DEV)
+    kv = torch.empty((0, 8, 128, 64), dtype=torch.float16, device=DEV)
+    n = torch.empty((0,), dtype=torch.int32, device=DEV)
+    idx = torch.empty((0, 4), dtype=torch.int32, device=DEV)
+    out = polar.sha_decode(e16, kv, kv, n, idx, 4)
+    assert tuple(out.shape) == (0, 8, 64)
+    got = polar.router_topk(torch.empty((0, 64), dtype=torch.float16, device=DEV),
+                            torch.zeros((64, 8), dtype=torch.float16, device=DEV), 4)
+    assert tuple(got.shape) == (0, 4)
+    torch.cuda.synchronize()
+
+
+def test_phases_compose_to_the_single_call():
+    w = wl.CONFIGS["C1_tiny"]
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV)
+    head_idx = wl.random_head_idx(w, DEV)
+    ws = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.k, DEV)
+    a = polar.sha_decode(q, K, V, seqlens, head_idx, w.k, workspace=ws)
+    out = torch.empty_like(a)
+    polar.sha_partial(q, K, V, seqlens, head_idx, w.k, ws)
+    polar.sha_merge(seqlens, head_idx, out, w.Hkv, w.S, w.k, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int32), out.view(torch.int32))
+
+
+def test_non_default_stream():
+    w = wl.CONFIGS["C1_tiny"]
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV)
+    hidden, Wr = wl.make_router_inputs(w, DEV)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        head_idx = polar.router_topk(hidden, Wr, w.k)
+        out = polar.sha_decode(q, K, V, seqlens, head_idx, w.k)
+    s.synchronize()
+    check_against_oracle(w, q, K, V, seqlens, head_idx, out)
+
+
+# ----------------------------------------------------------------------------- router edge cases
+def router_case(hidden, Wr, k, dtype):
+    got = polar.router_topk(hidden, Wr, k)
+    torch.cuda.synchronize()
+    want = orc.router_topk(host_bits(hidden), host_bits(Wr), k, dtype)
+    assert np.array_equal(got.cpu().numpy(), want)
+    return want
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,D,H,k", [(1, 1, 1, 1), (3, 17, 5, 2), (5, 1000, 72, 36),
+                                     (2, 4096, 256, 256), (7, 333, 100, 1), (4, 16384, 8, 4),
+                                     (2, 3, 200, 50)])
+def test_router_shapes(dtype, B, D, H, k):
+    say("\ncase router", dtype, B, D, H, k)
+    g = torch.Generator(device=DEV).manual_seed(B * 1000 + D + H)
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+    hidden = torch.randn((B, D), generator=g, device=DEV).to(tdt)
+    Wr = (torch.randn((D, H), generator=g, device=DEV) / D ** 0.5).to(tdt)
+    router_case(hidden, Wr, k, dtype)
+
+
+def test_router_ties():
+    say("\ncase router ties")
+    g = torch.Generator(device=DEV).manual_seed(77)
+    D, H = 512, 16
+    Wr = (torch.randn((D, H), generator=g, device=DEV) / D ** 0.5).to(torch.float16)
+    Wr[:, 9] = Wr[:, 4]
+    Wr[:, 15] = Wr[:, 4]                                       # three identical columns
+    hidden = torch.randn((32, D), generator=g, device=DEV).to(torch.float16)
+    want = router_case(hidden, Wr, H, "f16")
+    for row in want.tolist():
+        assert row.index(9) == row.index(4) + 1 and row.index(15) == row.index(9) + 1
+    zero = torch.zeros((3, D), dtype=torch.float16, device=DEV)
+    assert router_case(zero, Wr, 5, "f16").tolist() == [[0, 1, 2, 3, 4]] * 3
+    # small integers: every partial sum is exact, so many exact ties between different columns
+    hi = torch.randint(-2, 3, (16, 64), generator=g, device=DEV).to(torch.bfloat16)
+    Wi = torch.randint(-1, 2, (64, 24), generator=g, device=DEV).to(torch.bfloat16)
+    router_case(hi, Wi, 12, "bf16")
+    # signed zeros: +0 and -0 logits tie and fall back to the id order
+    hz = torch.zeros((1, 8), dtype=torch.float16, device=DEV)
+    hz[0, 0] = 1.0
+    Wz = torch.zeros((8, 6), dtype=torch.float16, device=DEV)
+    Wz[0] = torch.tensor([0.0, -0.0, 0.0, -0.0, 0.0, -0.0])
+    assert router_case(hz, Wz, 6, "f16").tolist() == [[0, 1, 2, 3, 4, 5]]
