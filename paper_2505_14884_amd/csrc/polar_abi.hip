@@ -126,8 +126,8 @@ int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t
     int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);
     if (rc != POLAR_OK) return rc;
     if (!dtype_ok(dt) || !(scale >= 0.0f) || isinf(scale)) return POLAR_EINVAL;
-    if (!head_idx && k != Hkv) return POLAR_EINVAL;
     if (B == 0) return POLAR_OK;
+    if (!head_idx && k != Hkv) return POLAR_EINVAL;
     if (!q || !K || !V || !seqlens) return POLAR_EINVAL;
     if ((rc = check_workspace(plan, workspace, workspace_bytes)) != POLAR_OK) return rc;
     const float s = scale == 0.0f ? 1.0f / sqrtf((float)d) : scale;
@@ -144,8 +144,8 @@ int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
     ShaPlan plan;
     int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);
     if (rc != POLAR_OK) return rc;
-    if (!head_idx && k != Hkv) return POLAR_EINVAL;
     if (B == 0) return POLAR_OK;
+    if (!head_idx && k != Hkv) return POLAR_EINVAL;
     if (!seqlens || !out) return POLAR_EINVAL;
     if ((rc = check_workspace(plan, workspace, workspace_bytes)) != POLAR_OK) return rc;
     return record(launch_sha_merge(seqlens, head_idx, out, static_cast<const float *>(workspace),
