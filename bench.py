@@ -25,6 +25,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+# HBM bytes per launch of the KV-streaming kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# (each scaled by the same counter's reading for a plain 4 GiB copy); measured with this file's
+# --phase partial / --phase copy on the default shape of each workload.  Source:
+# profiles/sha_decode_step_<workload>.md.  Reported only when the shape is that default.
+MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4539991968}
 DEFAULT_WORKLOAD = "C4_opt66b"
 
 
@@ -37,9 +43,14 @@ def parse_args():
     ap.add_argument("--k", type=int, default=0, help="override the number of selected units")
     ap.add_argument("--B", type=int, default=0, help="override the batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip the dense (k = H) comparison run, so a kernel trace of this command "
+                         "holds selective launches only")
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests the oracle is timed on")
-    ap.add_argument("--phase", choices=["all", "partial"], default="all",
-                    help="'partial' launches only the KV-streaming kernel (for counter runs)")
+    ap.add_argument("--phase", choices=["all", "partial", "copy"], default="all",
+                    help="'partial' launches only the KV-streaming kernel (for counter runs); "
+                         "'copy' runs a plain device copy of known size, the yardstick the "
+                         "FETCH_SIZE / WRITE_SIZE counters are scaled by")
     return ap.parse_args()
 
 
@@ -61,6 +72,17 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.phase == "copy":
+        nbytes = 4 << 30
+        src = torch.full((nbytes // 4,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup + args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"phase": "copy", "launches": args.warmup + args.steps,
+                          "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes}))
+        return
 
     w = wl.CONFIGS[args.workload]
     if args.k:
@@ -139,9 +161,12 @@ def main():
     sha_avg, _, _ = event_time(
         lambda i: polar.sha_decode(q, caches[i % R][0], caches[i % R][1], seqlens, head_idx, w.k,
                                    out=out, workspace=ws), n_ev)
-    for i in range(3):
-        dense_step(i)
-    dense_avg, _, _ = event_time(dense_step, max(5, n_ev // 4))
+    if args.no_dense:
+        dense_avg = float("nan")
+    else:
+        for i in range(3):
+            dense_step(i)
+        dense_avg, _, _ = event_time(dense_step, max(5, n_ev // 4))
     achieved = bytes_sel / (part_avg * 1e-3) / 1e9
 
     result = {
@@ -173,9 +198,9 @@ def main():
             "router_topk": round(router_avg * 1e3, 2),
             "sha_decode(partial+merge)": round(sha_avg * 1e3, 2),
             "sha_partial": round(part_avg * 1e3, 2),
-            "dense_k_eq_H": round(dense_avg * 1e3, 2),
+            "dense_k_eq_H": None if args.no_dense else round(dense_avg * 1e3, 2),
         },
-        "dense_over_selective": round(dense_avg / sha_avg, 3),
+        "dense_over_selective": None if args.no_dense else round(dense_avg / sha_avg, 3),
         "ideal_H_over_k": round(w.Hkv / w.k, 3),
         "roofline": {
             "kernel": "sha_partial_kernel",
@@ -187,7 +212,7 @@ def main():
             "avg_us": round(part_avg * 1e3, 2),
             "median_us": round(part_med * 1e3, 2),
             "min_us": round(part_min * 1e3, 2),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if w == wl.CONFIGS[w.name] else None,
         },
     }
 

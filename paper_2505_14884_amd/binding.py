@@ -40,9 +40,10 @@ def lib() -> ctypes.CDLL:
     """Load the shared library, compiling it first only when no built copy exists."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        path = os.environ.get("POLAR_LIBRARY", LIB_PATH)   # a specific build, e.g. a tuning variant
+        if path == LIB_PATH and not os.path.exists(LIB_PATH):
             build_library()
-        L = ctypes.CDLL(LIB_PATH)
+        L = ctypes.CDLL(path)
         i, vp, f, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
         L.polar_router_topk.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp]
         L.polar_router_topk.restype = i

@@ -4,6 +4,7 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+import sys
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
@@ -26,16 +27,26 @@ def hipcc() -> str:
     return exe
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source into one shared object; always recompiles."""
-    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
-    cmd = [hipcc()] + HIPCC_FLAGS + ["-I", os.path.join(_ROOT, "include"), "-I", CSRC, "-o", tmp]
+def build_library(verbose: bool = False, defines=(), out_path: str = LIB_PATH) -> str:
+    """Compile every HIP source into one shared object; always recompiles.
+    `defines` (e.g. ["POLAR_SHA_LOADS=8"]) and `out_path` serve tuning sweeps."""
+    tmp = out_path + ".tmp.%d" % os.getpid()
+    cmd = [hipcc()] + HIPCC_FLAGS + ["-D" + d for d in defines]
+    cmd += ["-I", os.path.join(_ROOT, "include"), "-I", CSRC, "-o", tmp]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB_PATH)
-    return LIB_PATH
+    proc = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    # hipcc's host pass does not know the packed-fp32 feature switch and says so once per
+    # compile step; that notice is harmless, everything else is passed through
+    noise = "is not a recognized feature for this target"
+    rest = [ln for ln in proc.stderr.splitlines() if noise not in ln]
+    if rest:
+        print("\n".join(rest), file=sys.stderr, flush=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed with exit code %d" % proc.returncode)
+    os.replace(tmp, out_path)
+    return out_path
 
 
 if __name__ == "__main__":

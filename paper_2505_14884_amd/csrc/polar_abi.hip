@@ -20,18 +20,33 @@ int record(hipError_t e)
 
 bool dtype_ok(polar_dtype dt) { return dt == POLAR_F16 || dt == POLAR_BF16; }
 
-// Rows per workgroup of the streaming kernel.  A multiple of 128 (the rows one workgroup
-// consumes per step at d = 64; 64 at d = 128) so only the last chunk of a request has a
-// ragged tail.  POLAR_SHA_CHUNK_ROWS overrides the default for tuning sweeps.
-int choose_chunk(int S)
+// Rows of the cache one workgroup of the streaming kernel covers.  Splitting a sequence costs
+// an epilogue per workgroup and a record for the merge kernel to read, so the chunk is as large
+// as occupancy allows: enough splits that the grid holds about four workgroups per compute
+// unit (kFillWorkgroups), but never more than kMaxChunk rows, which bounds the work a single
+// workgroup carries when lengths are ragged.  Always a multiple of 128 rows (what a workgroup
+// consumes per step at d = 64; 64 rows at d = 128), so only the last chunk of a request has
+// a ragged tail.  POLAR_SHA_CHUNK_ROWS overrides the choice for tuning sweeps.
+constexpr long kFillWorkgroups = 1024;
+constexpr int kMaxChunk = 1024;
+constexpr int kMinChunk = 256;
+
+int choose_chunk(int B, int k, int S)
 {
-    int chunk = 256;
-    if (const char *env = getenv("POLAR_SHA_CHUNK_ROWS")) {
-        const long v = strtol(env, nullptr, 10);
-        if (v >= 128 && v <= (1 << 20)) chunk = (int)((v + 127) / 128 * 128);
-    }
     const int cap = (S + 127) / 128 * 128;
-    return chunk < cap ? chunk : cap;
+    long chunk;
+    if (const char *env = getenv("POLAR_SHA_CHUNK_ROWS")) {
+        chunk = strtol(env, nullptr, 10);
+        if (chunk < 128 || chunk > (1 << 20)) chunk = kMinChunk;
+    } else {
+        const long units = (long)(B > 0 ? B : 1) * k;
+        const long want_splits = (kFillWorkgroups + units - 1) / units;
+        chunk = (S + want_splits - 1) / want_splits;
+        if (chunk > kMaxChunk) chunk = kMaxChunk;
+        if (chunk < kMinChunk) chunk = kMinChunk;
+    }
+    chunk = (chunk + 127) / 128 * 128;
+    return chunk < cap ? (int)chunk : cap;
 }
 
 int check_sha_sizes(int B, int Hq, int Hkv, int S, int d, int k)
@@ -41,7 +56,7 @@ int check_sha_sizes(int B, int Hq, int Hkv, int S, int d, int k)
     if (d != 64 && d != 128) return POLAR_EUNSUPPORTED;
     const int G = Hq / Hkv;
     if (G != 1 && G != 2 && G != 4 && G != 8) return POLAR_EUNSUPPORTED;
-    if (B > 65535 || k > 65535 || Hq > 65535) return POLAR_EUNSUPPORTED;   // grid y/z limits
+    if (B > 65535 || Hq > 65535) return POLAR_EUNSUPPORTED;   // grid.y limit of the merge kernel
     return POLAR_OK;
 }
 
@@ -52,8 +67,9 @@ int make_sha_plan(int B, int Hq, int Hkv, int S, int d, int k, ShaPlan *plan)
     const int rc = check_sha_sizes(B, Hq, Hkv, S, d, k);
     if (rc != POLAR_OK) return rc;
     plan->G = Hq / Hkv;
-    plan->chunk = choose_chunk(S);
+    plan->chunk = choose_chunk(B, k, S);
     plan->nsplit = (S + plan->chunk - 1) / plan->chunk;
+    if ((size_t)B * plan->nsplit * k > 0x7fffffffu) return POLAR_EUNSUPPORTED;   // 1-D grid limit
     const size_t units = (size_t)B * k * plan->G * plan->nsplit;
     plan->o_floats = (units * d + 63) / 64 * 64;   // keeps the (max, sum) region 256-byte aligned
     plan->ml_floats = units * 2;

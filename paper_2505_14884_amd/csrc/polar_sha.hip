@@ -29,9 +29,16 @@
 namespace polar {
 namespace {
 
-constexpr int kWaves = 4;                 // waves per workgroup of the streaming kernel
+// Tuning constants (overridable at build time for sweeps).
+#ifndef POLAR_SHA_WAVES
+#define POLAR_SHA_WAVES 4
+#endif
+#ifndef POLAR_SHA_LOADS
+#define POLAR_SHA_LOADS 4
+#endif
+constexpr int kWaves = POLAR_SHA_WAVES;   // waves per workgroup of the streaming kernel
 constexpr int kThreads = kWaves * 64;
-constexpr int kLoads = 4;                 // 16-byte loads of K (and of V) per lane per step
+constexpr int kLoads = POLAR_SHA_LOADS;   // 16-byte loads of K (and of V) per lane per step
 constexpr float kNegBig = -1.0e30f;       // "no row seen yet": finite, so exp2(x - max) never sees inf - inf
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -134,7 +141,12 @@ __device__ __forceinline__ void consume(const uint4 (&kr)[kLoads], const uint4 (
     }
 }
 
-// Streaming kernel.  grid = (nsplit, k, B); block = kThreads.
+// Streaming kernel.  1-D grid of B*nsplit*k workgroups; block = kThreads.
+// Workgroup L works on slot = L % k, split = (L / k) % nsplit, b = L / (k * nsplit).  The slot
+// varies fastest on purpose: the hardware deals consecutive workgroups round-robin over the 8
+// XCDs, and the k workgroups of one (request, split) all have the same amount of work, so every
+// XCD gets an equal share of each request however ragged the lengths are.  (With the split
+// fastest, XCD j would get exactly the splits congruent to j, and late splits are mostly empty.)
 // Workspace record of unit u = ((b*k + slot)*G + gi)*nsplit + split:
 //   ws_o[u*D .. u*D+D)   unnormalised output, ws_ml[2u] running max (base-2), ws_ml[2u+1] sum.
 // A workgroup whose chunk starts at or beyond n_b, or whose head id is out of range, writes
@@ -151,7 +163,9 @@ __global__ __launch_bounds__(kThreads) void sha_partial_kernel(
     constexpr int ROWS_WAVE = kLoads * RPL;
     constexpr int ROWS_WG = kWaves * ROWS_WAVE;
 
-    const int split = blockIdx.x, slot = blockIdx.y, b = blockIdx.z;
+    const int slot = blockIdx.x % k;
+    const int rest = blockIdx.x / k;
+    const int split = rest % nsplit, b = rest / nsplit;
     int n = seqlens[b];
     n = n < 0 ? 0 : (n > S ? S : n);
     const int row_begin = split * chunk;
@@ -269,41 +283,74 @@ __global__ __launch_bounds__(kThreads) void sha_partial_kernel(
     }
 }
 
-// Merge / zero-fill kernel.  grid = (Hq, B); block = D threads; thread t owns out[b,h,t].
-// The query head's group is looked up in the request's row of the batch head index (first
-// match wins, so duplicate ids are harmless); heads with no match are stored as +0.0.
+// Merge / zero-fill kernel.  grid = (ceil(Hq / kMergeHeads), B); block = 256 threads.
+// A workgroup owns kMergeHeads consecutive query heads of one request.  It first finds, with
+// one parallel pass over the request's row of the batch head index, the slot that selected
+// each of the (at most kMergeHeads) KV groups those heads belong to (lowest slot wins, so
+// duplicate ids are harmless); then D threads per head combine that head's chunk records
+// with the max/sum rescale of Algorithm 1 and normalise.  Heads whose group has no slot, and
+// requests of length 0, are stored as +0.0.
+constexpr int kMergeHeads = 8;
+constexpr int kMergeThreads = 256;
+constexpr int kNoSlot = 0x7fffffff;
+
 template <int D>
-__global__ __launch_bounds__(D) void sha_merge_kernel(
+__global__ __launch_bounds__(kMergeThreads) void sha_merge_kernel(
     const int32_t *__restrict__ seqlens, const int32_t *__restrict__ head_idx,
     const float *__restrict__ ws_o, const float *__restrict__ ws_ml, float *__restrict__ out,
     int Hq, int Hkv, int S, int k, int G, int chunk, int nsplit)
 {
-    const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
-    const int g_kv = h / G, gi = h % G;
+    constexpr int HEADS_PER_PASS = kMergeThreads / D;
+    __shared__ int slot_of[kMergeHeads];
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int h0 = blockIdx.x * kMergeHeads;
+    const int h_last = min(h0 + kMergeHeads, Hq) - 1;
+    const int g_first = h0 / G, g_last = h_last / G;
+
+    if (tid < kMergeHeads) slot_of[tid] = kNoSlot;
+    __syncthreads();
+    if (head_idx) {
+        for (int s = tid; s < k; s += kMergeThreads) {
+            const int id = head_idx[(size_t)b * k + s];
+            if (id >= g_first && id <= g_last) atomicMin(&slot_of[id - g_first], s);
+        }
+    } else if (tid <= g_last - g_first) {
+        slot_of[tid] = g_first + tid;               // dense: slot == KV head
+    }
+    __syncthreads();
+
     int n = seqlens[b];
     n = n < 0 ? 0 : (n > S ? S : n);
-    int slot = -1;
-    if (head_idx) {
-        for (int s = k - 1; s >= 0; --s)
-            if (head_idx[(size_t)b * k + s] == g_kv) slot = s;
-    } else {
-        slot = g_kv;
-    }
-    float result = 0.0f;
-    if (slot >= 0 && n > 0) {
-        const int used = (n + chunk - 1) / chunk;
-        const size_t unit0 = (((size_t)b * k + slot) * G + gi) * nsplit;
-        float mx = kNegBig;
-        for (int c = 0; c < used; ++c) mx = fmaxf(mx, ws_ml[(unit0 + c) * 2]);
-        float acc = 0.0f, lsum = 0.0f;
-        for (int c = 0; c < used; ++c) {
-            const float a = fast_exp2(ws_ml[(unit0 + c) * 2] - mx);
-            lsum = fmaf(a, ws_ml[(unit0 + c) * 2 + 1], lsum);
-            acc = fmaf(a, ws_o[(unit0 + c) * D + t], acc);
+    const int used = (n + chunk - 1) / chunk;
+    const int t = tid % D;
+#pragma unroll
+    for (int pass = 0; pass < kMergeHeads / HEADS_PER_PASS; ++pass) {
+        const int h = h0 + pass * HEADS_PER_PASS + tid / D;
+        if (h > h_last) continue;
+        const int slot = slot_of[h / G - g_first];
+        float result = 0.0f;
+        if (slot != kNoSlot && used > 0) {
+            const size_t unit0 = (((size_t)b * k + slot) * G + (h % G)) * nsplit;
+            // One pass with a running max (the recurrence of Algorithm 1 over chunks): the
+            // loads of different chunks are independent of the arithmetic, so unrolling puts
+            // several records in flight at once.
+            const float2 *ml = reinterpret_cast<const float2 *>(ws_ml) + unit0;
+            const float *oc = ws_o + unit0 * D + t;
+            float mx = kNegBig, acc = 0.0f, lsum = 0.0f;
+#pragma unroll 4
+            for (int c = 0; c < used; ++c) {
+                const float2 rec = ml[c];
+                const float part = oc[(size_t)c * D];
+                const float m_new = fmaxf(mx, rec.x);
+                const float a_old = fast_exp2(mx - m_new), a_new = fast_exp2(rec.x - m_new);
+                lsum = fmaf(a_new, rec.y, lsum * a_old);
+                acc = fmaf(a_new, part, acc * a_old);
+                mx = m_new;
+            }
+            result = lsum > 0.0f ? acc / lsum : 0.0f;
         }
-        result = lsum > 0.0f ? acc / lsum : 0.0f;
+        out[((size_t)b * Hq + h) * D + t] = result;
     }
-    out[((size_t)b * Hq + h) * D + t] = result;
 }
 
 template <class DT, int D>
@@ -333,7 +380,7 @@ hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const
                               int Hq, int Hkv, int S, int d, int k, polar_dtype dt,
                               float scale_log2e, hipStream_t stream)
 {
-    const dim3 grid((unsigned)plan.nsplit, (unsigned)k, (unsigned)B);
+    const dim3 grid((unsigned)((size_t)B * plan.nsplit * k));
     float *ws_o = ws, *ws_ml = ws + plan.o_floats;
     const uint16_t *q16 = static_cast<const uint16_t *>(q);
     const uint16_t *K16 = static_cast<const uint16_t *>(K);
@@ -355,13 +402,14 @@ hipError_t launch_sha_merge(const int32_t *seqlens, const int32_t *head_idx, flo
                             const float *ws, const ShaPlan &plan, int B, int Hq, int Hkv, int S,
                             int d, int k, hipStream_t stream)
 {
-    const dim3 grid((unsigned)Hq, (unsigned)B);
+    const dim3 grid((unsigned)((Hq + kMergeHeads - 1) / kMergeHeads), (unsigned)B);
     const float *ws_o = ws, *ws_ml = ws + plan.o_floats;
     if (d == 128)
-        hipLaunchKernelGGL((sha_merge_kernel<128>), grid, dim3(128), 0, stream, seqlens, head_idx,
-                           ws_o, ws_ml, out, Hq, Hkv, S, k, plan.G, plan.chunk, plan.nsplit);
+        hipLaunchKernelGGL((sha_merge_kernel<128>), grid, dim3(kMergeThreads), 0, stream, seqlens,
+                           head_idx, ws_o, ws_ml, out, Hq, Hkv, S, k, plan.G, plan.chunk,
+                           plan.nsplit);
     else if (d == 64)
-        hipLaunchKernelGGL((sha_merge_kernel<64>), grid, dim3(64), 0, stream, seqlens, head_idx,
+        hipLaunchKernelGGL((sha_merge_kernel<64>), grid, dim3(kMergeThreads), 0, stream, seqlens, head_idx,
                            ws_o, ws_ml, out, Hq, Hkv, S, k, plan.G, plan.chunk, plan.nsplit);
     else
         return hipErrorInvalidValue;
