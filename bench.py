@@ -104,11 +104,12 @@ def main():
     head_idx = torch.empty((w.B, w.k), dtype=torch.int32, device=dev)
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
     ws = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.Hkv, dev)   # sized for dense too
+    rws = polar.alloc_router_workspace(w.B, w.D, w.Hkv, dev)
     chunk = polar.sha_chunk_rows(w.B, w.Hq, w.Hkv, w.S, w.d, w.k)
 
     def step(i):
         Ki, Vi = caches[i % R]
-        polar.router_topk(hidden, Wr, w.k, head_idx=head_idx)
+        polar.router_topk(hidden, Wr, w.k, head_idx=head_idx, workspace=rws)
         polar.sha_decode(q, Ki, Vi, seqlens, head_idx, w.k, out=out, workspace=ws)
 
     def partial_only(i):
@@ -119,7 +120,7 @@ def main():
         Ki, Vi = caches[i % R]
         polar.sha_decode(q, Ki, Vi, seqlens, None, w.Hkv, out=out, workspace=ws)
 
-    polar.router_topk(hidden, Wr, w.k, head_idx=head_idx)
+    polar.router_topk(hidden, Wr, w.k, head_idx=head_idx, workspace=rws)
     torch.cuda.synchronize()
 
     if args.phase == "partial":
@@ -157,7 +158,7 @@ def main():
 
     n_ev = max(10, min(args.steps, 100))
     part_avg, part_med, part_min = event_time(partial_only, n_ev)
-    router_avg, _, _ = event_time(lambda i: polar.router_topk(hidden, Wr, w.k, head_idx=head_idx), n_ev)
+    router_avg, _, _ = event_time(lambda i: polar.router_topk(hidden, Wr, w.k, head_idx=head_idx, workspace=rws), n_ev)
     sha_avg, _, _ = event_time(
         lambda i: polar.sha_decode(q, caches[i % R][0], caches[i % R][1], seqlens, head_idx, w.k,
                                    out=out, workspace=ws), n_ev)

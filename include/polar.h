@@ -62,13 +62,23 @@ typedef enum {
  *   head_idx   out  [B, k]  int32
  *   logits_out out  [B, H]  float, nullable: the logits rounded to float, for inspection.
  *
+ *   workspace  nullable.  NULL: one workgroup per request does the whole row (no scratch
+ *                   needed; at most B compute units busy).  Otherwise at least
+ *                   polar_router_workspace_bytes(B, D, H) bytes, 256-byte aligned, contents
+ *                   need no initialisation: the D axis is split over many workgroups that
+ *                   leave partial sums there and a second small kernel adds and ranks them.
+ *
  * Products are exact and the sum over D is accumulated in double precision in a fixed,
- * column-independent order, so identical columns of Wr give bit-identical logits and the
- * result does not depend on launch timing.  1 <= k <= H <= POLAR_MAX_ROUTER_H,
- * 1 <= D <= POLAR_MAX_ROUTER_D.
+ * column-independent order (a different fixed order with and without a workspace), so
+ * identical columns of Wr give bit-identical logits and the result does not depend on launch
+ * timing.  1 <= k <= H <= POLAR_MAX_ROUTER_H, 1 <= D <= POLAR_MAX_ROUTER_D.
  */
 int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, int k,
-                      polar_dtype dt, int32_t *head_idx, float *logits_out, void *stream);
+                      polar_dtype dt, int32_t *head_idx, float *logits_out, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/* Bytes of device workspace the split path of polar_router_topk needs; 0 for invalid sizes. */
+size_t polar_router_workspace_bytes(int B, int D, int H);
 
 /*
  * Bytes of device workspace polar_sha_decode needs for these sizes (split-KV partial

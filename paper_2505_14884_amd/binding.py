@@ -19,7 +19,7 @@ from .build import LIB_PATH, build_library
 F16, BF16 = 0, 1
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
-EXPORTS = ("polar_router_topk", "polar_sha_workspace_bytes", "polar_sha_decode",
+EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
            "polar_sha_partial", "polar_sha_merge", "polar_sha_chunk_rows", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
@@ -45,8 +45,10 @@ def lib() -> ctypes.CDLL:
             build_library()
         L = ctypes.CDLL(path)
         i, vp, f, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
-        L.polar_router_topk.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp]
+        L.polar_router_topk.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp, sz, vp]
         L.polar_router_topk.restype = i
+        L.polar_router_workspace_bytes.argtypes = [i, i, i]
+        L.polar_router_workspace_bytes.restype = sz
         L.polar_sha_workspace_bytes.argtypes = [i] * 6
         L.polar_sha_workspace_bytes.restype = sz
         L.polar_sha_chunk_rows.argtypes = [i] * 6
@@ -94,19 +96,34 @@ def _check(rc: int, where: str) -> None:
         raise PolarError(rc, where)
 
 
+def router_workspace_bytes(B: int, D: int, H: int) -> int:
+    return int(lib().polar_router_workspace_bytes(B, D, H))
+
+
+def alloc_router_workspace(B: int, D: int, H: int, device) -> torch.Tensor:
+    nbytes = router_workspace_bytes(B, D, H)
+    if nbytes == 0:
+        raise PolarError(-2, "polar_router_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
 def router_topk(hidden: torch.Tensor, Wr: torch.Tensor, k: int,
                 head_idx: Optional[torch.Tensor] = None,
-                logits_out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """hidden [B,D], Wr [D,H] (fp16/bf16, GPU) -> head_idx int32 [B,k]."""
+                logits_out: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """hidden [B,D], Wr [D,H] (fp16/bf16, GPU) -> head_idx int32 [B,k].
+    With a workspace (alloc_router_workspace) the library uses its split-D kernels."""
     B, D = hidden.shape
     D2, H = Wr.shape
     if D != D2 or hidden.dtype != Wr.dtype:
         raise ValueError("hidden [B,D] and Wr [D,H] must agree in D and dtype")
     if head_idx is None:
         head_idx = torch.empty((B, max(k, 0)), dtype=torch.int32, device=hidden.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().polar_router_topk(_dev(hidden, "hidden"), _dev(Wr, "Wr"), B, D, H, k,
                                  _dtype_code(hidden), _dev(head_idx, "head_idx", torch.int32),
-                                 _dev(logits_out, "logits_out", torch.float32), _stream())
+                                 _dev(logits_out, "logits_out", torch.float32),
+                                 _dev(workspace, "workspace"), ws_bytes, _stream())
     _check(rc, "polar_router_topk")
     return head_idx
 

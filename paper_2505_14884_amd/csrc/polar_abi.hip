@@ -20,13 +20,15 @@ int record(hipError_t e)
 
 bool dtype_ok(polar_dtype dt) { return dt == POLAR_F16 || dt == POLAR_BF16; }
 
-// Rows of the cache one workgroup of the streaming kernel covers.  Splitting a sequence costs
-// an epilogue per workgroup and a record for the merge kernel to read, so the chunk is as large
-// as occupancy allows: enough splits that the grid holds about four workgroups per compute
-// unit (kFillWorkgroups), but never more than kMaxChunk rows, which bounds the work a single
-// workgroup carries when lengths are ragged.  Always a multiple of 128 rows (what a workgroup
-// consumes per step at d = 64; 64 rows at d = 128), so only the last chunk of a request has
-// a ragged tail.  POLAR_SHA_CHUNK_ROWS overrides the choice for tuning sweeps.
+// Rows of the cache one workgroup of the streaming kernel covers.  Every workgroup pays a fixed
+// few microseconds (index loads, first-load latency, the merge epilogue) and every split adds a
+// record for the merge kernel, so chunks are as large as two things allow: occupancy (enough
+// splits that the grid holds about kFillWorkgroups workgroups) and the tail of the grid (a
+// lone workgroup streams far below the chip's bandwidth, so the work one workgroup carries is
+// capped at kMaxChunk rows).  A cache of at most 2*kMaxChunk rows is not split at all when
+// the (request, head) units alone fill the chip.  Always a multiple of 128 rows, which every
+// kernel shape's per-wave step (16 to 64 rows) divides, so only a request's last chunk has a
+// ragged tail.  POLAR_SHA_CHUNK_ROWS overrides the choice for tuning sweeps.
 constexpr long kFillWorkgroups = 1024;
 constexpr int kMaxChunk = 1024;
 constexpr int kMinChunk = 256;
@@ -42,7 +44,7 @@ int choose_chunk(int B, int k, int S)
         const long units = (long)(B > 0 ? B : 1) * k;
         const long want_splits = (kFillWorkgroups + units - 1) / units;
         chunk = (S + want_splits - 1) / want_splits;
-        if (chunk > kMaxChunk) chunk = kMaxChunk;
+        if (chunk > kMaxChunk && !(want_splits == 1 && S <= 2 * kMaxChunk)) chunk = kMaxChunk;
         if (chunk < kMinChunk) chunk = kMinChunk;
     }
     chunk = (chunk + 127) / 128 * 128;
@@ -100,16 +102,29 @@ const char *polar_strerror(int status)
     }
 }
 
+size_t polar_router_workspace_bytes(int B, int D, int H)
+{
+    RouterPlan plan;
+    if (make_router_plan(B, D, H, &plan) != POLAR_OK) return 0;
+    return plan.bytes;
+}
+
 int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, int k,
-                      polar_dtype dt, int32_t *head_idx, float *logits_out, void *stream)
+                      polar_dtype dt, int32_t *head_idx, float *logits_out, void *workspace,
+                      size_t workspace_bytes, void *stream)
 {
     if (B < 0 || D < 1 || H < 1 || k < 1 || k > H || !dtype_ok(dt)) return POLAR_EINVAL;
-    if (H > POLAR_MAX_ROUTER_H || D > POLAR_MAX_ROUTER_D || B > 0x7fffffff / 2)
-        return POLAR_EUNSUPPORTED;
+    RouterPlan plan;
+    const int rc = make_router_plan(B, D, H, &plan);
+    if (rc != POLAR_OK) return rc;
     if (B == 0) return POLAR_OK;
     if (!hidden || !Wr || !head_idx) return POLAR_EINVAL;
-    return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
-                                     static_cast<hipStream_t>(stream)));
+    if (!workspace)
+        return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
+                                         static_cast<hipStream_t>(stream)));
+    if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < plan.bytes) return POLAR_EWORKSPACE;
+    return record(launch_router_split(hidden, Wr, B, D, H, k, dt, plan, head_idx, logits_out,
+                                      workspace, static_cast<hipStream_t>(stream)));
 }
 
 size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k)

@@ -23,6 +23,15 @@ struct ShaPlan {
 // Fills `plan`; returns POLAR_OK or the status the public calls must return for these sizes.
 int make_sha_plan(int B, int Hq, int Hkv, int S, int d, int k, ShaPlan *plan);
 
+// Launch geometry of the split-D router path.
+struct RouterPlan {
+    int RT;        // request tiles (kTileR requests each)
+    int P;         // slices of the D axis
+    int Dp;        // rows of Wr per slice
+    size_t bytes;  // workspace bytes, 256-aligned
+};
+int make_router_plan(int B, int D, int H, RouterPlan *plan);
+
 // Kernel launchers.  Arguments were validated by the caller; each returns the hipError_t of
 // its launch.
 hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
@@ -35,5 +44,8 @@ hipError_t launch_sha_merge(const int32_t *seqlens, const int32_t *head_idx, flo
 hipError_t launch_router_topk(const void *hidden, const void *Wr, int B, int D, int H, int k,
                               polar_dtype dt, int32_t *head_idx, float *logits_out,
                               hipStream_t stream);
+hipError_t launch_router_split(const void *hidden, const void *Wr, int B, int D, int H, int k,
+                               polar_dtype dt, const RouterPlan &plan, int32_t *head_idx,
+                               float *logits_out, void *workspace, hipStream_t stream);
 
 }  // namespace polar

@@ -26,6 +26,8 @@ namespace polar {
 namespace {
 
 constexpr int kRouterThreads = 1024;
+constexpr int kStageBatch = 4;   // hidden elements a thread stages per batch of loads
+constexpr int kRowBatch = 8;     // rows of Wr a thread loads before consuming any
 
 template <bool BF> __device__ __forceinline__ double widen_one(uint32_t bits16)
 {
@@ -79,7 +81,22 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
 
     const int b = blockIdx.x, tid = threadIdx.x;
     const uint16_t *hrow = hidden + (size_t)b * D;
-    for (int i = tid; i < D; i += kRouterThreads) sh_hidden[i] = hrow[i];
+    // Stage the request's hidden row.  Every load of a batch is issued before any is used:
+    // a dependent round trip to memory costs about a microsecond, so the kernel's time is
+    // the number of such rounds, not its arithmetic.
+    for (int base = 0; base < D; base += kStageBatch * kRouterThreads) {
+        uint16_t v[kStageBatch];
+#pragma unroll
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int i = base + u * kRouterThreads + tid;
+            v[u] = i < D ? hrow[i] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int i = base + u * kRouterThreads + tid;
+            if (i < D) sh_hidden[i] = v[u];
+        }
+    }
     __syncthreads();
 
     const int CG = H / VEC;                    // column groups per row of Wr
@@ -89,29 +106,27 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
         double a0[VEC], a1[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) a0[v] = a1[v] = 0.0;
-        int i = slice;
-        for (; i + 3 * nslice < D; i += 4 * nslice) {
-            const vec_t w0 = w[(size_t)i * CG];
-            const vec_t w1 = w[(size_t)(i + nslice) * CG];
-            const vec_t w2 = w[(size_t)(i + 2 * nslice) * CG];
-            const vec_t w3 = w[(size_t)(i + 3 * nslice) * CG];
-            const double h0 = widen_one<BF>(sh_hidden[i]);
-            const double h1 = widen_one<BF>(sh_hidden[i + nslice]);
-            const double h2 = widen_one<BF>(sh_hidden[i + 2 * nslice]);
-            const double h3 = widen_one<BF>(sh_hidden[i + 3 * nslice]);
+        // rows slice, slice + nslice, ...: kRowBatch loads in flight, then their multiply-adds,
+        // even rows of the batch into chain a0 and odd rows into a1
+        for (int i = slice; i < D; i += kRowBatch * nslice) {
+            vec_t wv[kRowBatch];
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                a0[v] = fma(h0, widen_one<BF>(lane16(w0, v)), a0[v]);
-                a1[v] = fma(h1, widen_one<BF>(lane16(w1, v)), a1[v]);
-                a0[v] = fma(h2, widen_one<BF>(lane16(w2, v)), a0[v]);
-                a1[v] = fma(h3, widen_one<BF>(lane16(w3, v)), a1[v]);
+            for (int u = 0; u < kRowBatch; ++u) {
+                const int row = i + u * nslice;
+                wv[u] = w[(size_t)(row < D ? row : i) * CG];
             }
-        }
-        for (; i < D; i += nslice) {
-            const vec_t w0 = w[(size_t)i * CG];
-            const double h0 = widen_one<BF>(sh_hidden[i]);
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) a0[v] = fma(h0, widen_one<BF>(lane16(w0, v)), a0[v]);
+            for (int u = 0; u < kRowBatch; ++u) {
+                const int row = i + u * nslice;
+                const double hv = row < D ? widen_one<BF>(sh_hidden[row]) : 0.0;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    if (u & 1)
+                        a1[v] = fma(hv, widen_one<BF>(lane16(wv[u], v)), a1[v]);
+                    else
+                        a0[v] = fma(hv, widen_one<BF>(lane16(wv[u], v)), a0[v]);
+                }
+            }
         }
 #pragma unroll
         for (int v = 0; v < VEC; ++v) sh_part[(size_t)slice * H + cg * VEC + v] = a0[v] + a1[v];
@@ -169,6 +184,184 @@ hipError_t launch_vec(const uint16_t *hidden, const uint16_t *Wr, int B, int D, 
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Split-D path (used when the caller supplies a workspace).  One workgroup per request keeps
+// at most B compute units busy and pays two conversions per multiply-add; here a workgroup
+// takes a tile of kTileR requests and one of P slices of the D axis, so a converted Wr
+// element feeds kTileR multiply-adds and the grid (P x ceil(B / kTileR)) covers the chip.
+// Phase 1 leaves, per (request tile, D slice), the kTileR x H partial sums in the workspace;
+// phase 2 adds the P partials of each request in ascending slice order and ranks.
+// The order of additions again depends on (D, H, VEC, P) only, never on the column.
+constexpr int kTileR = 2;
+constexpr int kSplitThreads = 256;
+constexpr int kFinishBatch = 16;
+
+// dynamic LDS: double h[kTileR][Dp] | double part[nslice][kTileR*H] | double part2[J][kTileR*H]
+template <bool BF, int VEC>
+__global__ __launch_bounds__(kSplitThreads) void router_partial_kernel(
+    const uint16_t *__restrict__ hidden, const uint16_t *__restrict__ Wr, int B, int D, int H,
+    int Dp, int nslice, int J, double *__restrict__ ws)
+{
+    typedef typename VecOf<VEC>::type vec_t;
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *sh_h = reinterpret_cast<double *>(smem);
+    double *sh_part = sh_h + (size_t)kTileR * Dp;
+    const int RH = kTileR * H;
+    double *sh_part2 = sh_part + (size_t)nslice * RH;
+
+    const int p = blockIdx.x, rt = blockIdx.y, P = gridDim.x, tid = threadIdx.x;
+    const int i0 = p * Dp;
+    const int rows = min(Dp, D - i0);
+
+    // stage (and widen once) the tile's hidden rows; all loads of a batch before any use
+    for (int base = 0; base < kTileR * rows; base += kStageBatch * kSplitThreads) {
+        uint16_t v[kStageBatch];
+#pragma unroll
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int e = base + u * kSplitThreads + tid;
+            const int r = e / rows, i = e - r * rows;
+            const int b = rt * kTileR + r;
+            v[u] = (e < kTileR * rows && b < B) ? hidden[(size_t)b * D + i0 + i] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int e = base + u * kSplitThreads + tid;
+            const int r = e / rows, i = e - r * rows;
+            if (e < kTileR * rows) sh_h[r * Dp + i] = widen_one<BF>(v[u]);
+        }
+    }
+    __syncthreads();
+
+    const int CG = H / VEC;
+    if (tid < nslice * CG) {
+        const int slice = tid / CG, cg = tid - slice * CG;
+        const vec_t *w = reinterpret_cast<const vec_t *>(Wr) + (size_t)i0 * CG + cg;
+        double acc[kTileR][VEC];
+#pragma unroll
+        for (int r = 0; r < kTileR; ++r)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[r][v] = 0.0;
+        for (int i = slice; i < rows; i += kRowBatch * nslice) {
+            vec_t wv[kRowBatch];
+#pragma unroll
+            for (int u = 0; u < kRowBatch; ++u) {
+                const int row = i + u * nslice;
+                wv[u] = w[(size_t)(row < rows ? row : i) * CG];
+            }
+#pragma unroll
+            for (int u = 0; u < kRowBatch; ++u) {
+                const int row = i + u * nslice;
+                if (row < rows) {
+                    double wd[VEC];
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) wd[v] = widen_one<BF>(lane16(wv[u], v));
+#pragma unroll
+                    for (int r = 0; r < kTileR; ++r) {
+                        const double hr = sh_h[r * Dp + row];
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc[r][v] = fma(hr, wd[v], acc[r][v]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kTileR; ++r)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+                sh_part[(size_t)slice * RH + r * H + cg * VEC + v] = acc[r][v];
+    }
+    __syncthreads();
+
+    for (int e = tid; e < J * RH; e += kSplitThreads) {      // level 1: slices j, j+J, ...
+        const int j = e / RH, x = e - j * RH;
+        double sum = 0.0;
+        for (int s = j; s < nslice; s += J) sum += sh_part[(size_t)s * RH + x];
+        sh_part2[e] = sum;
+    }
+    __syncthreads();
+    double *dst = ws + ((size_t)rt * P + p) * RH;
+    for (int x = tid; x < RH; x += kSplitThreads) {          // level 2: the J group sums
+        double sum = 0.0;
+        for (int j = 0; j < J; ++j) sum += sh_part2[j * RH + x];
+        dst[x] = sum;
+    }
+}
+
+// Phase 2: one workgroup per request; thread h adds the P slice partials in ascending order,
+// then the same rank counting as the single-kernel path.
+__global__ __launch_bounds__(POLAR_MAX_ROUTER_H) void router_finish_kernel(
+    const double *__restrict__ ws, int H, int k, int P, int32_t *__restrict__ head_idx,
+    float *__restrict__ logits_out)
+{
+    __shared__ double sh_logit[POLAR_MAX_ROUTER_H];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int rt = b / kTileR, r = b - rt * kTileR;
+    if (tid < H) {
+        const double *src = ws + ((size_t)rt * P * kTileR + r) * H + tid;
+        double sum = 0.0;
+        for (int p0 = 0; p0 < P; p0 += kFinishBatch) {      // a batch of loads, then ordered adds
+            double v[kFinishBatch];
+#pragma unroll
+            for (int u = 0; u < kFinishBatch; ++u)
+                v[u] = p0 + u < P ? src[(size_t)(p0 + u) * kTileR * H] : 0.0;
+#pragma unroll
+            for (int u = 0; u < kFinishBatch; ++u)
+                if (p0 + u < P) sum += v[u];
+        }
+        sh_logit[tid] = sum;
+        if (logits_out) logits_out[(size_t)b * H + tid] = (float)sum;
+    }
+    __syncthreads();
+    if (tid < H) {
+        const double mine = sh_logit[tid];
+        int rank = 0;
+        for (int j = 0; j < H; ++j) rank += precedes(sh_logit[j], j, mine, tid) ? 1 : 0;
+        if (rank < k) head_idx[(size_t)b * k + rank] = tid;
+    }
+}
+
+template <bool BF, int VEC>
+hipError_t launch_split_vec(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H, int k,
+                            const RouterPlan &plan, int32_t *head_idx, float *logits_out, double *ws,
+                            hipStream_t stream)
+{
+    const int CG = H / VEC;
+    int nslice = kSplitThreads / CG;
+    if (nslice < 1) nslice = 1;
+    int J = 1;
+    while (J * J < nslice) ++J;
+    const int RH = kTileR * H;
+    const size_t lds = ((size_t)kTileR * plan.Dp + (size_t)nslice * RH + (size_t)J * RH) * sizeof(double);
+    auto kern = router_partial_kernel<BF, VEC>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)plan.P, (unsigned)plan.RT), dim3(kSplitThreads), lds, stream,
+                       hidden, Wr, B, D, H, plan.Dp, nslice, J, ws);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(router_finish_kernel, dim3((unsigned)B), dim3(POLAR_MAX_ROUTER_H), 0, stream, ws, H,
+                       k, plan.P, head_idx, logits_out);
+    return hipGetLastError();
+}
+
+template <bool BF>
+hipError_t launch_split_dt(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H, int k,
+                           const RouterPlan &plan, int32_t *head_idx, float *logits_out, double *ws,
+                           hipStream_t stream)
+{
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(Wr);
+    if (H % 8 == 0 && addr % 16 == 0)
+        return launch_split_vec<BF, 8>(hidden, Wr, B, D, H, k, plan, head_idx, logits_out, ws, stream);
+    if (H % 4 == 0 && addr % 8 == 0)
+        return launch_split_vec<BF, 4>(hidden, Wr, B, D, H, k, plan, head_idx, logits_out, ws, stream);
+    if (H % 2 == 0 && addr % 4 == 0)
+        return launch_split_vec<BF, 2>(hidden, Wr, B, D, H, k, plan, head_idx, logits_out, ws, stream);
+    return launch_split_vec<BF, 1>(hidden, Wr, B, D, H, k, plan, head_idx, logits_out, ws, stream);
+}
+
 template <bool BF>
 hipError_t launch_dt(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H, int k,
                      int32_t *head_idx, float *logits_out, hipStream_t stream)
@@ -193,6 +386,37 @@ hipError_t launch_router_topk(const void *hidden, const void *Wr, int B, int D, 
     const uint16_t *w16 = static_cast<const uint16_t *>(Wr);
     if (dt == POLAR_BF16) return launch_dt<true>(h16, w16, B, D, H, k, head_idx, logits_out, stream);
     return launch_dt<false>(h16, w16, B, D, H, k, head_idx, logits_out, stream);
+}
+
+hipError_t launch_router_split(const void *hidden, const void *Wr, int B, int D, int H, int k,
+                               polar_dtype dt, const RouterPlan &plan, int32_t *head_idx,
+                               float *logits_out, void *workspace, hipStream_t stream)
+{
+    const uint16_t *h16 = static_cast<const uint16_t *>(hidden);
+    const uint16_t *w16 = static_cast<const uint16_t *>(Wr);
+    double *ws = static_cast<double *>(workspace);
+    if (dt == POLAR_BF16)
+        return launch_split_dt<true>(h16, w16, B, D, H, k, plan, head_idx, logits_out, ws, stream);
+    return launch_split_dt<false>(h16, w16, B, D, H, k, plan, head_idx, logits_out, ws, stream);
+}
+
+int make_router_plan(int B, int D, int H, RouterPlan *plan)
+{
+    if (B < 0 || D < 1 || H < 1) return POLAR_EINVAL;
+    if (H > POLAR_MAX_ROUTER_H || D > POLAR_MAX_ROUTER_D || B > 0x7fffffff / 2)
+        return POLAR_EUNSUPPORTED;
+    plan->RT = (B + kTileR - 1) / kTileR;
+    if (plan->RT > 65535) return POLAR_EUNSUPPORTED;             // grid.y limit
+    const int rt = plan->RT > 0 ? plan->RT : 1;
+    int P = (512 + rt - 1) / rt;                                 // aim at ~512 workgroups
+    const int p_max = (D + 127) / 128, p_min = (D + 511) / 512;  // 128..512 rows of Wr per workgroup
+    if (P > p_max) P = p_max;
+    if (P < p_min) P = p_min;
+    plan->Dp = (D + P - 1) / P;
+    plan->P = (D + plan->Dp - 1) / plan->Dp;
+    plan->bytes = ((size_t)plan->RT * plan->P * kTileR * H * sizeof(double) + 255) / 256 * 256;
+    if (plan->bytes == 0) plan->bytes = 256;
+    return POLAR_OK;
 }
 
 }  // namespace polar

@@ -38,8 +38,8 @@ def test_strerror_covers_every_status():
     assert L.polar_last_hip_error() == 0
 
 
-def router(L, hidden=FAKE, Wr=FAKE, B=4, D=512, H=8, k=4, dt=0, idx=FAKE):
-    return L.polar_router_topk(hidden, Wr, B, D, H, k, dt, idx, None, None)
+def router(L, hidden=FAKE, Wr=FAKE, B=4, D=512, H=8, k=4, dt=0, idx=FAKE, ws=None, ws_bytes=0):
+    return L.polar_router_topk(hidden, Wr, B, D, H, k, dt, idx, None, ws, ws_bytes, None)
 
 
 def test_router_argument_errors():
@@ -56,6 +56,12 @@ def test_router_argument_errors():
     assert router(L, H=257, k=4) == EUNSUPPORTED
     assert router(L, D=16385) == EUNSUPPORTED
     assert router(L, B=0, hidden=None, Wr=None, idx=None) == OK      # empty batch: no-op
+    need = L.polar_router_workspace_bytes(4, 512, 8)
+    assert need >= 4 * 8 * 8 and need % 256 == 0
+    assert router(L, ws=ALIGNED, ws_bytes=need - 1) == EWORKSPACE
+    assert router(L, ws=ctypes.c_void_p(0x10010), ws_bytes=need) == EWORKSPACE
+    assert L.polar_router_workspace_bytes(4, 0, 8) == 0
+    assert L.polar_router_workspace_bytes(4, 512, 257) == 0
 
 
 def decode(L, q=FAKE, K=FAKE, V=FAKE, n=FAKE, idx=FAKE, out=FAKE, B=4, Hq=8, Hkv=8, S=256, d=64,

@@ -56,14 +56,17 @@ def poison_unselected(w, q, K, V, head_idx):
 
 def run_router(w):
     hidden, Wr = wl.make_router_inputs(w, DEV)
-    logits = torch.empty((w.B, w.Hkv), dtype=torch.float32, device=DEV)
-    got = polar.router_topk(hidden, Wr, w.k, logits_out=logits)
-    torch.cuda.synchronize()
     ref_logits = orc.router_logits(host_bits(hidden), host_bits(Wr), w.dtype)
     want = orc.topk(ref_logits, w.k)
-    assert got.dtype == torch.int32 and tuple(got.shape) == (w.B, w.k)
-    assert np.array_equal(got.cpu().numpy(), want), "head_idx differs from the oracle"
-    np.testing.assert_allclose(logits.cpu().numpy(), ref_logits, rtol=2e-7, atol=1e-7)
+    rws = polar.alloc_router_workspace(w.B, w.D, w.Hkv, DEV)
+    rws.fill_(0xFF)
+    for ws in (None, rws):                    # one workgroup per request / split-D kernels
+        logits = torch.full((w.B, w.Hkv), float("nan"), dtype=torch.float32, device=DEV)
+        got = torch.full((w.B, w.k), -7, dtype=torch.int32, device=DEV)
+        polar.router_topk(hidden, Wr, w.k, head_idx=got, logits_out=logits, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), want), "head_idx differs from the oracle"
+        np.testing.assert_allclose(logits.cpu().numpy(), ref_logits, rtol=2e-7, atol=1e-7)
     srt = -np.sort(-ref_logits, axis=1)
     say("   router ok; smallest gap among the top-(k+1) logits: %.3e"
         % np.diff(-srt[:, : min(w.k + 1, w.Hkv)], axis=1).min(initial=np.inf))
@@ -211,9 +214,10 @@ def test_non_default_stream():
     q, K, V, seqlens = wl.make_attention_inputs(w, DEV)
     hidden, Wr = wl.make_router_inputs(w, DEV)
     torch.cuda.synchronize()
+    rws = polar.alloc_router_workspace(w.B, w.D, w.Hkv, DEV)
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
-        head_idx = polar.router_topk(hidden, Wr, w.k)
+        head_idx = polar.router_topk(hidden, Wr, w.k, workspace=rws)
         out = polar.sha_decode(q, K, V, seqlens, head_idx, w.k)
     s.synchronize()
     check_against_oracle(w, q, K, V, seqlens, head_idx, out)
@@ -221,17 +225,22 @@ def test_non_default_stream():
 
 # ----------------------------------------------------------------------------- router edge cases
 def router_case(hidden, Wr, k, dtype):
-    got = polar.router_topk(hidden, Wr, k)
-    torch.cuda.synchronize()
     want = orc.router_topk(host_bits(hidden), host_bits(Wr), k, dtype)
-    assert np.array_equal(got.cpu().numpy(), want)
+    B, D = hidden.shape
+    rws = polar.alloc_router_workspace(B, D, Wr.shape[1], DEV)
+    rws.fill_(0xFF)
+    for ws in (None, rws):                    # one workgroup per request / split-D kernels
+        got = polar.router_topk(hidden, Wr, k, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), want), "split" if ws is not None else "single"
     return want
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("B,D,H,k", [(1, 1, 1, 1), (3, 17, 5, 2), (5, 1000, 72, 36),
                                      (2, 4096, 256, 256), (7, 333, 100, 1), (4, 16384, 8, 4),
-                                     (2, 3, 200, 50)])
+                                     (2, 3, 200, 50), (9, 777, 6, 3), (130, 640, 32, 8),
+                                     (6, 513, 255, 17)])
 def test_router_shapes(dtype, B, D, H, k):
     say("\ncase router", dtype, B, D, H, k)
     g = torch.Generator(device=DEV).manual_seed(B * 1000 + D + H)
