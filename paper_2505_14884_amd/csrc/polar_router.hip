@@ -26,7 +26,7 @@ namespace polar {
 namespace {
 
 constexpr int kRouterThreads = 1024;
-constexpr int kStageBatch = 4;   // hidden elements a thread stages per batch of loads
+constexpr int kStageBatch = 8;   // hidden elements a thread stages per batch of loads
 constexpr int kRowBatch = 8;     // rows of Wr a thread loads before consuming any
 
 template <bool BF> __device__ __forceinline__ double widen_one(uint32_t bits16)
@@ -66,6 +66,25 @@ __device__ __forceinline__ bool precedes(double va, int a, double vb, int b)
     return va > vb || (va == vb && a < b);
 }
 
+// Rank counting spread over the whole workgroup: with `nthreads` threads, head h is handled
+// by nthreads / H threads that each compare it with a strided share of the other heads and
+// add their counts in LDS.  sh_rank[0..H) must be zero on entry (and visible to all threads).
+__device__ __forceinline__ void rank_and_emit(const double *sh_logit, int *sh_rank, int H, int k,
+                                              int nthreads, int tid, int32_t *row_out)
+{
+    const int parts = nthreads / H;            // >= 1: H never exceeds the workgroup size
+    if (tid < parts * H) {
+        const int part = tid / H, h = tid - part * H;
+        const double mine = sh_logit[h];
+        int cnt = 0;
+#pragma unroll 4
+        for (int j = part; j < H; j += parts) cnt += precedes(sh_logit[j], j, mine, h) ? 1 : 0;
+        if (cnt) atomicAdd(&sh_rank[h], cnt);
+    }
+    __syncthreads();
+    if (tid < H && sh_rank[tid] < k) row_out[sh_rank[tid]] = tid;
+}
+
 // dynamic LDS: uint16 hidden[Dpad] | double part[nslice*H] | double part2[J*H] | double logit[H]
 template <bool BF, int VEC>
 __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
@@ -78,6 +97,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
     double *sh_part = reinterpret_cast<double *>(smem + (size_t)Dpad * sizeof(uint16_t));
     double *sh_part2 = sh_part + (size_t)nslice * H;
     double *sh_logit = sh_part2 + (size_t)J * H;
+    __shared__ int sh_rank[POLAR_MAX_ROUTER_H];
 
     const int b = blockIdx.x, tid = threadIdx.x;
     const uint16_t *hrow = hidden + (size_t)b * D;
@@ -146,16 +166,11 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
         double sum = 0.0;
         for (int j = 0; j < J; ++j) sum += sh_part2[j * H + tid];
         sh_logit[tid] = sum;
+        sh_rank[tid] = 0;
         if (logits_out) logits_out[(size_t)b * H + tid] = (float)sum;
     }
     __syncthreads();
-
-    if (tid < H) {
-        const double mine = sh_logit[tid];
-        int rank = 0;
-        for (int j = 0; j < H; ++j) rank += precedes(sh_logit[j], j, mine, tid) ? 1 : 0;
-        if (rank < k) head_idx[(size_t)b * k + rank] = tid;
-    }
+    rank_and_emit(sh_logit, sh_rank, H, k, kRouterThreads, tid, head_idx + (size_t)b * k);
 }
 
 template <bool BF, int VEC>
@@ -194,7 +209,12 @@ hipError_t launch_vec(const uint16_t *hidden, const uint16_t *Wr, int B, int D, 
 // The order of additions again depends on (D, H, VEC, P) only, never on the column.
 constexpr int kTileR = 2;
 constexpr int kSplitThreads = 256;
-constexpr int kFinishBatch = 16;
+constexpr int kSplitStageBatch = 2;   // hidden elements per request a thread stages per batch
+#ifndef POLAR_ROUTER_DP_MAX
+#define POLAR_ROUTER_DP_MAX 512
+#endif
+constexpr int kDpMax = POLAR_ROUTER_DP_MAX;
+constexpr int kFinishBatch = 32;
 
 // dynamic LDS: double h[kTileR][Dp] | double part[nslice][kTileR*H] | double part2[J][kTileR*H]
 template <bool BF, int VEC>
@@ -213,40 +233,60 @@ __global__ __launch_bounds__(kSplitThreads) void router_partial_kernel(
     const int i0 = p * Dp;
     const int rows = min(Dp, D - i0);
 
+    // The first batch of Wr rows is requested before the hidden rows are staged, and each
+    // later batch before the previous one is consumed: the loads do not depend on the staging,
+    // and a dependent round trip to memory is what this kernel's time is made of.
+    const int CG = H / VEC;
+    const bool active = tid < nslice * CG;
+    const int slice = tid / CG, cg = tid - slice * CG;
+    const vec_t *w = reinterpret_cast<const vec_t *>(Wr) + (size_t)i0 * CG + cg;
+    vec_t wv[kRowBatch];
+    if (active && slice < rows) {
+#pragma unroll
+        for (int u = 0; u < kRowBatch; ++u) {
+            const int row = slice + u * nslice;
+            wv[u] = w[(size_t)(row < rows ? row : slice) * CG];
+        }
+    }
+
     // stage (and widen once) the tile's hidden rows; all loads of a batch before any use
-    for (int base = 0; base < kTileR * rows; base += kStageBatch * kSplitThreads) {
-        uint16_t v[kStageBatch];
+    for (int base = 0; base < rows; base += kSplitStageBatch * kSplitThreads) {
+        uint16_t v[kTileR][kSplitStageBatch];
 #pragma unroll
-        for (int u = 0; u < kStageBatch; ++u) {
-            const int e = base + u * kSplitThreads + tid;
-            const int r = e / rows, i = e - r * rows;
+        for (int r = 0; r < kTileR; ++r) {
             const int b = rt * kTileR + r;
-            v[u] = (e < kTileR * rows && b < B) ? hidden[(size_t)b * D + i0 + i] : (uint16_t)0;
+            const uint16_t *hrow = hidden + (size_t)(b < B ? b : 0) * D + i0;
+#pragma unroll
+            for (int u = 0; u < kSplitStageBatch; ++u) {
+                const int i = base + u * kSplitThreads + tid;
+                v[r][u] = (i < rows && b < B) ? hrow[i] : (uint16_t)0;
+            }
         }
 #pragma unroll
-        for (int u = 0; u < kStageBatch; ++u) {
-            const int e = base + u * kSplitThreads + tid;
-            const int r = e / rows, i = e - r * rows;
-            if (e < kTileR * rows) sh_h[r * Dp + i] = widen_one<BF>(v[u]);
-        }
+        for (int r = 0; r < kTileR; ++r)
+#pragma unroll
+            for (int u = 0; u < kSplitStageBatch; ++u) {
+                const int i = base + u * kSplitThreads + tid;
+                if (i < rows) sh_h[r * Dp + i] = widen_one<BF>(v[r][u]);
+            }
     }
     __syncthreads();
 
-    const int CG = H / VEC;
-    if (tid < nslice * CG) {
-        const int slice = tid / CG, cg = tid - slice * CG;
-        const vec_t *w = reinterpret_cast<const vec_t *>(Wr) + (size_t)i0 * CG + cg;
+    if (active) {
         double acc[kTileR][VEC];
 #pragma unroll
         for (int r = 0; r < kTileR; ++r)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc[r][v] = 0.0;
         for (int i = slice; i < rows; i += kRowBatch * nslice) {
-            vec_t wv[kRowBatch];
+            const int inext = i + kRowBatch * nslice;
+            vec_t wn[kRowBatch];
+            if (inext < rows) {
 #pragma unroll
-            for (int u = 0; u < kRowBatch; ++u) {
-                const int row = i + u * nslice;
-                wv[u] = w[(size_t)(row < rows ? row : i) * CG];
+                for (int u = 0; u < kRowBatch; ++u) {
+                    const int row = inext + u * nslice;
+                    wn[u] = w[(size_t)(row < rows ? row : inext) * CG];
+                }
             }
 #pragma unroll
             for (int u = 0; u < kRowBatch; ++u) {
@@ -263,6 +303,10 @@ __global__ __launch_bounds__(kSplitThreads) void router_partial_kernel(
                     }
                 }
             }
+            if (inext < rows) {
+#pragma unroll
+                for (int u = 0; u < kRowBatch; ++u) wv[u] = wn[u];
+            }
         }
 #pragma unroll
         for (int r = 0; r < kTileR; ++r)
@@ -275,7 +319,7 @@ __global__ __launch_bounds__(kSplitThreads) void router_partial_kernel(
     for (int e = tid; e < J * RH; e += kSplitThreads) {      // level 1: slices j, j+J, ...
         const int j = e / RH, x = e - j * RH;
         double sum = 0.0;
-        for (int s = j; s < nslice; s += J) sum += sh_part[(size_t)s * RH + x];
+        for (int s2 = j; s2 < nslice; s2 += J) sum += sh_part[(size_t)s2 * RH + x];
         sh_part2[e] = sum;
     }
     __syncthreads();
@@ -294,6 +338,7 @@ __global__ __launch_bounds__(POLAR_MAX_ROUTER_H) void router_finish_kernel(
     float *__restrict__ logits_out)
 {
     __shared__ double sh_logit[POLAR_MAX_ROUTER_H];
+    __shared__ int sh_rank[POLAR_MAX_ROUTER_H];
     const int b = blockIdx.x, tid = threadIdx.x;
     const int rt = b / kTileR, r = b - rt * kTileR;
     if (tid < H) {
@@ -309,15 +354,11 @@ __global__ __launch_bounds__(POLAR_MAX_ROUTER_H) void router_finish_kernel(
                 if (p0 + u < P) sum += v[u];
         }
         sh_logit[tid] = sum;
+        sh_rank[tid] = 0;
         if (logits_out) logits_out[(size_t)b * H + tid] = (float)sum;
     }
     __syncthreads();
-    if (tid < H) {
-        const double mine = sh_logit[tid];
-        int rank = 0;
-        for (int j = 0; j < H; ++j) rank += precedes(sh_logit[j], j, mine, tid) ? 1 : 0;
-        if (rank < k) head_idx[(size_t)b * k + rank] = tid;
-    }
+    rank_and_emit(sh_logit, sh_rank, H, k, POLAR_MAX_ROUTER_H, tid, head_idx + (size_t)b * k);
 }
 
 template <bool BF, int VEC>
@@ -409,7 +450,7 @@ int make_router_plan(int B, int D, int H, RouterPlan *plan)
     if (plan->RT > 65535) return POLAR_EUNSUPPORTED;             // grid.y limit
     const int rt = plan->RT > 0 ? plan->RT : 1;
     int P = (512 + rt - 1) / rt;                                 // aim at ~512 workgroups
-    const int p_max = (D + 127) / 128, p_min = (D + 511) / 512;  // 128..512 rows of Wr per workgroup
+    const int p_max = (D + 127) / 128, p_min = (D + kDpMax - 1) / kDpMax;  // 128..kDpMax rows of Wr per workgroup
     if (P > p_max) P = p_max;
     if (P < p_min) P = p_min;
     plan->Dp = (D + P - 1) / P;
