@@ -33,6 +33,13 @@ extern "C" {
 
 typedef enum { POLAR_F16 = 0, POLAR_BF16 = 1 } polar_dtype;
 
+/* Memory layout of the K and V caches (Section 3.2 gives both: the main-text layout and, in
+ * its footnote, the sequence-major one some implementations use). */
+typedef enum {
+    POLAR_KV_BHSD = 0, /* [B, Hkv, S, d]: the rows of one head are contiguous */
+    POLAR_KV_BSHD = 1  /* [B, S, Hkv, d]: the heads of one row are contiguous */
+} polar_kv_layout;
+
 typedef enum {
     POLAR_OK = 0,
     POLAR_EINVAL = -1,       /* NULL pointer, negative size, k outside [1,H], Hq % Hkv != 0 ... */
@@ -120,12 +127,25 @@ int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t 
                      size_t workspace_bytes, void *stream);
 
 /*
+ * polar_sha_decode for either cache layout (Section 3.2, footnote: K, V in R^{B x N x Hkv x d}).
+ * Identical to polar_sha_decode except that K and V are laid out as `layout` says; with
+ * POLAR_KV_BSHD a selected head's rows are d contiguous values every Hkv*d, so the kernel
+ * gathers 2*d-byte rows instead of streaming a contiguous slab.  q and out are unchanged
+ * ([B, Hq, d]; with one query row per request both of the paper's q layouts coincide).
+ */
+int polar_sha_decode_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                            const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S,
+                            int d, int k, polar_dtype dt, polar_kv_layout layout, float scale,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The two phases of polar_sha_decode as separate launches, with the same arguments and
  * checks (polar_sha_decode is exactly partial followed by merge on one stream).  They
  * exist so a harness can time the KV-streaming phase by itself.
  *   polar_sha_partial: streams K/V of the selected heads in chunks of rows and leaves a
  *     running (max, sum, unnormalised output) per chunk in the workspace (Algorithm 1's
  *     recurrence applied per chunk).
+ *   polar_sha_partial_layout: the same for either cache layout.
  *   polar_sha_merge: combines the chunks of each selected head with the same max/sum
  *     rescale, normalises, and writes zeros for unselected heads.
  */
@@ -133,6 +153,10 @@ int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t
                       const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
                       polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
                       void *stream);
+int polar_sha_partial_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                             const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
+                             polar_dtype dt, polar_kv_layout layout, float scale, void *workspace,
+                             size_t workspace_bytes, void *stream);
 int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out, int B, int Hq,
                     int Hkv, int S, int d, int k, const void *workspace, size_t workspace_bytes,
                     void *stream);

@@ -17,10 +17,11 @@ import torch
 from .build import LIB_PATH, build_library
 
 F16, BF16 = 0, 1
+KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_partial", "polar_sha_merge", "polar_sha_chunk_rows", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -57,6 +58,10 @@ def lib() -> ctypes.CDLL:
         L.polar_sha_decode.restype = i
         L.polar_sha_partial.argtypes = [vp] * 5 + [i] * 7 + [f, vp, sz, vp]
         L.polar_sha_partial.restype = i
+        L.polar_sha_decode_layout.argtypes = [vp] * 6 + [i] * 8 + [f, vp, sz, vp]
+        L.polar_sha_decode_layout.restype = i
+        L.polar_sha_partial_layout.argtypes = [vp] * 5 + [i] * 8 + [f, vp, sz, vp]
+        L.polar_sha_partial_layout.restype = i
         L.polar_sha_merge.argtypes = [vp] * 3 + [i] * 6 + [vp, sz, vp]
         L.polar_sha_merge.restype = i
         L.polar_strerror.argtypes = [i]
@@ -145,11 +150,16 @@ def alloc_workspace(B: int, Hq: int, Hkv: int, S: int, d: int, k: int, device) -
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
-def _sha_shapes(q, K, V, seqlens, head_idx, k):
+def _sha_shapes(q, K, V, seqlens, head_idx, k, kv_layout="bhsd"):
+    if kv_layout not in KV_LAYOUT:
+        raise ValueError("kv_layout must be 'bhsd' or 'bshd'")
     B, Hq, d = q.shape
-    B2, Hkv, S, d2 = K.shape
+    if kv_layout == "bhsd":
+        B2, Hkv, S, d2 = K.shape
+    else:
+        B2, S, Hkv, d2 = K.shape
     if (B, d) != (B2, d2) or V.shape != K.shape or q.dtype != K.dtype or V.dtype != K.dtype:
-        raise ValueError("q [B,Hq,d], K/V [B,Hkv,S,d] must agree in B, d and dtype")
+        raise ValueError("q [B,Hq,d] and K/V ([B,Hkv,S,d] or [B,S,Hkv,d]) must agree in B, d and dtype")
     if tuple(seqlens.shape) != (B,):
         raise ValueError("seqlens must be [B]")
     if head_idx is not None and tuple(head_idx.shape) != (B, k):
@@ -159,32 +169,36 @@ def _sha_shapes(q, K, V, seqlens, head_idx, k):
 
 def sha_decode(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, seqlens: torch.Tensor,
                head_idx: Optional[torch.Tensor], k: int, out: Optional[torch.Tensor] = None,
-               workspace: Optional[torch.Tensor] = None, scale: float = 0.0) -> torch.Tensor:
-    """Selective head attention, decode step -> out float32 [B,Hq,d] (unselected heads zero)."""
-    B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, head_idx, k)
+               workspace: Optional[torch.Tensor] = None, scale: float = 0.0,
+               kv_layout: str = "bhsd") -> torch.Tensor:
+    """Selective head attention, decode step -> out float32 [B,Hq,d] (unselected heads zero).
+    K/V are [B,Hkv,S,d] (kv_layout "bhsd") or [B,S,Hkv,d] ("bshd")."""
+    B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, head_idx, k, kv_layout)
     if out is None:
         out = torch.empty((B, Hq, d), dtype=torch.float32, device=q.device)
     if workspace is None:
         workspace = alloc_workspace(B, Hq, Hkv, S, d, k, q.device)
-    rc = lib().polar_sha_decode(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"),
-                                _dev(seqlens, "seqlens", torch.int32),
-                                _dev(head_idx, "head_idx", torch.int32),
-                                _dev(out, "out", torch.float32), B, Hq, Hkv, S, d, k,
-                                _dtype_code(q), float(scale), _dev(workspace, "workspace"),
-                                workspace.numel() * workspace.element_size(), _stream())
+    rc = lib().polar_sha_decode_layout(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"),
+                                       _dev(seqlens, "seqlens", torch.int32),
+                                       _dev(head_idx, "head_idx", torch.int32),
+                                       _dev(out, "out", torch.float32), B, Hq, Hkv, S, d, k,
+                                       _dtype_code(q), KV_LAYOUT[kv_layout], float(scale),
+                                       _dev(workspace, "workspace"),
+                                       workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "polar_sha_decode")
     return out
 
 
 def sha_partial(q, K, V, seqlens, head_idx, k: int, workspace: torch.Tensor,
-                scale: float = 0.0) -> None:
+                scale: float = 0.0, kv_layout: str = "bhsd") -> None:
     """The KV-streaming phase of sha_decode alone (leaves per-chunk partials in workspace)."""
-    B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, head_idx, k)
-    rc = lib().polar_sha_partial(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"),
-                                 _dev(seqlens, "seqlens", torch.int32),
-                                 _dev(head_idx, "head_idx", torch.int32), B, Hq, Hkv, S, d, k,
-                                 _dtype_code(q), float(scale), _dev(workspace, "workspace"),
-                                 workspace.numel() * workspace.element_size(), _stream())
+    B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, head_idx, k, kv_layout)
+    rc = lib().polar_sha_partial_layout(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"),
+                                        _dev(seqlens, "seqlens", torch.int32),
+                                        _dev(head_idx, "head_idx", torch.int32), B, Hq, Hkv, S, d, k,
+                                        _dtype_code(q), KV_LAYOUT[kv_layout], float(scale),
+                                        _dev(workspace, "workspace"),
+                                        workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "polar_sha_partial")
 
 

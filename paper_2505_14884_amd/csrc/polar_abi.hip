@@ -148,15 +148,16 @@ static int check_workspace(const ShaPlan &plan, const void *workspace, size_t wo
     return POLAR_OK;
 }
 
-int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
-                      const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
-                      polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
-                      void *stream)
+static int sha_partial_impl(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                            const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
+                            polar_dtype dt, polar_kv_layout layout, float scale, void *workspace,
+                            size_t workspace_bytes, void *stream)
 {
     ShaPlan plan;
     int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);
     if (rc != POLAR_OK) return rc;
     if (!dtype_ok(dt) || !(scale >= 0.0f) || isinf(scale)) return POLAR_EINVAL;
+    if (layout != POLAR_KV_BHSD && layout != POLAR_KV_BSHD) return POLAR_EINVAL;
     if (B == 0) return POLAR_OK;
     if (!head_idx && k != Hkv) return POLAR_EINVAL;
     if (!q || !K || !V || !seqlens) return POLAR_EINVAL;
@@ -164,8 +165,26 @@ int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t
     const float s = scale == 0.0f ? 1.0f / sqrtf((float)d) : scale;
     const float log2e = 1.4426950408889634f;
     return record(launch_sha_partial(q, K, V, seqlens, head_idx, static_cast<float *>(workspace),
-                                     plan, B, Hq, Hkv, S, d, k, dt, s * log2e,
+                                     plan, B, Hq, Hkv, S, d, k, dt, layout, s * log2e,
                                      static_cast<hipStream_t>(stream)));
+}
+
+int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                      const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
+                      polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
+                      void *stream)
+{
+    return sha_partial_impl(q, K, V, seqlens, head_idx, B, Hq, Hkv, S, d, k, dt, POLAR_KV_BHSD, scale,
+                            workspace, workspace_bytes, stream);
+}
+
+int polar_sha_partial_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                             const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
+                             polar_dtype dt, polar_kv_layout layout, float scale, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    return sha_partial_impl(q, K, V, seqlens, head_idx, B, Hq, Hkv, S, d, k, dt, layout, scale,
+                            workspace, workspace_bytes, stream);
 }
 
 int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out, int B, int Hq,
@@ -183,20 +202,29 @@ int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
                                    plan, B, Hq, Hkv, S, d, k, static_cast<hipStream_t>(stream)));
 }
 
-int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t *seqlens,
-                     const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
-                     int k, polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
-                     void *stream)
+int polar_sha_decode_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                            const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S,
+                            int d, int k, polar_dtype dt, polar_kv_layout layout, float scale,
+                            void *workspace, size_t workspace_bytes, void *stream)
 {
     ShaPlan plan;
     int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);   // size errors take precedence
     if (rc != POLAR_OK) return rc;
     if (B > 0 && !out) return POLAR_EINVAL;
-    rc = polar_sha_partial(q, K, V, seqlens, head_idx, B, Hq, Hkv, S, d, k, dt, scale,
-                               workspace, workspace_bytes, stream);
+    rc = sha_partial_impl(q, K, V, seqlens, head_idx, B, Hq, Hkv, S, d, k, dt, layout, scale,
+                          workspace, workspace_bytes, stream);
     if (rc != POLAR_OK) return rc;
     return polar_sha_merge(seqlens, head_idx, out, B, Hq, Hkv, S, d, k, workspace, workspace_bytes,
                            stream);
+}
+
+int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                     const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
+                     int k, polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
+                     void *stream)
+{
+    return polar_sha_decode_layout(q, K, V, seqlens, head_idx, out, B, Hq, Hkv, S, d, k, dt,
+                                   POLAR_KV_BHSD, scale, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -37,7 +37,7 @@ int make_router_plan(int B, int D, int H, RouterPlan *plan);
 hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
                               const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
                               int Hq, int Hkv, int S, int d, int k, polar_dtype dt,
-                              float scale_log2e, hipStream_t stream);
+                              polar_kv_layout layout, float scale_log2e, hipStream_t stream);
 hipError_t launch_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
                             const float *ws, const ShaPlan &plan, int B, int Hq, int Hkv, int S,
                             int d, int k, hipStream_t stream);

@@ -164,7 +164,10 @@ __device__ __forceinline__ void consume(const uint4 (&kr)[kLoads], const uint4 (
 //   ws_o[u*D .. u*D+D)   unnormalised output, ws_ml[2u] running max (base-2), ws_ml[2u+1] sum.
 // A workgroup whose chunk starts at or beyond n_b, or whose head id is out of range, writes
 // nothing; the merge kernel never reads those records.
-template <class DT, int D, int G>
+// ROW_MAJOR_SEQ selects the cache layout: false = [B, Hkv, S, d] (a head's rows are contiguous),
+// true = [B, S, Hkv, d] (a row of one head is d contiguous values, consecutive rows of that
+// head are Hkv*d apart).
+template <class DT, int D, int G, bool ROW_MAJOR_SEQ>
 __global__ __launch_bounds__(Shape<G>::kWaves * 64) void sha_partial_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int32_t *__restrict__ seqlens, const int32_t *__restrict__ head_idx,
@@ -192,7 +195,10 @@ __global__ __launch_bounds__(Shape<G>::kWaves * 64) void sha_partial_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane / LPR, cl = lane % LPR;
 
-    const size_t slab = ((size_t)b * Hkv + g_kv) * (size_t)S * D;
+    // first row of this (request, head), and the distance between its rows in 16-byte units
+    const size_t slab = ROW_MAJOR_SEQ ? ((size_t)b * S * Hkv + g_kv) * D
+                                      : ((size_t)b * Hkv + g_kv) * (size_t)S * D;
+    const size_t row_stride = ROW_MAJOR_SEQ ? (size_t)Hkv * LPR : (size_t)LPR;
     const uint4 *__restrict__ Kp = reinterpret_cast<const uint4 *>(K + slab) + cl;
     const uint4 *__restrict__ Vp = reinterpret_cast<const uint4 *>(V + slab) + cl;
 
@@ -216,11 +222,11 @@ __global__ __launch_bounds__(Shape<G>::kWaves * 64) void sha_partial_kernel(
         if (row0 + ROWS_WAVE <= row_end) {
 #pragma unroll
             for (int u = 0; u < kLoads; ++u) {
-                kr[u] = load_row16(Kp + (size_t)(row0 + u * RPL + r) * LPR);
+                kr[u] = load_row16(Kp + (size_t)(row0 + u * RPL + r) * row_stride);
                 ok[u] = true;
             }
 #pragma unroll
-            for (int u = 0; u < kLoads; ++u) vr[u] = load_row16(Vp + (size_t)(row0 + u * RPL + r) * LPR);
+            for (int u = 0; u < kLoads; ++u) vr[u] = load_row16(Vp + (size_t)(row0 + u * RPL + r) * row_stride);
             consume<DT, D, G, kLoads, false>(kr, vr, ok, qr, c, m, l, o);
         } else {
 #pragma unroll
@@ -230,8 +236,8 @@ __global__ __launch_bounds__(Shape<G>::kWaves * 64) void sha_partial_kernel(
                 kr[u] = make_uint4(0u, 0u, 0u, 0u);
                 vr[u] = make_uint4(0u, 0u, 0u, 0u);
                 if (ok[u]) {
-                    kr[u] = load_row16(Kp + (size_t)row * LPR);
-                    vr[u] = load_row16(Vp + (size_t)row * LPR);
+                    kr[u] = load_row16(Kp + (size_t)row * row_stride);
+                    vr[u] = load_row16(Vp + (size_t)row * row_stride);
                 }
             }
             consume<DT, D, G, kLoads, true>(kr, vr, ok, qr, c, m, l, o);
@@ -368,15 +374,15 @@ __global__ __launch_bounds__(kMergeThreads) void sha_merge_kernel(
     }
 }
 
-template <class DT, int D>
+template <class DT, int D, bool RMS>
 hipError_t launch_partial_g(int G, dim3 grid, hipStream_t st, const uint16_t *q, const uint16_t *K,
                             const uint16_t *V, const int32_t *seqlens, const int32_t *head_idx,
                             float *ws_o, float *ws_ml, int Hq, int Hkv, int S, int k, int chunk,
                             int nsplit, float c)
 {
-#define POLAR_LAUNCH(GG)                                                                         \
-    hipLaunchKernelGGL((sha_partial_kernel<DT, D, GG>), grid, dim3(Shape<GG>::kWaves * 64), 0, st, q, K, V, \
-                       seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, chunk, nsplit, c)
+#define POLAR_LAUNCH(GG)                                                                          \
+    hipLaunchKernelGGL((sha_partial_kernel<DT, D, GG, RMS>), grid, dim3(Shape<GG>::kWaves * 64), 0, \
+                       st, q, K, V, seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, chunk, nsplit, c)
     switch (G) {
     case 1: POLAR_LAUNCH(1); break;
     case 2: POLAR_LAUNCH(2); break;
@@ -388,26 +394,40 @@ hipError_t launch_partial_g(int G, dim3 grid, hipStream_t st, const uint16_t *q,
     return hipGetLastError();
 }
 
+template <class DT, int D>
+hipError_t launch_partial_layout(polar_kv_layout layout, int G, dim3 grid, hipStream_t st,
+                                 const uint16_t *q, const uint16_t *K, const uint16_t *V,
+                                 const int32_t *seqlens, const int32_t *head_idx, float *ws_o,
+                                 float *ws_ml, int Hq, int Hkv, int S, int k, int chunk, int nsplit,
+                                 float c)
+{
+    if (layout == POLAR_KV_BSHD)
+        return launch_partial_g<DT, D, true>(G, grid, st, q, K, V, seqlens, head_idx, ws_o, ws_ml, Hq,
+                                             Hkv, S, k, chunk, nsplit, c);
+    return launch_partial_g<DT, D, false>(G, grid, st, q, K, V, seqlens, head_idx, ws_o, ws_ml, Hq,
+                                          Hkv, S, k, chunk, nsplit, c);
+}
+
 }  // namespace
 
 hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
                               const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
                               int Hq, int Hkv, int S, int d, int k, polar_dtype dt,
-                              float scale_log2e, hipStream_t stream)
+                              polar_kv_layout layout, float scale_log2e, hipStream_t stream)
 {
     const dim3 grid((unsigned)((size_t)B * plan.nsplit * k));
     float *ws_o = ws, *ws_ml = ws + plan.o_floats;
     const uint16_t *q16 = static_cast<const uint16_t *>(q);
     const uint16_t *K16 = static_cast<const uint16_t *>(K);
     const uint16_t *V16 = static_cast<const uint16_t *>(V);
-#define POLAR_ARGS plan.G, grid, stream, q16, K16, V16, seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, \
+#define POLAR_ARGS layout, plan.G, grid, stream, q16, K16, V16, seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, \
                    plan.chunk, plan.nsplit, scale_log2e
     if (dt == POLAR_F16) {
-        if (d == 128) return launch_partial_g<F16, 128>(POLAR_ARGS);
-        if (d == 64) return launch_partial_g<F16, 64>(POLAR_ARGS);
+        if (d == 128) return launch_partial_layout<F16, 128>(POLAR_ARGS);
+        if (d == 64) return launch_partial_layout<F16, 64>(POLAR_ARGS);
     } else {
-        if (d == 128) return launch_partial_g<BF16, 128>(POLAR_ARGS);
-        if (d == 64) return launch_partial_g<BF16, 64>(POLAR_ARGS);
+        if (d == 128) return launch_partial_layout<BF16, 128>(POLAR_ARGS);
+        if (d == 64) return launch_partial_layout<BF16, 64>(POLAR_ARGS);
     }
 #undef POLAR_ARGS
     return hipErrorInvalidValue;

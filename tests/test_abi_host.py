@@ -95,6 +95,18 @@ def test_sha_argument_errors():
     assert decode(L, B=0, q=None, K=None, V=None, n=None, out=None, ws=None) == OK   # empty batch
 
 
+def test_layout_entry_points_share_the_checks():
+    L = binding.lib()
+    args = lambda layout, **kw: L.polar_sha_decode_layout(
+        kw.get("q", FAKE), FAKE, FAKE, FAKE, FAKE, FAKE, 4, 8, 8, 256, kw.get("d", 64), 4, 0, layout,
+        0.0, ALIGNED, L.polar_sha_workspace_bytes(4, 8, 8, 256, 64, 4), None)
+    assert args(2) == EINVAL and args(-1) == EINVAL           # unknown layout
+    assert args(1, q=None) == EINVAL
+    assert args(1, d=96) == EUNSUPPORTED
+    assert L.polar_sha_partial_layout(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 8, 8, 256, 64, 4, 0, 5, 0.0,
+                                      ALIGNED, 1 << 20, None) == EINVAL
+
+
 def test_workspace_size_is_consistent_with_the_chunking():
     L = binding.lib()
     for (B, Hq, Hkv, S, d, k) in [(4, 8, 8, 256, 64, 4), (32, 32, 32, 1920, 128, 16),

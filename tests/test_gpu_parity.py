@@ -183,6 +183,96 @@ def test_peaky_softmax_and_explicit_scale():
         assert err <= TOL
 
 
+@pytest.mark.parametrize("name,dtype,G,d", [("f16-mha", "f16", 1, 128), ("bf16-gqa", "bf16", 4, 128),
+                                            ("f16-d64", "f16", 2, 64)])
+def test_sequence_major_cache_layout(name, dtype, G, d):
+    """K/V stored [B, S, Hkv, d] (the footnote layout of Section 3.2): same result as the
+    head-major layout, and the oracle (which reads head-major) agrees."""
+    w = wl.ShaWorkload("bshd-" + name, B=5, Hq=6 * G, Hkv=6, d=d, S=777, k=3, D=64, dtype=dtype,
+                       seq_lo=1, seed=31 + G)
+    say("\ncase", w)
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV, poison_padding=True)
+    head_idx = wl.random_head_idx(w, DEV)
+    poison_unselected(w, q, K, V, head_idx)
+    Kt, Vt = K.permute(0, 2, 1, 3).contiguous(), V.permute(0, 2, 1, 3).contiguous()
+    out = polar.sha_decode(q, Kt, Vt, seqlens, head_idx, w.k, kv_layout="bshd")
+    ref = polar.sha_decode(q, K, V, seqlens, head_idx, w.k)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
+    check_against_oracle(w, q, K, V, seqlens, head_idx, out)
+    dense = polar.sha_decode(q, Kt, Vt, seqlens, None, w.Hkv, kv_layout="bshd")
+    torch.cuda.synchronize()
+    wd = w.scaled(k=w.Hkv)
+    K2, V2 = K.nan_to_num(0.0), V.nan_to_num(0.0)   # dense reads every head: un-poison a copy
+    dense2 = polar.sha_decode(q.nan_to_num(0.0), K2.permute(0, 2, 1, 3).contiguous(),
+                              V2.permute(0, 2, 1, 3).contiguous(), seqlens, None, w.Hkv,
+                              kv_layout="bshd")
+    torch.cuda.synchronize()
+    check_against_oracle(wd, q.nan_to_num(0.0), K2, V2, seqlens, None, dense2)
+    del dense
+
+
+def test_per_request_k_through_padding():
+    """Requests keep different numbers of heads: unused slots hold -1 (the adaptive routing the
+    paper lists as future work needs nothing else from the kernel)."""
+    w = wl.ShaWorkload("padk", B=6, Hq=8, Hkv=8, d=128, S=500, k=5, D=64, dtype="f16", seq_lo=50,
+                       seed=77)
+    say("\ncase", w)
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV, poison_padding=True)
+    head_idx = wl.random_head_idx(w, DEV)
+    keep = torch.tensor([5, 0, 1, 3, 2, 4], device=DEV)          # per-request k, 0 = nothing kept
+    pad = torch.arange(w.k, device=DEV)[None, :] >= keep[:, None]
+    head_idx[pad] = -1
+    poison_unselected(w, q, K, V, head_idx)
+    out = polar.sha_decode(q, K, V, seqlens, head_idx, w.k)
+    torch.cuda.synchronize()
+    check_against_oracle(w, q, K, V, seqlens, head_idx, out)
+    assert (out[1].view(torch.int32) == 0).all()
+    assert int((out.abs().sum(-1) > 0).sum()) == int(keep.sum())
+
+
+def test_hip_graph_replays_match_eager():
+    """Router + attention recorded into one HIP graph (as the paper's runs used CUDA graphs):
+    every replay, with eager work and synchronisation in between, equals the eager result."""
+    w = wl.ShaWorkload("graph", B=16, Hq=32, Hkv=8, d=128, S=900, k=3, D=1024, dtype="bf16",
+                       seq_lo=100, seed=55)
+    say("\ncase", w)
+    hidden, Wr = wl.make_router_inputs(w, DEV)
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV)
+    idx = torch.zeros((w.B, w.k), dtype=torch.int32, device=DEV)
+    out = torch.zeros((w.B, w.Hq, w.d), dtype=torch.float32, device=DEV)
+    ws = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.k, DEV)
+    rws = polar.alloc_router_workspace(w.B, w.D, w.Hkv, DEV)
+
+    def step(idx_buf, out_buf):
+        polar.router_topk(hidden, Wr, w.k, head_idx=idx_buf, workspace=rws)
+        polar.sha_decode(q, K, V, seqlens, idx_buf, w.k, out=out_buf, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture
+        step(idx, out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(idx, out)
+    gen = torch.Generator(device=DEV).manual_seed(4242)
+    for rep in range(4):
+        hidden.copy_(torch.randn(hidden.shape, generator=gen, device=DEV).to(hidden.dtype))
+        q.copy_(torch.randn(q.shape, generator=gen, device=DEV).to(q.dtype))
+        idx_e, out_e = torch.empty_like(idx), torch.empty_like(out)
+        step(idx_e, out_e)                             # eager, same workspaces, before the replay
+        torch.cuda.synchronize()
+        idx.fill_(-3)
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, idx_e), "replay %d: head_idx" % rep
+        assert torch.equal(out.view(torch.int32), out_e.view(torch.int32)), "replay %d: out" % rep
+    check_against_oracle(w, q, K, V, seqlens, idx, out)
+
+
 def test_empty_batch_is_a_noop():
     e16 = torch.empty((0, 8, 64), dtype=torch.float16, device=DEV)
     kv = torch.empty((0, 8, 128, 64), dtype=torch.float16, device=DEV)
