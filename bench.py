@@ -47,6 +47,8 @@ def parse_args():
                     help="skip the dense (k = H) comparison run, so a kernel trace of this command "
                          "holds selective launches only")
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests the oracle is timed on")
+    ap.add_argument("--kv-layout", choices=["bhsd", "bshd"], default="bhsd",
+                    help="cache layout: [B,Hkv,S,d] (default) or the sequence-major [B,S,Hkv,d]")
     ap.add_argument("--phase", choices=["all", "partial", "copy"], default="all",
                     help="'partial' launches only the KV-streaming kernel (for counter runs); "
                          "'copy' runs a plain device copy of known size, the yardstick the "
@@ -92,6 +94,9 @@ def main():
 
     hidden, Wr = wl.make_router_inputs(w, dev)
     q, K, V, seqlens = wl.make_attention_inputs(w, dev)
+    if args.kv_layout == "bshd":
+        K, V = K.permute(0, 2, 1, 3).contiguous(), V.permute(0, 2, 1, 3).contiguous()
+    lay = args.kv_layout
     bytes_sel = wl.selected_kv_bytes(w, seqlens)
     bytes_dense = wl.selected_kv_bytes(w, seqlens, k=w.Hkv)
 
@@ -110,15 +115,15 @@ def main():
     def step(i):
         Ki, Vi = caches[i % R]
         polar.router_topk(hidden, Wr, w.k, head_idx=head_idx, workspace=rws)
-        polar.sha_decode(q, Ki, Vi, seqlens, head_idx, w.k, out=out, workspace=ws)
+        polar.sha_decode(q, Ki, Vi, seqlens, head_idx, w.k, out=out, workspace=ws, kv_layout=lay)
 
     def partial_only(i):
         Ki, Vi = caches[i % R]
-        polar.sha_partial(q, Ki, Vi, seqlens, head_idx, w.k, ws)
+        polar.sha_partial(q, Ki, Vi, seqlens, head_idx, w.k, ws, kv_layout=lay)
 
     def dense_step(i):
         Ki, Vi = caches[i % R]
-        polar.sha_decode(q, Ki, Vi, seqlens, None, w.Hkv, out=out, workspace=ws)
+        polar.sha_decode(q, Ki, Vi, seqlens, None, w.Hkv, out=out, workspace=ws, kv_layout=lay)
 
     polar.router_topk(hidden, Wr, w.k, head_idx=head_idx, workspace=rws)
     torch.cuda.synchronize()
@@ -161,7 +166,7 @@ def main():
     router_avg, _, _ = event_time(lambda i: polar.router_topk(hidden, Wr, w.k, head_idx=head_idx, workspace=rws), n_ev)
     sha_avg, _, _ = event_time(
         lambda i: polar.sha_decode(q, caches[i % R][0], caches[i % R][1], seqlens, head_idx, w.k,
-                                   out=out, workspace=ws), n_ev)
+                                   out=out, workspace=ws, kv_layout=lay), n_ev)
     if args.no_dense:
         dense_avg = float("nan")
     else:
@@ -190,6 +195,7 @@ def main():
             "seqlens": "all %d" % w.S if w.seq_lo <= 0 else "uniform integers in [%d, %d]" % (w.seq_lo, w.S),
             "selected_kv_bytes": bytes_sel,
             "dense_kv_bytes": bytes_dense,
+            "kv_layout": lay,
             "chunk_rows": chunk,
             "kv_copies_rotated": R,
         },
@@ -213,7 +219,7 @@ def main():
             "avg_us": round(part_avg * 1e3, 2),
             "median_us": round(part_med * 1e3, 2),
             "min_us": round(part_min * 1e3, 2),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if w == wl.CONFIGS[w.name] else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (w == wl.CONFIGS[w.name] and lay == "bhsd") else None,
         },
     }
 
@@ -222,7 +228,8 @@ def main():
 
         nb = max(1, min(args.cpu_sample, w.B))
         hb, Wb = wl.bits_u16(hidden[:nb]), wl.bits_u16(Wr)
-        qb, Kb, Vb = wl.bits_u16(q[:nb]), wl.bits_u16(K[:nb]), wl.bits_u16(V[:nb])
+        Ks, Vs = (K[:nb], V[:nb]) if lay == "bhsd" else (K[:nb].permute(0, 2, 1, 3), V[:nb].permute(0, 2, 1, 3))
+        qb, Kb, Vb = wl.bits_u16(q[:nb]), wl.bits_u16(Ks), wl.bits_u16(Vs)
         nh = seqlens[:nb].cpu().numpy()
         step(0)                       # leave the selective result of copy 0 in `out`
         torch.cuda.synchronize()
