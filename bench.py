@@ -30,7 +30,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # (each scaled by the same counter's reading for a plain 4 GiB copy); measured with this file's
 # --phase partial / --phase copy on the default shape of each workload.  Source:
 # profiles/sha_decode_step_<workload>.md.  Reported only when the shape is that default.
-MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4539991968}
+MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4533957188, "C5_ragged": 4480271133,
+                          "C3_llama3_8b_gqa": 539715568, "C2_llama2_7b": 504125492}
 DEFAULT_WORKLOAD = "C4_opt66b"
 
 
@@ -149,17 +150,24 @@ def main():
     value = bytes_sel / (ms_per_step * 1e-3) / 1e9
 
     def event_time(fn, n):
-        """Average duration of n launches of fn, each bracketed by events on the launch stream."""
+        """Duration of one launch of fn from events on the launch stream: the average over n
+        back-to-back launches inside one event bracket, and median / minimum over n separately
+        bracketed launches (those include the dispatch latency of a cold queue)."""
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n):
+            fn(i)
+        b.record()
         pairs = []
         for i in range(n):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
+            c, d = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c.record()
             fn(i)
-            b.record()
-            pairs.append((a, b))
+            d.record()
+            pairs.append((c, d))
         torch.cuda.synchronize()
-        ts = sorted(a.elapsed_time(b) for a, b in pairs)
-        return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+        ts = sorted(c.elapsed_time(d) for c, d in pairs)
+        return a.elapsed_time(b) / n, ts[len(ts) // 2], ts[0]
 
     n_ev = max(10, min(args.steps, 100))
     part_avg, part_med, part_min = event_time(partial_only, n_ev)
