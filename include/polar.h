@@ -167,6 +167,24 @@ int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
  */
 int polar_sha_chunk_rows(int B, int Hq, int Hkv, int S, int d, int k);
 
+/*
+ * Head-importance labels (Section 3.2: heads ranked by the L2 norm of their attention output;
+ * Section 4.2: the k heads with the highest output norms are the router's training targets).
+ *
+ *   attn_out   in   [B, Hq, d] float: dense decode attention output, e.g. from
+ *                   polar_sha_decode(..., head_idx = NULL, k = Hkv, ...)
+ *   head_idx   out  [B, k] int32: the k selection units (KV groups; heads when Hq == Hkv) of
+ *                   each request with the largest output norm, best first
+ *   norms_out  out  [B, Hkv] float, nullable: the L2 norms, for inspection
+ *
+ * A group's score is the sum of squares of the outputs of all its Hq/Hkv query heads
+ * (accumulated in double; ranking by the sum of squares is ranking by the norm, without the
+ * rounding of a square root); ordering and tie rules are those of polar_router_topk.
+ * 1 <= k <= Hkv <= POLAR_MAX_ROUTER_H.
+ */
+int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,
+                         int32_t *head_idx, float *norms_out, void *stream);
+
 /* Text for a polar_status value; never NULL. */
 const char *polar_strerror(int status);
 /* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */

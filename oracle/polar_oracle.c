@@ -22,6 +22,9 @@
  *               is computed against that group's K/V                   (Section 4.2, last
  *               sentence: group sparsity for grouped-query attention)
  *
+ *   labels      the k heads (groups) whose attention output has the largest L2 norm
+ *               (Section 3.2 study; Section 4.2, router supervision targets)
+ *
  * A second routine, oracle_alg1_tiled, follows Algorithm 1 (Selective Head
  * FlashAttention, decode) step by step — tiles of B_c rows, running maximum and
  * sum, output renormalised every tile — so a test can show that the tiled
@@ -245,6 +248,31 @@ int oracle_sha_decode(const uint16_t *q, const uint16_t *K, const uint16_t *V,
         free(score);
     }
     return failed ? -2 : 0;
+}
+
+/* Head importance (Section 3.2: heads ranked by the L2 norm of their attention output;
+ * Section 4.2: the k heads with the highest output norms are the router's labels).
+ * attn [B,Hq,d] is dense attention output in double (oracle_sha_decode with head_idx NULL).
+ * score[b,g] = sum of squares over the G = Hq/Hkv query heads of group g (the squared L2 norm
+ * of the group's concatenated output); norms[b,g] = sqrt(score).  Ranking is done on the
+ * scores (same order as the norms, no rounding of the root). */
+int oracle_head_scores(const double *attn, int B, int Hq, int Hkv, int d, double *score,
+                       double *norms)
+{
+    if (!attn || !score || B < 0 || Hq < 1 || Hkv < 1 || d < 1 || Hq % Hkv != 0) return -1;
+    const int G = Hq / Hkv;
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hkv; ++g) {
+            double ss = 0.0;
+            for (int r = 0; r < G; ++r)
+                for (int e = 0; e < d; ++e) {
+                    double v = attn[((size_t)b * Hq + (size_t)g * G + r) * d + e];
+                    ss += v * v;
+                }
+            score[(size_t)b * Hkv + g] = ss;
+            if (norms) norms[(size_t)b * Hkv + g] = sqrt(ss);
+        }
+    return 0;
 }
 
 /* Algorithm 1 (Selective Head FlashAttention, decode) for ONE already-gathered

@@ -45,6 +45,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_router_logits.argtypes = [vp, vp, c_int, c_int, c_int, c_int, vp]
         L.oracle_topk.argtypes = [vp, c_int, c_int, c_int, vp]
         L.oracle_sha_decode.argtypes = [vp, vp, vp, vp, vp, vp] + [c_int] * 7 + [c_dbl]
+        L.oracle_head_scores.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp]
         L.oracle_alg1_tiled.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_dbl, vp]
         _lib = L
     return _lib
@@ -134,3 +135,23 @@ def alg1_tiled(q, K, V, Bc: int, scale: float) -> np.ndarray:
     rc = lib().oracle_alg1_tiled(_ptr(q), _ptr(K), _ptr(V), n, d, int(Bc), float(scale), _ptr(out))
     assert rc == 0, rc
     return out
+
+
+def head_scores(attn, Hkv: int):
+    """Dense attention output float64 [B,Hq,d] -> (sum of squares [B,Hkv], L2 norms [B,Hkv])."""
+    attn = np.ascontiguousarray(attn, dtype=np.float64)
+    B, Hq, d = attn.shape
+    score = np.empty((B, Hkv), dtype=np.float64)
+    norms = np.empty((B, Hkv), dtype=np.float64)
+    rc = lib().oracle_head_scores(_ptr(attn), B, Hq, Hkv, d, _ptr(score), _ptr(norms))
+    assert rc == 0, rc
+    return score, norms
+
+
+def head_importance_labels(q_bits, K_bits, V_bits, seqlens, k: int, dtype: str):
+    """The router's training labels: dense attention, per-group output norm, top-k.
+    Returns (labels int32 [B,k], scores float64 [B,Hkv])."""
+    Hkv = K_bits.shape[1]
+    attn = sha_decode(q_bits, K_bits, V_bits, seqlens, None, Hkv, dtype)
+    score, _ = head_scores(attn, Hkv)
+    return topk(score, k), score

@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_head_norm_topk", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.polar_sha_partial_layout.restype = i
         L.polar_sha_merge.argtypes = [vp] * 3 + [i] * 6 + [vp, sz, vp]
         L.polar_sha_merge.restype = i
+        L.polar_head_norm_topk.argtypes = [vp, i, i, i, i, i, vp, vp, vp]
+        L.polar_head_norm_topk.restype = i
         L.polar_strerror.argtypes = [i]
         L.polar_strerror.restype = ctypes.c_char_p
         L.polar_last_hip_error.restype = i
@@ -213,3 +215,18 @@ def sha_merge(seqlens, head_idx, out: torch.Tensor, Hkv: int, S: int, k: int,
                                workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "polar_sha_merge")
     return out
+
+
+def head_norm_topk(attn_out: torch.Tensor, Hkv: int, k: int,
+                   head_idx: Optional[torch.Tensor] = None,
+                   norms_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Dense attention output float32 [B,Hq,d] -> int32 [B,k]: the k KV groups with the largest
+    output L2 norm per request, best first (the router's training labels)."""
+    B, Hq, d = attn_out.shape
+    if head_idx is None:
+        head_idx = torch.empty((B, max(k, 0)), dtype=torch.int32, device=attn_out.device)
+    rc = lib().polar_head_norm_topk(_dev(attn_out, "attn_out", torch.float32), B, Hq, Hkv, d, k,
+                                    _dev(head_idx, "head_idx", torch.int32),
+                                    _dev(norms_out, "norms_out", torch.float32), _stream())
+    _check(rc, "polar_head_norm_topk")
+    return head_idx

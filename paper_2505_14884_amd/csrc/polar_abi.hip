@@ -227,4 +227,16 @@ int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t 
                                    POLAR_KV_BHSD, scale, workspace, workspace_bytes, stream);
 }
 
+int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,
+                         int32_t *head_idx, float *norms_out, void *stream)
+{
+    if (B < 0 || Hq < 1 || Hkv < 1 || d < 1 || k < 1 || k > Hkv || Hq % Hkv != 0) return POLAR_EINVAL;
+    if (Hkv > POLAR_MAX_ROUTER_H || B > 0x7fffffff / 2 || (long long)(Hq / Hkv) * d > (1 << 20))
+        return POLAR_EUNSUPPORTED;
+    if (B == 0) return POLAR_OK;
+    if (!attn_out || !head_idx) return POLAR_EINVAL;
+    return record(launch_head_norm_topk(attn_out, B, Hq, Hkv, d, k, head_idx, norms_out,
+                                        static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -48,4 +48,7 @@ hipError_t launch_router_split(const void *hidden, const void *Wr, int B, int D,
                                polar_dtype dt, const RouterPlan &plan, int32_t *head_idx,
                                float *logits_out, void *workspace, hipStream_t stream);
 
+hipError_t launch_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,
+                                 int32_t *head_idx, float *norms_out, hipStream_t stream);
+
 }  // namespace polar

@@ -107,6 +107,18 @@ def test_layout_entry_points_share_the_checks():
                                       ALIGNED, 1 << 20, None) == EINVAL
 
 
+def test_head_norm_topk_argument_errors():
+    L = binding.lib()
+    f = lambda out=FAKE, B=4, Hq=8, Hkv=8, d=64, k=4, idx=FAKE: L.polar_head_norm_topk(
+        out, B, Hq, Hkv, d, k, idx, None, None)
+    assert f(k=0) == EINVAL and f(k=9) == EINVAL
+    assert f(Hq=12) == EINVAL
+    assert f(d=0) == EINVAL
+    assert f(out=None) == EINVAL and f(idx=None) == EINVAL
+    assert f(Hq=512, Hkv=512, k=4) == EUNSUPPORTED
+    assert f(B=0, out=None, idx=None) == OK
+
+
 def test_workspace_size_is_consistent_with_the_chunking():
     L = binding.lib()
     for (B, Hq, Hkv, S, d, k) in [(4, 8, 8, 256, 64, 4), (32, 32, 32, 1920, 128, 16),

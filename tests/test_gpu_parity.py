@@ -273,6 +273,46 @@ def test_hip_graph_replays_match_eager():
     check_against_oracle(w, q, K, V, seqlens, idx, out)
 
 
+@pytest.mark.parametrize("name", ["C1_tiny", "C2_llama2_7b", "C3_llama3_8b_gqa"])
+def test_head_importance_labels(name):
+    """Labeller = dense attention + per-group output norm + top-k.  The GPU attention is
+    float, the oracle's is double, so a group whose score is within 1e-5 (relative) of the
+    selection boundary may legitimately fall on either side: labels must agree exactly
+    wherever the oracle's scores are separated by more than that, and every GPU label must be
+    valid under the oracle's scores up to that slack."""
+    w = wl.CONFIGS[name]
+    say("\ncase labels", name)
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV)
+    dense = polar.sha_decode(q, K, V, seqlens, None, w.Hkv)
+    norms = torch.empty((w.B, w.Hkv), dtype=torch.float32, device=DEV)
+    got = polar.head_norm_topk(dense, w.Hkv, w.k, norms_out=norms).cpu().numpy()
+    torch.cuda.synchronize()
+    want, score = orc.head_importance_labels(host_bits(q), host_bits(K), host_bits(V),
+                                             seqlens.cpu().numpy(), w.k, w.dtype)
+    np.testing.assert_allclose(norms.cpu().numpy(), np.sqrt(score), rtol=2e-6)
+    slack = 1e-5
+    exact_rows = 0
+    for b in range(w.B):
+        srt = -np.sort(-score[b])
+        gaps = (srt[:-1] - srt[1:]) / srt[:-1]
+        if gaps[: w.k].min(initial=1.0) > slack:          # no near-tie touches the top-k order
+            assert got[b].tolist() == want[b].tolist(), b
+            exact_rows += 1
+        else:
+            s_got = score[b][got[b]]
+            assert len(set(got[b].tolist())) == w.k
+            assert (np.diff(s_got) <= slack * s_got[:-1]).all()            # descending up to slack
+            assert s_got.min() >= srt[w.k - 1] * (1 - slack)               # nothing better left out
+    say("   %d of %d rows compared exactly" % (exact_rows, w.B))
+    assert exact_rows >= w.B // 2
+    # fed with the same float attention output, the kernel is deterministic and its ranking
+    # matches a double-precision ranking of those very values
+    ss = (dense.double().reshape(w.B, w.Hkv, -1) ** 2).sum(dim=2).cpu().numpy()
+    gap_ok = np.array([(np.diff(-np.sort(-ss[b]))[: w.k] < 0).all() for b in range(w.B)])
+    ref = np.argsort(-ss, axis=1, kind="stable")[:, : w.k]
+    assert np.array_equal(got[gap_ok], ref[gap_ok].astype(np.int32))
+
+
 def test_empty_batch_is_a_noop():
     e16 = torch.empty((0, 8, 64), dtype=torch.float16, device=DEV)
     kv = torch.empty((0, 8, 128, 64), dtype=torch.float16, device=DEV)

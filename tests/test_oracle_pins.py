@@ -390,6 +390,51 @@ def test_partition_merge_algebra():
         np.testing.assert_allclose(o_star, whole, rtol=1e-12, atol=1e-14)
 
 
+# ----------------------------------------------------------------------------- head importance
+def test_head_scores_equal_numpy_norms_and_group_pooling():
+    B, Hq, Hkv, d = 3, 12, 4, 16
+    attn = RNG.standard_normal((B, Hq, d))
+    score, norms = orc.head_scores(attn, Hkv)
+    want = np.linalg.norm(attn.reshape(B, Hkv, (Hq // Hkv) * d), axis=2)
+    np.testing.assert_allclose(norms, want, rtol=1e-14)
+    np.testing.assert_allclose(score, want ** 2, rtol=1e-13)
+    # MHA: one score per head
+    score1, norms1 = orc.head_scores(attn, Hq)
+    np.testing.assert_allclose(norms1, np.linalg.norm(attn, axis=2), rtol=1e-14)
+    # a wrong grouping (strided instead of contiguous heads) must not pass by accident
+    wrong = np.linalg.norm(attn.reshape(B, Hq // Hkv, Hkv, d).transpose(0, 2, 1, 3).reshape(B, Hkv, -1), axis=2)
+    assert not np.allclose(norms, wrong)
+
+
+def test_head_importance_labels_closed_form():
+    """Value rows of head h are all h+1 times a fixed unit vector, so every head's attention
+    output is (h+1)*u whatever the scores are, its norm is h+1, and the labels are the k
+    highest head ids in descending order."""
+    B, H, S, d, k = 2, 6, 20, 16, 3
+    q, K, V, n = random_case(B, H, H, S, d, "f16")
+    u = np.zeros(d); u[3] = 1.0
+    Vf = np.zeros((B, H, S, d))
+    for h in range(H):
+        Vf[:, h, :, :] = (h + 1) * u
+    labels, score = orc.head_importance_labels(q, K, f16_bits(Vf), n, k, "f16")
+    assert labels.tolist() == [[5, 4, 3]] * B
+    np.testing.assert_allclose(score, np.tile((np.arange(H) + 1.0) ** 2, (B, 1)), rtol=1e-12)
+    # equal norms: ties go to the lower id
+    Vf[:] = u
+    labels, _ = orc.head_importance_labels(q, K, f16_bits(Vf), n, k, "f16")
+    assert labels.tolist() == [[0, 1, 2]] * B
+
+
+def test_head_importance_labels_equal_numpy_route():
+    B, Hq, Hkv, S, d, k = 3, 8, 4, 50, 16, 2
+    q, K, V, n = random_case(B, Hq, Hkv, S, d, "bf16")
+    labels, score = orc.head_importance_labels(q, K, V, n, k, "bf16")
+    attn = orc.sha_decode(q, K, V, n, None, Hkv, "bf16")
+    norms = np.linalg.norm(attn.reshape(B, Hkv, -1), axis=2)
+    want = np.argsort(-norms, axis=1, kind="stable")[:, :k]
+    assert np.array_equal(labels, want.astype(np.int32))
+
+
 # ----------------------------------------------------------------------------- threads
 def test_result_does_not_depend_on_thread_count():
     q, K, V, n = random_case(4, 4, 4, 50, 16, "f16")
