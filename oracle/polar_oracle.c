@@ -25,6 +25,10 @@
  *   labels      the k heads (groups) whose attention output has the largest L2 norm
  *               (Section 3.2 study; Section 4.2, router supervision targets)
  *
+ *   select GEMM C = act(A W[idx,:]^T) with the rows of W gathered by a neuron index, and the
+ *               batch union of predicted neuron ids that forms that index (Section 3.1,
+ *               Section 4.1, Appendix "Sparse Kernels" Algorithm 3)
+ *
  * A second routine, oracle_alg1_tiled, follows Algorithm 1 (Selective Head
  * FlashAttention, decode) step by step — tiles of B_c rows, running maximum and
  * sum, output renormalised every tile — so a test can show that the tiled
@@ -271,6 +275,52 @@ int oracle_head_scores(const double *attn, int B, int Hq, int Hkv, int d, double
                 }
             score[(size_t)b * Hkv + g] = ss;
             if (norms) norms[(size_t)b * Hkv + g] = sqrt(ss);
+        }
+    return 0;
+}
+
+/* Neuron index tensor (Section 4.1: at inference the predicted activations are aggregated
+ * across the batch into a single index of the neurons that are active for any request;
+ * Section 3.1: the union set S_B).  topk [B,kn] holds each request's predicted neuron ids;
+ * the result is the ascending list of distinct ids in [0,N) (others are ignored). */
+int oracle_neuron_union(const int32_t *topk, int B, int kn, int N, int32_t *out, int32_t *count)
+{
+    if (!topk || !out || !count || B < 0 || kn < 0 || N < 1) return -1;
+    unsigned char *seen = calloc((size_t)N, 1);
+    if (!seen) return -2;
+    for (size_t i = 0; i < (size_t)B * kn; ++i)
+        if (topk[i] >= 0 && topk[i] < N) seen[topk[i]] = 1;
+    int32_t c = 0;
+    for (int n = 0; n < N; ++n)
+        if (seen[n]) out[c++] = n;
+    *count = c;
+    free(seen);
+    return 0;
+}
+
+/* Selective (fused-gather) GEMM (Appendix "Sparse Kernels", Algorithm 3; Section 3.1, the
+ * first factor sigma(x W_{1,S_B}) of the sparsified MLP): the rows of the weight matrix named
+ * by the index vector are gathered and multiplied with the activations, then the activation
+ * function is applied.
+ *   A [M,K] 16-bit activations; W [N,K] 16-bit, one contiguous row of K weights per neuron;
+ *   idx [n_sel] neuron ids;  C [M,n_sel] double:
+ *   C[m,j] = act( sum_{k<K} A[m,k] * W[idx[j],k] ),  act = ReLU when relu != 0, else identity.
+ * An id outside [0,N) gives a zero column. */
+int oracle_select_gemm(const uint16_t *A, const uint16_t *W, const int32_t *idx, int M, int K,
+                       int N, int n_sel, int dt, int relu, double *C)
+{
+    if (!A || !W || !idx || !C || M < 0 || K < 1 || N < 1 || n_sel < 0) return -1;
+    if (dt != ORACLE_F16 && dt != ORACLE_BF16) return -1;
+    for (int m = 0; m < M; ++m)
+        for (int j = 0; j < n_sel; ++j) {
+            double acc = 0.0;
+            int n = idx[j];
+            if (n >= 0 && n < N) {
+                for (int k = 0; k < K; ++k)
+                    acc += widen(A[(size_t)m * K + k], dt) * widen(W[(size_t)n * K + k], dt);
+                if (relu && !(acc > 0.0)) acc = 0.0;
+            }
+            C[(size_t)m * n_sel + j] = acc;
         }
     return 0;
 }

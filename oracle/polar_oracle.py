@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_topk.argtypes = [vp, c_int, c_int, c_int, vp]
         L.oracle_sha_decode.argtypes = [vp, vp, vp, vp, vp, vp] + [c_int] * 7 + [c_dbl]
         L.oracle_head_scores.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp]
+        L.oracle_neuron_union.argtypes = [vp, c_int, c_int, c_int, vp, vp]
+        L.oracle_select_gemm.argtypes = [vp, vp, vp] + [c_int] * 6 + [vp]
         L.oracle_alg1_tiled.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_dbl, vp]
         _lib = L
     return _lib
@@ -155,3 +157,29 @@ def head_importance_labels(q_bits, K_bits, V_bits, seqlens, k: int, dtype: str):
     attn = sha_decode(q_bits, K_bits, V_bits, seqlens, None, Hkv, dtype)
     score, _ = head_scores(attn, Hkv)
     return topk(score, k), score
+
+
+def neuron_union(topk_idx, N: int) -> np.ndarray:
+    """Per-request neuron ids int32 [B,kn] -> ascending distinct ids in [0,N) (int32 [count])."""
+    topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    B, kn = topk_idx.shape
+    out = np.empty(max(1, min(N, B * kn)), dtype=np.int32)
+    count = np.zeros(1, dtype=np.int32)
+    rc = lib().oracle_neuron_union(_ptr(topk_idx), B, kn, N, _ptr(out), _ptr(count))
+    assert rc == 0, rc
+    return out[: int(count[0])].copy()
+
+
+def select_gemm(A_bits, W_bits, idx, dtype: str, relu: bool = True) -> np.ndarray:
+    """A [M,K], W [N,K] uint16 patterns, idx int32 [n_sel] -> float64 [M,n_sel]:
+    act(A @ W[idx].T); ids outside [0,N) give zero columns."""
+    A_bits, W_bits = _u16(A_bits), _u16(W_bits)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    M, K = A_bits.shape
+    N, K2 = W_bits.shape
+    assert K == K2 and idx.ndim == 1
+    C = np.empty((M, idx.shape[0]), dtype=np.float64)
+    rc = lib().oracle_select_gemm(_ptr(A_bits), _ptr(W_bits), _ptr(idx), M, K, N, idx.shape[0],
+                                  _DT[dtype], 1 if relu else 0, _ptr(C))
+    assert rc == 0, rc
+    return C

@@ -435,6 +435,72 @@ def test_head_importance_labels_equal_numpy_route():
     assert np.array_equal(labels, want.astype(np.int32))
 
 
+# ----------------------------------------------------------------------------- selective GEMM
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("relu", [True, False])
+def test_select_gemm_equals_gathered_matrix_product(dtype, relu):
+    M, K, N = 5, 96, 40
+    A = bits_of(RNG.standard_normal((M, K)), dtype)
+    W = bits_of(RNG.standard_normal((N, K)) / math.sqrt(K), dtype)
+    idx = RNG.permutation(N)[:13].astype(np.int32)
+    got = orc.select_gemm(A, W, idx, dtype, relu=relu)
+    want = as_f64(A, dtype) @ as_f64(W, dtype)[idx].T
+    if relu:
+        want = np.maximum(want, 0.0)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+    assert relu == bool((got >= 0).all())
+    # reading W as [K,N] (input-major) instead of one row per neuron must not pass
+    wrong = as_f64(A, dtype) @ as_f64(W, dtype).reshape(K, N)[:, idx]
+    assert not np.allclose(got, np.maximum(wrong, 0.0) if relu else wrong, atol=1e-3)
+
+
+def test_select_gemm_one_hot_rows_pick_activation_columns():
+    """Neuron n's weight row is e_{n mod K}: its pre-activation is A[:, n mod K] exactly."""
+    M, K, N = 4, 16, 32
+    A = RNG.integers(-5, 6, size=(M, K)).astype(np.float64)
+    W = np.zeros((N, K)); W[np.arange(N), np.arange(N) % K] = 1.0
+    idx = np.array([3, 19, 0, 31, 19], np.int32)                  # a repeated id repeats the column
+    got = orc.select_gemm(f16_bits(A), f16_bits(W), idx, "f16", relu=True)
+    assert np.array_equal(got, np.maximum(A[:, idx % K], 0.0))
+    got_lin = orc.select_gemm(f16_bits(A), f16_bits(W), idx, "f16", relu=False)
+    assert np.array_equal(got_lin, A[:, idx % K])
+
+
+def test_select_gemm_invalid_ids_and_empty_selection():
+    M, K, N = 3, 8, 6
+    A = f16_bits(RNG.standard_normal((M, K)))
+    W = f16_bits(RNG.standard_normal((N, K)))
+    got = orc.select_gemm(A, W, np.array([2, -1, 6, 5], np.int32), "f16", relu=False)
+    full = orc.select_gemm(A, W, np.arange(N, dtype=np.int32), "f16", relu=False)
+    assert np.array_equal(got[:, 0], full[:, 2]) and np.array_equal(got[:, 3], full[:, 5])
+    assert not got[:, 1:3].any()
+    assert orc.select_gemm(A, W, np.zeros(0, np.int32), "f16").shape == (M, 0)
+
+
+def test_neuron_union_is_the_sorted_set_of_valid_ids():
+    B, kn, N = 7, 12, 50
+    topk = RNG.integers(-3, N + 3, size=(B, kn)).astype(np.int32)
+    got = orc.neuron_union(topk, N)
+    want = sorted({int(v) for v in topk.ravel() if 0 <= v < N})
+    assert got.tolist() == want
+    assert orc.neuron_union(np.full((2, 3), -1, np.int32), N).tolist() == []
+    assert orc.neuron_union(np.array([[4, 4, 4]], np.int32), N).tolist() == [4]
+
+
+def test_select_gemm_on_union_equals_masked_dense_layer():
+    """Section 3.1: with S_B the union of the requests' active sets, sigma(x W_{1,S_B}) is the
+    dense layer's activation restricted to the columns in S_B."""
+    B, K, N, kn = 6, 64, 48, 5
+    x = bf16_bits(RNG.standard_normal((B, K)))
+    W1 = bf16_bits(RNG.standard_normal((N, K)) / 8.0)
+    dense = np.maximum(as_f64(x, "bf16") @ as_f64(W1, "bf16").T, 0.0)
+    topk = np.argsort(-dense, axis=1)[:, :kn].astype(np.int32)       # each request's top neurons
+    S = orc.neuron_union(topk, N)
+    got = orc.select_gemm(x, W1, S, "bf16", relu=True)
+    np.testing.assert_allclose(got, dense[:, S], rtol=1e-12, atol=1e-14)
+    assert len(S) >= kn and len(S) <= min(N, B * kn)
+
+
 # ----------------------------------------------------------------------------- threads
 def test_result_does_not_depend_on_thread_count():
     q, K, V, n = random_case(4, 4, 4, 50, 16, "f16")
