@@ -185,6 +185,42 @@ int polar_sha_chunk_rows(int B, int Hq, int Hkv, int S, int d, int k);
 int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,
                          int32_t *head_idx, float *norms_out, void *stream);
 
+/*
+ * Selective (fused-gather) GEMM (Appendix "Sparse Kernels", Algorithm 3; Section 3.1, the
+ * first factor sigma(x W_{1,S_B}) of the sparsified MLP; Section 4.1).
+ *
+ *   C[m, j] = act( sum_{k<K} A[m,k] * W[idx[j], k] )   for m < M, j < count
+ *
+ *   A      in   [M, K] dt      activations (one row per request)
+ *   W      in   [N, K] dt      weights, one contiguous row of K values per neuron
+ *   idx    in   [cap] int32    neuron index; ids outside [0,N) give a zero column
+ *   count  in   [1] int32, nullable, DEVICE pointer: number of live entries of idx (clamped to
+ *               [0, cap]); NULL means all cap entries are live.  Lets the index be built on
+ *               the device (polar_neuron_union) without a host round trip.
+ *   C      out  [M, cap] float, row-major with leading dimension cap; columns at or beyond
+ *               the live count are not written.
+ *   relu        non-zero: act = max(., 0); zero: identity.
+ *
+ * 16-bit inputs, float accumulation on the matrix cores, float output.  K must be a multiple
+ * of 128; A and W 16-byte aligned.  M > 256 is processed 256 rows at a time.
+ */
+int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                      float *C, int M, int K, int N, int cap, polar_dtype dt, int relu, void *stream);
+
+/*
+ * Batch neuron index (Section 4.1: the predicted activations of all requests are aggregated
+ * into one index tensor; Section 3.1: the union set S_B).
+ *
+ *   topk       in   [B, kn] int32: each request's predicted neuron ids (any order; ids outside
+ *                   [0,N) are ignored)
+ *   idx_out    out  [cap] int32: the distinct ids in ascending order (first min(count, cap))
+ *   count_out  out  [1] int32: number of distinct ids, clamped to cap
+ *
+ * N <= 524288.  One launch, deterministic.
+ */
+int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
+                       int32_t *count_out, void *stream);
+
 /* Text for a polar_status value; never NULL. */
 const char *polar_strerror(int status);
 /* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */

@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_head_norm_topk", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_head_norm_topk", "polar_select_gemm", "polar_neuron_union", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.polar_sha_merge.restype = i
         L.polar_head_norm_topk.argtypes = [vp, i, i, i, i, i, vp, vp, vp]
         L.polar_head_norm_topk.restype = i
+        L.polar_select_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
+        L.polar_select_gemm.restype = i
+        L.polar_neuron_union.argtypes = [vp, i, i, i, i, vp, vp, vp]
+        L.polar_neuron_union.restype = i
         L.polar_strerror.argtypes = [i]
         L.polar_strerror.restype = ctypes.c_char_p
         L.polar_last_hip_error.restype = i
@@ -230,3 +234,35 @@ def head_norm_topk(attn_out: torch.Tensor, Hkv: int, k: int,
                                     _dev(norms_out, "norms_out", torch.float32), _stream())
     _check(rc, "polar_head_norm_topk")
     return head_idx
+
+
+def select_gemm(A: torch.Tensor, W: torch.Tensor, idx: torch.Tensor,
+                count: Optional[torch.Tensor] = None, relu: bool = True,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """act(A @ W[idx].T): A [M,K], W [N,K] (fp16/bf16, one row per neuron), idx int32 [cap],
+    count int32 [1] on the device (None: all of idx is live) -> float32 [M,cap]."""
+    M, K = A.shape
+    N, K2 = W.shape
+    if K != K2 or A.dtype != W.dtype:
+        raise ValueError("A [M,K] and W [N,K] must agree in K and dtype")
+    cap = idx.shape[0]
+    if out is None:
+        out = torch.zeros((M, cap), dtype=torch.float32, device=A.device)
+    rc = lib().polar_select_gemm(_dev(A, "A"), _dev(W, "W"), _dev(idx, "idx", torch.int32),
+                                 _dev(count, "count", torch.int32), _dev(out, "out", torch.float32),
+                                 M, K, N, cap, _dtype_code(A), 1 if relu else 0, _stream())
+    _check(rc, "polar_select_gemm")
+    return out
+
+
+def neuron_union(topk: torch.Tensor, N: int, cap: Optional[int] = None):
+    """Per-request neuron ids int32 [B,kn] -> (idx int32 [cap] ascending distinct ids, count int32 [1])."""
+    B, kn = topk.shape
+    cap = min(N, B * kn) if cap is None else cap
+    idx = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=topk.device)[:cap]
+    count = torch.zeros(1, dtype=torch.int32, device=topk.device)
+    rc = lib().polar_neuron_union(_dev(topk, "topk", torch.int32), B, kn, N, cap,
+                                  _dev(idx, "idx", torch.int32), _dev(count, "count", torch.int32),
+                                  _stream())
+    _check(rc, "polar_neuron_union")
+    return idx, count

@@ -239,4 +239,26 @@ int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, i
                                         static_cast<hipStream_t>(stream)));
 }
 
+int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                      float *C, int M, int K, int N, int cap, polar_dtype dt, int relu, void *stream)
+{
+    if (M < 0 || K < 1 || N < 1 || cap < 0 || !dtype_ok(dt)) return POLAR_EINVAL;
+    if (K % 128 != 0 || (long long)N * K > (1ll << 40)) return POLAR_EUNSUPPORTED;
+    if (M == 0 || cap == 0) return POLAR_OK;
+    if (!A || !W || !idx || !C) return POLAR_EINVAL;
+    if (((uintptr_t)A & 15u) || ((uintptr_t)W & 15u)) return POLAR_EINVAL;   // 16-byte loads
+    return record(launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
+                       int32_t *count_out, void *stream)
+{
+    if (B < 0 || kn < 0 || N < 1 || cap < 0) return POLAR_EINVAL;
+    if (N > neuron_union_max_n()) return POLAR_EUNSUPPORTED;
+    if (!count_out || (cap > 0 && !idx_out) || ((long long)B * kn > 0 && !topk)) return POLAR_EINVAL;
+    return record(launch_neuron_union(topk, B, kn, N, cap, idx_out, count_out,
+                                      static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -1,0 +1,279 @@
+// Selective (fused-gather) GEMM and the batch neuron index for gfx950 (Section 3.1: the
+// sparsified MLP sigma(x W_{1,S_B}) over the union S_B of the requests' active neurons;
+// Section 4.1: the neuron index tensor and the kernel that fuses indexing with the matrix
+// product; Appendix "Sparse Kernels", Algorithm 3: gather the indexed rows, multiply, apply
+// the activation, store).
+//
+//   C[m, j] = act( sum_k A[m, k] * W[idx[j], k] )       A [M,K], W [N,K] (one row per neuron)
+//
+// At decode batch sizes this is bound by HBM, not by the matrix cores: every gathered weight
+// row (K 16-bit values) is read once and used for only M <= 256 multiply-adds per element,
+// far below the ~300 flop/byte ridge of the part, but above what the vector ALUs sustain at
+// HBM speed, so the contraction runs on MFMA (v_mfma_f32_16x16x32) while the kernel is
+// organised around streaming the gathered rows:
+//   * a workgroup owns 32 selected neurons and walks K in blocks of 128 values; per block it
+//     loads its 32 x 256-byte row pieces with fully coalesced 16-byte loads (16 lanes per
+//     piece), parks them in LDS (padded rows, conflict-free 16-byte reads) and every wave
+//     reads them back as B operands.  The next block's loads are in flight while the
+//     current one is multiplied (registers -> LDS double buffer, one barrier per block).
+//   * the activations are small (M x K) and shared by all workgroups, so they come straight
+//     from L2 in operand layout: lane (m, kg) reads 64 contiguous bytes of row m per block.
+//     Within a block, MFMA step s contracts the k values {32*kg + 8*s + j}; A and B use the
+//     same assignment, which is all the contraction needs.
+//   * wave w owns rows [16*MT*w, 16*MT*(w+1)) of the output tile (MT = 1, 2 or 4 for M up to
+//     64, 128, 256) and both 16-column halves of the 32 neurons: 2*MT accumulators.
+// The gather costs nothing extra: a row index only changes the base address of a contiguous
+// 2K-byte stream, which is why the weights are stored one contiguous row per neuron.
+#include <atomic>
+
+#include "polar_internal.h"
+
+namespace polar {
+namespace {
+
+constexpr int kGemmThreads = 256;
+constexpr int kTileN = 32;                       // selected neurons per workgroup
+constexpr int kBlockK = 128;                     // K values per step (256 bytes of a row)
+constexpr int kRowBytes = kBlockK * 2 + 16;      // padded LDS row: 16-lane reads hit 64 banks
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <bool BF> __device__ __forceinline__ f32x4 mfma16x16x32(const uint4 &a, const uint4 &b, f32x4 c)
+{
+    if (BF)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// grid = ceil(cap / kTileN) workgroups; block = 256 threads (4 waves).
+// Rows m >= M of the tile are computed on clamped addresses and never stored; columns at or
+// beyond the live count are never stored; an id outside [0, N) yields a zero column.
+template <bool BF, int MT>
+__global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const int32_t *__restrict__ idx,
+    const int32_t *__restrict__ count_ptr, float *__restrict__ C, int M, int K, int N, int cap,
+    int relu)
+{
+    __shared__ __align__(16) unsigned char sh_w[2][kTileN * kRowBytes];
+    __shared__ int sh_row[kTileN];               // weight row to stream, -1 for an invalid id
+
+    int count = cap;
+    if (count_ptr) {
+        const int c = *count_ptr;
+        count = c < 0 ? 0 : (c < cap ? c : cap);
+    }
+    const int n0 = blockIdx.x * kTileN;
+    if (n0 >= count) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < kTileN) {
+        const int id = n0 + tid < count ? idx[n0 + tid] : -1;
+        sh_row[tid] = (id >= 0 && id < N) ? id : -1;
+    }
+    __syncthreads();
+
+    // global -> LDS assignment: 16 lanes per 256-byte row piece, two pieces per thread
+    const int g_chunk = tid & 15, g_row = tid >> 4;                 // rows g_row and g_row + 16
+    const int r0 = sh_row[g_row], r1 = sh_row[g_row + 16];
+    const uint4 *w0 = reinterpret_cast<const uint4 *>(W + (size_t)(r0 < 0 ? 0 : r0) * K) + g_chunk;
+    const uint4 *w1 = reinterpret_cast<const uint4 *>(W + (size_t)(r1 < 0 ? 0 : r1) * K) + g_chunk;
+    const int lds_w0 = g_row * kRowBytes + g_chunk * 16, lds_w1 = lds_w0 + 16 * kRowBytes;
+
+    // operand layout: lane (x = lane % 16, kg = lane / 16)
+    const int x = lane & 15, kg = lane >> 4;
+    const uint4 *a_src[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        int row = (wave * MT + t) * 16 + x;
+        row = row < M ? row : M - 1;
+        a_src[t] = reinterpret_cast<const uint4 *>(A + (size_t)row * K) + kg * 4;   // 64 bytes per block
+    }
+    const int lds_b = x * kRowBytes + kg * 64;                      // + 16*s, + 16*kRowBytes for half 1
+
+    f32x4 acc[MT][2];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t][0] = acc[t][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const int nblk = K / kBlockK;
+    uint4 wq0 = w0[0], wq1 = w1[0];
+    uint4 a_cur[MT][4];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) a_cur[t][s] = a_src[t][s];
+
+    for (int kb = 0; kb < nblk; ++kb) {
+        unsigned char *buf = sh_w[kb & 1];
+        *reinterpret_cast<uint4 *>(buf + lds_w0) = wq0;
+        *reinterpret_cast<uint4 *>(buf + lds_w1) = wq1;
+        __syncthreads();
+
+        uint4 a_nxt[MT][4];
+        if (kb + 1 < nblk) {                       // next block's loads fly during the MFMAs
+            wq0 = w0[(size_t)(kb + 1) * 16];
+            wq1 = w1[(size_t)(kb + 1) * 16];
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int s = 0; s < 4; ++s) a_nxt[t][s] = a_src[t][(size_t)(kb + 1) * 16 + s];
+        }
+
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint4 b0 = *reinterpret_cast<const uint4 *>(buf + lds_b + 16 * s);
+            const uint4 b1 = *reinterpret_cast<const uint4 *>(buf + lds_b + 16 * kRowBytes + 16 * s);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                acc[t][0] = mfma16x16x32<BF>(a_cur[t][s], b0, acc[t][0]);
+                acc[t][1] = mfma16x16x32<BF>(a_cur[t][s], b1, acc[t][1]);
+            }
+        }
+        if (kb + 1 < nblk) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int s = 0; s < 4; ++s) a_cur[t][s] = a_nxt[t][s];
+        }
+    }
+
+    // accumulator layout: lane holds rows 4*kg + i (i = 0..3) of column x
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int col = n0 + 16 * h + x;
+            if (col >= count) continue;
+            const bool valid = sh_row[16 * h + x] >= 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = (wave * MT + t) * 16 + kg * 4 + i;
+                if (row < M) {
+                    float v = acc[t][h][i];
+                    if (relu) v = v > 0.0f ? v : 0.0f;
+                    C[(size_t)row * cap + col] = valid ? v : 0.0f;
+                }
+            }
+        }
+}
+
+// Batch union of predicted neuron ids (Section 4.1: one index tensor for the whole batch).
+// One workgroup: an LDS bitmap of N bits is cleared, every valid id of topk [B*kn] sets its bit,
+// then each thread counts the bits of its contiguous share of the bitmap, an exclusive scan over
+// the threads gives its output offset, and it emits its ids in ascending order.  The result is
+// the ascending list of distinct ids, whatever the order of the input.
+constexpr int kUnionThreads = 1024;
+constexpr int kUnionMaxWords = 16384;            // N <= 524288 neurons (64 KB of LDS)
+
+__global__ __launch_bounds__(kUnionThreads) void neuron_union_kernel(
+    const int32_t *__restrict__ topk, long total, int N, int cap, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out)
+{
+    extern __shared__ unsigned int sh_bits[];     // words, then kUnionThreads scan slots
+    const int words = (N + 31) / 32;
+    unsigned int *sh_scan = sh_bits + words;
+    const int tid = threadIdx.x;
+    for (int wd = tid; wd < words; wd += kUnionThreads) sh_bits[wd] = 0u;
+    __syncthreads();
+    for (long i = tid; i < total; i += kUnionThreads) {
+        const int id = topk[i];
+        if (id >= 0 && id < N) atomicOr(&sh_bits[id >> 5], 1u << (id & 31));
+    }
+    __syncthreads();
+    const int per = (words + kUnionThreads - 1) / kUnionThreads;
+    const int w_begin = min(tid * per, words), w_end = min(w_begin + per, words);
+    unsigned int mine = 0;
+    for (int wd = w_begin; wd < w_end; ++wd) mine += __popc(sh_bits[wd]);
+    sh_scan[tid] = mine;
+    __syncthreads();
+    for (int off = 1; off < kUnionThreads; off <<= 1) {           // inclusive Hillis-Steele scan
+        const unsigned int add = tid >= off ? sh_scan[tid - off] : 0u;
+        __syncthreads();
+        sh_scan[tid] += add;
+        __syncthreads();
+    }
+    unsigned int pos = sh_scan[tid] - mine;
+    if (tid == kUnionThreads - 1) {
+        const unsigned int all = sh_scan[tid];
+        count_out[0] = (int32_t)(all < (unsigned)cap ? all : (unsigned)cap);
+    }
+    for (int wd = w_begin; wd < w_end; ++wd) {
+        unsigned int bits = sh_bits[wd];
+        while (bits) {
+            const int bit = __ffs(bits) - 1;
+            bits &= bits - 1;
+            if (pos < (unsigned)cap) idx_out[pos] = wd * 32 + bit;
+            ++pos;
+        }
+    }
+}
+
+template <bool BF>
+hipError_t launch_gemm_mt(int mt, dim3 grid, hipStream_t st, const uint16_t *A, const uint16_t *W,
+                          const int32_t *idx, const int32_t *count, float *C, int M, int K, int N,
+                          int cap, int relu)
+{
+    switch (mt) {
+    case 1:
+        hipLaunchKernelGGL((select_gemm_kernel<BF, 1>), grid, dim3(kGemmThreads), 0, st, A, W, idx,
+                           count, C, M, K, N, cap, relu);
+        break;
+    case 2:
+        hipLaunchKernelGGL((select_gemm_kernel<BF, 2>), grid, dim3(kGemmThreads), 0, st, A, W, idx,
+                           count, C, M, K, N, cap, relu);
+        break;
+    default:
+        hipLaunchKernelGGL((select_gemm_kernel<BF, 4>), grid, dim3(kGemmThreads), 0, st, A, W, idx,
+                           count, C, M, K, N, cap, relu);
+        break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                              float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                              hipStream_t stream)
+{
+    const uint16_t *A16 = static_cast<const uint16_t *>(A);
+    const uint16_t *W16 = static_cast<const uint16_t *>(W);
+    const dim3 grid((unsigned)((cap + kTileN - 1) / kTileN));
+    // batches beyond 256 rows are processed 256 rows at a time (the gathered rows are re-read)
+    for (int m0 = 0; m0 < M; m0 += 256) {
+        const int rows = M - m0 < 256 ? M - m0 : 256;
+        const int mt = rows <= 64 ? 1 : (rows <= 128 ? 2 : 4);
+        const uint16_t *Ap = A16 + (size_t)m0 * K;
+        float *Cp = C + (size_t)m0 * cap;
+        const hipError_t e =
+            dt == POLAR_BF16
+                ? launch_gemm_mt<true>(mt, grid, stream, Ap, W16, idx, count, Cp, rows, K, N, cap, relu)
+                : launch_gemm_mt<false>(mt, grid, stream, Ap, W16, idx, count, Cp, rows, K, N, cap, relu);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+int neuron_union_max_n() { return kUnionMaxWords * 32; }
+
+hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
+                               int32_t *count_out, hipStream_t stream)
+{
+    const int words = (N + 31) / 32;
+    const size_t lds = ((size_t)words + kUnionThreads) * sizeof(unsigned int);
+    static std::atomic<size_t> granted{0};
+    if (lds > 48 * 1024 && lds > granted.load(std::memory_order_acquire)) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(neuron_union_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        granted.store(lds, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(neuron_union_kernel, dim3(1), dim3(kUnionThreads), lds, stream, topk,
+                       (long)B * kn, N, cap, idx_out, count_out);
+    return hipGetLastError();
+}
+
+}  // namespace polar

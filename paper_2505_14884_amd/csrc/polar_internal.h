@@ -51,4 +51,11 @@ hipError_t launch_router_split(const void *hidden, const void *Wr, int B, int D,
 hipError_t launch_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,
                                  int32_t *head_idx, float *norms_out, hipStream_t stream);
 
+hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                              float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                              hipStream_t stream);
+int neuron_union_max_n();
+hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
+                               int32_t *count_out, hipStream_t stream);
+
 }  // namespace polar

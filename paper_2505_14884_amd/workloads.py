@@ -73,6 +73,53 @@ CONFIGS: Dict[str, ShaWorkload] = {
 }
 
 
+@dataclass(frozen=True)
+class MlpWorkload:
+    """First (up-projection) layer of a sparsified MLP at decode: B requests, hidden width K,
+    N neurons of which the batch union of predicted-active ones is computed."""
+
+    name: str
+    B: int          # requests
+    K: int          # model hidden size (contraction length)
+    N: int          # feed-forward width (neurons)
+    density: float  # target fraction of neurons in the batch union
+    dtype: str
+    seed: int = 0
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return _TORCH_DTYPE[self.dtype]
+
+
+# OPT-66B feed-forward shape (hidden 9216, 4x expansion) at the paper's kernel-figure batch size.
+MLP_CONFIGS: Dict[str, MlpWorkload] = {
+    "M1_tiny": MlpWorkload("M1_tiny", B=8, K=256, N=1024, density=0.3, dtype="f16", seed=201),
+    "M2_opt66b_ffn": MlpWorkload("M2_opt66b_ffn", B=64, K=9216, N=36864, density=0.3,
+                                 dtype="f16", seed=202),
+}
+
+
+def make_mlp_inputs(w: MlpWorkload, device="cpu"):
+    """x [B,K] ~ N(0,1), W1 [N,K] ~ N(0,1/K) (one row per neuron) and per-request predicted
+    neuron ids [B,kn]: every request draws kn = 5 % of a seeded "hot set" of density*N neurons,
+    so the batch union covers most of the hot set (the union grows with B as in the paper's
+    batch-activation study, while each request alone is sparse)."""
+    g = _gen(device, w.seed * 7919 + 1)
+    x = torch.randn((w.B, w.K), generator=g, device=device, dtype=torch.float32).to(w.torch_dtype)
+    W1 = torch.empty((w.N, w.K), device=device, dtype=w.torch_dtype)
+    step = max(1, (1 << 27) // w.K)
+    for n0 in range(0, w.N, step):
+        n1 = min(w.N, n0 + step)
+        blk = torch.randn((n1 - n0, w.K), generator=g, device=device, dtype=torch.float32)
+        W1[n0:n1] = (blk * (1.0 / math.sqrt(w.K))).to(w.torch_dtype)
+    gc = _gen("cpu", w.seed * 7919 + 2)
+    hot = torch.randperm(w.N, generator=gc)[: max(1, int(round(w.density * w.N)))]
+    kn = max(1, int(round(0.05 * hot.numel())))
+    rows = [hot[torch.randperm(hot.numel(), generator=gc)[:kn]] for _ in range(w.B)]
+    topk = torch.stack(rows).to(torch.int32).to(device)
+    return x, W1, topk
+
+
 def _gen(device, seed: int) -> torch.Generator:
     g = torch.Generator(device=device)
     g.manual_seed(seed)

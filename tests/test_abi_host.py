@@ -119,6 +119,25 @@ def test_head_norm_topk_argument_errors():
     assert f(B=0, out=None, idx=None) == OK
 
 
+def test_select_gemm_and_union_argument_errors():
+    L = binding.lib()
+    A16 = ctypes.c_void_p(0x1000)
+    g = lambda A=A16, W=A16, idx=FAKE, C=FAKE, M=4, K=256, N=64, cap=32, dt=0: L.polar_select_gemm(
+        A, W, idx, None, C, M, K, N, cap, dt, 1, None)
+    assert g(M=-1) == EINVAL and g(K=0) == EINVAL and g(N=0) == EINVAL and g(cap=-1) == EINVAL
+    assert g(dt=3) == EINVAL
+    assert g(K=200) == EUNSUPPORTED                       # K must be a multiple of 128
+    assert g(A=None) == EINVAL and g(W=None) == EINVAL and g(idx=None) == EINVAL and g(C=None) == EINVAL
+    assert g(A=ctypes.c_void_p(0x1008)) == EINVAL         # 16-byte alignment
+    assert g(M=0, A=None, W=None, idx=None, C=None) == OK
+    assert g(cap=0, idx=None, C=None) == OK
+    u = lambda topk=FAKE, B=2, kn=3, N=64, cap=6, idx=FAKE, cnt=FAKE: L.polar_neuron_union(
+        topk, B, kn, N, cap, idx, cnt, None)
+    assert u(B=-1) == EINVAL and u(N=0) == EINVAL and u(cap=-1) == EINVAL
+    assert u(cnt=None) == EINVAL and u(idx=None) == EINVAL and u(topk=None) == EINVAL
+    assert u(N=524289) == EUNSUPPORTED
+
+
 def test_workspace_size_is_consistent_with_the_chunking():
     L = binding.lib()
     for (B, Hq, Hkv, S, d, k) in [(4, 8, 8, 256, 64, 4), (32, 32, 32, 1920, 128, 16),

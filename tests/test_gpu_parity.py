@@ -313,6 +313,94 @@ def test_head_importance_labels(name):
     assert np.array_equal(got[gap_ok], ref[gap_ok].astype(np.int32))
 
 
+# ----------------------------------------------------------------------------- selective GEMM
+GEMM_TOL = 1e-3      # float accumulation of K <= 9216 products of O(1) x O(1/sqrt(K)) terms
+
+
+def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0):
+    g = torch.Generator(device=DEV).manual_seed(1000 + seed)
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+    A = torch.randn((M, K), generator=g, device=DEV).to(tdt)
+    W = (torch.randn((N, K), generator=g, device=DEV) / K ** 0.5).to(tdt)
+    idx = torch.tensor(idx_host, dtype=torch.int32, device=DEV)
+    cnt = None if count is None else torch.tensor([count], dtype=torch.int32, device=DEV)
+    out = torch.full((M, len(idx_host)), float("nan"), dtype=torch.float32, device=DEV)
+    polar.select_gemm(A, W, idx, count=cnt, relu=relu, out=out)
+    torch.cuda.synchronize()
+    live = len(idx_host) if count is None else max(0, min(count, len(idx_host)))
+    want = orc.select_gemm(host_bits(A), host_bits(W), np.array(idx_host[:live], np.int32), dtype, relu)
+    got = out.cpu().numpy()
+    assert np.isfinite(got[:, :live]).all()
+    err = np.abs(got[:, :live] - want).max() if want.size else 0.0
+    assert err <= GEMM_TOL, err
+    assert np.isnan(got[:, live:]).all()                   # columns beyond the live count untouched
+    return err
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("M", [1, 5, 64, 65, 130, 256, 300])
+def test_select_gemm_shapes(dtype, M):
+    say("\ncase select_gemm", dtype, M)
+    rng = np.random.default_rng(M)
+    N, K = 500, 384
+    idx = rng.permutation(N)[:77].tolist()                 # 77: two full tiles and a ragged one
+    say("   err %.2e" % gemm_case(M, K, N, idx, dtype, relu=True, seed=M))
+    say("   err %.2e" % gemm_case(M, K, N, idx, dtype, relu=False, seed=M + 1))
+
+
+def test_select_gemm_invalid_ids_count_and_long_k():
+    say("\ncase select_gemm ids")
+    idx = [3, -1, 3, 99, 100, 7, 0, 42] * 5                # invalid ids (-1, 100) and repeats
+    gemm_case(9, 128, 100, idx, "f16", relu=True)
+    gemm_case(9, 128, 100, idx, "bf16", relu=False, count=17)   # device-side live count
+    gemm_case(9, 128, 100, idx, "bf16", relu=False, count=0)
+    gemm_case(9, 128, 100, idx, "f16", relu=True, count=1000)   # count beyond capacity is clamped
+    gemm_case(33, 9216, 64, list(range(64)), "f16", relu=True)  # the OPT-66B contraction length
+
+
+def test_neuron_union_matches_oracle():
+    say("\ncase neuron union")
+    g = torch.Generator(device="cpu").manual_seed(5)
+    for (B, kn, N) in [(1, 1, 1), (7, 12, 50), (64, 1843, 36864), (3, 5, 524288), (16, 100, 33)]:
+        topk = torch.randint(-2, N + 2, (B, kn), generator=g, dtype=torch.int32).to(DEV)
+        idx, count = polar.neuron_union(topk, N)
+        torch.cuda.synchronize()
+        want = orc.neuron_union(topk.cpu().numpy(), N)
+        c = int(count.item())
+        assert c == len(want)
+        assert idx[:c].cpu().numpy().tolist() == want.tolist()
+    # a capacity smaller than the union truncates the ascending list
+    topk = torch.arange(40, dtype=torch.int32, device=DEV).reshape(4, 10)
+    idx, count = polar.neuron_union(topk, 64, cap=25)
+    torch.cuda.synchronize()
+    assert int(count.item()) == 25 and idx.cpu().tolist() == list(range(25))
+
+
+@pytest.mark.parametrize("name", ["M1_tiny", "M2_opt66b_ffn"])
+def test_sparse_mlp_first_layer(name):
+    """Union index built on the device feeds the selective GEMM without a host round trip;
+    the oracle recomputes a sample of the selected neurons."""
+    w = wl.MLP_CONFIGS[name]
+    say("\ncase", w)
+    x, W1, topk = wl.make_mlp_inputs(w, DEV)
+    idx, count = polar.neuron_union(topk, w.N)
+    out = polar.select_gemm(x, W1, idx, count=count, relu=True)
+    torch.cuda.synchronize()
+    S = orc.neuron_union(topk.cpu().numpy(), w.N)
+    c = int(count.item())
+    assert c == len(S) and np.array_equal(idx[:c].cpu().numpy(), S)
+    say("   union %d of %d neurons (%.1f %%)" % (c, w.N, 100.0 * c / w.N))
+    cols = np.unique(np.linspace(0, c - 1, num=min(c, 192)).astype(np.int64))
+    want = orc.select_gemm(host_bits(x), host_bits(W1[torch.from_numpy(S[cols]).long().to(DEV)]),
+                           np.arange(len(cols), dtype=np.int32), w.dtype, True)
+    got = out[:, torch.from_numpy(cols).to(DEV)].cpu().numpy()
+    err = np.abs(got - want).max()
+    say("   max-abs error %.3e on %d sampled neurons" % (err, len(cols)))
+    assert err <= GEMM_TOL
+    assert (out[:, :c] >= 0).all() and torch.isfinite(out[:, :c]).all()
+    assert 0.3 < float((out[:, :c] > 0).float().mean()) < 0.7      # ReLU of a symmetric pre-activation
+
+
 def test_empty_batch_is_a_noop():
     e16 = torch.empty((0, 8, 64), dtype=torch.float16, device=DEV)
     kv = torch.empty((0, 8, 128, 64), dtype=torch.float16, device=DEV)
