@@ -50,11 +50,121 @@ def parse_args():
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests the oracle is timed on")
     ap.add_argument("--kv-layout", choices=["bhsd", "bshd"], default="bhsd",
                     help="cache layout: [B,Hkv,S,d] (default) or the sequence-major [B,S,Hkv,d]")
-    ap.add_argument("--phase", choices=["all", "partial", "copy"], default="all",
+    ap.add_argument("--mlp-workload", default="M2_opt66b_ffn",
+                    help="workload of --phase select_gemm (see workloads.MLP_CONFIGS)")
+    ap.add_argument("--density", type=float, default=0.0,
+                    help="--phase select_gemm: override the target union density")
+    ap.add_argument("--phase", choices=["all", "partial", "copy", "select_gemm", "select_gemm_only"],
+                    default="all",
                     help="'partial' launches only the KV-streaming kernel (for counter runs); "
                          "'copy' runs a plain device copy of known size, the yardstick the "
-                         "FETCH_SIZE / WRITE_SIZE counters are scaled by")
+                         "FETCH_SIZE / WRITE_SIZE counters are scaled by; 'select_gemm' benchmarks "
+                         "the selective fused-gather GEMM (union index + GEMM) instead of the "
+                         "attention path; 'select_gemm_only' launches just that GEMM (counter runs)")
     return ap.parse_args()
+
+
+def bench_select_gemm(args, torch, np, polar, wl, dev):
+    """Step = batch union of the predicted neuron ids + selective GEMM with ReLU over the union
+    (first layer of the sparsified MLP).  value = bytes of the gathered weight rows / step time."""
+    w = wl.MLP_CONFIGS[args.mlp_workload]
+    if args.density:
+        w = wl.MlpWorkload(w.name, w.B, w.K, w.N, args.density, w.dtype, w.seed)
+    if args.B:
+        w = wl.MlpWorkload(w.name, args.B, w.K, w.N, w.density, w.dtype, w.seed)
+    x, W1, topk = wl.make_mlp_inputs(w, dev)
+    cap = min(w.N, topk.numel())
+    idx = torch.full((cap,), -1, dtype=torch.int32, device=dev)
+    count = torch.zeros(1, dtype=torch.int32, device=dev)
+    out = torch.zeros((w.B, cap), dtype=torch.float32, device=dev)
+    L = polar.binding.lib()
+    st = lambda: torch.cuda.current_stream().cuda_stream
+
+    def union():
+        rc = L.polar_neuron_union(topk.data_ptr(), w.B, topk.shape[1], w.N, cap, idx.data_ptr(),
+                                  count.data_ptr(), st())
+        assert rc == 0, rc
+
+    def gemm(i=0):
+        polar.select_gemm(x, W1, idx, count=count, relu=True, out=out)
+
+    union()
+    torch.cuda.synchronize()
+    n_sel = int(count.item())
+    bytes_sel = n_sel * w.K * 2
+    all_idx = torch.arange(w.N, dtype=torch.int32, device=dev)
+    dense_out = torch.empty((w.B, w.N), dtype=torch.float32, device=dev)
+
+    if args.phase == "select_gemm_only":
+        for i in range(args.warmup + args.steps):
+            gemm()
+        torch.cuda.synchronize()
+        print(json.dumps({"phase": "select_gemm_only", "workload": w.name,
+                          "launches": args.warmup + args.steps,
+                          "algorithmic_bytes_per_launch": bytes_sel}))
+        return
+
+    for i in range(args.warmup):
+        union(); gemm()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        union(); gemm()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def ev(fn, n):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    n_ev = max(10, min(args.steps, 100))
+    gemm_ms = ev(gemm, n_ev)
+    union_ms = ev(union, n_ev)
+    dense_ms = ev(lambda: polar.select_gemm(x, W1, all_idx, relu=True, out=dense_out), max(5, n_ev // 4))
+    achieved = bytes_sel / (gemm_ms * 1e-3) / 1e9
+    result = {
+        "metric": "selective fused-gather GEMM effective weight HBM GB/s (gathered rows' bytes / step "
+                  "time; step = batch neuron union + GEMM with ReLU)",
+        "value": round(bytes_sel / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: B=%d K=%d N=%d %s weights, union %d neurons (%.1f %%)"
+                               % (w.name, w.B, w.K, w.N, w.dtype, n_sel, 100.0 * n_sel / w.N),
+                   "selected_weight_bytes": bytes_sel, "dense_weight_bytes": w.N * w.K * 2},
+        "breakdown_us": {"neuron_union": round(union_ms * 1e3, 2), "select_gemm": round(gemm_ms * 1e3, 2),
+                         "dense_gemm_all_rows": round(dense_ms * 1e3, 2)},
+        "dense_over_selective": round(dense_ms / gemm_ms, 3),
+        "ideal_N_over_selected": round(w.N / max(n_sel, 1), 3),
+        "roofline": {"kernel": "select_gemm_kernel", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "avg_us": round(gemm_ms * 1e3, 2),
+                     "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import polar_oracle as orc
+
+        ncol = min(n_sel, 1024)
+        cols = idx[:ncol].long()
+        c0 = time.perf_counter()
+        ref = orc.select_gemm(wl.bits_u16(x), wl.bits_u16(W1[cols]), np.arange(ncol, dtype=np.int32),
+                              w.dtype, True)
+        c1 = time.perf_counter()
+        gemm()
+        torch.cuda.synchronize()
+        err = float(np.abs(out[:, :ncol].cpu().numpy() - ref).max())
+        result["cpu_baseline"] = {
+            "value": round(ncol * w.K * 2 / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": 1,
+            "kind": "oracle",
+            "sample": "first %d of the %d selected neurons, all %d requests, %.2f s" % (ncol, n_sel, w.B, c1 - c0),
+            "parity_on_sample": {"out_max_abs_err": err}}
+    print(json.dumps(result))
 
 
 def main():
@@ -85,6 +195,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"phase": "copy", "launches": args.warmup + args.steps,
                           "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes}))
+        return
+
+    if args.phase in ("select_gemm", "select_gemm_only"):
+        bench_select_gemm(args, torch, np, polar, wl, dev)
         return
 
     w = wl.CONFIGS[args.workload]

@@ -14,12 +14,14 @@
 //   * a workgroup owns 32 selected neurons and walks K in blocks of 128 values; per block it
 //     loads its 32 x 256-byte row pieces with fully coalesced 16-byte loads (16 lanes per
 //     piece), parks them in LDS (padded rows, conflict-free 16-byte reads) and every wave
-//     reads them back as B operands.  The next block's loads are in flight while the
-//     current one is multiplied (registers -> LDS double buffer, one barrier per block).
-//   * the activations are small (M x K) and shared by all workgroups, so they come straight
-//     from L2 in operand layout: lane (m, kg) reads 64 contiguous bytes of row m per block.
-//     Within a block, MFMA step s contracts the k values {32*kg + 8*s + j}; A and B use the
-//     same assignment, which is all the contraction needs.
+//     reads them back as B operands.  A register ring keeps the next 8 blocks' loads in
+//     flight while the current one is multiplied (registers -> LDS double buffer, one
+//     barrier per block).
+//   * the activations are small (M x K), shared by all workgroups and served by L2: each wave
+//     fetches its 16 rows x 256 bytes per block with the same row-piece loads and turns them
+//     into operand layout through a wave-private LDS tile (no barrier: one wave writes and
+//     reads it).  Within a block, MFMA step s contracts the k values {32*kg + 8*s + j}; A and
+//     B use the same assignment, which is all the contraction needs.
 //   * wave w owns rows [16*MT*w, 16*MT*(w+1)) of the output tile (MT = 1, 2 or 4 for M up to
 //     64, 128, 256) and both 16-column halves of the 32 neurons: 2*MT accumulators.
 // The gather costs nothing extra: a row index only changes the base address of a contiguous
@@ -35,12 +37,19 @@ constexpr int kGemmThreads = 256;
 constexpr int kTileN = 32;                       // selected neurons per workgroup
 constexpr int kBlockK = 128;                     // K values per step (256 bytes of a row)
 constexpr int kRowBytes = kBlockK * 2 + 16;      // padded LDS row: 16-lane reads hit 64 banks
+#ifndef POLAR_GEMM_RING
+#define POLAR_GEMM_RING 8
+#endif
+constexpr int kRingW = POLAR_GEMM_RING;          // K blocks of weights in flight per workgroup (even)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// 16 bytes as a native vector (not HIP's uint4 struct: arrays of the struct are copied with
+// memcpy, which keeps the register rings below from being promoted out of scratch memory)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <bool BF> __device__ __forceinline__ f32x4 mfma16x16x32(const uint4 &a, const uint4 &b, f32x4 c)
+template <bool BF> __device__ __forceinline__ f32x4 mfma16x16x32(const u32x4 &a, const u32x4 &b, f32x4 c)
 {
     if (BF)
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
@@ -59,6 +68,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
     int relu)
 {
     __shared__ __align__(16) unsigned char sh_w[2][kTileN * kRowBytes];
+    __shared__ __align__(16) unsigned char sh_a[kGemmThreads / 64][16 * kRowBytes];   // per wave
     __shared__ int sh_row[kTileN];               // weight row to stream, -1 for an invalid id
 
     int count = cap;
@@ -79,65 +89,141 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
     // global -> LDS assignment: 16 lanes per 256-byte row piece, two pieces per thread
     const int g_chunk = tid & 15, g_row = tid >> 4;                 // rows g_row and g_row + 16
     const int r0 = sh_row[g_row], r1 = sh_row[g_row + 16];
-    const uint4 *w0 = reinterpret_cast<const uint4 *>(W + (size_t)(r0 < 0 ? 0 : r0) * K) + g_chunk;
-    const uint4 *w1 = reinterpret_cast<const uint4 *>(W + (size_t)(r1 < 0 ? 0 : r1) * K) + g_chunk;
+    const u32x4 *w0 = reinterpret_cast<const u32x4 *>(W + (size_t)(r0 < 0 ? 0 : r0) * K) + g_chunk;
+    const u32x4 *w1 = reinterpret_cast<const u32x4 *>(W + (size_t)(r1 < 0 ? 0 : r1) * K) + g_chunk;
     const int lds_w0 = g_row * kRowBytes + g_chunk * 16, lds_w1 = lds_w0 + 16 * kRowBytes;
 
     // operand layout: lane (x = lane % 16, kg = lane / 16)
     const int x = lane & 15, kg = lane >> 4;
-    const uint4 *a_src[MT];
+    // Activations are fetched like cache rows (16 lanes per 256-byte row piece, 4 rows per
+    // wave-wide load: full cache lines per request) and turned into operand layout through a
+    // wave-private LDS tile; fetching them directly in operand layout (16 bytes from each of
+    // 16 rows per quarter-wave) made the L2 -> CU path the bottleneck at M >= 64.
+    const u32x4 *a_src[MT][4];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        int row = (wave * MT + t) * 16 + x;
-        row = row < M ? row : M - 1;
-        a_src[t] = reinterpret_cast<const uint4 *>(A + (size_t)row * K) + kg * 4;   // 64 bytes per block
-    }
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int row = (wave * MT + t) * 16 + 4 * u + kg;
+            row = row < M ? row : M - 1;
+            a_src[t][u] = reinterpret_cast<const u32x4 *>(A + (size_t)row * K) + x;   // chunk x of the block
+        }
+    unsigned char *a_tile = sh_a[wave];
+    const int lds_a_wr = kg * kRowBytes + x * 16;                   // + 4*u rows
+    const int lds_a_rd = x * kRowBytes + kg * 64;                   // + 16*s
     const int lds_b = x * kRowBytes + kg * 64;                      // + 16*s, + 16*kRowBytes for half 1
 
     f32x4 acc[MT][2];
 #pragma unroll
     for (int t = 0; t < MT; ++t) acc[t][0] = acc[t][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    const int nblk = K / kBlockK;
-    uint4 wq0 = w0[0], wq1 = w1[0];
-    uint4 a_cur[MT][4];
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) a_cur[t][s] = a_src[t][s];
+    // Register rings keep several K blocks in flight: kRingW blocks of this workgroup's weight
+    // rows (8 KiB each: what hides HBM latency when only one or two workgroups fit a compute
+    // unit's share of the grid) and RA blocks of activations (L2 latency).  The main loop is
+    // unrolled by the ring length so every ring slot is a fixed register, and its body has no
+    // branches: a slot is refilled kRingW blocks ahead with the block index clamped to the last
+    // block (the few repeated requests near the end hit in cache), which lets the compiler
+    // count outstanding loads instead of draining them at every join.
+    constexpr int RA = MT == 1 ? 4 : 2;
+    static_assert(kRingW % RA == 0 && kRingW % 2 == 0, "ring lengths");
+    const int nblk = K / kBlockK, last = nblk - 1;
 
-    for (int kb = 0; kb < nblk; ++kb) {
-        unsigned char *buf = sh_w[kb & 1];
-        *reinterpret_cast<uint4 *>(buf + lds_w0) = wq0;
-        *reinterpret_cast<uint4 *>(buf + lds_w1) = wq1;
+    // K blocks that do not fill a whole ring are done first, one at a time (plain loads, no
+    // ring); model widths are multiples of 1024, so this loop normally runs zero times.
+    const int head = nblk % kRingW;
+    for (int kb = 0; kb < head; ++kb) {
+        unsigned char *buf = sh_w[0];
+        const u32x4 h0 = w0[(size_t)kb * 16], h1 = w1[(size_t)kb * 16];
+        u32x4 ah[MT][4];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) ah[t][u] = a_src[t][u][(size_t)kb * 16];
+        __syncthreads();                                   // previous block's readers are done
+        *reinterpret_cast<u32x4 *>(buf + lds_w0) = h0;
+        *reinterpret_cast<u32x4 *>(buf + lds_w1) = h1;
         __syncthreads();
-
-        uint4 a_nxt[MT][4];
-        if (kb + 1 < nblk) {                       // next block's loads fly during the MFMAs
-            wq0 = w0[(size_t)(kb + 1) * 16];
-            wq1 = w1[(size_t)(kb + 1) * 16];
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+        for (int t = 0; t < MT; ++t) {
 #pragma unroll
-                for (int s = 0; s < 4; ++s) a_nxt[t][s] = a_src[t][(size_t)(kb + 1) * 16 + s];
-        }
-
+            for (int u = 0; u < 4; ++u)
+                *reinterpret_cast<u32x4 *>(a_tile + lds_a_wr + 4 * u * kRowBytes) = ah[t][u];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint4 b0 = *reinterpret_cast<const uint4 *>(buf + lds_b + 16 * s);
-            const uint4 b1 = *reinterpret_cast<const uint4 *>(buf + lds_b + 16 * kRowBytes + 16 * s);
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                acc[t][0] = mfma16x16x32<BF>(a_cur[t][s], b0, acc[t][0]);
-                acc[t][1] = mfma16x16x32<BF>(a_cur[t][s], b1, acc[t][1]);
+            for (int s = 0; s < 4; ++s) {
+                const u32x4 a = *reinterpret_cast<const u32x4 *>(a_tile + lds_a_rd + 16 * s);
+                const u32x4 b0 = *reinterpret_cast<const u32x4 *>(buf + lds_b + 16 * s);
+                const u32x4 b1 = *reinterpret_cast<const u32x4 *>(buf + lds_b + 16 * kRowBytes + 16 * s);
+                acc[t][0] = mfma16x16x32<BF>(a, b0, acc[t][0]);
+                acc[t][1] = mfma16x16x32<BF>(a, b1, acc[t][1]);
             }
         }
-        if (kb + 1 < nblk) {
+    }
+    if (head) __syncthreads();
+
+    if (head < nblk) {
+    u32x4 wq[kRingW][2];
+    u32x4 aq[RA][MT][4];
+    // Prologue: fill the rings in the order in which the steady-state loop leaves its loads
+    // pending at the top of an iteration (weight slots 0..R-RA, then activation slot i after
+    // weight slot R-RA+i), so that the compiler's count of outstanding loads at the loop
+    // header is the same on entry and on the back edge and nothing is drained there.
+#pragma unroll
+    for (int j = 0; j < kRingW; ++j) {
+        const size_t blk = (size_t)min(head + j, last) * 16;
+        wq[j][0] = w0[blk];
+        wq[j][1] = w1[blk];
+        if (j >= kRingW - RA) {
+            const int ja = j - (kRingW - RA);
+            const size_t ablk = (size_t)min(head + ja, last) * 16;
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int s = 0; s < 4; ++s) a_cur[t][s] = a_nxt[t][s];
+                for (int u = 0; u < 4; ++u) aq[ja][t][u] = a_src[t][u][ablk];
         }
+    }
+
+    // one K block: ring slot j (a compile-time constant after unrolling) holds block kb
+#define POLAR_GEMM_STEP(j, kb)                                                                     \
+    {                                                                                              \
+        unsigned char *buf = sh_w[(j) & 1]; /* ring starts are even, so kb & 1 == j & 1 */          \
+        *reinterpret_cast<u32x4 *>(buf + lds_w0) = wq[j][0];                                       \
+        *reinterpret_cast<u32x4 *>(buf + lds_w1) = wq[j][1];                                       \
+        __syncthreads();                                                                           \
+        const size_t nw = (size_t)min((kb) + kRingW, last) * 16;                                   \
+        wq[j][0] = w0[nw];                                                                         \
+        wq[j][1] = w1[nw];                                                                         \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
+        {                                                                                          \
+            _Pragma("unroll") for (int u = 0; u < 4; ++u)                                          \
+                *reinterpret_cast<u32x4 *>(a_tile + lds_a_wr + 4 * u * kRowBytes) =                \
+                    aq[(j) % RA][t][u];                                                            \
+            _Pragma("unroll") for (int s = 0; s < 4; ++s)                                          \
+            {                                                                                      \
+                const u32x4 a = *reinterpret_cast<const u32x4 *>(a_tile + lds_a_rd + 16 * s);      \
+                const u32x4 b0 = *reinterpret_cast<const u32x4 *>(buf + lds_b + 16 * s);           \
+                const u32x4 b1 =                                                                   \
+                    *reinterpret_cast<const u32x4 *>(buf + lds_b + 16 * kRowBytes + 16 * s);       \
+                acc[t][0] = mfma16x16x32<BF>(a, b0, acc[t][0]);                                    \
+                acc[t][1] = mfma16x16x32<BF>(a, b1, acc[t][1]);                                    \
+            }                                                                                      \
+        }                                                                                          \
+        const size_t na = (size_t)min((kb) + RA, last) * 16;                                       \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
+            _Pragma("unroll") for (int u = 0; u < 4; ++u) aq[(j) % RA][t][u] = a_src[t][u][na];    \
+    }
+
+    static_assert(kRingW == 8, "the ring loop below is written out for 8 slots");
+    for (int kb0 = head; kb0 < nblk; kb0 += kRingW) {      // nblk - head is a multiple of the ring
+        POLAR_GEMM_STEP(0, kb0 + 0)
+        POLAR_GEMM_STEP(1, kb0 + 1)
+        POLAR_GEMM_STEP(2, kb0 + 2)
+        POLAR_GEMM_STEP(3, kb0 + 3)
+        POLAR_GEMM_STEP(4, kb0 + 4)
+        POLAR_GEMM_STEP(5, kb0 + 5)
+        POLAR_GEMM_STEP(6, kb0 + 6)
+        POLAR_GEMM_STEP(7, kb0 + 7)
+    }
+#undef POLAR_GEMM_STEP
     }
 
     // accumulator layout: lane holds rows 4*kg + i (i = 0..3) of column x

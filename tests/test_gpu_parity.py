@@ -314,7 +314,7 @@ def test_head_importance_labels(name):
 
 
 # ----------------------------------------------------------------------------- selective GEMM
-GEMM_TOL = 1e-3      # float accumulation of K <= 9216 products of O(1) x O(1/sqrt(K)) terms
+GEMM_TOL = 1e-4      # float accumulation of K <= 9216 products whose sum is O(1): ~sqrt(K) * 2^-24 * |sum| ~ 1e-5
 
 
 def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0):
