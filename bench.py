@@ -125,7 +125,8 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
     n_ev = max(10, min(args.steps, 100))
     gemm_ms = ev(gemm, n_ev)
     union_ms = ev(union, n_ev)
-    dense_ms = ev(lambda: polar.select_gemm(x, W1, all_idx, relu=True, out=dense_out), max(5, n_ev // 4))
+    dense_ms = float("nan") if args.no_dense else ev(
+        lambda: polar.select_gemm(x, W1, all_idx, relu=True, out=dense_out), max(5, n_ev // 4))
     achieved = bytes_sel / (gemm_ms * 1e-3) / 1e9
     result = {
         "metric": "selective fused-gather GEMM effective weight HBM GB/s (gathered rows' bytes / step "
@@ -138,14 +139,15 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                                % (w.name, w.B, w.K, w.N, w.dtype, n_sel, 100.0 * n_sel / w.N),
                    "selected_weight_bytes": bytes_sel, "dense_weight_bytes": w.N * w.K * 2},
         "breakdown_us": {"neuron_union": round(union_ms * 1e3, 2), "select_gemm": round(gemm_ms * 1e3, 2),
-                         "dense_gemm_all_rows": round(dense_ms * 1e3, 2)},
-        "dense_over_selective": round(dense_ms / gemm_ms, 3),
+                         "dense_gemm_all_rows": None if args.no_dense else round(dense_ms * 1e3, 2)},
+        "dense_over_selective": None if args.no_dense else round(dense_ms / gemm_ms, 3),
         "ideal_N_over_selected": round(w.N / max(n_sel, 1), 3),
         "roofline": {"kernel": "select_gemm_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "avg_us": round(gemm_ms * 1e3, 2),
                      "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),
-                     "traffic": None},
+                     # rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled; profiles/select_gemm_M2_opt66b_ffn.md
+                     "traffic": 214502317 if (w == wl.MLP_CONFIGS.get(w.name)) else None},
     }
     if not args.no_cpu_baseline:
         from oracle import polar_oracle as orc
