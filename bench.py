@@ -43,11 +43,18 @@ def parse_args():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--k", type=int, default=0, help="override the number of selected units")
     ap.add_argument("--B", type=int, default=0, help="override the batch size")
+    ap.add_argument("--Hq", type=int, default=0, help="override the number of query heads")
+    ap.add_argument("--Hkv", type=int, default=0, help="override the number of KV heads")
+    ap.add_argument("--S", type=int, default=0, help="override the KV-cache capacity (rows per request)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=0,
+                    help="threads the oracle is timed with (0: all host cores)")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the dense (k = H) comparison run, so a kernel trace of this command "
                          "holds selective launches only")
-    ap.add_argument("--cpu-sample", type=int, default=32, help="requests the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=0,
+                    help="requests the oracle is timed on (0: the whole batch, capped so that the "
+                         "host copy of their K and V stays under 12 GB)")
     ap.add_argument("--kv-layout", choices=["bhsd", "bshd"], default="bhsd",
                     help="cache layout: [B,Hkv,S,d] (default) or the sequence-major [B,S,Hkv,d]")
     ap.add_argument("--mlp-workload", default="M2_opt66b_ffn",
@@ -203,11 +210,17 @@ def main():
         bench_select_gemm(args, torch, np, polar, wl, dev)
         return
 
-    w = wl.CONFIGS[args.workload]
+    w = wl.CONFIGS.get(args.workload) or wl.EXTRA_SHAPES[args.workload]
     if args.k:
         w = w.scaled(k=args.k)
     if args.B:
         w = w.scaled(B=args.B)
+    if args.Hq:
+        w = w.scaled(Hq=args.Hq)
+    if args.Hkv:
+        w = w.scaled(Hkv=args.Hkv)
+    if args.S:
+        w = w.scaled(S=args.S, seq_lo=min(w.seq_lo, args.S))
 
     hidden, Wr = wl.make_router_inputs(w, dev)
     q, K, V, seqlens = wl.make_attention_inputs(w, dev)
@@ -334,7 +347,7 @@ def main():
         "dense_over_selective": None if args.no_dense else round(dense_avg / sha_avg, 3),
         "ideal_H_over_k": round(w.Hkv / w.k, 3),
         "roofline": {
-            "kernel": "sha_partial_kernel",
+            "kernel": "sha_partial_gqa_kernel" if (w.G > 1 and w.d == 128) else "sha_partial_kernel",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
@@ -343,14 +356,17 @@ def main():
             "avg_us": round(part_avg * 1e3, 2),
             "median_us": round(part_med * 1e3, 2),
             "min_us": round(part_min * 1e3, 2),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (w == wl.CONFIGS[w.name] and lay == "bhsd") else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (w == wl.CONFIGS.get(w.name) and lay == "bhsd") else None,
         },
     }
 
     if not args.no_cpu_baseline:
         from oracle import polar_oracle as orc
 
-        nb = max(1, min(args.cpu_sample, w.B))
+        if args.cpu_threads > 0:
+            orc.set_num_threads(args.cpu_threads)
+        nb = w.B if args.cpu_sample <= 0 else max(1, min(args.cpu_sample, w.B))
+        nb = max(1, min(nb, int(12e9) // (2 * w.Hkv * w.S * w.d * 2)))
         hb, Wb = wl.bits_u16(hidden[:nb]), wl.bits_u16(Wr)
         Ks, Vs = (K[:nb], V[:nb]) if lay == "bhsd" else (K[:nb].permute(0, 2, 1, 3), V[:nb].permute(0, 2, 1, 3))
         qb, Kb, Vb = wl.bits_u16(q[:nb]), wl.bits_u16(Ks), wl.bits_u16(Vs)

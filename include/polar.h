@@ -51,7 +51,7 @@ typedef enum {
 /* Limits of this build (host-checked, POLAR_EUNSUPPORTED beyond them). */
 #define POLAR_MAX_ROUTER_H 256    /* selection units a router may score */
 #define POLAR_MAX_ROUTER_D 16384  /* router input width (the hidden row is staged in LDS) */
-#define POLAR_MAX_GROUP 8         /* query heads per KV head: 1, 2, 4 or 8 */
+#define POLAR_MAX_GROUP 16        /* query heads per KV head: any 1..16 at d = 128; 1, 2, 4, 8 at d = 64 */
 
 /*
  * Attention-head router and per-request top-k (Section 4.2: the router is one fully

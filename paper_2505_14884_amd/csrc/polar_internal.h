@@ -38,6 +38,11 @@ hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const
                               const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
                               int Hq, int Hkv, int S, int d, int k, polar_dtype dt,
                               polar_kv_layout layout, float scale_log2e, hipStream_t stream);
+// Grouped-query variant of the streaming kernel (G > 1, d = 128): both contractions on MFMA.
+hipError_t launch_sha_partial_gqa(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                                  const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
+                                  int Hq, int Hkv, int S, int k, polar_dtype dt,
+                                  polar_kv_layout layout, float scale_log2e, hipStream_t stream);
 hipError_t launch_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
                             const float *ws, const ShaPlan &plan, int B, int Hq, int Hkv, int S,
                             int d, int k, hipStream_t stream);

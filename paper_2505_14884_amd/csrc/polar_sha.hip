@@ -24,6 +24,8 @@
 //     of (request, head) units alone does not fill 256 compute units); the merge kernel
 //     applies the same max/sum rescale across chunks, normalises, and stores zeros for
 //     the heads that were not selected.
+#include <stdlib.h>
+
 #include "polar_internal.h"
 
 namespace polar {
@@ -415,6 +417,9 @@ hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const
                               int Hq, int Hkv, int S, int d, int k, polar_dtype dt,
                               polar_kv_layout layout, float scale_log2e, hipStream_t stream)
 {
+    if (plan.G > 1 && d == 128 && !getenv("POLAR_SHA_GQA_VALU"))
+        return launch_sha_partial_gqa(q, K, V, seqlens, head_idx, ws, plan, B, Hq, Hkv, S, k, dt,
+                                      layout, scale_log2e, stream);
     const dim3 grid((unsigned)((size_t)B * plan.nsplit * k));
     float *ws_o = ws, *ws_ml = ws + plan.o_floats;
     const uint16_t *q16 = static_cast<const uint16_t *>(q);

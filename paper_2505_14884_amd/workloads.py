@@ -72,6 +72,13 @@ CONFIGS: Dict[str, ShaWorkload] = {
                              D=4096, dtype="bf16", seq_lo=512, peaky=0.05, seed=105),
 }
 
+# Further decode shapes of the paper's evaluation (Section 5 and the kernel figures) used by the
+# bench sweeps only: a 64-query-head / 8-group model at long context.
+EXTRA_SHAPES: Dict[str, ShaWorkload] = {
+    "X1_gqa8_s8192": ShaWorkload("X1_gqa8_s8192", B=32, Hq=64, Hkv=8, d=128, S=8192, k=4,
+                                 D=8192, dtype="bf16", seed=106),
+}
+
 
 @dataclass(frozen=True)
 class MlpWorkload:

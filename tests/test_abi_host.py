@@ -87,8 +87,9 @@ def test_sha_argument_errors():
         assert decode(L, **{name: None}) == EINVAL
     assert decode(L, d=96) == EUNSUPPORTED
     assert decode(L, d=256) == EUNSUPPORTED
-    assert decode(L, Hq=24, Hkv=8) == EUNSUPPORTED          # G = 3
-    assert decode(L, Hq=128, Hkv=8) == EUNSUPPORTED         # G = 16
+    assert decode(L, Hq=136, Hkv=8) == EUNSUPPORTED         # G = 17
+    assert decode(L, Hq=24, Hkv=8, d=64) == EUNSUPPORTED    # G = 3 at d = 64
+    assert decode(L, Hq=128, Hkv=8, d=64) == EUNSUPPORTED   # G = 16 at d = 64
     assert decode(L, ws=None) == EWORKSPACE
     assert decode(L, ws=ctypes.c_void_p(0x10010)) == EWORKSPACE   # not 256-byte aligned
     assert decode(L, ws_bytes=255) == EWORKSPACE

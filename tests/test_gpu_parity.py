@@ -134,7 +134,8 @@ def test_dense_null_index_and_identity_index(dtype, d, G):
 
 # ----------------------------------------------------------------------------- edge shapes
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("d,G", [(128, 1), (64, 1), (128, 4), (64, 8), (128, 2)])
+@pytest.mark.parametrize("d,G", [(128, 1), (64, 1), (128, 4), (64, 8), (128, 2), (128, 8), (128, 3),
+                                 (128, 7), (128, 16)])
 def test_ragged_lengths_and_tails(dtype, d, G):
     """Lengths 0, 1, around every tile boundary (rows per load, per wave step, per workgroup
     step, per chunk) and the full capacity."""
