@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # (each scaled by the same counter's reading for a plain 4 GiB copy); measured with this file's
 # --phase partial / --phase copy on the default shape of each workload.  Source:
 # profiles/sha_decode_step_<workload>.md.  Reported only when the shape is that default.
-MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4533957188, "C5_ragged": 4480271133,
-                          "C3_llama3_8b_gqa": 539715568, "C2_llama2_7b": 504125492}
+MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4534002381, "C5_ragged": 4480318976,
+                          "C3_llama3_8b_gqa": 540179661, "C2_llama2_7b": 504130355}
 DEFAULT_WORKLOAD = "C4_opt66b"
 
 
@@ -154,7 +154,7 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                      "avg_us": round(gemm_ms * 1e3, 2),
                      "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),
                      # rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled; profiles/select_gemm_M2_opt66b_ffn.md
-                     "traffic": 214502317 if (w == wl.MLP_CONFIGS.get(w.name)) else None},
+                     "traffic": 214354185 if (w == wl.MLP_CONFIGS.get(w.name)) else None},
     }
     if not args.no_cpu_baseline:
         from oracle import polar_oracle as orc
@@ -238,7 +238,12 @@ def main():
 
     head_idx = torch.empty((w.B, w.k), dtype=torch.int32, device=dev)
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
-    ws = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.Hkv, dev)   # sized for dense too
+    # one workspace for the selective and the dense call: the chunking depends on k, so neither
+    # requirement bounds the other
+    ws_sel = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.k, dev)
+    ws_dense = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.Hkv, dev)
+    ws = ws_sel if ws_sel.numel() >= ws_dense.numel() else ws_dense
+    del ws_sel, ws_dense
     rws = polar.alloc_router_workspace(w.B, w.D, w.Hkv, dev)
     chunk = polar.sha_chunk_rows(w.B, w.Hq, w.Hkv, w.S, w.d, w.k)
 

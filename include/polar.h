@@ -119,7 +119,8 @@ size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k);
  *   workspace     at least polar_sha_workspace_bytes(...) bytes, 256-byte aligned.
  *
  * Scores, softmax statistics and the output are accumulated in float.  A request with
- * n_b == 0 gets zeros.  Supported: d in {64, 128}; G in {1, 2, 4, 8}; 1 <= k <= Hkv.
+ * n_b == 0 gets zeros.  Supported: d in {64, 128}; G = Hq / Hkv in 1..16 at d = 128, in {1, 2, 4, 8} at d = 64;
+ * 1 <= k <= Hkv.
  */
 int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t *seqlens,
                      const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,

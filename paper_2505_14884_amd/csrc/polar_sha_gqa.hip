@@ -40,7 +40,11 @@ namespace polar {
 namespace {
 
 constexpr int kD = 128;                 // head dimension this kernel is written for
+#if defined(POLAR_GQA_WAVES)
+constexpr int kGqaWaves = POLAR_GQA_WAVES;   // build-time override for sweeps
+#else
 constexpr int kGqaWaves = 4;            // waves per workgroup
+#endif
 constexpr int kBlockRows = 32;          // cache rows one wave consumes per iteration
 constexpr int kTilePitch = 2 * kD + 16; // bytes between rows of a wave's K tile in LDS: the 16
                                         // lanes of an operand read then fall in distinct banks
