@@ -72,8 +72,10 @@ typedef enum {
  *   workspace  nullable.  NULL: one workgroup per request does the whole row (no scratch
  *                   needed; at most B compute units busy).  Otherwise at least
  *                   polar_router_workspace_bytes(B, D, H) bytes, 256-byte aligned, contents
- *                   need no initialisation: the D axis is split over many workgroups that
- *                   leave partial sums there and a second small kernel adds and ranks them.
+ *                   need no initialisation: the library may then split the D axis over many
+ *                   workgroups that leave partial sums there, with a second small kernel adding
+ *                   and ranking them; it does so when that is the faster path for the shape
+ *                   (small batches of wide routers) and otherwise runs the one-kernel path.
  *
  * Products are exact and the sum over D is accumulated in double precision in a fixed,
  * column-independent order (a different fixed order with and without a workspace), so
@@ -119,8 +121,13 @@ size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k);
  *   workspace     at least polar_sha_workspace_bytes(...) bytes, 256-byte aligned.
  *
  * Scores, softmax statistics and the output are accumulated in float.  A request with
- * n_b == 0 gets zeros.  Supported: d in {64, 128}; G = Hq / Hkv in 1..16 at d = 128, in {1, 2, 4, 8} at d = 64;
- * 1 <= k <= Hkv.
+ * n_b == 0 gets zeros.  Supported: d in {64, 128}; G = Hq / Hkv in 1..16 at d = 128, in
+ * {1, 2, 4, 8} at d = 64; 1 <= k <= Hkv.
+ *
+ * Launches: when the sizes lead to an unsplit cache (polar_sha_chunk_rows(...) >= S) one
+ * kernel streams the rows, normalises, stores `out` and zero-fills the unselected heads, and
+ * the workspace is left untouched; otherwise the streaming kernel leaves per-chunk records in
+ * the workspace and a second small kernel combines them.  Both forms give the same bits.
  */
 int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t *seqlens,
                      const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
@@ -140,8 +147,9 @@ int polar_sha_decode_layout(const void *q, const void *K, const void *V, const i
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * The two phases of polar_sha_decode as separate launches, with the same arguments and
- * checks (polar_sha_decode is exactly partial followed by merge on one stream).  They
+ * The two phases of the split form of polar_sha_decode as separate launches, with the same
+ * arguments and checks (partial followed by merge on one stream gives polar_sha_decode's
+ * result bit for bit, also where polar_sha_decode itself takes its one-kernel form).  They
  * exist so a harness can time the KV-streaming phase by itself.
  *   polar_sha_partial: streams K/V of the selected heads in chunks of rows and leaves a
  *     running (max, sum, unnormalised output) per chunk in the workspace (Algorithm 1's

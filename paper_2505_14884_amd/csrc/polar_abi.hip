@@ -25,14 +25,20 @@ bool dtype_ok(polar_dtype dt) { return dt == POLAR_F16 || dt == POLAR_BF16; }
 // record for the merge kernel, so chunks are as large as two things allow: occupancy (enough
 // splits that the grid holds about kFillWorkgroups workgroups) and the tail of the grid (a
 // lone workgroup streams far below the chip's bandwidth, so the work one workgroup carries is
-// capped at kMaxChunk rows).  A cache of at most 2*kMaxChunk rows is not split at all when
-// the (request, head) units alone fill the chip.  Always a multiple of 128 rows, which every
-// kernel shape's per-wave step (16 to 64 rows) divides, so only a request's last chunk has a
-// ragged tail.  POLAR_SHA_CHUNK_ROWS overrides the choice for tuning sweeps.
+// capped at kMaxChunk rows).  A cache of at most 2*kMaxChunk rows is not split at all once the
+// (request, head) units alone give every compute unit a workgroup (kUnsplitUnits) and fill whole
+// rounds of compute units to at least 90 %: an unsplit
+// cache needs no merge kernel and no workspace traffic, which outweighs the lower occupancy
+// (LLaMA-2-7B-shaped layer, 512 units: 93.1 -> 87.7 us per step; LLaMA-3-8B GQA layer, 256
+// units: 96.6 -> 92.3 us).  Always a multiple of 128 rows, which every kernel shape's per-wave
+// step (16 to 64 rows) divides, so only a request's last chunk has a ragged tail.
+// POLAR_SHA_CHUNK_ROWS overrides the choice for tuning sweeps.
 // The grouped-query kernel holds only two 4-wave workgroups per compute unit (its two register
 // stages are large), so a workgroup in its prologue or epilogue idles a bigger share of the
 // unit; its cap is 4 times higher (76 % -> 83 % of peak on a 64/8-head, 8192-row shape).
 constexpr long kFillWorkgroups = 1024;
+constexpr long kComputeUnits = 256;
+constexpr long kUnsplitUnits = kComputeUnits;
 constexpr int kMaxChunkPerHead = 1024;
 constexpr int kMaxChunkGrouped = 4096;
 constexpr int kMinChunk = 256;
@@ -48,11 +54,38 @@ int choose_chunk(int B, int k, int S, int kMaxChunk)
         const long units = (long)(B > 0 ? B : 1) * k;
         const long want_splits = (kFillWorkgroups + units - 1) / units;
         chunk = (S + want_splits - 1) / want_splits;
-        if (chunk > kMaxChunk && !(want_splits == 1 && S <= 2 * kMaxChunk)) chunk = kMaxChunk;
+        // one workgroup per unit keeps the compute units evenly loaded only if the units fill
+        // whole rounds of them (320 units on 256 compute units: 134 us unsplit, 117 us split)
+        const long rounds = (units + kComputeUnits - 1) / kComputeUnits;
+        const bool even = units * 10 >= rounds * kComputeUnits * 9;
+        if (units >= kUnsplitUnits && even && S <= 2 * kMaxChunk) chunk = S;
+        else if (chunk > kMaxChunk) chunk = kMaxChunk;
         if (chunk < kMinChunk) chunk = kMinChunk;
     }
     chunk = (chunk + 127) / 128 * 128;
     return chunk < cap ? (int)chunk : cap;
+}
+
+// Which router path is faster when the caller offers a workspace.  The one-workgroup-per-request
+// kernel is a single launch whose time depends on D*H only while B fits the chip (256 compute
+// units); the split-D pair spreads small batches over the whole chip but pays a second launch.
+// Both estimates are fits to event timings on MI355X over B = 1..1024, D*H = 32 K..2 M
+// (microseconds): single = max(7.5, 5.2 + ceil(B/256) * D*H / 31e3), split = 10.5 + B*D*H / 8.5e6.
+// Examples: B=64, D=4096, H=8: 7.5 vs 11.0 measured (single); B=128, D=9216, H=72: 28.6 vs 24.6
+// (split); B=256, D=4096, H=32: 9.6 vs 14.2 (single).
+// POLAR_ROUTER_PATH=split|single overrides the choice (tests use it to reach both paths).
+bool router_split_pays(int B, int D, int H)
+{
+    if (const char *env = getenv("POLAR_ROUTER_PATH")) {
+        if (env[0] == 's' && env[1] == 'p') return true;
+        if (env[0] == 's' && env[1] == 'i') return false;
+    }
+    const double dh = (double)D * H;
+    const double rounds = (double)((B + 255) / 256);
+    double single_us = 5.2 + rounds * dh / 31.0e3;
+    if (single_us < 7.5) single_us = 7.5;
+    const double split_us = 10.5 + (double)B * dh / 8.5e6;
+    return split_us < single_us;
 }
 
 int check_sha_sizes(int B, int Hq, int Hkv, int S, int d, int k)
@@ -130,6 +163,9 @@ int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, i
         return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
                                          static_cast<hipStream_t>(stream)));
     if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < plan.bytes) return POLAR_EWORKSPACE;
+    if (!router_split_pays(B, D, H))
+        return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
+                                         static_cast<hipStream_t>(stream)));
     return record(launch_router_split(hidden, Wr, B, D, H, k, dt, plan, head_idx, logits_out,
                                       workspace, static_cast<hipStream_t>(stream)));
 }
@@ -155,10 +191,11 @@ static int check_workspace(const ShaPlan &plan, const void *workspace, size_t wo
     return POLAR_OK;
 }
 
+// `direct_out` non-NULL asks for the one-kernel form (the caller has checked plan.nsplit == 1).
 static int sha_partial_impl(const void *q, const void *K, const void *V, const int32_t *seqlens,
-                            const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
-                            polar_dtype dt, polar_kv_layout layout, float scale, void *workspace,
-                            size_t workspace_bytes, void *stream)
+                            const int32_t *head_idx, float *direct_out, int B, int Hq, int Hkv, int S,
+                            int d, int k, polar_dtype dt, polar_kv_layout layout, float scale,
+                            void *workspace, size_t workspace_bytes, void *stream)
 {
     ShaPlan plan;
     int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);
@@ -172,7 +209,7 @@ static int sha_partial_impl(const void *q, const void *K, const void *V, const i
     const float s = scale == 0.0f ? 1.0f / sqrtf((float)d) : scale;
     const float log2e = 1.4426950408889634f;
     return record(launch_sha_partial(q, K, V, seqlens, head_idx, static_cast<float *>(workspace),
-                                     plan, B, Hq, Hkv, S, d, k, dt, layout, s * log2e,
+                                     direct_out, plan, B, Hq, Hkv, S, d, k, dt, layout, s * log2e,
                                      static_cast<hipStream_t>(stream)));
 }
 
@@ -181,8 +218,8 @@ int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t
                       polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
                       void *stream)
 {
-    return sha_partial_impl(q, K, V, seqlens, head_idx, B, Hq, Hkv, S, d, k, dt, POLAR_KV_BHSD, scale,
-                            workspace, workspace_bytes, stream);
+    return sha_partial_impl(q, K, V, seqlens, head_idx, nullptr, B, Hq, Hkv, S, d, k, dt, POLAR_KV_BHSD,
+                            scale, workspace, workspace_bytes, stream);
 }
 
 int polar_sha_partial_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
@@ -190,7 +227,7 @@ int polar_sha_partial_layout(const void *q, const void *K, const void *V, const 
                              polar_dtype dt, polar_kv_layout layout, float scale, void *workspace,
                              size_t workspace_bytes, void *stream)
 {
-    return sha_partial_impl(q, K, V, seqlens, head_idx, B, Hq, Hkv, S, d, k, dt, layout, scale,
+    return sha_partial_impl(q, K, V, seqlens, head_idx, nullptr, B, Hq, Hkv, S, d, k, dt, layout, scale,
                             workspace, workspace_bytes, stream);
 }
 
@@ -218,9 +255,13 @@ int polar_sha_decode_layout(const void *q, const void *K, const void *V, const i
     int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);   // size errors take precedence
     if (rc != POLAR_OK) return rc;
     if (B > 0 && !out) return POLAR_EINVAL;
-    rc = sha_partial_impl(q, K, V, seqlens, head_idx, B, Hq, Hkv, S, d, k, dt, layout, scale,
-                          workspace, workspace_bytes, stream);
-    if (rc != POLAR_OK) return rc;
+    // An unsplit cache needs no merge: the streaming kernel finishes the rows itself and
+    // zero-fills the unselected heads (POLAR_SHA_DIRECT=0 keeps the two-kernel form, for comparisons).
+    const char *env = getenv("POLAR_SHA_DIRECT");
+    const bool direct = plan.nsplit == 1 && !(env && env[0] == '0');
+    rc = sha_partial_impl(q, K, V, seqlens, head_idx, direct ? out : nullptr, B, Hq, Hkv, S, d, k, dt,
+                          layout, scale, workspace, workspace_bytes, stream);
+    if (rc != POLAR_OK || direct) return rc;
     return polar_sha_merge(seqlens, head_idx, out, B, Hq, Hkv, S, d, k, workspace, workspace_bytes,
                            stream);
 }

@@ -34,15 +34,21 @@ int make_router_plan(int B, int D, int H, RouterPlan *plan);
 
 // Kernel launchers.  Arguments were validated by the caller; each returns the hipError_t of
 // its launch.
+// `direct_out` non-NULL (allowed only when plan.nsplit == 1): the streaming kernel normalises and
+// writes the final output itself, and zero-fills the unselected heads, instead of leaving records
+// for the merge kernel; the workspace is then not touched.
 hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
-                              const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
-                              int Hq, int Hkv, int S, int d, int k, polar_dtype dt,
-                              polar_kv_layout layout, float scale_log2e, hipStream_t stream);
+                              const int32_t *head_idx, float *ws, float *direct_out,
+                              const ShaPlan &plan, int B, int Hq, int Hkv, int S, int d, int k,
+                              polar_dtype dt, polar_kv_layout layout, float scale_log2e,
+                              hipStream_t stream);
 // Grouped-query variant of the streaming kernel (G > 1, d = 128): both contractions on MFMA.
 hipError_t launch_sha_partial_gqa(const void *q, const void *K, const void *V, const int32_t *seqlens,
-                                  const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
-                                  int Hq, int Hkv, int S, int k, polar_dtype dt,
-                                  polar_kv_layout layout, float scale_log2e, hipStream_t stream);
+                                  const int32_t *head_idx, float *ws, float *direct_out,
+                                  const ShaPlan &plan, int B, int Hq, int Hkv, int S, int k,
+                                  polar_dtype dt, polar_kv_layout layout, float scale_log2e,
+                                  hipStream_t stream);
+
 hipError_t launch_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
                             const float *ws, const ShaPlan &plan, int B, int Hq, int Hkv, int S,
                             int d, int k, hipStream_t stream);
@@ -62,5 +68,35 @@ hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, 
 int neuron_union_max_n();
 hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                                int32_t *count_out, hipStream_t stream);
+
+#if defined(__HIPCC__)
+// Direct mode's zero fill, run by one wave of the workgroup of (request b, slot): that workgroup
+// owns the KV heads h = slot, slot + k, slot + 2k, ... and stores +0.0 to the G query heads of
+// every one of them that no entry of the request's head_idx row names (all of them when the
+// request is empty).  The k workgroups of a request cover every head exactly once, and a head
+// that some slot selected is written by that slot's workgroup, never here.  `id0` is the lane's
+// entry of the row (entry `lane`, or -1 beyond k), loaded by the caller together with its other
+// index loads; longer rows are re-read in 64-entry pieces.  Control flow is wave-uniform.
+__device__ __forceinline__ void direct_zero_fill(const int32_t *__restrict__ head_idx_row, int id0,
+                                                 bool any_selected, int slot, int k, int Hkv,
+                                                 int group_floats, float *__restrict__ out_request,
+                                                 int lane)
+{
+    for (int h = slot; h < Hkv; h += k) {
+        bool member = false;
+        if (any_selected) {
+            member = __builtin_amdgcn_ballot_w64(id0 == h) != 0;
+            for (int c = 64; c < k && !member; c += 64) {
+                const int id = (c + lane < k) ? head_idx_row[c + lane] : -1;
+                member = __builtin_amdgcn_ballot_w64(id == h) != 0;
+            }
+        }
+        if (!member) {
+            float4 *dst = reinterpret_cast<float4 *>(out_request + (size_t)h * group_floats);
+            for (int i = lane; i < group_floats / 4; i += 64) dst[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+}
+#endif
 
 }  // namespace polar

@@ -169,12 +169,15 @@ __device__ __forceinline__ void consume(const uint4 (&kr)[kLoads], const uint4 (
 // ROW_MAJOR_SEQ selects the cache layout: false = [B, Hkv, S, d] (a head's rows are contiguous),
 // true = [B, S, Hkv, d] (a row of one head is d contiguous values, consecutive rows of that
 // head are Hkv*d apart).
-template <class DT, int D, int G, bool ROW_MAJOR_SEQ>
+// DIRECT (only launched with nsplit == 1, where a workgroup sees all rows of its (request, slot)):
+// the epilogue divides by the sum and stores the final rows to `out`, and one wave of the
+// workgroup zero-fills this slot's share of the unselected heads, so no merge kernel runs.
+template <class DT, int D, int G, bool ROW_MAJOR_SEQ, bool DIRECT>
 __global__ __launch_bounds__(Shape<G>::kWaves * 64) void sha_partial_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int32_t *__restrict__ seqlens, const int32_t *__restrict__ head_idx,
-    float *__restrict__ ws_o, float *__restrict__ ws_ml, int Hq, int Hkv, int S, int k, int chunk,
-    int nsplit, float c)
+    float *__restrict__ ws_o, float *__restrict__ ws_ml, float *__restrict__ out, int Hq, int Hkv,
+    int S, int k, int chunk, int nsplit, float c)
 {
     constexpr int kWaves = Shape<G>::kWaves, kLoads = Shape<G>::kLoads;
     constexpr int LPR = D / 8;             // lanes per row
@@ -188,13 +191,24 @@ __global__ __launch_bounds__(Shape<G>::kWaves * 64) void sha_partial_kernel(
     // both index loads are issued before either is tested: one round trip instead of two
     int n = seqlens[b];
     const int g_kv = head_idx ? head_idx[(size_t)b * k + slot] : slot;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int id0 = -1;
+    if (DIRECT && head_idx && wave == kWaves - 1 && lane < k) id0 = head_idx[(size_t)b * k + lane];
     n = n < 0 ? 0 : (n > S ? S : n);
+    // The zero fill is left to the last wave, after the workgroup's barrier, while the first
+    // waves finish the output rows (its index loads are issued here, with the others): any
+    // earlier and the whole workgroup would wait for it.
+#define POLAR_DIRECT_ZERO_FILL()                                                                   \
+    if (DIRECT && wave == kWaves - 1 && (head_idx || n == 0))                                      \
+        direct_zero_fill(head_idx ? head_idx + (size_t)b * k : nullptr, id0, head_idx && n > 0,    \
+                         slot, k, Hkv, G * D, out + (size_t)b * Hq * D, lane)
     const int row_begin = split * chunk;
-    if (row_begin >= n) return;
-    if ((unsigned)g_kv >= (unsigned)Hkv) return;
+    if (row_begin >= n || (unsigned)g_kv >= (unsigned)Hkv) {
+        POLAR_DIRECT_ZERO_FILL();
+        return;
+    }
     const int row_end = min(row_begin + chunk, n);
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane / LPR, cl = lane % LPR;
 
     // first row of this (request, head), and the distance between its rows in 16-byte units
@@ -280,6 +294,9 @@ __global__ __launch_bounds__(Shape<G>::kWaves * 64) void sha_partial_kernel(
         }
     }
     __syncthreads();
+    static_assert(D <= (kWaves - 1) * 64, "the last wave must be free of the final merge");
+    POLAR_DIRECT_ZERO_FILL();
+#undef POLAR_DIRECT_ZERO_FILL
 
     // Merge the waves: thread t owns output column t of every query head of the group.
     const int t = threadIdx.x;
@@ -296,11 +313,15 @@ __global__ __launch_bounds__(Shape<G>::kWaves * 64) void sha_partial_kernel(
                 acc = fmaf(a, sm_o[w][g][t], acc);
                 lsum = fmaf(a, sm_ml[w][g][1], lsum);
             }
-            const size_t unit = (((size_t)b * k + slot) * G + g) * nsplit + split;
-            ws_o[unit * D + t] = acc;
-            if (t == 0) {
-                ws_ml[unit * 2 + 0] = mx;
-                ws_ml[unit * 2 + 1] = lsum;
+            if (DIRECT) {
+                out[((size_t)b * Hq + (size_t)g_kv * G + g) * D + t] = lsum > 0.0f ? acc / lsum : 0.0f;
+            } else {
+                const size_t unit = (((size_t)b * k + slot) * G + g) * nsplit + split;
+                ws_o[unit * D + t] = acc;
+                if (t == 0) {
+                    ws_ml[unit * 2 + 0] = mx;
+                    ws_ml[unit * 2 + 1] = lsum;
+                }
             }
         }
     }
@@ -379,12 +400,18 @@ __global__ __launch_bounds__(kMergeThreads) void sha_merge_kernel(
 template <class DT, int D, bool RMS>
 hipError_t launch_partial_g(int G, dim3 grid, hipStream_t st, const uint16_t *q, const uint16_t *K,
                             const uint16_t *V, const int32_t *seqlens, const int32_t *head_idx,
-                            float *ws_o, float *ws_ml, int Hq, int Hkv, int S, int k, int chunk,
-                            int nsplit, float c)
+                            float *ws_o, float *ws_ml, float *out, int Hq, int Hkv, int S, int k,
+                            int chunk, int nsplit, float c)
 {
 #define POLAR_LAUNCH(GG)                                                                          \
-    hipLaunchKernelGGL((sha_partial_kernel<DT, D, GG, RMS>), grid, dim3(Shape<GG>::kWaves * 64), 0, \
-                       st, q, K, V, seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, chunk, nsplit, c)
+    if (out)                                                                                      \
+        hipLaunchKernelGGL((sha_partial_kernel<DT, D, GG, RMS, true>), grid,                      \
+                           dim3(Shape<GG>::kWaves * 64), 0, st, q, K, V, seqlens, head_idx, ws_o, \
+                           ws_ml, out, Hq, Hkv, S, k, chunk, nsplit, c);                          \
+    else                                                                                          \
+        hipLaunchKernelGGL((sha_partial_kernel<DT, D, GG, RMS, false>), grid,                     \
+                           dim3(Shape<GG>::kWaves * 64), 0, st, q, K, V, seqlens, head_idx, ws_o, \
+                           ws_ml, out, Hq, Hkv, S, k, chunk, nsplit, c)
     switch (G) {
     case 1: POLAR_LAUNCH(1); break;
     case 2: POLAR_LAUNCH(2); break;
@@ -400,33 +427,35 @@ template <class DT, int D>
 hipError_t launch_partial_layout(polar_kv_layout layout, int G, dim3 grid, hipStream_t st,
                                  const uint16_t *q, const uint16_t *K, const uint16_t *V,
                                  const int32_t *seqlens, const int32_t *head_idx, float *ws_o,
-                                 float *ws_ml, int Hq, int Hkv, int S, int k, int chunk, int nsplit,
-                                 float c)
+                                 float *ws_ml, float *out, int Hq, int Hkv, int S, int k, int chunk,
+                                 int nsplit, float c)
 {
     if (layout == POLAR_KV_BSHD)
-        return launch_partial_g<DT, D, true>(G, grid, st, q, K, V, seqlens, head_idx, ws_o, ws_ml, Hq,
-                                             Hkv, S, k, chunk, nsplit, c);
-    return launch_partial_g<DT, D, false>(G, grid, st, q, K, V, seqlens, head_idx, ws_o, ws_ml, Hq,
-                                          Hkv, S, k, chunk, nsplit, c);
+        return launch_partial_g<DT, D, true>(G, grid, st, q, K, V, seqlens, head_idx, ws_o, ws_ml, out,
+                                             Hq, Hkv, S, k, chunk, nsplit, c);
+    return launch_partial_g<DT, D, false>(G, grid, st, q, K, V, seqlens, head_idx, ws_o, ws_ml, out,
+                                          Hq, Hkv, S, k, chunk, nsplit, c);
 }
 
 }  // namespace
 
 hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
-                              const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
-                              int Hq, int Hkv, int S, int d, int k, polar_dtype dt,
-                              polar_kv_layout layout, float scale_log2e, hipStream_t stream)
+                              const int32_t *head_idx, float *ws, float *direct_out,
+                              const ShaPlan &plan, int B, int Hq, int Hkv, int S, int d, int k,
+                              polar_dtype dt, polar_kv_layout layout, float scale_log2e,
+                              hipStream_t stream)
 {
+    if (direct_out && plan.nsplit != 1) return hipErrorInvalidValue;
     if (plan.G > 1 && d == 128 && !getenv("POLAR_SHA_GQA_VALU"))
-        return launch_sha_partial_gqa(q, K, V, seqlens, head_idx, ws, plan, B, Hq, Hkv, S, k, dt,
-                                      layout, scale_log2e, stream);
+        return launch_sha_partial_gqa(q, K, V, seqlens, head_idx, ws, direct_out, plan, B, Hq, Hkv, S,
+                                      k, dt, layout, scale_log2e, stream);
     const dim3 grid((unsigned)((size_t)B * plan.nsplit * k));
     float *ws_o = ws, *ws_ml = ws + plan.o_floats;
     const uint16_t *q16 = static_cast<const uint16_t *>(q);
     const uint16_t *K16 = static_cast<const uint16_t *>(K);
     const uint16_t *V16 = static_cast<const uint16_t *>(V);
-#define POLAR_ARGS layout, plan.G, grid, stream, q16, K16, V16, seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, \
-                   plan.chunk, plan.nsplit, scale_log2e
+#define POLAR_ARGS layout, plan.G, grid, stream, q16, K16, V16, seqlens, head_idx, ws_o, ws_ml, direct_out, Hq, \
+                   Hkv, S, k, plan.chunk, plan.nsplit, scale_log2e
     if (dt == POLAR_F16) {
         if (d == 128) return launch_partial_layout<F16, 128>(POLAR_ARGS);
         if (d == 64) return launch_partial_layout<F16, 64>(POLAR_ARGS);

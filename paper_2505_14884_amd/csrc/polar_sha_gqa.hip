@@ -184,26 +184,37 @@ __device__ __forceinline__ void consume_block(const u32x4 (&kx)[8], const u32x4 
 // over the XCDs); block = 4 waves.  Wave w takes blocks w, w+4, ... of the chunk.  Two register
 // stages: the loads of the next block are in flight while the current one is consumed.
 // Workspace records as in the per-head kernel: unit = ((b*k + slot)*G + g)*nsplit + split.
-template <bool BF, bool ROW_MAJOR_SEQ>
+// DIRECT (only with nsplit == 1): final normalised rows go to `out` and one wave zero-fills this
+// slot's share of the unselected heads, as in the per-head kernel; no merge kernel runs.
+template <bool BF, bool ROW_MAJOR_SEQ, bool DIRECT>
 __global__ __launch_bounds__(kGqaWaves * 64) void sha_partial_gqa_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int32_t *__restrict__ seqlens, const int32_t *__restrict__ head_idx,
-    float *__restrict__ ws_o, float *__restrict__ ws_ml, int Hq, int Hkv, int S, int k, int G,
-    int chunk, int nsplit, float c)
+    float *__restrict__ ws_o, float *__restrict__ ws_ml, float *__restrict__ out, int Hq, int Hkv,
+    int S, int k, int G, int chunk, int nsplit, float c)
 {
     const int slot = blockIdx.x % k;
     const int rest = blockIdx.x / k;
     const int split = rest % nsplit, b = rest / nsplit;
     int n = seqlens[b];
     const int g_kv = head_idx ? head_idx[(size_t)b * k + slot] : slot;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int id0 = -1;
+    if (DIRECT && head_idx && wave == kGqaWaves - 1 && lane < k) id0 = head_idx[(size_t)b * k + lane];
     n = n < 0 ? 0 : (n > S ? S : n);
+    // The zero fill runs last (one wave, after the output rows), so that no wave waits for it.
+#define POLAR_DIRECT_ZERO_FILL()                                                                   \
+    if (DIRECT && wave == kGqaWaves - 1 && (head_idx || n == 0))                                   \
+        direct_zero_fill(head_idx ? head_idx + (size_t)b * k : nullptr, id0, head_idx && n > 0,    \
+                         slot, k, Hkv, G * kD, out + (size_t)b * Hq * kD, lane)
     const int row_begin = split * chunk;
-    if (row_begin >= n) return;
-    if ((unsigned)g_kv >= (unsigned)Hkv) return;
+    if (row_begin >= n || (unsigned)g_kv >= (unsigned)Hkv) {
+        POLAR_DIRECT_ZERO_FILL();
+        return;
+    }
     const int row_end = min(row_begin + chunk, n);
     const int last = row_end - 1;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lo = lane & 15, hi = lane >> 4;
 
     const size_t slab = ROW_MAJOR_SEQ ? ((size_t)b * S * Hkv + g_kv) * kD
@@ -294,21 +305,28 @@ __global__ __launch_bounds__(kGqaWaves * 64) void sha_partial_gqa_kernel(
             acc = fmaf(a, sm_o[w][g][t], acc);
             lsum = fmaf(a, sm_ml[w][g][1], lsum);
         }
-        const size_t unit = (((size_t)b * k + slot) * G + g) * nsplit + split;
-        ws_o[unit * kD + t] = acc;
-        if (t == 0) {
-            ws_ml[unit * 2 + 0] = mx;
-            ws_ml[unit * 2 + 1] = lsum;
+        if (DIRECT) {
+            out[((size_t)b * Hq + (size_t)g_kv * G + g) * kD + t] = lsum > 0.0f ? acc / lsum : 0.0f;
+        } else {
+            const size_t unit = (((size_t)b * k + slot) * G + g) * nsplit + split;
+            ws_o[unit * kD + t] = acc;
+            if (t == 0) {
+                ws_ml[unit * 2 + 0] = mx;
+                ws_ml[unit * 2 + 1] = lsum;
+            }
         }
     }
+    POLAR_DIRECT_ZERO_FILL();
+#undef POLAR_DIRECT_ZERO_FILL
 }
 
 }  // namespace
 
 hipError_t launch_sha_partial_gqa(const void *q, const void *K, const void *V, const int32_t *seqlens,
-                                  const int32_t *head_idx, float *ws, const ShaPlan &plan, int B,
-                                  int Hq, int Hkv, int S, int k, polar_dtype dt,
-                                  polar_kv_layout layout, float scale_log2e, hipStream_t stream)
+                                  const int32_t *head_idx, float *ws, float *direct_out,
+                                  const ShaPlan &plan, int B, int Hq, int Hkv, int S, int k,
+                                  polar_dtype dt, polar_kv_layout layout, float scale_log2e,
+                                  hipStream_t stream)
 {
     if (plan.G > POLAR_MAX_GROUP) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((size_t)B * plan.nsplit * k)), block(kGqaWaves * 64);
@@ -317,14 +335,24 @@ hipError_t launch_sha_partial_gqa(const void *q, const void *K, const void *V, c
     const uint16_t *K16 = static_cast<const uint16_t *>(K);
     const uint16_t *V16 = static_cast<const uint16_t *>(V);
 #define POLAR_GQA_LAUNCH(BF, RMS)                                                                   \
-    hipLaunchKernelGGL((sha_partial_gqa_kernel<BF, RMS>), grid, block, 0, stream, q16, K16, V16,    \
-                       seqlens, head_idx, ws_o, ws_ml, Hq, Hkv, S, k, plan.G, plan.chunk,           \
-                       plan.nsplit, scale_log2e)
+    if (direct_out)                                                                                 \
+        hipLaunchKernelGGL((sha_partial_gqa_kernel<BF, RMS, true>), grid, block, 0, stream, q16,    \
+                           K16, V16, seqlens, head_idx, ws_o, ws_ml, direct_out, Hq, Hkv, S, k,     \
+                           plan.G, plan.chunk, plan.nsplit, scale_log2e);                           \
+    else                                                                                            \
+        hipLaunchKernelGGL((sha_partial_gqa_kernel<BF, RMS, false>), grid, block, 0, stream, q16,   \
+                           K16, V16, seqlens, head_idx, ws_o, ws_ml, direct_out, Hq, Hkv, S, k,     \
+                           plan.G, plan.chunk, plan.nsplit, scale_log2e)
     const bool bf = dt == POLAR_BF16, rms = layout == POLAR_KV_BSHD;
-    if (bf && rms) POLAR_GQA_LAUNCH(true, true);
-    else if (bf) POLAR_GQA_LAUNCH(true, false);
-    else if (rms) POLAR_GQA_LAUNCH(false, true);
-    else POLAR_GQA_LAUNCH(false, false);
+    if (bf && rms) {
+        POLAR_GQA_LAUNCH(true, true);
+    } else if (bf) {
+        POLAR_GQA_LAUNCH(true, false);
+    } else if (rms) {
+        POLAR_GQA_LAUNCH(false, true);
+    } else {
+        POLAR_GQA_LAUNCH(false, false);
+    }
 #undef POLAR_GQA_LAUNCH
     return hipGetLastError();
 }

@@ -4,6 +4,9 @@ Bar: head_idx bit-exact; attention output max-abs error <= 2e-3 (16-bit inputs, 
 accumulation); skipped heads exactly +0.0.  Inputs are seeded and synthetic, shaped like the
 configurations the bench uses.  Every case prints its name before it touches the GPU.
 """
+import contextlib
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -54,16 +57,38 @@ def poison_unselected(w, q, K, V, head_idx):
     q.view(w.B, w.Hkv, w.G, w.d)[~keep] = float("nan")
 
 
+# (pass a workspace?, forced path): without a workspace the one-kernel path runs; with one the
+# library picks the faster path for the shape unless POLAR_ROUTER_PATH forces the split-D kernels.
+ROUTER_MODES = [(False, None), (True, "split"), (True, None)]
+
+
+@contextlib.contextmanager
+def router_path(path):
+    old = os.environ.get("POLAR_ROUTER_PATH")
+    if path is not None:
+        os.environ["POLAR_ROUTER_PATH"] = path
+    try:
+        yield
+    finally:
+        if path is not None:
+            if old is None:
+                del os.environ["POLAR_ROUTER_PATH"]
+            else:
+                os.environ["POLAR_ROUTER_PATH"] = old
+
+
 def run_router(w):
     hidden, Wr = wl.make_router_inputs(w, DEV)
     ref_logits = orc.router_logits(host_bits(hidden), host_bits(Wr), w.dtype)
     want = orc.topk(ref_logits, w.k)
     rws = polar.alloc_router_workspace(w.B, w.D, w.Hkv, DEV)
     rws.fill_(0xFF)
-    for ws in (None, rws):                    # one workgroup per request / split-D kernels
+    for ws, path in ROUTER_MODES:             # one workgroup per request / split-D kernels / library's choice
         logits = torch.full((w.B, w.Hkv), float("nan"), dtype=torch.float32, device=DEV)
         got = torch.full((w.B, w.k), -7, dtype=torch.int32, device=DEV)
-        polar.router_topk(hidden, Wr, w.k, head_idx=got, logits_out=logits, workspace=ws)
+        with router_path(path):
+            polar.router_topk(hidden, Wr, w.k, head_idx=got, logits_out=logits,
+                              workspace=rws if ws else None)
         torch.cuda.synchronize()
         assert np.array_equal(got.cpu().numpy(), want), "head_idx differs from the oracle"
         np.testing.assert_allclose(logits.cpu().numpy(), ref_logits, rtol=2e-7, atol=1e-7)
@@ -211,6 +236,57 @@ def test_sequence_major_cache_layout(name, dtype, G, d):
     torch.cuda.synchronize()
     check_against_oracle(wd, q.nan_to_num(0.0), K2, V2, seqlens, None, dense2)
     del dense
+
+
+@contextlib.contextmanager
+def two_kernel_form():
+    """Keep the streaming + merge pair even where an unsplit cache would take the one-kernel form."""
+    os.environ["POLAR_SHA_DIRECT"] = "0"
+    try:
+        yield
+    finally:
+        del os.environ["POLAR_SHA_DIRECT"]
+
+
+@pytest.mark.parametrize("dtype,Hkv,G,d,k,S", [("f16", 8, 1, 128, 3, 250), ("bf16", 6, 4, 128, 2, 256),
+                                               ("f16", 128, 1, 64, 100, 130), ("bf16", 72, 1, 128, 7, 200),
+                                               ("f16", 5, 3, 128, 5, 255), ("bf16", 4, 8, 64, 1, 90)])
+def test_one_kernel_form_for_unsplit_caches(dtype, Hkv, G, d, k, S):
+    """A cache that is not split is finished by the streaming kernel alone (it normalises, and
+    zero-fills the unselected heads).  Same bits as the streaming + merge pair, and parity with the
+    oracle, with -1 padding, duplicates, an empty request and rows of more than 64 ids."""
+    w = wl.ShaWorkload("direct", B=6, Hq=Hkv * G, Hkv=Hkv, d=d, S=S, k=k, D=64, dtype=dtype,
+                       seq_lo=1, seed=900 + Hkv + G)
+    say("\ncase one-kernel form", w)
+    assert polar.sha_chunk_rows(w.B, w.Hq, w.Hkv, w.S, w.d, w.k) >= w.S      # really unsplit
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV, poison_padding=True)
+    seqlens[2] = 0
+    K[2], V[2] = float("nan"), float("nan")
+    head_idx = wl.random_head_idx(w, DEV)
+    head_idx[1, 0] = -1                                   # an empty slot
+    if k > 1:
+        head_idx[3, 1] = head_idx[3, 0]                   # a duplicate
+        head_idx[4, :] = -1                               # a request with nothing selected
+    poison_unselected(w, q, K, V, head_idx)
+    out = torch.full((w.B, w.Hq, w.d), float("nan"), dtype=torch.float32, device=DEV)
+    polar.sha_decode(q, K, V, seqlens, head_idx, w.k, out=out)
+    with two_kernel_form():
+        ref = polar.sha_decode(q, K, V, seqlens, head_idx, w.k)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
+    assert (out[2].view(torch.int32) == 0).all()
+    assert k == 1 or (out[4].view(torch.int32) == 0).all()
+    check_against_oracle(w, q, K, V, seqlens, head_idx, out)
+    # dense call (NULL index) on clean inputs, with an empty request
+    q2, K2, V2, n2 = wl.make_attention_inputs(w, DEV, poison_padding=True)
+    n2[0] = 0
+    dense = torch.full((w.B, w.Hq, w.d), float("nan"), dtype=torch.float32, device=DEV)
+    polar.sha_decode(q2, K2, V2, n2, None, w.Hkv, out=dense)
+    with two_kernel_form():
+        dref = polar.sha_decode(q2, K2, V2, n2, None, w.Hkv)
+    torch.cuda.synchronize()
+    assert torch.equal(dense.view(torch.int32), dref.view(torch.int32))
+    assert (dense[0].view(torch.int32) == 0).all()
 
 
 def test_per_request_k_through_padding():
@@ -448,10 +524,11 @@ def router_case(hidden, Wr, k, dtype):
     B, D = hidden.shape
     rws = polar.alloc_router_workspace(B, D, Wr.shape[1], DEV)
     rws.fill_(0xFF)
-    for ws in (None, rws):                    # one workgroup per request / split-D kernels
-        got = polar.router_topk(hidden, Wr, k, workspace=ws)
+    for ws, path in ROUTER_MODES:
+        with router_path(path):
+            got = polar.router_topk(hidden, Wr, k, workspace=rws if ws else None)
         torch.cuda.synchronize()
-        assert np.array_equal(got.cpu().numpy(), want), "split" if ws is not None else "single"
+        assert np.array_equal(got.cpu().numpy(), want), (ws, path)
     return want
 
 
