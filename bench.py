@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # (each scaled by the same counter's reading for a plain 4 GiB copy); measured with this file's
 # --phase partial / --phase copy on the default shape of each workload.  Source:
 # profiles/sha_decode_step_<workload>.md.  Reported only when the shape is that default.
-MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4534002381, "C5_ragged": 4480318976,
-                          "C3_llama3_8b_gqa": 540179661, "C2_llama2_7b": 504130355}
+MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4533969067, "C5_ragged": 4480275675,
+                          "C3_llama3_8b_gqa": 538463068, "C2_llama2_7b": 504121882}
 DEFAULT_WORKLOAD = "C4_opt66b"
 
 
@@ -254,7 +254,7 @@ def main():
 
     # An unsplit cache is finished by the streaming kernel alone (it normalises and zero-fills,
     # no merge kernel): then the attention call itself is one launch of the dominant kernel.
-    one_kernel = chunk >= w.S and os.environ.get("POLAR_SHA_DIRECT", "1")[:1] != "0"
+    one_kernel = polar.sha_launches(w.B, w.Hq, w.Hkv, w.S, w.d, w.k) == 1
 
     def partial_only(i):
         Ki, Vi = caches[i % R]

@@ -124,7 +124,7 @@ size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k);
  * n_b == 0 gets zeros.  Supported: d in {64, 128}; G = Hq / Hkv in 1..16 at d = 128, in
  * {1, 2, 4, 8} at d = 64; 1 <= k <= Hkv.
  *
- * Launches: when the sizes lead to an unsplit cache (polar_sha_chunk_rows(...) >= S) one
+ * Launches (polar_sha_launches tells which): for an unsplit cache of moderate size one
  * kernel streams the rows, normalises, stores `out` and zero-fills the unselected heads, and
  * the workspace is left untouched; otherwise the streaming kernel leaves per-chunk records in
  * the workspace and a second small kernel combines them.  Both forms give the same bits.
@@ -175,6 +175,13 @@ int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
  * (the split granularity the workspace size is computed from).  0 for invalid sizes.
  */
 int polar_sha_chunk_rows(int B, int Hq, int Hkv, int S, int d, int k);
+
+/*
+ * Kernels polar_sha_decode launches for these sizes: 1 (an unsplit cache finished by the
+ * streaming kernel alone) or 2 (streaming kernel + merge kernel); 0 for invalid sizes.  For
+ * harnesses that attribute time to kernels; results do not depend on it.
+ */
+int polar_sha_launches(int B, int Hq, int Hkv, int S, int d, int k);
 
 /*
  * Head-importance labels (Section 3.2: heads ranked by the L2 norm of their attention output;

@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_head_norm_topk", "polar_select_gemm", "polar_neuron_union", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_head_norm_topk", "polar_select_gemm", "polar_neuron_union", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -54,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.polar_sha_workspace_bytes.restype = sz
         L.polar_sha_chunk_rows.argtypes = [i] * 6
         L.polar_sha_chunk_rows.restype = i
+        L.polar_sha_launches.argtypes = [i] * 6
+        L.polar_sha_launches.restype = i
         L.polar_sha_decode.argtypes = [vp] * 6 + [i] * 7 + [f, vp, sz, vp]
         L.polar_sha_decode.restype = i
         L.polar_sha_partial.argtypes = [vp] * 5 + [i] * 7 + [f, vp, sz, vp]
@@ -145,6 +147,11 @@ def sha_workspace_bytes(B: int, Hq: int, Hkv: int, S: int, d: int, k: int) -> in
 
 def sha_chunk_rows(B: int, Hq: int, Hkv: int, S: int, d: int, k: int) -> int:
     return int(lib().polar_sha_chunk_rows(B, Hq, Hkv, S, d, k))
+
+
+def sha_launches(B: int, Hq: int, Hkv: int, S: int, d: int, k: int) -> int:
+    """Kernels sha_decode launches for these sizes (1: streaming kernel alone, 2: + merge)."""
+    return int(lib().polar_sha_launches(B, Hq, Hkv, S, d, k))
 
 
 def alloc_workspace(B: int, Hq: int, Hkv: int, S: int, d: int, k: int, device) -> torch.Tensor:

@@ -42,6 +42,7 @@ constexpr long kUnsplitUnits = kComputeUnits;
 constexpr int kMaxChunkPerHead = 1024;
 constexpr int kMaxChunkGrouped = 4096;
 constexpr int kMinChunk = 256;
+constexpr long kDirectMaxUnits = 2048;
 
 int choose_chunk(int B, int k, int S, int kMaxChunk)
 {
@@ -111,6 +112,17 @@ int make_sha_plan(int B, int Hq, int Hkv, int S, int d, int k, ShaPlan *plan)
     const bool grouped_mfma = plan->G > 1 && d == 128;   // which streaming kernel will run
     plan->chunk = choose_chunk(B, k, S, grouped_mfma ? kMaxChunkGrouped : kMaxChunkPerHead);
     plan->nsplit = (S + plan->chunk - 1) / plan->chunk;
+    // One-kernel form: an unsplit cache needs no merge; the streaming kernel can normalise, store
+    // the rows and zero-fill the unselected heads itself.  That saves a launch (4 to 6 us per step
+    // on layers of 0.5 to 1.5 GB) but its scattered zero stores land in the middle of the read
+    // stream and cost about 2.5 ns per workgroup (12 us at 4608 workgroups, where the merge
+    // kernel takes 6), so it is used up to kDirectMaxUnits workgroups.  POLAR_SHA_DIRECT=0/1
+    // forces the choice, for comparisons.
+    plan->direct = plan->nsplit == 1 && (long)B * k <= kDirectMaxUnits;
+    if (const char *env = getenv("POLAR_SHA_DIRECT")) {
+        if (env[0] == '0') plan->direct = false;
+        if (env[0] == '1') plan->direct = plan->nsplit == 1;
+    }
     if ((size_t)B * plan->nsplit * k > 0x7fffffffu) return POLAR_EUNSUPPORTED;   // 1-D grid limit
     const size_t units = (size_t)B * k * plan->G * plan->nsplit;
     plan->o_floats = (units * d + 63) / 64 * 64;   // keeps the (max, sum) region 256-byte aligned
@@ -175,6 +187,13 @@ size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k)
     ShaPlan plan;
     if (make_sha_plan(B, Hq, Hkv, S, d, k, &plan) != POLAR_OK) return 0;
     return plan.bytes;
+}
+
+int polar_sha_launches(int B, int Hq, int Hkv, int S, int d, int k)
+{
+    ShaPlan plan;
+    if (make_sha_plan(B, Hq, Hkv, S, d, k, &plan) != POLAR_OK) return 0;
+    return plan.direct ? 1 : 2;
 }
 
 int polar_sha_chunk_rows(int B, int Hq, int Hkv, int S, int d, int k)
@@ -255,10 +274,7 @@ int polar_sha_decode_layout(const void *q, const void *K, const void *V, const i
     int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);   // size errors take precedence
     if (rc != POLAR_OK) return rc;
     if (B > 0 && !out) return POLAR_EINVAL;
-    // An unsplit cache needs no merge: the streaming kernel finishes the rows itself and
-    // zero-fills the unselected heads (POLAR_SHA_DIRECT=0 keeps the two-kernel form, for comparisons).
-    const char *env = getenv("POLAR_SHA_DIRECT");
-    const bool direct = plan.nsplit == 1 && !(env && env[0] == '0');
+    const bool direct = plan.direct;
     rc = sha_partial_impl(q, K, V, seqlens, head_idx, direct ? out : nullptr, B, Hq, Hkv, S, d, k, dt,
                           layout, scale, workspace, workspace_bytes, stream);
     if (rc != POLAR_OK || direct) return rc;

@@ -15,6 +15,7 @@ struct ShaPlan {
     int G;            // query heads per KV head
     int chunk;        // cache rows one workgroup of the streaming kernel covers
     int nsplit;       // chunks per (request, slot): ceil(S / chunk)
+    bool direct;      // polar_sha_decode runs the streaming kernel alone (it finishes the output)
     size_t o_floats;  // floats in the partial-output region of the workspace
     size_t ml_floats; // floats in the (max, sum) region
     size_t bytes;     // total workspace bytes, 256-aligned

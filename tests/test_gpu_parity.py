@@ -258,7 +258,9 @@ def test_one_kernel_form_for_unsplit_caches(dtype, Hkv, G, d, k, S):
     w = wl.ShaWorkload("direct", B=6, Hq=Hkv * G, Hkv=Hkv, d=d, S=S, k=k, D=64, dtype=dtype,
                        seq_lo=1, seed=900 + Hkv + G)
     say("\ncase one-kernel form", w)
-    assert polar.sha_chunk_rows(w.B, w.Hq, w.Hkv, w.S, w.d, w.k) >= w.S      # really unsplit
+    assert polar.sha_launches(w.B, w.Hq, w.Hkv, w.S, w.d, w.k) == 1          # really one kernel
+    with two_kernel_form():
+        assert polar.sha_launches(w.B, w.Hq, w.Hkv, w.S, w.d, w.k) == 2
     q, K, V, seqlens = wl.make_attention_inputs(w, DEV, poison_padding=True)
     seqlens[2] = 0
     K[2], V[2] = float("nan"), float("nan")
