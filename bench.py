@@ -324,6 +324,16 @@ def main():
         dense_avg, _, _ = event_time(dense_step, max(5, n_ev // 4))
     achieved = bytes_sel / (part_avg * 1e-3) / 1e9
 
+    # Read-only yardstick over the same K cache with the streaming kernel's launch shape: what this
+    # GPU gives a kernel that does nothing but read, with non-temporal and with plain loads.
+    slab = w.S * w.d * 2 if lay == "bhsd" else w.S * w.Hkv * w.d * 2
+    probe_bytes = (K.numel() * 2) // slab * slab
+    sink = torch.empty(probe_bytes // slab, dtype=torch.int32, device=dev)
+    probe = {}
+    for label, nt in (("nontemporal", True), ("plain", False)):
+        t_avg, _, _ = event_time(lambda i: polar.probe_read(caches[i % R][0], slab, nt, sink), max(5, n_ev // 4))
+        probe[label] = round(probe_bytes / (t_avg * 1e-3) / 1e9, 1)
+
     result = {
         "metric": "selective-head decode attention effective KV HBM GB/s "
                   "(selected-head K+V bytes / step time; us per layer = 1000*ms_per_step)",
@@ -370,6 +380,7 @@ def main():
             "avg_us": round(part_avg * 1e3, 2),
             "median_us": round(part_med * 1e3, 2),
             "min_us": round(part_min * 1e3, 2),
+            "read_probe_GBps": probe,
             "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (w == wl.CONFIGS.get(w.name) and lay == "bhsd") else None,
         },
     }

@@ -237,6 +237,19 @@ int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const in
 int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                        int32_t *count_out, void *stream);
 
+/*
+ * Streaming-read yardstick for harnesses (not an operation of the paper): `slabs` workgroups
+ * each read one contiguous slab of `slab_bytes` bytes (slab w starts at src + w * slab_bytes)
+ * with the per-head streaming kernel's launch shape and fold what they read into sink[w].
+ * Timing it over the bytes of a K cache gives the read bandwidth this GPU reaches for that
+ * access pattern, to set beside the nominal HBM peak.  nontemporal != 0 marks the loads
+ * non-temporal, as the attention kernels do.
+ *   src  in   slabs * slab_bytes bytes, 16-byte aligned; slab_bytes a multiple of 16
+ *   sink out  [slabs] uint32
+ */
+int polar_probe_read(const void *src, size_t slabs, size_t slab_bytes, int nontemporal, uint32_t *sink,
+                     void *stream);
+
 /* Text for a polar_status value; never NULL. */
 const char *polar_strerror(int status);
 /* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */

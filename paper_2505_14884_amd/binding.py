@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_head_norm_topk", "polar_select_gemm", "polar_neuron_union", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_head_norm_topk", "polar_select_gemm", "polar_neuron_union", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.polar_sha_chunk_rows.restype = i
         L.polar_sha_launches.argtypes = [i] * 6
         L.polar_sha_launches.restype = i
+        L.polar_probe_read.argtypes = [vp, sz, sz, i, vp, vp]
+        L.polar_probe_read.restype = i
         L.polar_sha_decode.argtypes = [vp] * 6 + [i] * 7 + [f, vp, sz, vp]
         L.polar_sha_decode.restype = i
         L.polar_sha_partial.argtypes = [vp] * 5 + [i] * 7 + [f, vp, sz, vp]
@@ -226,6 +228,19 @@ def sha_merge(seqlens, head_idx, out: torch.Tensor, Hkv: int, S: int, k: int,
                                workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "polar_sha_merge")
     return out
+
+
+def probe_read(src: torch.Tensor, slab_bytes: int, nontemporal: bool = True,
+               sink: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Streaming-read yardstick over the whole slabs of `src` (see polar_probe_read)."""
+    nbytes = src.numel() * src.element_size()
+    slabs = nbytes // slab_bytes
+    if sink is None:
+        sink = torch.empty(max(slabs, 1), dtype=torch.int32, device=src.device)
+    rc = lib().polar_probe_read(_dev(src, "src"), slabs, slab_bytes, 1 if nontemporal else 0,
+                                _dev(sink, "sink"), _stream())
+    _check(rc, "polar_probe_read")
+    return sink
 
 
 def head_norm_topk(attn_out: torch.Tensor, Hkv: int, k: int,

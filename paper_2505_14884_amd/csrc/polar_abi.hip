@@ -291,6 +291,16 @@ int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t 
                                    POLAR_KV_BHSD, scale, workspace, workspace_bytes, stream);
 }
 
+int polar_probe_read(const void *src, size_t slabs, size_t slab_bytes, int nontemporal, uint32_t *sink,
+                     void *stream)
+{
+    if (slab_bytes < 16 || slab_bytes % 16 != 0 || slabs > 0x7fffffffu) return POLAR_EINVAL;
+    if (slabs == 0) return POLAR_OK;
+    if (!src || !sink || ((uintptr_t)src & 15u) != 0) return POLAR_EINVAL;
+    return record(launch_read_probe(src, slabs, slab_bytes, nontemporal, sink,
+                                    static_cast<hipStream_t>(stream)));
+}
+
 int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,
                          int32_t *head_idx, float *norms_out, void *stream)
 {

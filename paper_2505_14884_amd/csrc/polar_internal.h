@@ -66,6 +66,8 @@ hipError_t launch_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, 
 hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
                               float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
                               hipStream_t stream);
+hipError_t launch_read_probe(const void *src, size_t slabs, size_t slab_bytes, int nontemporal,
+                             uint32_t *sink, hipStream_t stream);
 int neuron_union_max_n();
 hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                                int32_t *count_out, hipStream_t stream);

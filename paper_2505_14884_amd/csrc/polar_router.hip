@@ -217,7 +217,10 @@ hipError_t launch_vec(const uint16_t *hidden, const uint16_t *Wr, int B, int D, 
 // Phase 1 leaves, per (request tile, D slice), the kTileR x H partial sums in the workspace;
 // phase 2 adds the P partials of each request in ascending slice order and ranks.
 // The order of additions again depends on (D, H, VEC, P) only, never on the column.
-constexpr int kTileR = 2;
+#ifndef POLAR_ROUTER_TILE_R
+#define POLAR_ROUTER_TILE_R 2
+#endif
+constexpr int kTileR = POLAR_ROUTER_TILE_R;
 constexpr int kSplitThreads = 256;
 constexpr int kSplitStageBatch = 2;   // hidden elements per request a thread stages per batch
 #ifndef POLAR_ROUTER_DP_MAX

@@ -169,3 +169,19 @@ def test_binding_refuses_cpu_tensors():
                           head_idx=torch.zeros((1, 2), dtype=torch.int32))
     with pytest.raises(polar.PolarError):
         polar.alloc_workspace(4, 8, 8, 256, 96, 4, "cpu")
+
+
+def test_probe_and_launch_query_argument_checks():
+    L = binding.lib()
+    assert L.polar_probe_read(FAKE, 4, 8, 1, FAKE, None) == EINVAL          # slab under 16 bytes
+    assert L.polar_probe_read(FAKE, 4, 4100, 1, FAKE, None) == EINVAL       # not a multiple of 16
+    assert L.polar_probe_read(None, 4, 4096, 1, FAKE, None) == EINVAL
+    assert L.polar_probe_read(FAKE, 4, 4096, 1, None, None) == EINVAL
+    assert L.polar_probe_read(ctypes.c_void_p(0x10008), 4, 4096, 1, FAKE, None) == EINVAL   # misaligned
+    assert L.polar_probe_read(None, 0, 4096, 1, None, None) == OK           # nothing to read
+    # launches of polar_sha_decode: 1 for a moderate unsplit cache, 2 when split or very large, 0 if invalid
+    assert polar.sha_launches(32, 32, 32, 1920, 128, 16) == 1
+    assert polar.sha_launches(64, 32, 8, 4096, 128, 4) == 1
+    assert polar.sha_launches(128, 72, 72, 1920, 128, 36) == 2
+    assert polar.sha_launches(256, 32, 32, 8192, 128, 8) == 2
+    assert polar.sha_launches(4, 8, 8, 256, 96, 4) == 0

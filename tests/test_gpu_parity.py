@@ -291,6 +291,45 @@ def test_one_kernel_form_for_unsplit_caches(dtype, Hkv, G, d, k, S):
     assert (dense[0].view(torch.int32) == 0).all()
 
 
+def test_random_shapes_against_the_oracle():
+    """Forty seeded random valid shapes (group size, head dimension, lengths, k, dtype, cache layout,
+    padded and duplicate ids, forced chunk sizes): every one element by element against the oracle."""
+    rng = np.random.default_rng(20250514)
+    for case in range(40):
+        d = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 2, 4, 8])) if d == 64 else int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 12, 16]))
+        Hkv = int(rng.integers(1, 13))
+        k = int(rng.integers(1, Hkv + 1))
+        B = int(rng.integers(1, 9))
+        S = int(rng.integers(1, 1400))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        layout = str(rng.choice(["bhsd", "bshd"]))
+        chunk = int(rng.choice([0, 128, 256, 384, 1024]))        # 0: the library's own choice
+        w = wl.ShaWorkload("rnd%d" % case, B=B, Hq=Hkv * G, Hkv=Hkv, d=d, S=S, k=k, D=64, dtype=dtype,
+                           seq_lo=1, seed=5000 + case)
+        say("\ncase", case, w, layout, "chunk", chunk)
+        seqlens = wl.make_seqlens(w, DEV)
+        seqlens[int(rng.integers(0, B))] = int(rng.choice([0, 1, S]))
+        q, K, V, _ = wl.make_attention_inputs(w, DEV, poison_padding=True, seqlens=seqlens)
+        head_idx = wl.random_head_idx(w, DEV, seed_offset=case)
+        if k > 1 and rng.random() < 0.5:
+            head_idx[int(rng.integers(0, B)), int(rng.integers(0, k))] = -1
+        if k > 1 and rng.random() < 0.3:
+            head_idx[0, 1] = head_idx[0, 0]
+        poison_unselected(w, q, K, V, head_idx)
+        Kc, Vc = (K, V) if layout == "bhsd" else (K.permute(0, 2, 1, 3).contiguous(),
+                                                  V.permute(0, 2, 1, 3).contiguous())
+        if chunk:
+            os.environ["POLAR_SHA_CHUNK_ROWS"] = str(chunk)
+        try:
+            out = torch.full((B, w.Hq, d), float("nan"), dtype=torch.float32, device=DEV)
+            polar.sha_decode(q, Kc, Vc, seqlens, head_idx, k, out=out, kv_layout=layout)
+            torch.cuda.synchronize()
+        finally:
+            os.environ.pop("POLAR_SHA_CHUNK_ROWS", None)
+        check_against_oracle(w, q, K, V, seqlens, head_idx, out)
+
+
 def test_per_request_k_through_padding():
     """Requests keep different numbers of heads: unused slots hold -1 (the adaptive routing the
     paper lists as future work needs nothing else from the kernel)."""
@@ -478,6 +517,20 @@ def test_sparse_mlp_first_layer(name):
     assert err <= GEMM_TOL
     assert (out[:, :c] >= 0).all() and torch.isfinite(out[:, :c]).all()
     assert 0.3 < float((out[:, :c] > 0).float().mean()) < 0.7      # ReLU of a symmetric pre-activation
+
+
+def test_read_probe_folds_every_word_of_every_slab():
+    """The bandwidth yardstick really reads what it claims: each slab's result is the XOR of its
+    words (slabs of whole 16 KiB wave steps, so no clamped tail load repeats a word)."""
+    g = torch.Generator(device=DEV).manual_seed(3)
+    slab_bytes, slabs = 3 * 16384, 37
+    data = torch.randint(-2 ** 31, 2 ** 31 - 1, (slabs, slab_bytes // 4), generator=g, device=DEV,
+                         dtype=torch.int32)
+    want = np.bitwise_xor.reduce(data.cpu().numpy().view(np.uint32), axis=1)
+    for nt in (True, False):
+        got = polar.probe_read(data, slab_bytes, nt)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), want)
 
 
 def test_empty_batch_is_a_noop():

@@ -339,8 +339,9 @@ def test_output_lies_in_the_convex_hull_of_value_rows():
 
 
 # ----------------------------------------------------------------------------- GQA
-def test_group_selection_equals_mha_on_repeated_kv():
-    B, Hq, Hkv, S, d, k = 2, 8, 2, 30, 16, 1
+@pytest.mark.parametrize("Hq", [8, 6, 14])          # groups of 4, 3 and 7 query heads
+def test_group_selection_equals_mha_on_repeated_kv(Hq):
+    B, Hkv, S, d, k = 2, 2, 30, 16, 1
     G = Hq // Hkv
     q, K, V, n = random_case(B, Hq, Hkv, S, d, "bf16")
     idx = np.array([[1], [0]], np.int32)
@@ -350,8 +351,8 @@ def test_group_selection_equals_mha_on_repeated_kv():
     idx_q = np.stack([np.concatenate([np.arange(g * G, (g + 1) * G) for g in row]) for row in idx])
     want = orc.sha_decode(q, Krep, Vrep, n, idx_q.astype(np.int32), k * G, "bf16")
     assert np.array_equal(got, want)
-    assert not got[0, :4].any() and got[0, 4:].all()        # request 0 skips group 0
-    assert got[1, :4].all() and not got[1, 4:].any()
+    assert not got[0, :G].any() and got[0, G:].all()        # request 0 skips group 0
+    assert got[1, :G].all() and not got[1, G:].any()
 
 
 # ----------------------------------------------------------------------------- Algorithm 1
