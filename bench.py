@@ -326,7 +326,7 @@ def main():
 
     # Read-only yardstick over the same K cache with the streaming kernel's launch shape: what this
     # GPU gives a kernel that does nothing but read, with non-temporal and with plain loads.
-    slab = w.S * w.d * 2 if lay == "bhsd" else w.S * w.Hkv * w.d * 2
+    slab = w.S * w.d * 2          # bytes of one head's rows; the probe reads contiguous slabs of that size
     probe_bytes = (K.numel() * 2) // slab * slab
     sink = torch.empty(probe_bytes // slab, dtype=torch.int32, device=dev)
     probe = {}
