@@ -1,5 +1,6 @@
-// Selective Head Attention, decode step, for gfx950 (CDNA4): split-KV streaming kernel
-// and merge / zero-fill kernel.
+// Selective Head Attention, decode step, for gfx950 (CDNA4): split-KV streaming kernel for
+// one query head per KV head (also grouped heads at d = 64; grouped heads at d = 128 take the
+// matrix-core kernel in polar_sha_gqa.hip) and the merge / zero-fill kernel both share.
 //
 // What is computed (Section 3.2, per-head attention equation; Algorithm 1, Selective Head
 // FlashAttention (decode)): for every request b and selected KV head g, one query row per
@@ -23,7 +24,8 @@
 //   * Long sequences are split across workgroups in chunks of rows (occupancy: the number
 //     of (request, head) units alone does not fill 256 compute units); the merge kernel
 //     applies the same max/sum rescale across chunks, normalises, and stores zeros for
-//     the heads that were not selected.
+//     the heads that were not selected.  A cache that is not split can skip the merge: the
+//     streaming kernel then finishes the rows and zero-fills by itself (DIRECT below).
 #include <stdlib.h>
 
 #include "polar_internal.h"
