@@ -69,13 +69,15 @@ int choose_chunk(int B, int k, int S, int kMaxChunk)
 
 // Which router path is faster when the caller offers a workspace.  The one-workgroup-per-request
 // kernel is a single launch whose time depends on D*H only while B fits the chip (256 compute
-// units); the split-D pair spreads small batches over the whole chip but pays a second launch.
-// Both estimates are fits to event timings on MI355X over B = 1..1024, D*H = 32 K..2 M
-// (microseconds): single = max(7.5, 5.2 + ceil(B/256) * D*H / 31e3), split = 10.5 + B*D*H / 8.5e6.
-// Examples: B=64, D=4096, H=8: 7.5 vs 11.0 measured (single); B=128, D=9216, H=72: 28.6 vs 24.6
-// (split); B=256, D=4096, H=32: 9.6 vs 14.2 (single).
+// units); the split-D pair spreads the work over the whole chip but pays a second launch.  The
+// estimates are fits to event timings on MI355X over B = 1..1024, D*H = 32 K..2 M (microseconds):
+//   single            = ceil(B/256) * max(7.5, 5.2 + D*H / 31e3)
+//   split, B >= 16    = 11.5 + 2.6e-5 * ceil(B/16) * D * padded 16-column tiles   (fp64 matrix cores)
+//   split, B <  16    = 10.5 + B*D*H / 8.5e6                                      (vector ALU)
+// Examples (single vs split measured): B=64, D=4096, H=8: 8.4 vs 11.3; B=128, D=9216, H=72:
+// 29.3 vs 20.4; B=256, D=4096, H=32: 9.8 vs 13.4; B=1024, D=8192, H=64: 89 vs 48.
 // POLAR_ROUTER_PATH=split|single overrides the choice (tests use it to reach both paths).
-bool router_split_pays(int B, int D, int H)
+bool router_split_pays(int B, int D, int H, const RouterPlan &plan)
 {
     if (const char *env = getenv("POLAR_ROUTER_PATH")) {
         if (env[0] == 's' && env[1] == 'p') return true;
@@ -83,9 +85,17 @@ bool router_split_pays(int B, int D, int H)
     }
     const double dh = (double)D * H;
     const double rounds = (double)((B + 255) / 256);
-    double single_us = 5.2 + rounds * dh / 31.0e3;
+    double single_us = 5.2 + dh / 31.0e3;
     if (single_us < 7.5) single_us = 7.5;
-    const double split_us = 10.5 + (double)B * dh / 8.5e6;
+    single_us *= rounds;
+    double split_us;
+    if (plan.mfma) {
+        const int nt = (H + 15) / 16, grp = nt < 5 ? nt : 5;
+        const double tiles = (double)((nt + grp - 1) / grp * grp);
+        split_us = 11.5 + 2.6e-5 * (double)((B + 15) / 16) * D * tiles;
+    } else {
+        split_us = 10.5 + (double)B * dh / 8.5e6;
+    }
     return split_us < single_us;
 }
 
@@ -175,7 +185,7 @@ int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, i
         return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
                                          static_cast<hipStream_t>(stream)));
     if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < plan.bytes) return POLAR_EWORKSPACE;
-    if (!router_split_pays(B, D, H))
+    if (!router_split_pays(B, D, H, plan))
         return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
                                          static_cast<hipStream_t>(stream)));
     return record(launch_router_split(hidden, Wr, B, D, H, k, dt, plan, head_idx, logits_out,

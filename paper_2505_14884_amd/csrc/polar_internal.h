@@ -26,7 +26,8 @@ int make_sha_plan(int B, int Hq, int Hkv, int S, int d, int k, ShaPlan *plan);
 
 // Launch geometry of the split-D router path.
 struct RouterPlan {
-    int RT;        // request tiles (kTileR requests each)
+    bool mfma;     // phase 1 on the fp64 matrix cores (tiles of 16 requests) or on the vector ALU (tiles of 2)
+    int RT;        // request tiles
     int P;         // slices of the D axis
     int Dp;        // rows of Wr per slice
     size_t bytes;  // workspace bytes, 256-aligned

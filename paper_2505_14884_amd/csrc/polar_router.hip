@@ -20,6 +20,13 @@
 // Top-k is rank counting in LDS (H <= 256): the rank of head h is the number of heads that
 // precede it in the order "larger logit first, equal logits by lower id, NaN last"; heads
 // of rank < k write their id at position rank.
+//
+// Further down: the split-D pair of kernels (partial sums per slice of D into a workspace, then
+// a finish kernel that adds the slices and ranks), whose first phase runs on the vector ALU
+// for batches under 16 requests and on the fp64 matrix cores (v_mfma_f64_16x16x4_f64, tiles of
+// 16 requests) otherwise.  All paths share the arithmetic contract above.
+#include <stdlib.h>
+
 #include <atomic>
 
 #include "polar_internal.h"
@@ -347,21 +354,21 @@ __global__ __launch_bounds__(kSplitThreads) void router_partial_kernel(
 // Phase 2: one workgroup per request; thread h adds the P slice partials in ascending order,
 // then the same rank counting as the single-kernel path.
 __global__ __launch_bounds__(POLAR_MAX_ROUTER_H) void router_finish_kernel(
-    const double *__restrict__ ws, int H, int k, int P, int32_t *__restrict__ head_idx,
+    const double *__restrict__ ws, int H, int k, int P, int tile, int32_t *__restrict__ head_idx,
     float *__restrict__ logits_out)
 {
     __shared__ double sh_logit[POLAR_MAX_ROUTER_H];
     __shared__ int sh_rank[POLAR_MAX_ROUTER_H];
     const int b = blockIdx.x, tid = threadIdx.x;
-    const int rt = b / kTileR, r = b - rt * kTileR;
+    const int rt = b / tile, r = b - rt * tile;       // workspace: [request tile][slice][row of tile][H]
     if (tid < H) {
-        const double *src = ws + ((size_t)rt * P * kTileR + r) * H + tid;
+        const double *src = ws + ((size_t)rt * P * tile + r) * H + tid;
         double sum = 0.0;
         for (int p0 = 0; p0 < P; p0 += kFinishBatch) {      // a batch of loads, then ordered adds
             double v[kFinishBatch];
 #pragma unroll
             for (int u = 0; u < kFinishBatch; ++u)
-                v[u] = p0 + u < P ? src[(size_t)(p0 + u) * kTileR * H] : 0.0;
+                v[u] = p0 + u < P ? src[(size_t)(p0 + u) * tile * H] : 0.0;
 #pragma unroll
             for (int u = 0; u < kFinishBatch; ++u)
                 if (p0 + u < P) sum += v[u];
@@ -394,8 +401,218 @@ hipError_t launch_split_vec(const uint16_t *hidden, const uint16_t *Wr, int B, i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(router_finish_kernel, dim3((unsigned)B), dim3(POLAR_MAX_ROUTER_H), 0, stream, ws, H,
-                       k, plan.P, head_idx, logits_out);
+                       k, plan.P, kTileR, head_idx, logits_out);
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Matrix-core form of phase 1 (batches of at least kMmTileR requests).  The same partial sums,
+// logit[b, h] over one slice of D, are a [16 requests x Dp] by [Dp x H] product in double, which
+// is what v_mfma_f64_16x16x4_f64 computes: a converted Wr element then feeds 16 multiply-adds
+// instead of 2, and the vector ALU is left with two conversions per operand element.  The
+// slice of Wr (one contiguous block of Dp*H values, H innermost) and the tile's hidden rows are
+// staged in LDS as raw 16-bit patterns; a lane reads and widens the one A element and the one
+// B element it supplies to each instruction: lane 16*kk + lo gives A[request lo][row 4t + kk]
+// and B[row 4t + kk][column 16*tile + lo], and receives D[request kk + 4r][column lo] in
+// register r.  The four waves take the 4-row steps t = wave, wave + 4, ... and their sums are
+// added in the fixed order ((w3 + w2) + w1) + w0, so the result depends on (D, H, Dp) only and
+// every column goes through the same sequence of operations (identical columns of Wr give
+// bit-identical logits, as in the other paths).
+constexpr int kMmTileR = 16;
+constexpr int kMmWaves = 4;
+constexpr int kMmThreads = kMmWaves * 64;
+constexpr int kMmGroupMax = 5;      // 16-column tiles accumulated together (up to 80 columns)
+constexpr int kMmHiddenBatch = 16;  // hidden elements a thread stages per batch
+constexpr int kMmSlabBatch = 12;    // 16-byte pieces of the Wr slice a thread stages per batch
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
+
+__host__ __device__ inline int mm_hidden_pitch(int Dp) { return Dp + 2; }   // odd number of dwords per row
+// tiles per group for H columns: all of them when they fit one group, else the maximum
+__host__ __device__ inline int mm_group(int H)
+{
+    const int nt = (H + 15) / 16;
+    return nt < kMmGroupMax ? nt : kMmGroupMax;
+}
+// columns of the LDS copy of the Wr slice: whole groups of tiles, zero beyond H, so the inner
+// loop needs no bounds test
+__host__ __device__ inline int mm_slab_pitch(int H)
+{
+    const int grp = mm_group(H);
+    const int groups = ((H + 15) / 16 + grp - 1) / grp;
+    return groups * grp * 16;
+}
+
+template <bool BF, int kMmGroup>
+__global__ __launch_bounds__(kMmThreads) void router_partial_mfma_kernel(
+    const uint16_t *__restrict__ hidden, const uint16_t *__restrict__ Wr, int B, int D, int H,
+    int Dp, double *__restrict__ ws)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int p = blockIdx.x, rt = blockIdx.y, P = gridDim.x, tid = threadIdx.x;
+    // the wave number as a scalar: the loop over this wave's steps is then uniform and its
+    // accumulators stay in the matrix cores' registers instead of being moved every iteration
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i0 = p * Dp;
+    const int rows = min(Dp, D - i0);
+    const int Dp4 = (Dp + 3) & ~3;
+
+    // LDS: slab[Dp4][Hp] (16-bit) | hd[16][pitch] (16-bit) | red[kMmGroup][4][64] (double)
+    const int Hp = mm_slab_pitch(H);
+    uint16_t *slab = reinterpret_cast<uint16_t *>(smem);
+    const size_t slab_bytes = (size_t)Dp4 * Hp * 2;                 // Hp is a multiple of 16
+    const int pitch = mm_hidden_pitch(Dp);
+    uint16_t *hd = reinterpret_cast<uint16_t *>(smem + slab_bytes);
+    const size_t hd_bytes = ((size_t)kMmTileR * pitch * 2 + 15) / 16 * 16;
+    double *red = reinterpret_cast<double *>(smem + slab_bytes + hd_bytes);
+
+    // Stage the tile's hidden rows (zeros for requests beyond B and rows beyond the slice) and the
+    // slice of Wr, row by row into the padded pitch (zeros beyond the slice and beyond H).  All
+    // loads of a batch are issued before any store, and the hidden rows travel with the first
+    // batch of the slice: a dependent round trip per piece would cost more than everything else.
+    const int hd_elems = kMmTileR * Dp4;
+    const uint16_t *src = Wr + (size_t)i0 * H;
+    const bool vec = H % 8 == 0 && (reinterpret_cast<uintptr_t>(Wr) & 15u) == 0;
+    const int h8 = H / 8, hp8 = Hp / 8, nv = vec ? Dp4 * hp8 : 0;   // 16-byte pieces of the padded slab
+    const u32x4v *sv = reinterpret_cast<const u32x4v *>(src);
+    u32x4v *dv = reinterpret_cast<u32x4v *>(slab);
+    for (int base = 0, sbase = 0; base < hd_elems || sbase < nv;
+         base += kMmHiddenBatch * kMmThreads, sbase += kMmSlabBatch * kMmThreads) {
+        uint16_t hv[kMmHiddenBatch];
+        u32x4v wv[kMmSlabBatch];
+#pragma unroll
+        for (int u = 0; u < kMmHiddenBatch; ++u) {
+            const int e = base + u * kMmThreads + tid;
+            const int r = e / Dp4, i = e - r * Dp4, b = rt * kMmTileR + r;
+            const bool live = e < hd_elems && b < B && i < rows;
+            const uint16_t x = hidden[live ? (size_t)b * D + i0 + i : 0];
+            hv[u] = live ? x : (uint16_t)0;
+        }
+#pragma unroll
+        for (int u = 0; u < kMmSlabBatch; ++u) {
+            const int i = sbase + u * kMmThreads + tid;
+            const int row = i / hp8, c8 = i - row * hp8;
+            const bool live = i < nv && row < rows && c8 < h8;
+            const u32x4v x = sv[live ? row * h8 + c8 : 0];
+            wv[u] = live ? x : u32x4v{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < kMmHiddenBatch; ++u) {
+            const int e = base + u * kMmThreads + tid;
+            if (e < hd_elems) {
+                const int r = e / Dp4, i = e - r * Dp4;
+                hd[r * pitch + i] = hv[u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kMmSlabBatch; ++u) {
+            const int i = sbase + u * kMmThreads + tid;
+            if (i < nv) dv[i] = wv[u];
+        }
+    }
+    if (!vec) {
+        const int ne = Dp4 * Hp;
+        for (int e = tid; e < ne; e += kMmThreads) {
+            const int row = e / Hp, col = e - row * Hp;
+            slab[e] = (row < rows && col < H) ? src[(size_t)row * H + col] : (uint16_t)0;
+        }
+    }
+    __syncthreads();
+
+    const int lo = lane & 15, kk = lane >> 4;
+    const int NT = (H + 15) / 16;
+    const int steps = Dp4 / 4;                                       // 4-row steps of the slice
+    double *dst = ws + ((size_t)rt * P + p) * kMmTileR * H;          // [16][H]
+    for (int g0 = 0; g0 < NT; g0 += kMmGroup) {
+        f64x4 acc[kMmGroup];
+#pragma unroll
+        for (int u = 0; u < kMmGroup; ++u) acc[u] = f64x4{0.0, 0.0, 0.0, 0.0};
+        const uint16_t *a_ptr = hd + lo * pitch + kk;                // + 4t
+        const uint16_t *b_ptr = slab + (size_t)kk * Hp + 16 * g0 + lo;   // + 4t*Hp + 16u
+        // operands of the next step are read from LDS while this step's products run
+        uint16_t an = 0, wn[kMmGroup];
+        if (wave < steps) {
+            an = a_ptr[4 * wave];
+#pragma unroll
+            for (int u = 0; u < kMmGroup; ++u) wn[u] = b_ptr[(size_t)4 * wave * Hp + 16 * u];
+        }
+        for (int t = wave; t < steps; t += kMmWaves) {
+            const uint16_t ab = an;
+            uint16_t wb[kMmGroup];
+#pragma unroll
+            for (int u = 0; u < kMmGroup; ++u) wb[u] = wn[u];
+            const int tn = min(t + kMmWaves, steps - 1);             // clamped: always a valid step
+            an = a_ptr[4 * tn];
+#pragma unroll
+            for (int u = 0; u < kMmGroup; ++u) wn[u] = b_ptr[(size_t)4 * tn * Hp + 16 * u];
+            const double a = widen_one<BF>(ab);
+#pragma unroll
+            for (int u = 0; u < kMmGroup; ++u)
+                acc[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, widen_one<BF>(wb[u]), acc[u], 0, 0, 0);
+        }
+        // add the waves' sums in a fixed order: ((w3 + w2) + w1) + w0
+        for (int w = kMmWaves - 1; w >= 0; --w) {
+            if (w != kMmWaves - 1) __syncthreads();
+            if (wave == w) {
+#pragma unroll
+                for (int u = 0; u < kMmGroup; ++u)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        double *slot = red + ((size_t)u * 4 + r) * 64 + lane;
+                        if (w == kMmWaves - 1) {
+                            *slot = acc[u][r];
+                        } else if (w > 0) {
+                            *slot = *slot + acc[u][r];
+                        } else {
+                            const int col = 16 * (g0 + u) + lo;
+                            if (col < H) dst[(size_t)(kk + 4 * r) * H + col] = *slot + acc[u][r];
+                        }
+                    }
+            }
+        }
+        __syncthreads();      // red is reused by the next group of columns
+    }
+}
+
+size_t mm_lds_bytes(int Dp, int H)
+{
+    const size_t slab = (size_t)((Dp + 3) / 4 * 4) * mm_slab_pitch(H) * 2;
+    const size_t hd = ((size_t)kMmTileR * mm_hidden_pitch(Dp) * 2 + 15) / 16 * 16;
+    return slab + hd + (size_t)kMmGroupMax * 4 * 64 * sizeof(double);
+}
+
+template <bool BF, int GRP>
+hipError_t launch_split_mfma_grp(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H, int k,
+                                 const RouterPlan &plan, int32_t *head_idx, float *logits_out,
+                                 double *ws, hipStream_t stream)
+{
+    const size_t lds = mm_lds_bytes(plan.Dp, H);
+    auto kern = router_partial_mfma_kernel<BF, GRP>;
+    static std::atomic<size_t> granted{0};
+    if (hipError_t e = ensure_dynamic_lds(kern, lds, granted); e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)plan.P, (unsigned)plan.RT), dim3(kMmThreads), lds, stream,
+                       hidden, Wr, B, D, H, plan.Dp, ws);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(router_finish_kernel, dim3((unsigned)B), dim3(POLAR_MAX_ROUTER_H), 0, stream, ws, H,
+                       k, plan.P, kMmTileR, head_idx, logits_out);
+    return hipGetLastError();
+}
+
+template <bool BF>
+hipError_t launch_split_mfma(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H, int k,
+                             const RouterPlan &plan, int32_t *head_idx, float *logits_out, double *ws,
+                             hipStream_t stream)
+{
+#define POLAR_MM_ARGS hidden, Wr, B, D, H, k, plan, head_idx, logits_out, ws, stream
+    switch (mm_group(H)) {
+    case 1: return launch_split_mfma_grp<BF, 1>(POLAR_MM_ARGS);
+    case 2: return launch_split_mfma_grp<BF, 2>(POLAR_MM_ARGS);
+    case 3: return launch_split_mfma_grp<BF, 3>(POLAR_MM_ARGS);
+    case 4: return launch_split_mfma_grp<BF, 4>(POLAR_MM_ARGS);
+    default: return launch_split_mfma_grp<BF, 5>(POLAR_MM_ARGS);
+    }
+#undef POLAR_MM_ARGS
 }
 
 template <bool BF>
@@ -403,6 +620,8 @@ hipError_t launch_split_dt(const uint16_t *hidden, const uint16_t *Wr, int B, in
                            const RouterPlan &plan, int32_t *head_idx, float *logits_out, double *ws,
                            hipStream_t stream)
 {
+    if (plan.mfma)
+        return launch_split_mfma<BF>(hidden, Wr, B, D, H, k, plan, head_idx, logits_out, ws, stream);
     const uintptr_t addr = reinterpret_cast<uintptr_t>(Wr);
     if (H % 8 == 0 && addr % 16 == 0)
         return launch_split_vec<BF, 8>(hidden, Wr, B, D, H, k, plan, head_idx, logits_out, ws, stream);
@@ -456,6 +675,40 @@ int make_router_plan(int B, int D, int H, RouterPlan *plan)
     if (B < 0 || D < 1 || H < 1) return POLAR_EINVAL;
     if (H > POLAR_MAX_ROUTER_H || D > POLAR_MAX_ROUTER_D || B > 0x7fffffff / 2)
         return POLAR_EUNSUPPORTED;
+    const char *env = getenv("POLAR_ROUTER_MFMA");          // 0 / 1 force the choice (tests, sweeps)
+    plan->mfma = B >= kMmTileR;
+    if (env && env[0] == '0') plan->mfma = false;
+    if (env && env[0] == '1') plan->mfma = true;
+    if (plan->mfma) {
+        // 16 requests per workgroup.  The slice length Dp (rows of Wr per workgroup, a multiple of
+        // 32 whose padded 16-bit copy fits 80 KiB of LDS) is the one that minimises
+        //   rounds of the 256 compute units x rows per workgroup   (the matrix-core time: an fp64
+        //                                                           tile product takes ~110 cycles)
+        //   + 40 rows' worth per 32 slices                          (the finish kernel adds the
+        //                                                           slices of a request 32 at a time).
+        // OPT-66B-shaped router (B=128, D=9216): Dp = 288, 32 slices x 8 tiles = 256 workgroups.
+        plan->RT = (B + kMmTileR - 1) / kMmTileR;
+        if (plan->RT > 65535) return POLAR_EUNSUPPORTED;         // grid.y limit
+        const long rt = plan->RT > 0 ? plan->RT : 1;
+        int dp_max = 320;
+        while (dp_max > 32 && (size_t)dp_max * mm_slab_pitch(H) * 2 > 81920) dp_max -= 32;
+        int dp = 32;
+        long best = -1;
+        for (int cand = 32; cand <= dp_max; cand += 32) {
+            const long slices = (D + cand - 1) / cand;
+            const long rounds = (rt * slices + 255) / 256;
+            const long cost = rounds * cand + 40 * ((slices + 31) / 32);
+            if (best < 0 || cost < best) {
+                best = cost;
+                dp = cand;
+            }
+        }
+        plan->Dp = dp;
+        plan->P = (D + dp - 1) / dp;
+        plan->bytes = ((size_t)plan->RT * plan->P * kMmTileR * H * sizeof(double) + 255) / 256 * 256;
+        if (plan->bytes == 0) plan->bytes = 256;
+        return POLAR_OK;
+    }
     plan->RT = (B + kTileR - 1) / kTileR;
     if (plan->RT > 65535) return POLAR_EUNSUPPORTED;             // grid.y limit
     const int rt = plan->RT > 0 ? plan->RT : 1;

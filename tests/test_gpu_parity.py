@@ -57,38 +57,39 @@ def poison_unselected(w, q, K, V, head_idx):
     q.view(w.B, w.Hkv, w.G, w.d)[~keep] = float("nan")
 
 
-# (pass a workspace?, forced path): without a workspace the one-kernel path runs; with one the
-# library picks the faster path for the shape unless POLAR_ROUTER_PATH forces the split-D kernels.
-ROUTER_MODES = [(False, None), (True, "split"), (True, None)]
+# (pass a workspace?, forced path, forced phase-1 kernel): without a workspace the one-kernel path
+# runs; with one the library picks the faster path for the shape unless POLAR_ROUTER_PATH forces the
+# split-D kernels, whose first phase runs on the vector ALU or (POLAR_ROUTER_MFMA) the matrix cores.
+ROUTER_MODES = [(False, None, None), (True, "split", "0"), (True, "split", "1"), (True, None, None)]
 
 
 @contextlib.contextmanager
-def router_path(path):
-    old = os.environ.get("POLAR_ROUTER_PATH")
-    if path is not None:
-        os.environ["POLAR_ROUTER_PATH"] = path
+def router_path(path, mfma=None):
+    saved = {}
+    for name, value in (("POLAR_ROUTER_PATH", path), ("POLAR_ROUTER_MFMA", mfma)):
+        if value is not None:
+            saved[name] = os.environ.get(name)
+            os.environ[name] = value
     try:
         yield
     finally:
-        if path is not None:
+        for name, old in saved.items():
             if old is None:
-                del os.environ["POLAR_ROUTER_PATH"]
+                del os.environ[name]
             else:
-                os.environ["POLAR_ROUTER_PATH"] = old
+                os.environ[name] = old
 
 
 def run_router(w):
     hidden, Wr = wl.make_router_inputs(w, DEV)
     ref_logits = orc.router_logits(host_bits(hidden), host_bits(Wr), w.dtype)
     want = orc.topk(ref_logits, w.k)
-    rws = polar.alloc_router_workspace(w.B, w.D, w.Hkv, DEV)
-    rws.fill_(0xFF)
-    for ws, path in ROUTER_MODES:             # one workgroup per request / split-D kernels / library's choice
+    for ws, path, mfma in ROUTER_MODES:
         logits = torch.full((w.B, w.Hkv), float("nan"), dtype=torch.float32, device=DEV)
         got = torch.full((w.B, w.k), -7, dtype=torch.int32, device=DEV)
-        with router_path(path):
-            polar.router_topk(hidden, Wr, w.k, head_idx=got, logits_out=logits,
-                              workspace=rws if ws else None)
+        with router_path(path, mfma):          # the workspace size depends on the phase-1 kernel
+            rws = polar.alloc_router_workspace(w.B, w.D, w.Hkv, DEV).fill_(0xFF) if ws else None
+            polar.router_topk(hidden, Wr, w.k, head_idx=got, logits_out=logits, workspace=rws)
         torch.cuda.synchronize()
         assert np.array_equal(got.cpu().numpy(), want), "head_idx differs from the oracle"
         np.testing.assert_allclose(logits.cpu().numpy(), ref_logits, rtol=2e-7, atol=1e-7)
@@ -577,13 +578,12 @@ def test_non_default_stream():
 def router_case(hidden, Wr, k, dtype):
     want = orc.router_topk(host_bits(hidden), host_bits(Wr), k, dtype)
     B, D = hidden.shape
-    rws = polar.alloc_router_workspace(B, D, Wr.shape[1], DEV)
-    rws.fill_(0xFF)
-    for ws, path in ROUTER_MODES:
-        with router_path(path):
-            got = polar.router_topk(hidden, Wr, k, workspace=rws if ws else None)
+    for ws, path, mfma in ROUTER_MODES:
+        with router_path(path, mfma):
+            rws = polar.alloc_router_workspace(B, D, Wr.shape[1], DEV).fill_(0xFF) if ws else None
+            got = polar.router_topk(hidden, Wr, k, workspace=rws)
         torch.cuda.synchronize()
-        assert np.array_equal(got.cpu().numpy(), want), (ws, path)
+        assert np.array_equal(got.cpu().numpy(), want), (ws, path, mfma)
     return want
 
 
