@@ -127,12 +127,12 @@ def test_config_full_parity(name):
     run_attention(w, head_idx)
 
 
-@pytest.mark.parametrize("name", ["C4_opt66b", "C5_ragged"])
+@pytest.mark.parametrize("name", ["C4_opt66b", "C5_ragged", "X1_gqa8_s8192"])
 def test_config_full_size_sampled_parity(name):
     """Full-size launch exactly as the bench times it; the oracle recomputes a sample of
     requests (shortest, longest and a few others), every other request is checked for
     finiteness and for exact zeros on skipped heads."""
-    w = wl.CONFIGS[name]
+    w = wl.CONFIGS.get(name) or wl.EXTRA_SHAPES[name]
     say("\ncase", name, w)
     head_idx = run_router(w)
     seqlens = wl.make_seqlens(w, "cpu")
