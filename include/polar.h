@@ -254,7 +254,7 @@ int polar_probe_read(const void *src, size_t slabs, size_t slab_bytes, int nonte
 const char *polar_strerror(int status);
 /* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */
 int polar_last_hip_error(void);
-/* ABI version: major * 1000 + minor. */
+/* ABI version: major * 1000 + minor (1100: adds polar_sha_launches and polar_probe_read; group sizes up to 16). */
 int polar_version(void);
 
 #ifdef __cplusplus

@@ -148,7 +148,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 1000; }
+int polar_version(void) { return 1100; }
 
 int polar_last_hip_error(void) { return g_last_hip_error; }
 
