@@ -20,51 +20,65 @@ int record(hipError_t e)
 
 bool dtype_ok(polar_dtype dt) { return dt == POLAR_F16 || dt == POLAR_BF16; }
 
-// Rows of the cache one workgroup of the streaming kernel covers.  Every workgroup pays a fixed
-// few microseconds (index loads, first-load latency, the merge epilogue) and every split adds a
-// record for the merge kernel, so chunks are as large as two things allow: occupancy (enough
-// splits that the grid holds about kFillWorkgroups workgroups) and the tail of the grid (a
-// lone workgroup streams far below the chip's bandwidth, so the work one workgroup carries is
-// capped at kMaxChunk rows).  A cache of at most 2*kMaxChunk rows is not split at all once the
-// (request, head) units alone give every compute unit a workgroup (kUnsplitUnits) and fill whole
-// rounds of compute units to at least 90 %: an unsplit
-// cache needs no merge kernel and no workspace traffic, which outweighs the lower occupancy
-// (LLaMA-2-7B-shaped layer, 512 units: 93.1 -> 87.7 us per step; LLaMA-3-8B GQA layer, 256
-// units: 96.6 -> 92.3 us).  Always a multiple of 128 rows, which every kernel shape's per-wave
-// step (16 to 64 rows) divides, so only a request's last chunk has a ragged tail.
-// POLAR_SHA_CHUNK_ROWS overrides the choice for tuning sweeps.
-// The grouped-query kernel holds only two 4-wave workgroups per compute unit (its two register
-// stages are large), so a workgroup in its prologue or epilogue idles a bigger share of the
-// unit; its cap is 4 times higher (76 % -> 83 % of peak on a 64/8-head, 8192-row shape).
-constexpr long kFillWorkgroups = 1024;
+// Rows of the cache one workgroup of the streaming kernel covers, i.e. into how many chunks a
+// (request, head) unit is split.  Every workgroup pays a fixed few microseconds (index loads,
+// first-load latency, the epilogue) and every split adds a record for the merge kernel, so the
+// number of splits is the smallest one for which
+//   (a) a chunk is short enough for the tail of the grid: a lone workgroup streams far below the
+//       chip's bandwidth, so the rows one workgroup carries are capped (kMaxChunk; an unsplit
+//       cache may be up to kMaxUnsplit rows: it saves the merge kernel and the workspace traffic),
+//   (b) the grid fills the chip (kFill workgroups; kComputeUnits for an unsplit cache), and
+//   (c) the workgroups fill whole rounds of the 256 compute units to at least 90 % (320 units on
+//       256 compute units: 134 us unsplit against 117 us in 3 chunks);
+// without (c) if no split count meets it.  Measured choices: LLaMA-2-7B-shaped layer, 512 units,
+// unsplit: 93.1 -> 87.7 us per step; LLaMA-3-8B GQA layer, 256 units, unsplit: 96.6 -> 92.3 us.
+// The grouped-query kernel has fewer, longer-lived workgroups per compute unit, so its fixed
+// costs weigh more: chunks up to 4096 rows, and 256 workgroups already fill the chip (a
+// 64-query-head / 8-group layer with 8192-row caches and 128 units: 84.6 us in chunks of 1024,
+// 82.4 us in chunks of 4096).  Its unsplit limit stays at 4096 rows: with ragged lengths longer
+// unsplit caches lose more to the grid's tail (770 against 697 us) than uniform ones gain.
+// Chunks are multiples of 128 rows, which every kernel shape's per-wave step divides, so only a
+// request's last chunk has a ragged tail.  POLAR_SHA_CHUNK_ROWS overrides the choice (sweeps).
 constexpr long kComputeUnits = 256;
-constexpr long kUnsplitUnits = kComputeUnits;
-constexpr int kMaxChunkPerHead = 1024;
-constexpr int kMaxChunkGrouped = 4096;
 constexpr int kMinChunk = 256;
 constexpr long kDirectMaxUnits = 2048;
+struct ChunkPolicy {
+    int max_chunk;     // rows per workgroup when the cache is split
+    int max_unsplit;   // longest cache that may stay in one piece
+    long fill;         // workgroups wanted in the grid when splitting
+};
+constexpr ChunkPolicy kPerHeadPolicy = {1024, 2048, 1024};
+constexpr ChunkPolicy kGroupedPolicy = {4096, 4096, 256};
 
-int choose_chunk(int B, int k, int S, int kMaxChunk)
+int choose_chunk(int B, int k, int S, const ChunkPolicy &pol)
 {
     const int cap = (S + 127) / 128 * 128;
-    long chunk;
     if (const char *env = getenv("POLAR_SHA_CHUNK_ROWS")) {
-        chunk = strtol(env, nullptr, 10);
+        long chunk = strtol(env, nullptr, 10);
         if (chunk < 128 || chunk > (1 << 20)) chunk = kMinChunk;
-    } else {
-        const long units = (long)(B > 0 ? B : 1) * k;
-        const long want_splits = (kFillWorkgroups + units - 1) / units;
-        chunk = (S + want_splits - 1) / want_splits;
-        // one workgroup per unit keeps the compute units evenly loaded only if the units fill
-        // whole rounds of them (320 units on 256 compute units: 134 us unsplit, 117 us split)
-        const long rounds = (units + kComputeUnits - 1) / kComputeUnits;
-        const bool even = units * 10 >= rounds * kComputeUnits * 9;
-        if (units >= kUnsplitUnits && even && S <= 2 * kMaxChunk) chunk = S;
-        else if (chunk > kMaxChunk) chunk = kMaxChunk;
-        if (chunk < kMinChunk) chunk = kMinChunk;
+        chunk = (chunk + 127) / 128 * 128;
+        return chunk < cap ? (int)chunk : cap;
     }
-    chunk = (chunk + 127) / 128 * 128;
-    return chunk < cap ? (int)chunk : cap;
+    const long units = (long)(B > 0 ? B : 1) * k;
+    int fallback = 0;
+    for (int want = 1;; ++want) {
+        int chunk = ((S + want - 1) / want + 127) / 128 * 128;
+        if (chunk < kMinChunk) chunk = kMinChunk;
+        if (chunk > cap) chunk = cap;
+        const int nsplit = (S + chunk - 1) / chunk;
+        const bool smallest = chunk <= kMinChunk;                    // no finer split exists
+        if (nsplit < want && !smallest) continue;                    // same chunk as an earlier `want`
+        const bool short_enough = nsplit == 1 ? S <= pol.max_unsplit : chunk <= pol.max_chunk;
+        const long wgs = units * nsplit;
+        const bool fills = wgs >= (nsplit == 1 ? kComputeUnits : pol.fill);
+        if ((short_enough && fills) || smallest) {
+            const long rounds = (wgs + kComputeUnits - 1) / kComputeUnits;
+            const bool even = wgs * 10 >= rounds * kComputeUnits * 9;
+            if (even || smallest) return fallback && !even ? fallback : chunk;
+            if (!fallback) fallback = chunk;
+            if (want - (S + fallback - 1) / fallback >= 8) return fallback;   // looked far enough
+        }
+    }
 }
 
 // Which router path is faster when the caller offers a workspace.  The one-workgroup-per-request
@@ -120,7 +134,7 @@ int make_sha_plan(int B, int Hq, int Hkv, int S, int d, int k, ShaPlan *plan)
     if (rc != POLAR_OK) return rc;
     plan->G = Hq / Hkv;
     const bool grouped_mfma = plan->G > 1 && d == 128;   // which streaming kernel will run
-    plan->chunk = choose_chunk(B, k, S, grouped_mfma ? kMaxChunkGrouped : kMaxChunkPerHead);
+    plan->chunk = choose_chunk(B, k, S, grouped_mfma ? kGroupedPolicy : kPerHeadPolicy);
     plan->nsplit = (S + plan->chunk - 1) / plan->chunk;
     // One-kernel form: an unsplit cache needs no merge; the streaming kernel can normalise, store
     // the rows and zero-fill the unselected heads itself.  That saves a launch (4 to 6 us per step

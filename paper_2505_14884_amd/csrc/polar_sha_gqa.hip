@@ -10,30 +10,35 @@
 // Why a second kernel: with G query rows per K/V row the vector-ALU formulation needs G dot
 // products, G cross-lane reductions and G*d multiply-adds per cache row, and at G = 4 and 8
 // that arithmetic, not HBM, sets the time.  A G x d by d x rows product is a (thin) matrix
-// product, so here S = K Q^T and O^T = V^T P^T run on v_mfma_f32_16x16x32 with the G heads
-// padded to the 16 columns of a tile; the vector ALU is left with the softmax of 8 scores per
-// lane and a few register permutes per 32 rows, the same for every G <= 16.
+// product, so here S = K Q^T runs on v_mfma_f32_16x16x32 and O^T = V^T P^T on
+// v_mfma_f32_16x16x16, with the G heads padded to the 16 columns of a tile; the vector ALU is
+// left with the softmax of 4 scores per lane and a few shifts per 16 rows, the same for every
+// G <= 16.
 //
-// Register layouts (lane = 16*hi + lo, one wave handles blocks of 32 consecutive rows):
+// Register layouts (lane = 16*hi + lo, one wave handles blocks of 16 consecutive rows):
 //   * K and V are both loaded with wave-wide reads of four whole 256-byte rows: lane (lo, hi),
-//     load u reads row 16(u/4) + 4hi + u%4 of the block, 16-byte piece lo (dims 8lo .. 8lo+7).
+//     load u reads row 4hi + u of the block, 16-byte piece lo (dims 8lo .. 8lo+7).
 //     (Loading K straight into the operand layout below would read 64-byte pieces of 16 rows
 //     per instruction, i.e. every 128-byte line twice; under load the second request often
 //     misses and K is fetched twice from HBM: 828 -> 721 us on a ragged 128/32-head layer.)
 //   * S = K Q^T: the K rows go through a wave-private LDS tile (no workgroup barrier) into
-//     the operand layout: tile T (rows 16T .. 16T+15), step s: lane holds row 16T + lo, dims
-//     32s + 8hi .. +7.  Q^T operand: lane holds head lo (zero for lo >= G), same dims.
-//     Result: lane holds the scores of head lo for rows 16T + 4hi + i, i = 0..3.
-//   * Those 8 scores (two tiles) are exactly the 8 contraction slots a lane must supply to
-//     the second product if slot u = 4T + i stands for row 16T + 4hi + i, which is the row
-//     that load u brought into this lane's group.  V is transposed *inside each lane* with
-//     shifts and masks: for dim e of the piece, the operand is {V[row(u)][8lo + e]}, u = 0..7.
-//     O^T tile e = (V^T)_e P^T: lane holds head lo, dims 8(4hi + i) + e, i = 0..3.
+//     the operand layout: step s: lane holds row lo, dims 32s + 8hi .. +7.  Q^T operand: lane
+//     holds head lo (zero for lo >= G), same dims.  Result: lane holds the scores of head lo
+//     for rows 4hi + i, i = 0..3.
+//   * Those 4 scores are exactly the 4 contraction slots a lane must supply to the second
+//     product (slot u = row 4hi + u, the row that load u brought into this lane's group).  V is
+//     transposed *inside each lane* with shifts and masks: for dim e of the piece, the operand
+//     is {V[4hi + u][8lo + e]}, u = 0..3.  O^T tile e = (V^T)_e P^T: lane holds head lo, dims
+//     8(4hi + i) + e, i = 0..3.
 //   * P is fed as two 16-bit terms (the rounded value and the rounded remainder), so the
 //     probabilities keep ~17 (bf16) or ~22 (fp16) significant bits; the products with the
 //     16-bit V values are exact and accumulate in fp32.
 //   * One running max per head, shared by the 4 lanes (hi = 0..3) of the head through two
 //     cross-lane exchanges per block; sums are kept per lane and added at the end.
+//   * Blocks of 16 rows rather than 32 keep the register stages (K: one, V: two) small enough
+//     for three waves per SIMD, i.e. three workgroups per compute unit: one that is starting or
+//     finishing then idles a third of the unit instead of half (LLaMA-3-8B GQA layer: 82.4 ->
+//     79.7 us; ragged 128/32-head layer in chunks of 4096: 719 -> 697 us).
 #include "polar_internal.h"
 
 namespace polar {
@@ -45,7 +50,7 @@ constexpr int kGqaWaves = POLAR_GQA_WAVES;   // build-time override for sweeps
 #else
 constexpr int kGqaWaves = 4;            // waves per workgroup
 #endif
-constexpr int kBlockRows = 32;          // cache rows one wave consumes per iteration
+constexpr int kBlockRows = 16;          // cache rows one wave consumes per iteration
 constexpr int kTilePitch = 2 * kD + 16; // bytes between rows of a wave's K tile in LDS: the 16
                                         // lanes of an operand read then fall in distinct banks
 constexpr int kTileBytes = kBlockRows * kTilePitch;
@@ -86,61 +91,57 @@ template <bool BF> __device__ __forceinline__ uint32_t round16(float x, float &b
     }
 }
 
-// Issue the loads of one 32-row block starting at row `rb`: 8 loads of K and 8 of V, each a
-// wave-wide read of four whole 256-byte rows (lane (lo, hi), load u: row 16(u/4) + 4hi + u%4 of
-// the block, 16-byte piece lo).  Row numbers are clamped to `last` (the last valid row of the
-// chunk), so every address is a valid row of this head whatever the block's overhang.
-__device__ __forceinline__ void load_block(u32x4 (&kx)[8], u32x4 (&vx)[8], const u32x4 *__restrict__ Kp,
-                                           const u32x4 *__restrict__ Vp, int rb, int last,
-                                           int row_stride, int lo, int hi)
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+// D[i][j] += sum_k A[i][k] * B[k][j] with k = 16: lane 16*hi + lo supplies A[lo][4hi..4hi+3] and
+// B[4hi..4hi+3][lo] (four 16-bit values each) and receives D[4hi + 0..3][lo].
+template <bool BF> __device__ __forceinline__ f32x4 mfma_k16(const u32x2 &a, const u32x2 &b, f32x4 c)
 {
-    size_t off[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-        off[u] = (size_t)min(rb + 16 * (u / 4) + 4 * hi + (u % 4), last) * row_stride + lo;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) kx[u] = load_nt(Kp + off[u]);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) vx[u] = load_nt(Vp + off[u]);
+    if constexpr (BF)
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4, a),
+                                                         __builtin_bit_cast(i16x4, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, a),
+                                                     __builtin_bit_cast(f16x4, b), c, 0, 0, 0);
 }
 
-// Consume one block: scores, online softmax step, and the P V accumulation.
-template <bool BF>
-__device__ __forceinline__ void consume_block(const u32x4 (&kx)[8], const u32x4 (&vx)[8],
-                                              const u32x4 (&qs)[4], unsigned char *tile, int rb,
-                                              int last, int lo, int hi, float c, float &m, float &l,
-                                              f32x4 (&o)[8])
+// Four wave-wide loads of four whole rows each: lane (lo, hi), load u reads row 4hi + u of the
+// 16-row block at `rb`, 16-byte piece lo; rows clamped to `last`.
+__device__ __forceinline__ void load_rows16(u32x4 (&x)[4], const u32x4 *__restrict__ p, int rb, int last,
+                                            int row_stride, int lo, int hi)
 {
-    // K rows -> wave-private LDS tile (row pitch padded by 16 bytes) -> operand layout.  LDS
-    // serves one wave's accesses in program order, so the reads see the writes of all lanes.
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-        *reinterpret_cast<u32x4 *>(tile + (16 * (u / 4) + 4 * hi + (u % 4)) * kTilePitch + 16 * lo) = kx[u];
+    for (int u = 0; u < 4; ++u)
+        x[u] = load_nt(p + (size_t)min(rb + 4 * hi + u, last) * row_stride + lo);
+}
+
+__device__ __forceinline__ void stash_k16(unsigned char *tile, const u32x4 (&kx)[4], int lo, int hi)
+{
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        *reinterpret_cast<u32x4 *>(tile + (4 * hi + u) * kTilePitch + 16 * lo) = kx[u];
     __builtin_amdgcn_wave_barrier();
-    f32x4 s0 = {0.0f, 0.0f, 0.0f, 0.0f}, s1 = {0.0f, 0.0f, 0.0f, 0.0f};
+}
+
+// One 16-row block: K already in the wave's LDS tile, V rows in registers.
+template <bool BF>
+__device__ __forceinline__ void consume_block16(const unsigned char *tile, const u32x4 (&vx)[4],
+                                                const u32x4 (&qs)[4], int rb, int last, int lo, int hi,
+                                                float c, float &m, float &l, f32x4 (&o)[8])
+{
+    f32x4 s0 = {0.0f, 0.0f, 0.0f, 0.0f};
     const unsigned char *rd = tile + lo * kTilePitch + 16 * hi;
 #pragma unroll
     for (int s = 0; s < 4; ++s)
         s0 = mfma<BF>(*reinterpret_cast<const u32x4 *>(rd + 64 * s), qs[s], s0);
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-        s1 = mfma<BF>(*reinterpret_cast<const u32x4 *>(rd + 16 * kTilePitch + 64 * s), qs[s], s1);
     __builtin_amdgcn_wave_barrier();
 
-    float sc[8];
+    float sc[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        sc[i] = s0[i] * c;
-        sc[4 + i] = s1[i] * c;
-    }
-    const int row0 = rb + 4 * hi;      // slot u stands for row row0 + 16(u/4) + u%4
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-        if (row0 + 16 * (u / 4) + (u % 4) > last) sc[u] = -INFINITY;
-
-    float mx = sc[0];
-#pragma unroll
-    for (int u = 1; u < 8; ++u) mx = fmaxf(mx, sc[u]);
+    for (int i = 0; i < 4; ++i) sc[i] = (rb + 4 * hi + i > last) ? -INFINITY : s0[i] * c;
+    float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m, mx);
@@ -148,9 +149,9 @@ __device__ __forceinline__ void consume_block(const u32x4 (&kx)[8], const u32x4 
     m = m_new;
 
     float psum = 0.0f;
-    uint32_t ph[8], pl[8];
+    uint32_t ph[4], pl[4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < 4; ++u) {
         const float p = fast_exp2(sc[u] - m_new);
         psum += p;
         float back, unused;
@@ -158,36 +159,31 @@ __device__ __forceinline__ void consume_block(const u32x4 (&kx)[8], const u32x4 
         pl[u] = round16<BF>(p - back, unused);
     }
     l = l * alpha + psum;
-    u32x4 bh, bl;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        bh[t] = ph[2 * t] | (ph[2 * t + 1] << 16);
-        bl[t] = pl[2 * t] | (pl[2 * t + 1] << 16);
-    }
+    const u32x2 bh = {ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16)};
+    const u32x2 bl = {pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16)};
 
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        // rows (2t, 2t+1) of dim e of this lane's 16-byte piece: halves of dword e/2
-        u32x4 a;
+        u32x2 a;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < 2; ++t)
             a[t] = (e & 1) ? ((vx[2 * t][e / 2] >> 16) | (vx[2 * t + 1][e / 2] & 0xffff0000u))
                            : ((vx[2 * t][e / 2] & 0xffffu) | (vx[2 * t + 1][e / 2] << 16));
         f32x4 acc = o[e] * alpha;
-        acc = mfma<BF>(a, bh, acc);
-        o[e] = mfma<BF>(a, bl, acc);
+        acc = mfma_k16<BF>(a, bh, acc);
+        o[e] = mfma_k16<BF>(a, bl, acc);
     }
 }
 
 // Streaming kernel for grouped heads.  1-D grid of B*nsplit*k workgroups decoded as in the
 // per-head kernel (slot fastest, so the equal-sized workgroups of one (request, chunk) spread
-// over the XCDs); block = 4 waves.  Wave w takes blocks w, w+4, ... of the chunk.  Two register
-// stages: the loads of the next block are in flight while the current one is consumed.
+// over the XCDs); block = 4 waves.  Wave w takes blocks w, w+4, ... of the chunk; the loads of
+// the next block are in flight while the current one is consumed.
 // Workspace records as in the per-head kernel: unit = ((b*k + slot)*G + g)*nsplit + split.
 // DIRECT (only with nsplit == 1): final normalised rows go to `out` and one wave zero-fills this
 // slot's share of the unselected heads, as in the per-head kernel; no merge kernel runs.
 template <bool BF, bool ROW_MAJOR_SEQ, bool DIRECT>
-__global__ __launch_bounds__(kGqaWaves * 64) void sha_partial_gqa_kernel(
+__global__ __launch_bounds__(kGqaWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 3))) void sha_partial_gqa_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int32_t *__restrict__ seqlens, const int32_t *__restrict__ head_idx,
     float *__restrict__ ws_o, float *__restrict__ ws_ml, float *__restrict__ out, int Hq, int Hkv,
@@ -223,9 +219,10 @@ __global__ __launch_bounds__(kGqaWaves * 64) void sha_partial_gqa_kernel(
     const u32x4 *__restrict__ Kp = reinterpret_cast<const u32x4 *>(K + slab);
     const u32x4 *__restrict__ Vp = reinterpret_cast<const u32x4 *>(V + slab);
 
-    static_assert(kGqaWaves * kTileBytes >= (int)(kGqaWaves * POLAR_MAX_GROUP * kD * sizeof(float)),
-                  "the merge buffers alias the K tiles");
-    __shared__ __align__(16) unsigned char smem[kGqaWaves * kTileBytes];
+    // one buffer: the waves' K tiles during the loop, their partial results after it
+    constexpr int kMergeBytes = kGqaWaves * POLAR_MAX_GROUP * kD * (int)sizeof(float);
+    constexpr int kSmemBytes = kGqaWaves * kTileBytes > kMergeBytes ? kGqaWaves * kTileBytes : kMergeBytes;
+    __shared__ __align__(16) unsigned char smem[kSmemBytes];
     unsigned char *tile = smem + wave * kTileBytes;
 
     u32x4 qs[4];
@@ -244,32 +241,40 @@ __global__ __launch_bounds__(kGqaWaves * 64) void sha_partial_gqa_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // blocks of this wave: rows row_begin + 32*(wave + 4*it), it = 0 .. n_it-1
+    // Blocks of 16 rows: wave w takes blocks w, w+4, ... of the chunk.  K has one register stage
+    // (its rows go to the wave's LDS tile first thing, which frees the registers for the next
+    // block's loads), V two.  Blocks are taken in pairs so that the body has no branch between a
+    // load and its use (the compiler would otherwise sink the loads below the branch, next to the
+    // use); the scheduling fences keep the next block's loads ahead of the waits on this one.
     const int rows = row_end - row_begin;
+    constexpr int kStep = kBlockRows * kGqaWaves;
     const int n_blocks = (rows + kBlockRows - 1) / kBlockRows;
     const int n_it = n_blocks > wave ? (n_blocks - wave + kGqaWaves - 1) / kGqaWaves : 0;
     const int rb0 = row_begin + kBlockRows * wave;
-    constexpr int kStep = kBlockRows * kGqaWaves;
-
     if (n_it > 0) {
-        u32x4 ka[8], va[8], kb[8], vb[8];
-        load_block(ka, va, Kp, Vp, rb0, last, row_stride, lo, hi);
-        // Blocks are taken in pairs so that the body has no branch between a load and its use
-        // (the compiler would otherwise sink the loads below the branch, next to the use); the
-        // scheduling fences keep the next block's loads ahead of the waits on the current one.
+        u32x4 kr[4], va[4], vb[4];
+        load_rows16(kr, Kp, rb0, last, row_stride, lo, hi);
+        load_rows16(va, Vp, rb0, last, row_stride, lo, hi);
         int it = 0;
         for (; it + 2 <= n_it; it += 2) {
             const int rb = rb0 + it * kStep;
-            load_block(kb, vb, Kp, Vp, rb + kStep, last, row_stride, lo, hi);
+            stash_k16(tile, kr, lo, hi);
+            load_rows16(kr, Kp, rb + kStep, last, row_stride, lo, hi);
+            load_rows16(vb, Vp, rb + kStep, last, row_stride, lo, hi);
             __builtin_amdgcn_sched_barrier(0);
-            consume_block<BF>(ka, va, qs, tile, rb, last, lo, hi, c, m, l, o);
+            consume_block16<BF>(tile, va, qs, rb, last, lo, hi, c, m, l, o);
             __builtin_amdgcn_sched_barrier(0);
-            load_block(ka, va, Kp, Vp, rb + 2 * kStep, last, row_stride, lo, hi);
+            stash_k16(tile, kr, lo, hi);
+            load_rows16(kr, Kp, rb + 2 * kStep, last, row_stride, lo, hi);
+            load_rows16(va, Vp, rb + 2 * kStep, last, row_stride, lo, hi);
             __builtin_amdgcn_sched_barrier(0);
-            consume_block<BF>(kb, vb, qs, tile, rb + kStep, last, lo, hi, c, m, l, o);
+            consume_block16<BF>(tile, vb, qs, rb + kStep, last, lo, hi, c, m, l, o);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (it < n_it) consume_block<BF>(ka, va, qs, tile, rb0 + it * kStep, last, lo, hi, c, m, l, o);
+        if (it < n_it) {
+            stash_k16(tile, kr, lo, hi);
+            consume_block16<BF>(tile, va, qs, rb0 + it * kStep, last, lo, hi, c, m, l, o);
+        }
     }
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
@@ -334,15 +339,16 @@ hipError_t launch_sha_partial_gqa(const void *q, const void *K, const void *V, c
     const uint16_t *q16 = static_cast<const uint16_t *>(q);
     const uint16_t *K16 = static_cast<const uint16_t *>(K);
     const uint16_t *V16 = static_cast<const uint16_t *>(V);
+#define POLAR_GQA_LAUNCH3(BF, RMS, DIR)                                                             \
+    hipLaunchKernelGGL((sha_partial_gqa_kernel<BF, RMS, DIR>), grid, block, 0, stream, q16, K16, V16,  \
+                       seqlens, head_idx, ws_o, ws_ml, direct_out, Hq, Hkv, S, k, plan.G, plan.chunk, \
+                       plan.nsplit, scale_log2e)
 #define POLAR_GQA_LAUNCH(BF, RMS)                                                                   \
-    if (direct_out)                                                                                 \
-        hipLaunchKernelGGL((sha_partial_gqa_kernel<BF, RMS, true>), grid, block, 0, stream, q16,    \
-                           K16, V16, seqlens, head_idx, ws_o, ws_ml, direct_out, Hq, Hkv, S, k,     \
-                           plan.G, plan.chunk, plan.nsplit, scale_log2e);                           \
-    else                                                                                            \
-        hipLaunchKernelGGL((sha_partial_gqa_kernel<BF, RMS, false>), grid, block, 0, stream, q16,   \
-                           K16, V16, seqlens, head_idx, ws_o, ws_ml, direct_out, Hq, Hkv, S, k,     \
-                           plan.G, plan.chunk, plan.nsplit, scale_log2e)
+    if (direct_out) {                                                                               \
+        POLAR_GQA_LAUNCH3(BF, RMS, true);                                                           \
+    } else {                                                                                        \
+        POLAR_GQA_LAUNCH3(BF, RMS, false);                                                          \
+    }
     const bool bf = dt == POLAR_BF16, rms = layout == POLAR_KV_BSHD;
     if (bf && rms) {
         POLAR_GQA_LAUNCH(true, true);
@@ -354,6 +360,7 @@ hipError_t launch_sha_partial_gqa(const void *q, const void *K, const void *V, c
         POLAR_GQA_LAUNCH(false, false);
     }
 #undef POLAR_GQA_LAUNCH
+#undef POLAR_GQA_LAUNCH3
     return hipGetLastError();
 }
 
