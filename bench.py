@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # --phase partial / --phase copy on the default shape of each workload.  Source:
 # profiles/sha_decode_step_<workload>.md.  Reported only when the shape is that default.
 MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4533969067, "C5_ragged": 4480275675,
-                          "C3_llama3_8b_gqa": 538463068, "C2_llama2_7b": 504121882}
+                          "C3_llama3_8b_gqa": 538364712, "C2_llama2_7b": 504121882}
 DEFAULT_WORKLOAD = "C4_opt66b"
 
 
