@@ -61,6 +61,9 @@ def parse_args():
                     help="workload of --phase select_gemm (see workloads.MLP_CONFIGS)")
     ap.add_argument("--density", type=float, default=0.0,
                     help="--phase select_gemm: override the target union density")
+    ap.add_argument("--gemm-form", choices=["wide", "narrow"], default="wide",
+                    help="--phase select_gemm: 'wide' passes a workspace (128-neuron tiles, evenly split "
+                         "fixed-size launch + reduction), 'narrow' calls the 32-neuron one-launch kernel")
     ap.add_argument("--phase", choices=["all", "partial", "copy", "select_gemm", "select_gemm_only"],
                     default="all",
                     help="'partial' launches only the KV-streaming kernel (for counter runs); "
@@ -92,8 +95,11 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                                   count.data_ptr(), st())
         assert rc == 0, rc
 
+    workspace = polar.alloc_select_gemm_workspace(w.B, dev) if args.gemm_form == "wide" else None
+    wide = workspace is not None
+
     def gemm(i=0):
-        polar.select_gemm(x, W1, idx, count=count, relu=True, out=out)
+        polar.select_gemm(x, W1, idx, count=count, relu=True, out=out, workspace=workspace)
 
     union()
     torch.cuda.synchronize()
@@ -133,7 +139,7 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
     gemm_ms = ev(gemm, n_ev)
     union_ms = ev(union, n_ev)
     dense_ms = float("nan") if args.no_dense else ev(
-        lambda: polar.select_gemm(x, W1, all_idx, relu=True, out=dense_out), max(5, n_ev // 4))
+        lambda: polar.select_gemm(x, W1, all_idx, relu=True, out=dense_out, workspace=workspace), max(5, n_ev // 4))
     achieved = bytes_sel / (gemm_ms * 1e-3) / 1e9
     result = {
         "metric": "selective fused-gather GEMM effective weight HBM GB/s (gathered rows' bytes / step "
@@ -149,7 +155,8 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                          "dense_gemm_all_rows": None if args.no_dense else round(dense_ms * 1e3, 2)},
         "dense_over_selective": None if args.no_dense else round(dense_ms / gemm_ms, 3),
         "ideal_N_over_selected": round(w.N / max(n_sel, 1), 3),
-        "roofline": {"kernel": "select_gemm_kernel", "bound": "hbm", "achieved": round(achieved, 1),
+        "roofline": {"kernel": "select_gemm_stream_kernel + select_gemm_reduce_kernel" if wide else "select_gemm_kernel",
+                     "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "avg_us": round(gemm_ms * 1e3, 2),
                      "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),

@@ -224,6 +224,25 @@ int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const in
                       float *C, int M, int K, int N, int cap, polar_dtype dt, int relu, void *stream);
 
 /*
+ * The same operation with a workspace (Appendix "Sparse Kernels", Algorithm 3; same arguments,
+ * same result up to the order of the float additions).  For M <= 64 the library then runs a
+ * form built for decode batches: 128-neuron tiles and a fixed-size launch whose workgroups
+ * split the (neuron tile, K block) work evenly whatever the live count is, followed by a
+ * small kernel that adds the pieces of each tile in a fixed order (two launches; results are
+ * reproducible for given sizes, count and workspace size).  For larger M, or with workspace
+ * NULL, it runs the kernel of polar_select_gemm.
+ *   workspace        scratch, DEVICE pointer, 16-byte aligned, caller-owned; contents are
+ *                    overwritten; calls that overlap in time need separate workspaces
+ *   workspace_bytes  its size; polar_select_gemm_workspace_bytes(M) gives the size at which
+ *                    the launch is as wide as the library wants it (0 for M > 64); a smaller
+ *                    workspace narrows the launch, it is not an error
+ */
+int polar_select_gemm_workspace_bytes(int M, size_t *bytes);
+int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                         float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Batch neuron index (Section 4.1: the predicted activations of all requests are aggregated
  * into one index tensor; Section 3.1: the union set S_B).
  *
@@ -254,7 +273,8 @@ int polar_probe_read(const void *src, size_t slabs, size_t slab_bytes, int nonte
 const char *polar_strerror(int status);
 /* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */
 int polar_last_hip_error(void);
-/* ABI version: major * 1000 + minor (1100: adds polar_sha_launches and polar_probe_read; group sizes up to 16). */
+/* ABI version: major * 1000 + minor (1100: adds polar_sha_launches and polar_probe_read; group sizes up to 16;
+ * 1200: adds polar_select_gemm_ws and polar_select_gemm_workspace_bytes). */
 int polar_version(void);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_head_norm_topk", "polar_select_gemm", "polar_neuron_union", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_neuron_union", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.polar_head_norm_topk.restype = i
         L.polar_select_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
         L.polar_select_gemm.restype = i
+        L.polar_select_gemm_ws.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp, ctypes.c_size_t, vp]
+        L.polar_select_gemm_ws.restype = i
+        L.polar_select_gemm_workspace_bytes.argtypes = [i, ctypes.POINTER(ctypes.c_size_t)]
+        L.polar_select_gemm_workspace_bytes.restype = i
         L.polar_neuron_union.argtypes = [vp, i, i, i, i, vp, vp, vp]
         L.polar_neuron_union.restype = i
         L.polar_strerror.argtypes = [i]
@@ -258,11 +262,25 @@ def head_norm_topk(attn_out: torch.Tensor, Hkv: int, k: int,
     return head_idx
 
 
+def select_gemm_workspace_bytes(M: int) -> int:
+    """Workspace size at which polar_select_gemm_ws launches as wide as it wants (0 for M > 64)."""
+    n = ctypes.c_size_t(0)
+    _check(lib().polar_select_gemm_workspace_bytes(M, ctypes.byref(n)), "polar_select_gemm_workspace_bytes")
+    return int(n.value)
+
+
+def alloc_select_gemm_workspace(M: int, device) -> Optional[torch.Tensor]:
+    n = select_gemm_workspace_bytes(M)
+    return torch.empty(n, dtype=torch.uint8, device=device) if n else None
+
+
 def select_gemm(A: torch.Tensor, W: torch.Tensor, idx: torch.Tensor,
                 count: Optional[torch.Tensor] = None, relu: bool = True,
-                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """act(A @ W[idx].T): A [M,K], W [N,K] (fp16/bf16, one row per neuron), idx int32 [cap],
-    count int32 [1] on the device (None: all of idx is live) -> float32 [M,cap]."""
+    count int32 [1] on the device (None: all of idx is live) -> float32 [M,cap].  With a
+    workspace (alloc_select_gemm_workspace) the call goes to polar_select_gemm_ws."""
     M, K = A.shape
     N, K2 = W.shape
     if K != K2 or A.dtype != W.dtype:
@@ -270,6 +288,13 @@ def select_gemm(A: torch.Tensor, W: torch.Tensor, idx: torch.Tensor,
     cap = idx.shape[0]
     if out is None:
         out = torch.zeros((M, cap), dtype=torch.float32, device=A.device)
+    if workspace is not None:
+        rc = lib().polar_select_gemm_ws(_dev(A, "A"), _dev(W, "W"), _dev(idx, "idx", torch.int32),
+                                        _dev(count, "count", torch.int32), _dev(out, "out", torch.float32),
+                                        M, K, N, cap, _dtype_code(A), 1 if relu else 0,
+                                        _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
+        _check(rc, "polar_select_gemm_ws")
+        return out
     rc = lib().polar_select_gemm(_dev(A, "A"), _dev(W, "W"), _dev(idx, "idx", torch.int32),
                                  _dev(count, "count", torch.int32), _dev(out, "out", torch.float32),
                                  M, K, N, cap, _dtype_code(A), 1 if relu else 0, _stream())

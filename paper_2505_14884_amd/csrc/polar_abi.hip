@@ -162,7 +162,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 1100; }
+int polar_version(void) { return 1200; }
 
 int polar_last_hip_error(void) { return g_last_hip_error; }
 
@@ -347,6 +347,26 @@ int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const in
     if (((uintptr_t)A & 15u) || ((uintptr_t)W & 15u)) return POLAR_EINVAL;   // 16-byte loads
     return record(launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu,
                                      static_cast<hipStream_t>(stream)));
+}
+
+int polar_select_gemm_workspace_bytes(int M, size_t *bytes)
+{
+    if (M < 0 || !bytes) return POLAR_EINVAL;
+    *bytes = select_gemm_workspace_bytes(M);
+    return POLAR_OK;
+}
+
+int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                         float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (M < 0 || K < 1 || N < 1 || cap < 0 || !dtype_ok(dt)) return POLAR_EINVAL;
+    if (K % 128 != 0 || (long long)N * K > (1ll << 40)) return POLAR_EUNSUPPORTED;
+    if (M == 0 || cap == 0) return POLAR_OK;
+    if (!A || !W || !idx || !C) return POLAR_EINVAL;
+    if (((uintptr_t)A & 15u) || ((uintptr_t)W & 15u) || ((uintptr_t)workspace & 15u)) return POLAR_EINVAL;
+    return record(launch_select_gemm_ws(A, W, idx, count, C, M, K, N, cap, dt, relu, workspace,
+                                        workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream)));
 }
 
 int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,

@@ -132,6 +132,24 @@ def test_select_gemm_and_union_argument_errors():
     assert g(A=ctypes.c_void_p(0x1008)) == EINVAL         # 16-byte alignment
     assert g(M=0, A=None, W=None, idx=None, C=None) == OK
     assert g(cap=0, idx=None, C=None) == OK
+    # the workspace form checks the same things, and its workspace's alignment
+    gw = lambda A=A16, W=A16, idx=FAKE, C=FAKE, M=4, K=256, N=64, cap=32, dt=0, ws=None, wsb=0: \
+        L.polar_select_gemm_ws(A, W, idx, None, C, M, K, N, cap, dt, 1, ws, wsb, None)
+    assert gw(M=-1) == EINVAL and gw(K=0) == EINVAL and gw(N=0) == EINVAL and gw(cap=-1) == EINVAL
+    assert gw(dt=3) == EINVAL and gw(K=200) == EUNSUPPORTED
+    assert gw(A=None) == EINVAL and gw(W=None) == EINVAL and gw(idx=None) == EINVAL and gw(C=None) == EINVAL
+    assert gw(ws=ctypes.c_void_p(0x1004), wsb=1 << 20) == EINVAL
+    assert gw(M=0, A=None, W=None, idx=None, C=None) == OK and gw(cap=0, idx=None, C=None) == OK
+    n = ctypes.c_size_t(7)
+    assert L.polar_select_gemm_workspace_bytes(-1, ctypes.byref(n)) == EINVAL
+    assert L.polar_select_gemm_workspace_bytes(4, None) == EINVAL
+    sizes = []
+    for M in (1, 16, 17, 32, 33, 64, 65, 4096):
+        assert L.polar_select_gemm_workspace_bytes(M, ctypes.byref(n)) == OK
+        sizes.append(n.value)
+    assert sizes[0] == sizes[1] > 0 and sizes[2] == sizes[3] == 2 * sizes[0]
+    assert sizes[4] == sizes[5] == 4 * sizes[0] and sizes[6] == sizes[7] == 0
+    assert polar.select_gemm_workspace_bytes(64) == sizes[5]
     u = lambda topk=FAKE, B=2, kn=3, N=64, cap=6, idx=FAKE, cnt=FAKE: L.polar_neuron_union(
         topk, B, kn, N, cap, idx, cnt, None)
     assert u(B=-1) == EINVAL and u(N=0) == EINVAL and u(cap=-1) == EINVAL

@@ -436,7 +436,25 @@ def test_head_importance_labels(name):
 GEMM_TOL = 1e-4      # float accumulation of K <= 9216 products whose sum is O(1): ~sqrt(K) * 2^-24 * |sum| ~ 1e-5
 
 
-def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0):
+@contextlib.contextmanager
+def gemm_workgroups(G):
+    """Pin the launch width of the wide-tile GEMM form (None: the library's own)."""
+    saved = os.environ.get("POLAR_GEMM_WGS")
+    if G is not None:
+        os.environ["POLAR_GEMM_WGS"] = str(G)
+    try:
+        yield
+    finally:
+        if G is not None:
+            if saved is None:
+                del os.environ["POLAR_GEMM_WGS"]
+            else:
+                os.environ["POLAR_GEMM_WGS"] = saved
+
+
+def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0, ws=False, G=None, ws_bytes=None):
+    """ws: call the workspace entry point (wide-tile form for M <= 64); G pins its launch width;
+    ws_bytes shrinks the workspace below the recommended size."""
     g = torch.Generator(device=DEV).manual_seed(1000 + seed)
     tdt = torch.float16 if dtype == "f16" else torch.bfloat16
     A = torch.randn((M, K), generator=g, device=DEV).to(tdt)
@@ -444,7 +462,14 @@ def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0):
     idx = torch.tensor(idx_host, dtype=torch.int32, device=DEV)
     cnt = None if count is None else torch.tensor([count], dtype=torch.int32, device=DEV)
     out = torch.full((M, len(idx_host)), float("nan"), dtype=torch.float32, device=DEV)
-    polar.select_gemm(A, W, idx, count=cnt, relu=relu, out=out)
+    workspace = None
+    if ws:
+        nbytes = polar.select_gemm_workspace_bytes(M) if ws_bytes is None else ws_bytes
+        # poisoned: the kernels must write every slot they later read; a zero-size recommendation
+        # (M > 64) still goes through the workspace entry point with a token buffer
+        workspace = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    with gemm_workgroups(G):
+        polar.select_gemm(A, W, idx, count=cnt, relu=relu, out=out, workspace=workspace)
     torch.cuda.synchronize()
     live = len(idx_host) if count is None else max(0, min(count, len(idx_host)))
     want = orc.select_gemm(host_bits(A), host_bits(W), np.array(idx_host[:live], np.int32), dtype, relu)
@@ -456,15 +481,44 @@ def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0):
     return err
 
 
+@pytest.mark.parametrize("ws", [False, True])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("M", [1, 5, 64, 65, 130, 256, 300])
-def test_select_gemm_shapes(dtype, M):
-    say("\ncase select_gemm", dtype, M)
+@pytest.mark.parametrize("M", [1, 5, 17, 33, 64, 65, 130, 256, 300])
+def test_select_gemm_shapes(dtype, M, ws):
+    say("\ncase select_gemm", dtype, M, "workspace" if ws else "")
     rng = np.random.default_rng(M)
     N, K = 500, 384
     idx = rng.permutation(N)[:77].tolist()                 # 77: two full tiles and a ragged one
-    say("   err %.2e" % gemm_case(M, K, N, idx, dtype, relu=True, seed=M))
-    say("   err %.2e" % gemm_case(M, K, N, idx, dtype, relu=False, seed=M + 1))
+    say("   err %.2e" % gemm_case(M, K, N, idx, dtype, relu=True, seed=M, ws=ws))
+    say("   err %.2e" % gemm_case(M, K, N, idx, dtype, relu=False, seed=M + 1, ws=ws))
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 5, 7, 11, 24, None])
+def test_select_gemm_wide_form_spans(G):
+    """The wide-tile form cuts 3 tiles x 8 K blocks into G spans: whole tiles finished in place
+    (G = 1, 3), tiles shared by several workgroups (first / last slot), odd and even block
+    counts, and spans left empty when the live count is below the capacity."""
+    say("\ncase select_gemm spans G =", G)
+    rng = np.random.default_rng(77)
+    N, K = 700, 1024
+    idx = rng.permutation(N)[:300].tolist()                # 3 tiles of 128, the last ragged
+    idx[5], idx[200] = -1, N                               # invalid ids give zero columns
+    for M, dtype in ((64, "f16"), (20, "bf16"), (3, "f16")):
+        gemm_case(M, K, N, idx, dtype, relu=True, seed=3, ws=True, G=G)
+        gemm_case(M, K, N, idx, dtype, relu=False, seed=4, ws=True, G=G, count=130)   # 2 live tiles
+        gemm_case(M, K, N, idx, dtype, relu=False, seed=5, ws=True, G=G, count=0)
+
+
+def test_select_gemm_small_workspace_narrows_the_launch():
+    say("\ncase select_gemm small workspace")
+    rng = np.random.default_rng(78)
+    idx = rng.permutation(700)[:300].tolist()
+    full = polar.select_gemm_workspace_bytes(64)
+    assert full > 0 and polar.select_gemm_workspace_bytes(65) == 0
+    one = 2 * 4 * 8 * 64 * 16          # a workgroup's two slots: 4 waves x 8 accumulator tiles x 64 lanes x 16 B
+    assert full % one == 0
+    for nbytes in (one, 3 * one, one - 16, 0):             # launch of 1 workgroup, of 3, narrow kernel, narrow kernel
+        gemm_case(64, 1024, 700, idx, "f16", relu=True, seed=6, ws=True, ws_bytes=nbytes)
 
 
 def test_select_gemm_invalid_ids_count_and_long_k():
@@ -475,6 +529,9 @@ def test_select_gemm_invalid_ids_count_and_long_k():
     gemm_case(9, 128, 100, idx, "bf16", relu=False, count=0)
     gemm_case(9, 128, 100, idx, "f16", relu=True, count=1000)   # count beyond capacity is clamped
     gemm_case(33, 9216, 64, list(range(64)), "f16", relu=True)  # the OPT-66B contraction length
+    for ws in (False, True):
+        gemm_case(9, 128, 100, idx, "bf16", relu=False, count=17, ws=ws)
+        gemm_case(64, 9216, 300, list(range(299, -1, -1)), "bf16", relu=True, ws=ws)
 
 
 def test_neuron_union_matches_oracle():
@@ -495,15 +552,17 @@ def test_neuron_union_matches_oracle():
     assert int(count.item()) == 25 and idx.cpu().tolist() == list(range(25))
 
 
+@pytest.mark.parametrize("ws", [False, True])
 @pytest.mark.parametrize("name", ["M1_tiny", "M2_opt66b_ffn"])
-def test_sparse_mlp_first_layer(name):
+def test_sparse_mlp_first_layer(name, ws):
     """Union index built on the device feeds the selective GEMM without a host round trip;
     the oracle recomputes a sample of the selected neurons."""
     w = wl.MLP_CONFIGS[name]
     say("\ncase", w)
     x, W1, topk = wl.make_mlp_inputs(w, DEV)
+    workspace = polar.alloc_select_gemm_workspace(w.B, DEV) if ws else None
     idx, count = polar.neuron_union(topk, w.N)
-    out = polar.select_gemm(x, W1, idx, count=count, relu=True)
+    out = polar.select_gemm(x, W1, idx, count=count, relu=True, workspace=workspace)
     torch.cuda.synchronize()
     S = orc.neuron_union(topk.cpu().numpy(), w.N)
     c = int(count.item())
