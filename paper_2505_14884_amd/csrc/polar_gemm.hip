@@ -248,205 +248,213 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Wide-tile form for M <= 64 with a caller-supplied workspace.
+// Evenly split form for M <= 64 with a caller-supplied workspace.
 //
-// With 32 neurons per workgroup every weight byte drags M/32 activation bytes through L2 and
-// LDS, and the number of workgroups follows the live count, which the host does not know (it
-// stays on the device).  Here a workgroup's tile is 128 neurons (wave w owns 32 of them and all
-// M rows: the weights are wave-private, the activation block is staged once per workgroup and
-// shared by the four waves: M/128 activation bytes per weight byte), and the work is cut the
-// other way round: the launch has a fixed number G of workgroups, each reads the live count,
-// lays all (tile, K block) units out in one line, tile-major, and takes the g-th of G equal
-// spans of that line.  Every compute unit gets the same number of bytes whatever the count is.
-// A span covers the end of one tile and the start of the next (or, for short K, whole tiles in
-// between): a segment that covers all of a tile's K blocks is finished in place (activation,
-// store to C); any other is stored as raw accumulators in one of the workgroup's two workspace
-// slots (slot 0: the span's first tile, slot 1: its last), and a second kernel adds each tile's
-// segments in ascending workgroup order, applies the activation and stores.  The order of the
-// additions depends only on (count, K, G), so results are reproducible.
-constexpr int kStreamTileN = 128;                // neurons per workgroup tile
+// In the kernel above the number of workgroups follows the live count, which the host does not
+// know (it stays on the device): at a 29 % union 332 workgroups land on 256 compute units, one
+// or two each, and the machine waits for the doubly loaded ones; and with every wave owning
+// other rows of the batch, each weight byte drags M/32 activation bytes through L2 and LDS.
+// Here the work is cut the other way round.  A workgroup's tile is 64 neurons; wave w owns 32 of
+// them and all M rows, so the weights are wave-private and the activation block is staged once
+// per workgroup and shared (M/64 activation bytes per weight byte).  The launch has a fixed
+// number G of workgroups; each reads the live count, lays all (tile, K unit) pairs out in one
+// line, tile-major, and takes the g-th of G equal spans of that line, so every compute unit
+// streams the same number of bytes whatever the count is.  A span covers the end of one tile and
+// the start of the next (or, for short K, whole tiles in between): a segment that covers all of
+// a tile's K is finished in place (activation, store to C); any other is stored as raw
+// accumulators in one of the workgroup's two workspace slots (slot 0: the span's first tile,
+// slot 1: its last), and a second kernel adds each tile's segments in ascending workgroup
+// order, applies the activation and stores.  The order of the additions depends only on
+// (count, K, G), so results are reproducible.
+constexpr int kStreamWaves = 2;                  // waves per workgroup
+constexpr int kStreamThreads = 64 * kStreamWaves;
 constexpr int kStreamWaveN = 32;                 // neurons per wave
+constexpr int kStreamTileN = kStreamWaveN * kStreamWaves;  // neurons per workgroup tile
 
 // units * G < 2^31 (checked by the host), so 32-bit arithmetic is exact
 __device__ __forceinline__ int span_bound(int units, int G, int g) { return (int)((unsigned)units * (unsigned)g / (unsigned)G); }
 
+// A unit is a pair of K blocks (K a multiple of 256), so every segment is a whole number of
+// passes of the two-slot ring below.  The span is walked as one stream: the loads for the next
+// unit are issued while the current one is multiplied, also when that unit belongs to the next
+// tile (its row addresses are fetched a tile ahead), so the memory pipeline is filled once per
+// workgroup, not once per tile.
+constexpr int kUnitBlocks = 2;                   // K blocks per unit = ring slots
+constexpr int kSpanTiles = 8;                    // tiles a span may touch (row ids kept in LDS)
+
 template <bool BF, int MT>
-__global__ __launch_bounds__(kGemmThreads) void select_gemm_stream_kernel(
+__global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const int32_t *__restrict__ idx,
     const int32_t *__restrict__ count_ptr, float *__restrict__ C, float *__restrict__ part, int M,
     int K, int N, int cap, int relu)
 {
-    __shared__ __align__(16) unsigned char sh_wt[kGemmThreads / 64][kStreamWaveN * kRowBytes];
+    __shared__ __align__(16) unsigned char sh_wt[kStreamWaves][kStreamWaveN * kRowBytes];
     __shared__ __align__(16) unsigned char sh_at[2][16 * MT * kRowBytes];
-    __shared__ int sh_row[kStreamTileN];
+    __shared__ int sh_id[kSpanTiles * kStreamTileN];
 
     int count = cap;
     if (count_ptr) {
         const int c = *count_ptr;
         count = c < 0 ? 0 : (c < cap ? c : cap);
     }
-    const int nblk = K / kBlockK;
-    const int units = (count + kStreamTileN - 1) / kStreamTileN * nblk;
+    const int upt = K / (kBlockK * kUnitBlocks);                    // units per tile
+    const int units = (count + kStreamTileN - 1) / kStreamTileN * upt;
     int u = span_bound(units, (int)gridDim.x, (int)blockIdx.x);
-    const int u_end = span_bound(units, (int)gridDim.x, (int)blockIdx.x + 1);
-    const int first_tile = u / nblk;
+    const int u0 = u, u1 = span_bound(units, (int)gridDim.x, (int)blockIdx.x + 1);
+    if (u0 >= u1) return;
+    const int first_tile = u0 / upt;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 15, kg = lane >> 4;
-    // activation block: 16 lanes per 256-byte row piece, rows a_row + 16*i
+    // activation block: 16 lanes per 256-byte row piece, rows a_row + kARows*i
+    constexpr int kARows = kStreamThreads / 16, AP = 16 * MT / kARows;
     const int a_row = tid >> 4;
-    const u32x4 *ap[MT];
+    const u32x4 *ap[AP];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-        int row = a_row + 16 * i;
+    for (int i = 0; i < AP; ++i) {
+        int row = a_row + kARows * i;
         row = row < M ? row : M - 1;
         ap[i] = reinterpret_cast<const u32x4 *>(A + (size_t)row * K) + x;
     }
-#ifdef POLAR_GEMM_ABLATE_A
-#define POLAR_A_BLOCK(b) 0
-#else
-#define POLAR_A_BLOCK(b) (b)
-#endif
     unsigned char *wt = sh_wt[wave];
     const int lds_w_wr = kg * kRowBytes + x * 16;                   // + 4*i rows
-    const int lds_a_wr = a_row * kRowBytes + x * 16;                // + 16*i rows
+    const int lds_a_wr = a_row * kRowBytes + x * 16;                // + kARows*i rows
     const int lds_op = x * kRowBytes + kg * 64;                     // operand reads: + 16*s, + 16 rows per tile
 
-    while (u < u_end) {
-        const int tile = u / nblk;
-        const int kb_begin = u - tile * nblk;
-        const int nb = min(u_end - u, nblk - kb_begin);
-        const int n0 = tile * kStreamTileN;
-        u += nb;
-
-        __syncthreads();                         // the previous segment no longer reads sh_row or the tiles
-        if (tid < kStreamTileN) {
-            const int id = n0 + tid < count ? idx[n0 + tid] : -1;
-            sh_row[tid] = (id >= 0 && id < N) ? id : -1;
-        }
-        __syncthreads();
-        // this wave's 32 weight rows: 16 lanes per 256-byte row piece, rows kg + 4*i
-        const u32x4 *wp[8];
+    // Row ids of every tile the span can touch (the host keeps that below kSpanTiles), fetched
+    // once: after this, the ring's loads are the only global loads in the loop, so waiting for
+    // the oldest of them never has to wait for anything else.  An id outside [0, N) or beyond
+    // the live count is kept as -1: it streams row 0 and its column is zeroed when stored.
+    for (int e = tid; e < kSpanTiles * kStreamTileN; e += kStreamThreads) {
+        const long col = (long)first_tile * kStreamTileN + e;
+        const int id = col < count ? idx[col] : -1;
+        sh_id[e] = (id >= 0 && id < N) ? id : -1;
+    }
+    __syncthreads();
+    // this wave's 32 weight rows of a tile: 16 lanes per 256-byte row piece, rows kg + 4*i
+    const int my_first = wave * kStreamWaveN + kg;
+    auto row_offset = [&](int tile_in_span, int i) -> size_t {
+        const int id = sh_id[(tile_in_span % kSpanTiles) * kStreamTileN + my_first + 4 * i];
+        return (size_t)(id < 0 ? 0 : id) * K;
+    };
+    // row offsets (in elements) of the tile being multiplied and of the tile after it; kept as
+    // offsets from W so that every load is known to be a global one
+    size_t cur[8], nxt[8];
+    int tile = first_tile;
+    int tile_base = tile * upt, tile_end = tile_base + upt;         // its units
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int r = sh_row[wave * kStreamWaveN + kg + 4 * i];
-            wp[i] = reinterpret_cast<const u32x4 *>(W + (size_t)(r < 0 ? 0 : r) * K) + x;
-        }
-
-        f32x4 acc[MT][2];
-#pragma unroll
-        for (int t = 0; t < MT; ++t) acc[t][0] = acc[t][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-#define POLAR_STREAM_MULTIPLY(abuf)                                                                \
-    _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                  \
-    {                                                                                              \
-        const u32x4 b0 = *reinterpret_cast<const u32x4 *>(wt + lds_op + 16 * s);                   \
-        const u32x4 b1 = *reinterpret_cast<const u32x4 *>(wt + lds_op + 16 * kRowBytes + 16 * s);  \
-        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
-        {                                                                                          \
-            const u32x4 a =                                                                        \
-                *reinterpret_cast<const u32x4 *>((abuf) + lds_op + 16 * t * kRowBytes + 16 * s);   \
-            acc[t][0] = mfma16x16x32<BF>(a, b0, acc[t][0]);                                        \
-            acc[t][1] = mfma16x16x32<BF>(a, b1, acc[t][1]);                                        \
-        }                                                                                          \
+    for (int i = 0; i < 8; ++i) {
+        cur[i] = row_offset(0, i);
+        nxt[i] = row_offset(1, i);
     }
 
-        // an odd block count is evened out by one unpipelined block
-        int kb = kb_begin;
-        const int kb_end = kb_begin + nb, last = kb_end - 1;
-        if (nb & 1) {
-            u32x4 hw[8], ha[MT];
-            const size_t blk = (size_t)kb * 16;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) hw[i] = wp[i][blk];
-#pragma unroll
-            for (int i = 0; i < MT; ++i) ha[i] = ap[i][POLAR_A_BLOCK(blk)];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4 *>(wt + lds_w_wr + 4 * i * kRowBytes) = hw[i];
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-                *reinterpret_cast<u32x4 *>(sh_at[0] + lds_a_wr + 16 * i * kRowBytes) = ha[i];
-            __syncthreads();
-            POLAR_STREAM_MULTIPLY(sh_at[0])
-            __syncthreads();
-            ++kb;
-        }
-
-        if (kb < kb_end) {
-            // two blocks in flight per wave (16 KiB of weights), slot j holds block kb + j
-            u32x4 wq[2][8], aq[2][MT];
-#pragma unroll
-            // The loads are issued in the order in which the loop below leaves them pending
-            // (weights of a block, then its activations; block kb before kb + 1) and fenced so
-            // that the compiler keeps that order: its count of outstanding loads at the loop
-            // header is then the same on entry and on the back edge, and nothing is drained.
-            for (int j = 0; j < 2; ++j) {
-                const size_t blk = (size_t)min(kb + j, last) * 16;
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) wq[j][i] = wp[i][blk];
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int i = 0; i < MT; ++i) aq[j][i] = ap[i][POLAR_A_BLOCK(blk)];
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#define POLAR_STREAM_STEP(j, kblock)                                                               \
+    // loads of block j of unit v (clamped to the span's last unit) into ring slot j; fenced so
+    // that the compiler keeps the order (weights before activations, slot 0 before slot 1): its
+    // count of outstanding loads at the loop header is then the same on entry and on the back
+    // edge, and nothing is drained there
+    u32x4 wq[kUnitBlocks][8], aq[kUnitBlocks][AP];
+#define POLAR_STREAM_FETCH(j, unit)                                                                \
+    {                                                                                              \
+        const int v = min((unit), u1 - 1);                                                         \
+        const bool ahead = v >= tile_end;                                                          \
+        const size_t blk = (size_t)((v - (ahead ? tile_end : tile_base)) * kUnitBlocks + (j)) * 16; \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
+        {                                                                                          \
+            const u32x4 *p = reinterpret_cast<const u32x4 *>(W + (ahead ? nxt[i] : cur[i])) + x;   \
+            wq[j][i] = p[blk];                                                                     \
+        }                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+        _Pragma("unroll") for (int i = 0; i < AP; ++i) aq[j][i] = ap[i][blk];                     \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+    }
+    // block j of unit u: ring slot j goes to LDS, is refilled for unit u + 1, and is multiplied;
+    // the wave's B operands (two 16-neuron halves, four k steps) stay in registers while the M
+    // rows go by, 16 at a time
+#define POLAR_STREAM_STEP(j)                                                                       \
     {                                                                                              \
         unsigned char *abuf = sh_at[j];                                                            \
         _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
             *reinterpret_cast<u32x4 *>(wt + lds_w_wr + 4 * i * kRowBytes) = wq[j][i];              \
-        _Pragma("unroll") for (int i = 0; i < MT; ++i)                                             \
-            *reinterpret_cast<u32x4 *>(abuf + lds_a_wr + 16 * i * kRowBytes) = aq[j][i];           \
-        const size_t nx = (size_t)min((kblock) + 2, last) * 16;                                    \
-        __builtin_amdgcn_sched_barrier(0);                                                         \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i) wq[j][i] = wp[i][nx];                        \
-        __builtin_amdgcn_sched_barrier(0);                                                         \
-        _Pragma("unroll") for (int i = 0; i < MT; ++i) aq[j][i] = ap[i][POLAR_A_BLOCK(nx)];       \
-        __builtin_amdgcn_sched_barrier(0);                                                         \
+        _Pragma("unroll") for (int i = 0; i < AP; ++i)                                             \
+            *reinterpret_cast<u32x4 *>(abuf + lds_a_wr + kARows * i * kRowBytes) = aq[j][i];       \
+        POLAR_STREAM_FETCH(j, u + 1)                                                               \
         __syncthreads();                                                                           \
-        POLAR_STREAM_MULTIPLY(abuf)                                                                \
+        u32x4 bq[2][4];                                                                            \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h)                                              \
+            _Pragma("unroll") for (int s = 0; s < 4; ++s) bq[h][s] =                               \
+                *reinterpret_cast<const u32x4 *>(wt + lds_op + 16 * h * kRowBytes + 16 * s);       \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
+        {                                                                                          \
+            u32x4 a[4];                                                                            \
+            _Pragma("unroll") for (int s = 0; s < 4; ++s) a[s] =                                   \
+                *reinterpret_cast<const u32x4 *>(abuf + lds_op + 16 * t * kRowBytes + 16 * s);     \
+            _Pragma("unroll") for (int s = 0; s < 4; ++s)                                          \
+            {                                                                                      \
+                acc[t][0] = mfma16x16x32<BF>(a[s], bq[0][s], acc[t][0]);                           \
+                acc[t][1] = mfma16x16x32<BF>(a[s], bq[1][s], acc[t][1]);                           \
+            }                                                                                      \
+        }                                                                                          \
     }
-            for (; kb < kb_end; kb += 2) {
-                POLAR_STREAM_STEP(0, kb)
-                POLAR_STREAM_STEP(1, kb + 1)
-            }
-#undef POLAR_STREAM_STEP
-        }
-#undef POLAR_STREAM_MULTIPLY
 
-        if (nb == nblk) {
+    POLAR_STREAM_FETCH(0, u)
+    POLAR_STREAM_FETCH(1, u)
+    while (u < u1) {
+        const int seg_begin = u, seg_end = tile_end < u1 ? tile_end : u1;
+        f32x4 acc[MT][2];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[t][0] = acc[t][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (; u < seg_end; ++u) {
+            POLAR_STREAM_STEP(0)
+            POLAR_STREAM_STEP(1)
+        }
+
+        if (seg_end - seg_begin == upt) {
             // the whole contraction of this tile: finish in place (accumulator layout: this
             // lane holds rows 16*t + 4*kg + i of column x of each 16-neuron half)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int col = n0 + wave * kStreamWaveN + 16 * h + x;
+                const int col = tile * kStreamTileN + wave * kStreamWaveN + 16 * h + x;
                 if (col >= count) continue;
-                const bool valid = sh_row[wave * kStreamWaveN + 16 * h + x] >= 0;
+                const bool valid = sh_id[(tile - first_tile) * kStreamTileN + wave * kStreamWaveN + 16 * h + x] >= 0;
 #pragma unroll
                 for (int t = 0; t < MT; ++t)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int row = 16 * t + 4 * kg + i;
                         if (row < M) {
-                            float v = acc[t][h][i];
-                            if (relu) v = v > 0.0f ? v : 0.0f;
-                            C[(size_t)row * cap + col] = valid ? v : 0.0f;
+                            float val = acc[t][h][i];
+                            if (relu) val = val > 0.0f ? val : 0.0f;
+                            C[(size_t)row * cap + col] = valid ? val : 0.0f;
                         }
                     }
             }
         } else {
+            // part of it: raw accumulators to the workspace (slot 0: the span's first tile)
             const int slot = tile == first_tile ? 0 : 1;
             f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
-                         (((size_t)blockIdx.x * 2 + slot) * (kGemmThreads / 64) + wave) * (MT * 2) * 64 + lane;
+                         (((size_t)blockIdx.x * 2 + slot) * (kStreamWaves) + wave) * (MT * 2) * 64 + lane;
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) dst[(t * 2 + h) * 64] = acc[t][h];
         }
+        if (u < u1) {                            // on to the next tile; fetch the row ids of the one after it
+            ++tile;
+            tile_base = tile_end;
+            tile_end += upt;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                cur[i] = nxt[i];
+                nxt[i] = row_offset(tile + 1 - first_tile, i);
+            }
+        }
     }
+#undef POLAR_STREAM_STEP
+#undef POLAR_STREAM_FETCH
 }
 
-// grid = ceil(cap / 128) * 4 * ceil(MT * 2 / 4) workgroups: workgroup (tile, w, q) adds four of the
+// grid = tiles * waves per tile * ceil(MT * 2 / 4) workgroups: workgroup (tile, w, q) adds four of the
 // MT * 2 accumulator tiles that wave w of the kernel above left for that tile (thread (j, lane)
 // owns entry e = 4 * q + j = t * 2 + h); G is that kernel's grid.
 template <int MT>
@@ -459,10 +467,10 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
         const int c = *count_ptr;
         count = c < 0 ? 0 : (c < cap ? c : cap);
     }
-    const int nblk = K / kBlockK;
+    const int nblk = K / (kBlockK * kUnitBlocks);            // units per tile
     const int tiles = (count + kStreamTileN - 1) / kStreamTileN;
     constexpr int kQuads = (MT * 2 + 3) / 4;
-    const int tile = blockIdx.x / (4 * kQuads), wave = blockIdx.x / kQuads & 3;
+    const int tile = blockIdx.x / (kStreamWaves * kQuads), wave = blockIdx.x / kQuads % kStreamWaves;
     const int e = (blockIdx.x % kQuads) * 4 + (threadIdx.x >> 6);
     if (tile >= tiles || e >= MT * 2) return;
     const int units = tiles * nblk, lo = tile * nblk, hi = lo + nblk;
@@ -494,7 +502,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
                 if (span_bound(units, G, g + 1) <= b) continue;
                 const int slot = b / nblk == tile ? 0 : 1;
                 v[q] = *(reinterpret_cast<const f32x4 *>(part) +
-                         ((((size_t)g * 2 + slot) * (kGemmThreads / 64) + wave) * (MT * 2) + e) * 64 + lane);
+                         ((((size_t)g * 2 + slot) * (kStreamWaves) + wave) * (MT * 2) + e) * 64 + lane);
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) sum += v[q];
@@ -613,9 +621,10 @@ hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, 
 }
 
 // Workspace of the wide-tile form: two slots of raw accumulators per workgroup.
-static size_t stream_slot_bytes(int mt) { return (size_t)2 * (kGemmThreads / 64) * mt * 2 * 64 * sizeof(f32x4); }
+static size_t stream_slot_bytes(int mt) { return (size_t)2 * (kStreamWaves) * mt * 2 * 64 * sizeof(f32x4); }
 static int stream_mt(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : 4); }
-constexpr int kStreamGrid = 256;                 // one workgroup per compute unit
+constexpr int kStreamGrid = 512;                 // two workgroups per compute unit: all that fit, and enough to
+                                                 // overlap one's LDS and barrier phases with the other's loads
 
 size_t select_gemm_workspace_bytes(int M)
 {
@@ -627,19 +636,19 @@ static hipError_t launch_stream_mt(int mt, int G, int tiles, hipStream_t st, con
                                    const uint16_t *W, const int32_t *idx, const int32_t *count, float *C,
                                    float *part, int M, int K, int N, int cap, int relu)
 {
-    const dim3 grid((unsigned)G), rgrid((unsigned)tiles * 4 * ((mt * 2 + 3) / 4)), block(kGemmThreads);
+    const dim3 grid((unsigned)G), rgrid((unsigned)tiles * kStreamWaves * ((mt * 2 + 3) / 4)), block(kStreamThreads), rblock(kGemmThreads);
     switch (mt) {
     case 1:
         hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 1>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
-        hipLaunchKernelGGL((select_gemm_reduce_kernel<1>), rgrid, block, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
+        hipLaunchKernelGGL((select_gemm_reduce_kernel<1>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
         break;
     case 2:
         hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 2>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
-        hipLaunchKernelGGL((select_gemm_reduce_kernel<2>), rgrid, block, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
+        hipLaunchKernelGGL((select_gemm_reduce_kernel<2>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
         break;
     default:
         hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 4>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
-        hipLaunchKernelGGL((select_gemm_reduce_kernel<4>), rgrid, block, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
+        hipLaunchKernelGGL((select_gemm_reduce_kernel<4>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
         break;
     }
     return hipGetLastError();
@@ -650,20 +659,22 @@ hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *id
                                  void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
     const char *form = getenv("POLAR_GEMM_FORM");            // "narrow": always the 32-neuron kernel
-    if (!workspace || M > 64 || (form && form[0] == 'n'))
+    if (!workspace || M > 64 || K % (kBlockK * kUnitBlocks) != 0 || (form && form[0] == 'n'))
         return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
     const int mt = stream_mt(M);
     const int tiles = (cap + kStreamTileN - 1) / kStreamTileN;
-    const long units = (long)tiles * (K / kBlockK);
+    const long units = (long)tiles * (K / (kBlockK * kUnitBlocks));
     long G = kStreamGrid;
     if (const char *e = getenv("POLAR_GEMM_WGS")) {
         const long v = atol(e);
         if (v >= 1 && v <= kStreamGrid) G = v;
     }
     if (G > units) G = units;
-    if (units * G >= (1l << 31)) return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
     if ((size_t)G * stream_slot_bytes(mt) > workspace_bytes) G = (long)(workspace_bytes / stream_slot_bytes(mt));
-    if (G < 1) return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
+    // a span of at most units / G + 1 units touches at most tiles / G + 2 tiles, whose row ids
+    // the kernel keeps in LDS; the span arithmetic is 32-bit
+    if (G < 1 || tiles / G + 2 > kSpanTiles || units * G >= (1l << 31))
+        return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
     const uint16_t *A16 = static_cast<const uint16_t *>(A);
     const uint16_t *W16 = static_cast<const uint16_t *>(W);
     float *part = static_cast<float *>(workspace);
