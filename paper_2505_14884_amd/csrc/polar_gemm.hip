@@ -267,6 +267,8 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
 // order, applies the activation and stores.  The order of the additions depends only on
 // (count, K, G), so results are reproducible.
 constexpr int kStreamWaves = 2;                  // waves per workgroup
+constexpr int kStreamGrid = 512;                 // workgroups per launch, two per compute unit: all that fit, and
+                                                 // enough to overlap one's LDS and barrier phases with the other's loads
 constexpr int kStreamThreads = 64 * kStreamWaves;
 constexpr int kStreamWaveN = 32;                 // neurons per wave
 constexpr int kStreamTileN = kStreamWaveN * kStreamWaves;  // neurons per workgroup tile
@@ -281,6 +283,8 @@ __device__ __forceinline__ int span_bound(int units, int G, int g) { return (int
 // workgroup, not once per tile.
 constexpr int kUnitBlocks = 2;                   // K blocks per unit = ring slots
 constexpr int kSpanTiles = 8;                    // tiles a span may touch (row ids kept in LDS)
+constexpr int kPhaseBuckets = 64;                // K positions the spans are sorted by (one per lane)
+constexpr int kSpanWords = (kStreamGrid + 31) / 32;   // words of a bitmap over the spans
 
 template <bool BF, int MT>
 __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
@@ -291,6 +295,9 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     __shared__ __align__(16) unsigned char sh_wt[kStreamWaves][kStreamWaveN * kRowBytes];
     __shared__ __align__(16) unsigned char sh_at[2][16 * MT * kRowBytes];
     __shared__ int sh_id[kSpanTiles * kStreamTileN];
+    __shared__ unsigned sh_bits[kPhaseBuckets * kSpanWords];
+    __shared__ int sh_bucket[kPhaseBuckets];
+    __shared__ unsigned short sh_order[kStreamGrid];
 
     int count = cap;
     if (count_ptr) {
@@ -299,13 +306,69 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     }
     const int upt = K / (kBlockK * kUnitBlocks);                    // units per tile
     const int units = (count + kStreamTileN - 1) / kStreamTileN * upt;
-    int u = span_bound(units, (int)gridDim.x, (int)blockIdx.x);
-    const int u0 = u, u1 = span_bound(units, (int)gridDim.x, (int)blockIdx.x + 1);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int x = lane & 15, kg = lane >> 4;
+
+    // Which span this workgroup takes.  Workgroups go to the eight dies in turn (g % 8), each
+    // die has its own L2, and the activations only stay in an L2 if its workgroups want the same
+    // K range at about the same time.  The spans are therefore sorted by the K position they
+    // start at (64 buckets, ties by span number) and die x takes the x-th eighth of that order:
+    // its workgroups walk K side by side.  Every workgroup computes the same order: a span
+    // marks its bit in its bucket's bitmap (order-free), a bucket's size and a span's rank in
+    // its bucket are bit counts.  Any one-to-one assignment gives the same result, since spans
+    // and workspace slots go by span number.
+    const int G = (int)gridDim.x;
+    int span;
+    {
+        constexpr int kMine = (kStreamGrid + kStreamThreads - 1) / kStreamThreads;
+        for (int e = tid; e < kPhaseBuckets * kSpanWords; e += kStreamThreads) sh_bits[e] = 0u;
+        __syncthreads();
+        int bucket[kMine];
+#pragma unroll
+        for (int q = 0; q < kMine; ++q) {
+            const int sp = tid + q * kStreamThreads;
+            bucket[q] = 0;
+            if (sp < G) {
+                bucket[q] = (span_bound(units, G, sp) % upt) * kPhaseBuckets / upt;
+                atomicOr(&sh_bits[bucket[q] * kSpanWords + (sp >> 5)], 1u << (sp & 31));
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {                         // bucket sizes, exclusive scan over the 64 buckets
+            int mine = 0;
+#pragma unroll
+            for (int wd = 0; wd < kSpanWords; ++wd) mine += __popc(sh_bits[lane * kSpanWords + wd]);
+            int incl = mine;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            sh_bucket[lane] = incl - mine;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < kMine; ++q) {
+            const int sp = tid + q * kStreamThreads;
+            if (sp < G) {
+                const unsigned *bits = sh_bits + bucket[q] * kSpanWords;
+                int pos = sh_bucket[bucket[q]] + __popc(bits[sp >> 5] & ((1u << (sp & 31)) - 1u));
+                for (int wd = 0; wd < (sp >> 5); ++wd) pos += __popc(bits[wd]);
+                sh_order[pos] = (unsigned short)sp;
+            }
+        }
+        __syncthreads();
+        const int die = (int)blockIdx.x & 7, turn = (int)blockIdx.x >> 3;
+        // dies 0 .. die-1 hold ceil((G - d) / 8) workgroups each
+        int before = 0;
+        for (int d = 0; d < die; ++d) before += (G - d + 7) >> 3;
+        span = __builtin_amdgcn_readfirstlane(sh_order[before + turn]);   // the same in every lane: keep it scalar
+    }
+    int u = span_bound(units, G, span);
+    const int u0 = u, u1 = span_bound(units, G, span + 1);
     if (u0 >= u1) return;
     const int first_tile = u0 / upt;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int x = lane & 15, kg = lane >> 4;
     // activation block: 16 lanes per 256-byte row piece, rows a_row + kARows*i
     constexpr int kARows = kStreamThreads / 16, AP = 16 * MT / kARows;
     const int a_row = tid >> 4;
@@ -433,7 +496,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
             // part of it: raw accumulators to the workspace (slot 0: the span's first tile)
             const int slot = tile == first_tile ? 0 : 1;
             f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
-                         (((size_t)blockIdx.x * 2 + slot) * (kStreamWaves) + wave) * (MT * 2) * 64 + lane;
+                         (((size_t)span * 2 + slot) * kStreamWaves + wave) * (MT * 2) * 64 + lane;
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -502,7 +565,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
                 if (span_bound(units, G, g + 1) <= b) continue;
                 const int slot = b / nblk == tile ? 0 : 1;
                 v[q] = *(reinterpret_cast<const f32x4 *>(part) +
-                         ((((size_t)g * 2 + slot) * (kStreamWaves) + wave) * (MT * 2) + e) * 64 + lane);
+                         ((((size_t)g * 2 + slot) * kStreamWaves + wave) * (MT * 2) + e) * 64 + lane);
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) sum += v[q];
@@ -623,8 +686,6 @@ hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, 
 // Workspace of the wide-tile form: two slots of raw accumulators per workgroup.
 static size_t stream_slot_bytes(int mt) { return (size_t)2 * (kStreamWaves) * mt * 2 * 64 * sizeof(f32x4); }
 static int stream_mt(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : 4); }
-constexpr int kStreamGrid = 512;                 // two workgroups per compute unit: all that fit, and enough to
-                                                 // overlap one's LDS and barrier phases with the other's loads
 
 size_t select_gemm_workspace_bytes(int M)
 {
