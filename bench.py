@@ -90,13 +90,15 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
     L = polar.binding.lib()
     st = lambda: torch.cuda.current_stream().cuda_stream
 
-    def union():
-        rc = L.polar_neuron_union(topk.data_ptr(), w.B, topk.shape[1], w.N, cap, idx.data_ptr(),
-                                  count.data_ptr(), st())
-        assert rc == 0, rc
-
     workspace = polar.alloc_select_gemm_workspace(w.B, dev) if args.gemm_form == "wide" else None
     wide = workspace is not None
+    union_ws = None
+    if wide:
+        nbytes = polar.neuron_union_workspace_bytes(w.B, topk.shape[1], w.N)
+        union_ws = torch.empty(nbytes, dtype=torch.uint8, device=dev) if nbytes else None
+
+    def union():
+        polar.neuron_union(topk, w.N, workspace=union_ws, out=(idx, count))
 
     def gemm(i=0):
         polar.select_gemm(x, W1, idx, count=count, relu=True, out=out, workspace=workspace)
@@ -161,7 +163,7 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                      "avg_us": round(gemm_ms * 1e3, 2),
                      "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),
                      # rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled; profiles/select_gemm_M2_opt66b_ffn.md
-                     "traffic": 214354185 if (w == wl.MLP_CONFIGS.get(w.name)) else None},
+                     "traffic": (224878494 if wide else 214354185) if (w == wl.MLP_CONFIGS.get(w.name)) else None},
     }
     if not args.no_cpu_baseline:
         from oracle import polar_oracle as orc

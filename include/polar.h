@@ -257,6 +257,21 @@ int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32
                        int32_t *count_out, void *stream);
 
 /*
+ * The same index with a workspace (Section 4.1; same arguments, same result): several
+ * workgroups each mark their share of the ids in a bitmap of their own, stored to the
+ * workspace, and a last launch ORs the bitmaps, counts and emits (two launches,
+ * deterministic).  Worth it from a few thousand ids on; for smaller inputs, workspace NULL or a
+ * workspace too small for two bitmaps it runs the one-launch kernel of polar_neuron_union.
+ *   workspace        scratch, DEVICE pointer, 4-byte aligned, caller-owned; contents are
+ *                    overwritten; calls that overlap in time need separate workspaces
+ *   workspace_bytes  its size; polar_neuron_union_workspace_bytes(B, kn, N) gives the size the
+ *                    library wants (0: the input is too small to split)
+ */
+int polar_neuron_union_workspace_bytes(int B, int kn, int N, size_t *bytes);
+int polar_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
+                          int32_t *count_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Streaming-read yardstick for harnesses (not an operation of the paper): `slabs` workgroups
  * each read one contiguous slab of `slab_bytes` bytes (slab w starts at src + w * slab_bytes)
  * with the per-head streaming kernel's launch shape and fold what they read into sink[w].
@@ -274,7 +289,8 @@ const char *polar_strerror(int status);
 /* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */
 int polar_last_hip_error(void);
 /* ABI version: major * 1000 + minor (1100: adds polar_sha_launches and polar_probe_read; group sizes up to 16;
- * 1200: adds polar_select_gemm_ws and polar_select_gemm_workspace_bytes). */
+ * 1200: adds polar_select_gemm_ws and polar_select_gemm_workspace_bytes; 1300: adds polar_neuron_union_ws and
+ * polar_neuron_union_workspace_bytes). */
 int polar_version(void);
 
 #ifdef __cplusplus

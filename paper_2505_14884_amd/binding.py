@@ -10,7 +10,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional
+from typing import Optional, Tuple
 
 import torch
 
@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_neuron_union", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -78,6 +78,10 @@ def lib() -> ctypes.CDLL:
         L.polar_select_gemm_workspace_bytes.restype = i
         L.polar_neuron_union.argtypes = [vp, i, i, i, i, vp, vp, vp]
         L.polar_neuron_union.restype = i
+        L.polar_neuron_union_ws.argtypes = [vp, i, i, i, i, vp, vp, vp, ctypes.c_size_t, vp]
+        L.polar_neuron_union_ws.restype = i
+        L.polar_neuron_union_workspace_bytes.argtypes = [i, i, i, ctypes.POINTER(ctypes.c_size_t)]
+        L.polar_neuron_union_workspace_bytes.restype = i
         L.polar_strerror.argtypes = [i]
         L.polar_strerror.restype = ctypes.c_char_p
         L.polar_last_hip_error.restype = i
@@ -302,12 +306,34 @@ def select_gemm(A: torch.Tensor, W: torch.Tensor, idx: torch.Tensor,
     return out
 
 
-def neuron_union(topk: torch.Tensor, N: int, cap: Optional[int] = None):
-    """Per-request neuron ids int32 [B,kn] -> (idx int32 [cap] ascending distinct ids, count int32 [1])."""
+def neuron_union_workspace_bytes(B: int, kn: int, N: int) -> int:
+    """Workspace size polar_neuron_union_ws wants for this input (0: too small to split)."""
+    n = ctypes.c_size_t(0)
+    _check(lib().polar_neuron_union_workspace_bytes(B, kn, N, ctypes.byref(n)), "polar_neuron_union_workspace_bytes")
+    return int(n.value)
+
+
+def neuron_union(topk: torch.Tensor, N: int, cap: Optional[int] = None,
+                 workspace: Optional[torch.Tensor] = None,
+                 out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None):
+    """Per-request neuron ids int32 [B,kn] -> (idx int32 [cap] ascending distinct ids, count int32 [1]).
+    With a workspace (neuron_union_workspace_bytes) the call goes to polar_neuron_union_ws; `out`
+    = (idx, count) reuses existing outputs."""
     B, kn = topk.shape
-    cap = min(N, B * kn) if cap is None else cap
-    idx = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=topk.device)[:cap]
-    count = torch.zeros(1, dtype=torch.int32, device=topk.device)
+    if out is not None:
+        idx, count = out
+        cap = idx.shape[0]
+    else:
+        cap = min(N, B * kn) if cap is None else cap
+        idx = torch.full((max(cap, 1),), -1, dtype=torch.int32, device=topk.device)[:cap]
+        count = torch.zeros(1, dtype=torch.int32, device=topk.device)
+    if workspace is not None:
+        rc = lib().polar_neuron_union_ws(_dev(topk, "topk", torch.int32), B, kn, N, cap,
+                                         _dev(idx, "idx", torch.int32), _dev(count, "count", torch.int32),
+                                         _dev(workspace, "workspace"),
+                                         workspace.numel() * workspace.element_size(), _stream())
+        _check(rc, "polar_neuron_union_ws")
+        return idx, count
     rc = lib().polar_neuron_union(_dev(topk, "topk", torch.int32), B, kn, N, cap,
                                   _dev(idx, "idx", torch.int32), _dev(count, "count", torch.int32),
                                   _stream())

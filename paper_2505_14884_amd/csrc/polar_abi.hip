@@ -162,7 +162,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 1200; }
+int polar_version(void) { return 1300; }
 
 int polar_last_hip_error(void) { return g_last_hip_error; }
 
@@ -377,6 +377,25 @@ int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32
     if (!count_out || (cap > 0 && !idx_out) || ((long long)B * kn > 0 && !topk)) return POLAR_EINVAL;
     return record(launch_neuron_union(topk, B, kn, N, cap, idx_out, count_out,
                                       static_cast<hipStream_t>(stream)));
+}
+
+int polar_neuron_union_workspace_bytes(int B, int kn, int N, size_t *bytes)
+{
+    if (B < 0 || kn < 0 || N < 1 || !bytes) return POLAR_EINVAL;
+    if (N > neuron_union_max_n()) return POLAR_EUNSUPPORTED;
+    *bytes = neuron_union_workspace_bytes(B, kn, N);
+    return POLAR_OK;
+}
+
+int polar_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
+                          int32_t *count_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (B < 0 || kn < 0 || N < 1 || cap < 0) return POLAR_EINVAL;
+    if (N > neuron_union_max_n()) return POLAR_EUNSUPPORTED;
+    if (!count_out || (cap > 0 && !idx_out) || ((long long)B * kn > 0 && !topk)) return POLAR_EINVAL;
+    if ((uintptr_t)workspace & 3u) return POLAR_EINVAL;
+    return record(launch_neuron_union_ws(topk, B, kn, N, cap, idx_out, count_out, workspace,
+                                         workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

@@ -587,45 +587,68 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
 }
 
 // Batch union of predicted neuron ids (Section 4.1: one index tensor for the whole batch).
-// One workgroup: an LDS bitmap of N bits is cleared, every valid id of topk [B*kn] sets its bit,
-// then each thread counts the bits of its contiguous share of the bitmap, an exclusive scan over
-// the threads gives its output offset, and it emits its ids in ascending order.  The result is
-// the ascending list of distinct ids, whatever the order of the input.
+// An LDS bitmap of N bits is cleared, every valid id of topk sets its bit, then each thread
+// counts the bits of its contiguous share of the bitmap, an exclusive scan over the threads gives
+// its output offset, and it emits its ids in ascending order.  The result is the ascending list
+// of distinct ids, whatever the order of the input.  One workgroup does all of it; with a
+// workspace the bitmap is built by several workgroups instead, each over its share of the ids
+// (the slow part: B * kn ids through one compute unit's LDS atomics), and the last kernel ORs
+// their bitmaps together before it counts and emits.
 constexpr int kUnionThreads = 1024;
 constexpr int kUnionMaxWords = 16384;            // N <= 524288 neurons (64 KB of LDS)
+constexpr int kUnionBuilders = 32;               // workgroups that build partial bitmaps
+constexpr int kUnionMinIdsPerBuilder = 2048;
+constexpr int kUnionScanSlots = 32;               // wave totals of the scan (16 used)
 
-__global__ __launch_bounds__(kUnionThreads) void neuron_union_kernel(
-    const int32_t *__restrict__ topk, long total, int N, int cap, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ count_out)
+// sh_bits[0, words) cleared, then the bits of topk[begin, end) set; ends with a barrier
+__device__ __forceinline__ void union_mark(unsigned int *sh_bits, int words, const int32_t *__restrict__ topk,
+                                           long begin, long end, int N)
 {
-    extern __shared__ unsigned int sh_bits[];     // words, then kUnionThreads scan slots
-    const int words = (N + 31) / 32;
-    unsigned int *sh_scan = sh_bits + words;
     const int tid = threadIdx.x;
     for (int wd = tid; wd < words; wd += kUnionThreads) sh_bits[wd] = 0u;
     __syncthreads();
-    for (long i = tid; i < total; i += kUnionThreads) {
+    for (long i = begin + tid; i < end; i += kUnionThreads) {
         const int id = topk[i];
         if (id >= 0 && id < N) atomicOr(&sh_bits[id >> 5], 1u << (id & 31));
     }
     __syncthreads();
-    const int per = (words + kUnionThreads - 1) / kUnionThreads;
-    const int w_begin = min(tid * per, words), w_end = min(w_begin + per, words);
+}
+
+// thread t counts and emits the words [first(t), first(t + 1)): contiguous, in thread order, as
+// even as it gets (at most one word apart)
+__device__ __forceinline__ int union_first_word(int t, int words)
+{
+    return (int)((long)t * words / kUnionThreads);
+}
+
+// sh_bits[0, words) holds the union: count, scan, emit (sh_scan: kUnionScanSlots words)
+__device__ __forceinline__ void union_emit(const unsigned int *sh_bits, unsigned int *sh_scan, int words,
+                                           int cap, int32_t *__restrict__ idx_out,
+                                           int32_t *__restrict__ count_out)
+{
+    const int tid = threadIdx.x;
+    const int w_begin = union_first_word(tid, words), w_end = union_first_word(tid + 1, words);
     unsigned int mine = 0;
     for (int wd = w_begin; wd < w_end; ++wd) mine += __popc(sh_bits[wd]);
-    sh_scan[tid] = mine;
+    // exclusive scan over the threads: shuffles inside a wave, then the 16 wave totals
+    const int lane = tid & 63, wave = tid >> 6;
+    unsigned int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned int up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+    }
+    if (lane == 63) sh_scan[wave] = incl;
     __syncthreads();
-    for (int off = 1; off < kUnionThreads; off <<= 1) {           // inclusive Hillis-Steele scan
-        const unsigned int add = tid >= off ? sh_scan[tid - off] : 0u;
-        __syncthreads();
-        sh_scan[tid] += add;
-        __syncthreads();
+    unsigned int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kUnionThreads / 64; ++w) {
+        const unsigned int t = sh_scan[w];
+        before += w < wave ? t : 0u;
+        all += t;
     }
-    unsigned int pos = sh_scan[tid] - mine;
-    if (tid == kUnionThreads - 1) {
-        const unsigned int all = sh_scan[tid];
-        count_out[0] = (int32_t)(all < (unsigned)cap ? all : (unsigned)cap);
-    }
+    unsigned int pos = before + incl - mine;
+    if (tid == 0) count_out[0] = (int32_t)(all < (unsigned)cap ? all : (unsigned)cap);
     for (int wd = w_begin; wd < w_end; ++wd) {
         unsigned int bits = sh_bits[wd];
         while (bits) {
@@ -635,6 +658,51 @@ __global__ __launch_bounds__(kUnionThreads) void neuron_union_kernel(
             ++pos;
         }
     }
+}
+
+__global__ __launch_bounds__(kUnionThreads) void neuron_union_kernel(
+    const int32_t *__restrict__ topk, long total, int N, int cap, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out)
+{
+    extern __shared__ unsigned int sh_bits[];     // words, then the scan slots
+    const int words = (N + 31) / 32;
+    union_mark(sh_bits, words, topk, 0, total, N);
+    union_emit(sh_bits, sh_bits + words, words, cap, idx_out, count_out);
+}
+
+// grid = builders: workgroup g marks its share of the ids and stores its bitmap to maps[g][words]
+__global__ __launch_bounds__(kUnionThreads) void neuron_bitmap_kernel(
+    const int32_t *__restrict__ topk, long total, int N, unsigned int *__restrict__ maps)
+{
+    extern __shared__ unsigned int sh_bits[];
+    const int words = (N + 31) / 32;
+    const long per = (total + gridDim.x - 1) / gridDim.x;
+    const long begin = min((long)blockIdx.x * per, total), end = min(begin + per, total);
+    union_mark(sh_bits, words, topk, begin, end, N);
+    unsigned int *dst = maps + (size_t)blockIdx.x * words;
+    for (int wd = threadIdx.x; wd < words; wd += kUnionThreads) dst[wd] = sh_bits[wd];
+}
+
+// one workgroup: OR of the builders' bitmaps, then count, scan, emit
+__global__ __launch_bounds__(kUnionThreads) void neuron_emit_kernel(
+    const unsigned int *__restrict__ maps, int builders, int N, int cap, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ count_out)
+{
+    extern __shared__ unsigned int sh_bits[];
+    const int words = (N + 31) / 32;
+    // each thread ORs the words it will count and emit itself, so no barrier is needed in between
+    const int w_begin = union_first_word(threadIdx.x, words), w_end = union_first_word(threadIdx.x + 1, words);
+    for (int wd = w_begin; wd < w_end; ++wd) {
+        // all loads in flight at once (a plain loop would wait for each in turn)
+        unsigned int v[kUnionBuilders];
+#pragma unroll
+        for (int g = 0; g < kUnionBuilders; ++g) v[g] = g < builders ? maps[(size_t)g * words + wd] : 0u;
+        unsigned int bits = 0u;
+#pragma unroll
+        for (int g = 0; g < kUnionBuilders; ++g) bits |= v[g];
+        sh_bits[wd] = bits;
+    }
+    union_emit(sh_bits, sh_bits + words, words, cap, idx_out, count_out);
 }
 
 template <bool BF>
@@ -746,20 +814,62 @@ hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *id
 
 int neuron_union_max_n() { return kUnionMaxWords * 32; }
 
+// dynamic LDS of the union kernels: the bitmap and the scan slots
+static hipError_t union_lds(const void *kernel, std::atomic<size_t> &granted, size_t lds)
+{
+    if (lds > 48 * 1024 && lds > granted.load(std::memory_order_acquire)) {
+        const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        granted.store(lds, std::memory_order_release);
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                                int32_t *count_out, hipStream_t stream)
 {
     const int words = (N + 31) / 32;
-    const size_t lds = ((size_t)words + kUnionThreads) * sizeof(unsigned int);
+    const size_t lds = ((size_t)words + kUnionScanSlots) * sizeof(unsigned int);
     static std::atomic<size_t> granted{0};
-    if (lds > 48 * 1024 && lds > granted.load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(neuron_union_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        granted.store(lds, std::memory_order_release);
-    }
+    const hipError_t e = union_lds(reinterpret_cast<const void *>(neuron_union_kernel), granted, lds);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(neuron_union_kernel, dim3(1), dim3(kUnionThreads), lds, stream, topk,
                        (long)B * kn, N, cap, idx_out, count_out);
+    return hipGetLastError();
+}
+
+// builders the split form would use for this input (0: not worth splitting)
+static int union_builders(long total)
+{
+    const long want = total / kUnionMinIdsPerBuilder;
+    return want < 2 ? 0 : (int)(want < kUnionBuilders ? want : kUnionBuilders);
+}
+
+size_t neuron_union_workspace_bytes(int B, int kn, int N)
+{
+    return (size_t)union_builders((long)B * kn) * ((N + 31) / 32) * sizeof(unsigned int);
+}
+
+hipError_t launch_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
+                                  int32_t *count_out, void *workspace, size_t workspace_bytes,
+                                  hipStream_t stream)
+{
+    const int words = (N + 31) / 32;
+    const long total = (long)B * kn;
+    int builders = union_builders(total);
+    const size_t per = (size_t)words * sizeof(unsigned int);
+    if (workspace && (size_t)builders * per > workspace_bytes) builders = (int)(workspace_bytes / per);
+    if (!workspace || builders < 2) return launch_neuron_union(topk, B, kn, N, cap, idx_out, count_out, stream);
+    static std::atomic<size_t> granted_build{0}, granted_emit{0};
+    hipError_t e = union_lds(reinterpret_cast<const void *>(neuron_bitmap_kernel), granted_build, per);
+    if (e != hipSuccess) return e;
+    const size_t lds = ((size_t)words + kUnionScanSlots) * sizeof(unsigned int);
+    e = union_lds(reinterpret_cast<const void *>(neuron_emit_kernel), granted_emit, lds);
+    if (e != hipSuccess) return e;
+    unsigned int *maps = static_cast<unsigned int *>(workspace);
+    hipLaunchKernelGGL(neuron_bitmap_kernel, dim3(builders), dim3(kUnionThreads), per, stream, topk, total, N, maps);
+    hipLaunchKernelGGL(neuron_emit_kernel, dim3(1), dim3(kUnionThreads), lds, stream, maps, builders, N, cap,
+                       idx_out, count_out);
     return hipGetLastError();
 }
 

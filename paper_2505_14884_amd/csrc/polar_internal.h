@@ -79,6 +79,13 @@ int neuron_union_max_n();
 hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                                int32_t *count_out, hipStream_t stream);
 
+// With a workspace of neuron_union_workspace_bytes(B, kn, N) bytes (0: the input is too small to
+// split) several workgroups build the bitmap; without one this is launch_neuron_union.
+size_t neuron_union_workspace_bytes(int B, int kn, int N);
+hipError_t launch_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
+                                  int32_t *count_out, void *workspace, size_t workspace_bytes,
+                                  hipStream_t stream);
+
 #if defined(__HIPCC__)
 // Direct mode's zero fill, run by one wave of the workgroup of (request b, slot): that workgroup
 // owns the KV heads h = slot, slot + k, slot + 2k, ... and stores +0.0 to the G query heads of

@@ -155,6 +155,18 @@ def test_select_gemm_and_union_argument_errors():
     assert u(B=-1) == EINVAL and u(N=0) == EINVAL and u(cap=-1) == EINVAL
     assert u(cnt=None) == EINVAL and u(idx=None) == EINVAL and u(topk=None) == EINVAL
     assert u(N=524289) == EUNSUPPORTED
+    uw = lambda topk=FAKE, B=2, kn=3, N=64, cap=6, idx=FAKE, cnt=FAKE, ws=None, wsb=0: L.polar_neuron_union_ws(
+        topk, B, kn, N, cap, idx, cnt, ws, wsb, None)
+    assert uw(B=-1) == EINVAL and uw(N=0) == EINVAL and uw(cap=-1) == EINVAL
+    assert uw(cnt=None) == EINVAL and uw(idx=None) == EINVAL and uw(topk=None) == EINVAL
+    assert uw(N=524289) == EUNSUPPORTED
+    assert uw(ws=ctypes.c_void_p(0x1002), wsb=1 << 20) == EINVAL
+    assert L.polar_neuron_union_workspace_bytes(-1, 3, 64, ctypes.byref(n)) == EINVAL
+    assert L.polar_neuron_union_workspace_bytes(2, 3, 64, None) == EINVAL
+    assert L.polar_neuron_union_workspace_bytes(2, 3, 524289, ctypes.byref(n)) == EUNSUPPORTED
+    assert polar.neuron_union_workspace_bytes(2, 3, 64) == 0                 # too few ids to split
+    assert polar.neuron_union_workspace_bytes(64, 1843, 36864) == 32 * 1152 * 4
+    assert polar.neuron_union_workspace_bytes(4, 1024, 36864) == 2 * 1152 * 4
 
 
 def test_workspace_size_is_consistent_with_the_chunking():

@@ -534,12 +534,18 @@ def test_select_gemm_invalid_ids_count_and_long_k():
         gemm_case(64, 9216, 300, list(range(299, -1, -1)), "bf16", relu=True, ws=ws)
 
 
-def test_neuron_union_matches_oracle():
-    say("\ncase neuron union")
+@pytest.mark.parametrize("ws", [False, True])
+def test_neuron_union_matches_oracle(ws):
+    say("\ncase neuron union", "workspace" if ws else "")
     g = torch.Generator(device="cpu").manual_seed(5)
-    for (B, kn, N) in [(1, 1, 1), (7, 12, 50), (64, 1843, 36864), (3, 5, 524288), (16, 100, 33)]:
+    for (B, kn, N) in [(1, 1, 1), (7, 12, 50), (64, 1843, 36864), (3, 5, 524288), (16, 100, 33),
+                       (5, 1000, 524288), (128, 300, 4097)]:
         topk = torch.randint(-2, N + 2, (B, kn), generator=g, dtype=torch.int32).to(DEV)
-        idx, count = polar.neuron_union(topk, N)
+        workspace = None
+        if ws:        # poisoned, and at least a token buffer so that the workspace entry point is the one called
+            nbytes = polar.neuron_union_workspace_bytes(B, kn, N)
+            workspace = torch.full((max(nbytes, 4) // 4,), -1, dtype=torch.int32, device=DEV)
+        idx, count = polar.neuron_union(topk, N, workspace=workspace)
         torch.cuda.synchronize()
         want = orc.neuron_union(topk.cpu().numpy(), N)
         c = int(count.item())
@@ -550,6 +556,18 @@ def test_neuron_union_matches_oracle():
     idx, count = polar.neuron_union(topk, 64, cap=25)
     torch.cuda.synchronize()
     assert int(count.item()) == 25 and idx.cpu().tolist() == list(range(25))
+    # a workspace that holds fewer bitmaps than the library wants narrows the launch; one that
+    # holds fewer than two falls back to the one-launch kernel
+    B, kn, N = 64, 1843, 36864
+    topk = torch.randint(0, N, (B, kn), generator=g, dtype=torch.int32).to(DEV)
+    want = orc.neuron_union(topk.cpu().numpy(), N)
+    one = (N + 31) // 32 * 4
+    for nbytes in (3 * one, 2 * one, one, 4):
+        workspace = torch.full((nbytes // 4,), -1, dtype=torch.int32, device=DEV)
+        idx, count = polar.neuron_union(topk, N, cap=len(want) - 7, workspace=workspace)
+        torch.cuda.synchronize()
+        assert int(count.item()) == len(want) - 7
+        assert idx.cpu().numpy().tolist() == want[:-7].tolist()
 
 
 @pytest.mark.parametrize("ws", [False, True])
@@ -561,7 +579,9 @@ def test_sparse_mlp_first_layer(name, ws):
     say("\ncase", w)
     x, W1, topk = wl.make_mlp_inputs(w, DEV)
     workspace = polar.alloc_select_gemm_workspace(w.B, DEV) if ws else None
-    idx, count = polar.neuron_union(topk, w.N)
+    union_ws = (torch.empty(max(polar.neuron_union_workspace_bytes(w.B, topk.shape[1], w.N), 4), dtype=torch.uint8,
+                            device=DEV) if ws else None)
+    idx, count = polar.neuron_union(topk, w.N, workspace=union_ws)
     out = polar.select_gemm(x, W1, idx, count=count, relu=True, workspace=workspace)
     torch.cuda.synchronize()
     S = orc.neuron_union(topk.cpu().numpy(), w.N)
