@@ -10,7 +10,8 @@
 // row (K 16-bit values) is read once and used for only M <= 256 multiply-adds per element,
 // far below the ~300 flop/byte ridge of the part, but above what the vector ALUs sustain at
 // HBM speed, so the contraction runs on MFMA (v_mfma_f32_16x16x32) while the kernel is
-// organised around streaming the gathered rows:
+// organised around streaming the gathered rows.  Two forms: the one-launch kernel described
+// here, and, further down, an evenly split form for M <= 64 that needs a workspace and is faster:
 //   * a workgroup owns 32 selected neurons and walks K in blocks of 128 values; per block it
 //     loads its 32 x 256-byte row pieces with fully coalesced 16-byte loads (16 lanes per
 //     piece), parks them in LDS (padded rows, conflict-free 16-byte reads) and every wave
