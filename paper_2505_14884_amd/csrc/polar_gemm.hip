@@ -600,6 +600,7 @@ constexpr int kUnionMaxWords = 16384;            // N <= 524288 neurons (64 KB o
 constexpr int kUnionBuilders = 32;               // workgroups that build partial bitmaps
 constexpr int kUnionMinIdsPerBuilder = 2048;
 constexpr int kUnionScanSlots = 32;               // wave totals of the scan (16 used)
+constexpr int kUnionEmitters = 16;               // workgroups of the split form's last launch (one wave's share each)
 
 // sh_bits[0, words) cleared, then the bits of topk[begin, end) set; ends with a barrier
 __device__ __forceinline__ void union_mark(unsigned int *sh_bits, int words, const int32_t *__restrict__ topk,
@@ -623,9 +624,12 @@ __device__ __forceinline__ int union_first_word(int t, int words)
 }
 
 // sh_bits[0, words) holds the union: count, scan, emit (sh_scan: kUnionScanSlots words)
+// Workgroup `part` of `parts` emits the ids of the threads [part, part + 1) * kUnionThreads / parts
+// (every workgroup does the whole count and scan; the bit loops with their scattered 4-byte
+// stores, the slow part, are what is shared out); part 0 stores the count.
 __device__ __forceinline__ void union_emit(const unsigned int *sh_bits, unsigned int *sh_scan, int words,
                                            int cap, int32_t *__restrict__ idx_out,
-                                           int32_t *__restrict__ count_out)
+                                           int32_t *__restrict__ count_out, int part, int parts)
 {
     const int tid = threadIdx.x;
     const int w_begin = union_first_word(tid, words), w_end = union_first_word(tid + 1, words);
@@ -649,7 +653,8 @@ __device__ __forceinline__ void union_emit(const unsigned int *sh_bits, unsigned
         all += t;
     }
     unsigned int pos = before + incl - mine;
-    if (tid == 0) count_out[0] = (int32_t)(all < (unsigned)cap ? all : (unsigned)cap);
+    if (tid == 0 && part == 0) count_out[0] = (int32_t)(all < (unsigned)cap ? all : (unsigned)cap);
+    if (tid < part * kUnionThreads / parts || tid >= (part + 1) * kUnionThreads / parts) return;
     for (int wd = w_begin; wd < w_end; ++wd) {
         unsigned int bits = sh_bits[wd];
         while (bits) {
@@ -668,7 +673,7 @@ __global__ __launch_bounds__(kUnionThreads) void neuron_union_kernel(
     extern __shared__ unsigned int sh_bits[];     // words, then the scan slots
     const int words = (N + 31) / 32;
     union_mark(sh_bits, words, topk, 0, total, N);
-    union_emit(sh_bits, sh_bits + words, words, cap, idx_out, count_out);
+    union_emit(sh_bits, sh_bits + words, words, cap, idx_out, count_out, 0, 1);
 }
 
 // grid = builders: workgroup g marks its share of the ids and stores its bitmap to maps[g][words]
@@ -684,7 +689,7 @@ __global__ __launch_bounds__(kUnionThreads) void neuron_bitmap_kernel(
     for (int wd = threadIdx.x; wd < words; wd += kUnionThreads) dst[wd] = sh_bits[wd];
 }
 
-// one workgroup: OR of the builders' bitmaps, then count, scan, emit
+// grid = emitters: every workgroup ORs the builders' bitmaps, counts and scans; each emits its share
 __global__ __launch_bounds__(kUnionThreads) void neuron_emit_kernel(
     const unsigned int *__restrict__ maps, int builders, int N, int cap, int32_t *__restrict__ idx_out,
     int32_t *__restrict__ count_out)
@@ -703,7 +708,7 @@ __global__ __launch_bounds__(kUnionThreads) void neuron_emit_kernel(
         for (int g = 0; g < kUnionBuilders; ++g) bits |= v[g];
         sh_bits[wd] = bits;
     }
-    union_emit(sh_bits, sh_bits + words, words, cap, idx_out, count_out);
+    union_emit(sh_bits, sh_bits + words, words, cap, idx_out, count_out, (int)blockIdx.x, (int)gridDim.x);
 }
 
 template <bool BF>
@@ -869,7 +874,7 @@ hipError_t launch_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int
     if (e != hipSuccess) return e;
     unsigned int *maps = static_cast<unsigned int *>(workspace);
     hipLaunchKernelGGL(neuron_bitmap_kernel, dim3(builders), dim3(kUnionThreads), per, stream, topk, total, N, maps);
-    hipLaunchKernelGGL(neuron_emit_kernel, dim3(1), dim3(kUnionThreads), lds, stream, maps, builders, N, cap,
+    hipLaunchKernelGGL(neuron_emit_kernel, dim3(kUnionEmitters), dim3(kUnionThreads), lds, stream, maps, builders, N, cap,
                        idx_out, count_out);
     return hipGetLastError();
 }
