@@ -215,3 +215,13 @@ def test_probe_and_launch_query_argument_checks():
     assert polar.sha_launches(128, 72, 72, 1920, 128, 36) == 2
     assert polar.sha_launches(256, 32, 32, 8192, 128, 8) == 2
     assert polar.sha_launches(4, 8, 8, 256, 96, 4) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark runs on one GPU only and says so before it touches torch or the GPU."""
+    import subprocess
+    import sys
+    proc = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                          capture_output=True, text=True, timeout=120)
+    assert proc.returncode == 2
+    assert "one GPU" in proc.stderr and proc.stdout.strip() == ""

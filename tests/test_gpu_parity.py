@@ -597,6 +597,16 @@ def test_sparse_mlp_first_layer(name, ws):
     assert err <= GEMM_TOL
     assert (out[:, :c] >= 0).all() and torch.isfinite(out[:, :c]).all()
     assert 0.3 < float((out[:, :c] > 0).float().mean()) < 0.7      # ReLU of a symmetric pre-activation
+    if ws:
+        # every element, not only the sampled columns: the two forms differ in the order of the
+        # float additions only; and the split form is reproducible bit for bit
+        narrow = polar.select_gemm(x, W1, idx, count=count, relu=True)
+        again = polar.select_gemm(x, W1, idx, count=count, relu=True, workspace=workspace)
+        torch.cuda.synchronize()
+        diff = float((out[:, :c] - narrow[:, :c]).abs().max())
+        say("   max-abs difference between the forms %.3e over %d x %d outputs" % (diff, w.B, c))
+        assert diff <= GEMM_TOL
+        assert torch.equal(out[:, :c], again[:, :c])
 
 
 def test_read_probe_folds_every_word_of_every_slab():
