@@ -325,6 +325,53 @@ int oracle_select_gemm(const uint16_t *A, const uint16_t *W, const int32_t *idx,
     return 0;
 }
 
+/* Nearest value of the 16-bit storage type to v, ties to even, as a double (what a 16-bit
+ * model holds after it stores an activation).  binary16 has 11 significant bits, exponents down
+ * to 2^-14 and subnormals in steps of 2^-24; bfloat16 has 8 significant bits on binary32's
+ * exponent range (subnormal step 2^-133).  rint() rounds to even in the default mode. */
+static double round_to_storage(double v, int dt)
+{
+    if (v == 0.0 || isnan(v) || isinf(v)) return v;
+    const int digits = dt == ORACLE_BF16 ? 8 : 11;
+    const int min_step = dt == ORACLE_BF16 ? -133 : -24;
+    const double largest = dt == ORACLE_BF16 ? ldexp(255.0, 120) : 65504.0;
+    int e;
+    (void)frexp(v, &e);                            /* |v| in [2^(e-1), 2^e) */
+    int step = e - digits;                         /* spacing of the type's values there */
+    if (step < min_step) step = min_step;
+    double r = ldexp(rint(ldexp(v, -step)), step);
+    if (fabs(r) > largest) r = copysign(INFINITY, v);
+    return r;
+}
+
+/* Second factor of the sparsified MLP (Section 3.1: MLP_{S_B}(x) = sigma(x W_{1,S_B}) W_{2,S_B}^T,
+ * the sum running over the neurons of S_B only):
+ *   H [M,n_sel] float: the activations of the selected neurons (the first factor's output);
+ *   W2 [N,Kout] 16-bit, one contiguous row of Kout weights per neuron (the layout of Appendix
+ *   "Sparse Kernels"); idx [n_sel] neuron ids;  Y [M,Kout] double:
+ *   Y[m,c] = sum_{j<n_sel} h16(H[m,j]) * W2[idx[j],c],
+ * h16 = the activation as the 16-bit model stores it (rounded to the storage type, ties to even).
+ * An id outside [0,N) contributes nothing; an id that appears twice contributes twice. */
+int oracle_select_gemm_down(const float *H, const uint16_t *W2, const int32_t *idx, int M, int Kout,
+                            int N, int n_sel, int dt, double *Y)
+{
+    if (!Y || M < 0 || Kout < 1 || N < 1 || n_sel < 0) return -1;
+    if (n_sel > 0 && (!H || !W2 || !idx)) return -1;
+    if (dt != ORACLE_F16 && dt != ORACLE_BF16) return -1;
+    for (int m = 0; m < M; ++m)
+        for (int c = 0; c < Kout; ++c) {
+            double acc = 0.0;
+            for (int j = 0; j < n_sel; ++j) {
+                int n = idx[j];
+                if (n < 0 || n >= N) continue;
+                acc += round_to_storage((double)H[(size_t)m * n_sel + j], dt) *
+                       widen(W2[(size_t)n * Kout + c], dt);
+            }
+            Y[(size_t)m * Kout + c] = acc;
+        }
+    return 0;
+}
+
 /* Algorithm 1 (Selective Head FlashAttention, decode) for ONE already-gathered
  * head, followed in its own order: the cache is visited in tiles of Bc rows;
  * each tile yields its scores, their maximum, the shifted exponentials and

@@ -48,6 +48,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_head_scores.argtypes = [vp, c_int, c_int, c_int, c_int, vp, vp]
         L.oracle_neuron_union.argtypes = [vp, c_int, c_int, c_int, vp, vp]
         L.oracle_select_gemm.argtypes = [vp, vp, vp] + [c_int] * 6 + [vp]
+        L.oracle_select_gemm_down.argtypes = [vp, vp, vp] + [c_int] * 5 + [vp]
         L.oracle_alg1_tiled.argtypes = [vp, vp, vp, c_int, c_int, c_int, c_dbl, vp]
         _lib = L
     return _lib
@@ -183,3 +184,18 @@ def select_gemm(A_bits, W_bits, idx, dtype: str, relu: bool = True) -> np.ndarra
                                   _DT[dtype], 1 if relu else 0, _ptr(C))
     assert rc == 0, rc
     return C
+
+
+def select_gemm_down(H, W2_bits, idx, dtype: str) -> np.ndarray:
+    """H float32 [M,n_sel], W2 [N,Kout] uint16 patterns, idx int32 [n_sel] -> float64 [M,Kout]:
+    sum_j h16(H[:,j]) * W2[idx[j],:] with H rounded to the storage type; ids outside [0,N) are skipped."""
+    H = np.ascontiguousarray(H, dtype=np.float32)
+    W2_bits = _u16(W2_bits)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    M, n_sel = H.shape
+    N, Kout = W2_bits.shape
+    assert idx.shape == (n_sel,)
+    Y = np.empty((M, Kout), dtype=np.float64)
+    rc = lib().oracle_select_gemm_down(_ptr(H), _ptr(W2_bits), _ptr(idx), M, Kout, N, n_sel, _DT[dtype], _ptr(Y))
+    assert rc == 0, rc
+    return Y

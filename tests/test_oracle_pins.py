@@ -502,6 +502,81 @@ def test_select_gemm_on_union_equals_masked_dense_layer():
     assert len(S) >= kn and len(S) <= min(N, B * kn)
 
 
+# ----------------------------------------------------------------------------- second MLP factor
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_select_gemm_down_equals_library_product_of_rounded_activations(dtype):
+    """The definition against library routines: the activations cast to the storage type by
+    numpy (binary16) or torch (bfloat16), the gathered rows multiplied by numpy in double."""
+    import torch
+    M, n_sel, N, Kout = 7, 37, 50, 24
+    H = (RNG.standard_normal((M, n_sel)) * 3.0).astype(np.float32)
+    H[0, :4] = [0.0, 1e-7, 70000.0 if dtype == "bf16" else 60000.0, -2.5]
+    W2 = (f16_bits if dtype == "f16" else bf16_bits)(RNG.standard_normal((N, Kout)))
+    idx = RNG.integers(0, N, n_sel).astype(np.int32)
+    if dtype == "f16":
+        h16 = H.astype(np.float16).astype(np.float64)
+    else:
+        h16 = torch.from_numpy(H).to(torch.bfloat16).double().numpy()
+    want = h16 @ as_f64(W2, dtype)[idx]
+    got = orc.select_gemm_down(H, W2, idx, dtype)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_select_gemm_down_rounds_activations_to_nearest_even():
+    """One-hot weight rows hand the rounded activation through: halfway cases of binary16 go to
+    the even neighbour, also among subnormals; bfloat16 keeps 8 significant bits."""
+    cases16 = [(1.0 + 2.0 ** -11, 1.0), (1.0 + 2.0 ** -11 + 2.0 ** -20, 1.0 + 2.0 ** -10),
+               (1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -9), (2.0 ** -25, 0.0), (3 * 2.0 ** -25, 2.0 ** -23),
+               (2.0 ** -24, 2.0 ** -24), (65519.0, 65504.0), (-0.3, float(np.float16(-0.3)))]
+    H = np.array([[c[0] for c in cases16]], np.float32)
+    n = H.shape[1]
+    eye = f16_bits(np.eye(n))
+    got = orc.select_gemm_down(H, eye, np.arange(n, dtype=np.int32), "f16")
+    assert got[0].tolist() == [c[1] for c in cases16]
+    casesb = [(1.0 + 2.0 ** -8, 1.0), (1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -6),
+              (1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 2.0 ** -7), (-7.0, -7.0), (2.0 ** -130, 2.0 ** -130)]
+    Hb = np.array([[c[0] for c in casesb]], np.float32)
+    nb = Hb.shape[1]
+    gotb = orc.select_gemm_down(Hb, bf16_bits(np.eye(nb)), np.arange(nb, dtype=np.int32), "bf16")
+    assert gotb[0].tolist() == [c[1] for c in casesb]
+
+
+def test_select_gemm_down_ids_and_empty_selection():
+    M, N, Kout = 3, 8, 5
+    H = RNG.standard_normal((M, 4)).astype(np.float32)
+    W2 = f16_bits(RNG.standard_normal((N, Kout)))
+    w = as_f64(W2, "f16")
+    h = H.astype(np.float16).astype(np.float64)
+    got = orc.select_gemm_down(H, W2, np.array([2, -1, 8, 5], np.int32), "f16")     # -1 and 8 are skipped
+    np.testing.assert_allclose(got, np.outer(h[:, 0], w[2]) + np.outer(h[:, 3], w[5]), rtol=1e-13, atol=1e-15)
+    twice = orc.select_gemm_down(H[:, :2], W2, np.array([3, 3], np.int32), "f16")    # a repeated id adds twice
+    np.testing.assert_allclose(twice, np.outer(h[:, 0] + h[:, 1], w[3]), rtol=1e-13, atol=1e-15)
+    empty = orc.select_gemm_down(np.zeros((M, 0), np.float32), W2, np.zeros(0, np.int32), "f16")
+    assert empty.shape == (M, Kout) and not empty.any()
+
+
+def test_sparsified_mlp_over_all_neurons_is_the_dense_mlp():
+    """Section 3.1: with S_B = every neuron, sigma(x W_1) W_2^T restricted to S_B is the dense
+    two-layer block (numpy in double, activations held in the storage type)."""
+    B, K, N = 5, 32, 24
+    x = f16_bits(RNG.standard_normal((B, K)))
+    W1 = f16_bits(RNG.standard_normal((N, K)) / 6.0)
+    W2 = f16_bits(RNG.standard_normal((N, K)) / 5.0)                 # one row per neuron: W_2^T row-major
+    hidden = np.maximum(as_f64(x, "f16") @ as_f64(W1, "f16").T, 0.0)
+    dense = hidden.astype(np.float32).astype(np.float16).astype(np.float64) @ as_f64(W2, "f16")
+    all_ids = np.arange(N, dtype=np.int32)
+    up = orc.select_gemm(x, W1, all_ids, "f16", relu=True)
+    got = orc.select_gemm_down(up.astype(np.float32), W2, all_ids, "f16")
+    np.testing.assert_allclose(got, dense, rtol=1e-12, atol=1e-13)
+    # and over a subset S it is the dense block with the other neurons' activations zeroed
+    S = np.array([1, 4, 5, 11, 20], np.int32)
+    masked = np.zeros_like(hidden)
+    masked[:, S] = hidden[:, S]
+    want = masked.astype(np.float32).astype(np.float16).astype(np.float64) @ as_f64(W2, "f16")
+    got_s = orc.select_gemm_down(orc.select_gemm(x, W1, S, "f16", relu=True).astype(np.float32), W2, S, "f16")
+    np.testing.assert_allclose(got_s, want, rtol=1e-12, atol=1e-13)
+
+
 # ----------------------------------------------------------------------------- threads
 def test_result_does_not_depend_on_thread_count():
     q, K, V, n = random_case(4, 4, 4, 50, 16, "f16")
