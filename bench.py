@@ -143,6 +143,14 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
     dense_ms = float("nan") if args.no_dense else ev(
         lambda: polar.select_gemm(x, W1, all_idx, relu=True, out=dense_out, workspace=workspace), max(5, n_ev // 4))
     achieved = bytes_sel / (gemm_ms * 1e-3) / 1e9
+    # second factor of the sparsified MLP on the same index: Y = h16(hidden) W2[idx,:]
+    g2 = torch.Generator(device=dev).manual_seed(w.seed + 1)
+    W2 = (torch.randn((w.N, w.K), generator=g2, device=dev) / 100.0).to(W1.dtype)
+    y = torch.empty((w.B, w.K), dtype=torch.float32, device=dev)
+    down_ws = torch.empty(polar.select_gemm_down_workspace_bytes(w.B, w.K, cap), dtype=torch.uint8, device=dev)
+    down = lambda: polar.select_gemm_down(out, W2, idx, count=count, out=y, workspace=down_ws)
+    down_ms = ev(down, n_ev)
+    mlp_ms = ev(lambda: (union(), gemm(), down()), n_ev)
     result = {
         "metric": "selective fused-gather GEMM effective weight HBM GB/s (gathered rows' bytes / step "
                   "time; step = batch neuron union + GEMM with ReLU)",
@@ -154,7 +162,14 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                                % (w.name, w.B, w.K, w.N, w.dtype, n_sel, 100.0 * n_sel / w.N),
                    "selected_weight_bytes": bytes_sel, "dense_weight_bytes": w.N * w.K * 2},
         "breakdown_us": {"neuron_union": round(union_ms * 1e3, 2), "select_gemm": round(gemm_ms * 1e3, 2),
-                         "dense_gemm_all_rows": None if args.no_dense else round(dense_ms * 1e3, 2)},
+                         "dense_gemm_all_rows": None if args.no_dense else round(dense_ms * 1e3, 2),
+                         "select_gemm_down": round(down_ms * 1e3, 2),
+                         "union_and_both_factors": round(mlp_ms * 1e3, 2)},
+        # the second factor streams the same number of weight bytes (one row of W2 per live neuron)
+        "second_factor": {"kernel": "select_gemm_down_kernel + select_gemm_down_reduce_kernel", "bound": "hbm",
+                          "achieved": round(bytes_sel / (down_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                          "unit": "GB/s", "frac": round(bytes_sel / (down_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          "avg_us": round(down_ms * 1e3, 2)},
         "dense_over_selective": None if args.no_dense else round(dense_ms / gemm_ms, 3),
         "ideal_N_over_selected": round(w.N / max(n_sel, 1), 3),
         "roofline": {"kernel": "select_gemm_stream_kernel + select_gemm_reduce_kernel" if wide else "select_gemm_kernel",

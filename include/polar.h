@@ -243,6 +243,38 @@ int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Second factor of the sparsified MLP (Section 3.1: MLP_{S_B}(x) = sigma(x W_{1,S_B}) W_{2,S_B}^T;
+ * Section 4.1 and Appendix "Sparse Kernels": indexing fused into the product, weights stored one
+ * contiguous row per neuron).  The gather runs along the contraction axis:
+ *
+ *   Y[m, c] = sum_{j < live} h16(Hact[m, j]) * W2[idx[j], c]
+ *
+ *   Hact   in   [M, cap] float, row-major with leading dimension cap: the selected neurons'
+ *               activations, as polar_select_gemm[_ws] writes them.  h16: each value is rounded
+ *               to dt (nearest, ties to even) before the multiply, as a 16-bit model holds it.
+ *               Columns at or beyond the live count are not read.  4-byte aligned.
+ *   W2     in   [N, Kout] dt: row n holds neuron n's Kout output weights.  16-byte aligned.
+ *   idx    in   [cap] int32 neuron ids, position j pairs with column j of Hact; an id outside
+ *               [0,N) contributes nothing
+ *   count  in   [1] int32, nullable, DEVICE pointer: live entries of idx (clamped to [0, cap]);
+ *               NULL means all cap
+ *   Y      out  [M, Kout] float, row-major; every element is written (zeros when nothing is
+ *               live).  16-byte aligned.
+ *   workspace   required scratch, DEVICE pointer, 16-byte aligned, caller-owned, at least
+ *               polar_select_gemm_down_workspace_bytes(M, Kout, cap) bytes (else POLAR_EWORKSPACE);
+ *               contents are overwritten; calls that overlap in time need separate workspaces
+ *
+ * 16-bit operands, float accumulation on the matrix cores, float output.  M <= 64 and Kout a
+ * multiple of 256, else POLAR_EUNSUPPORTED.  Two launches; the contraction is cut into ranges
+ * whose sums are added in a fixed order, so results are reproducible for given sizes and count.
+ * Hact and idx may be NULL when cap == 0.
+ */
+int polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap, size_t *bytes);
+int polar_select_gemm_down(const float *Hact, const void *W2, const int32_t *idx, const int32_t *count,
+                           float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/*
  * Batch neuron index (Section 4.1: the predicted activations of all requests are aggregated
  * into one index tensor; Section 3.1: the union set S_B).
  *
@@ -290,7 +322,7 @@ const char *polar_strerror(int status);
 int polar_last_hip_error(void);
 /* ABI version: major * 1000 + minor (1100: adds polar_sha_launches and polar_probe_read; group sizes up to 16;
  * 1200: adds polar_select_gemm_ws and polar_select_gemm_workspace_bytes; 1300: adds polar_neuron_union_ws and
- * polar_neuron_union_workspace_bytes). */
+ * polar_neuron_union_workspace_bytes; 1400: adds polar_select_gemm_down and its workspace query). */
 int polar_version(void);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down", "polar_select_gemm_down_workspace_bytes", "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -76,6 +76,10 @@ def lib() -> ctypes.CDLL:
         L.polar_select_gemm_ws.restype = i
         L.polar_select_gemm_workspace_bytes.argtypes = [i, ctypes.POINTER(ctypes.c_size_t)]
         L.polar_select_gemm_workspace_bytes.restype = i
+        L.polar_select_gemm_down.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, ctypes.c_size_t, vp]
+        L.polar_select_gemm_down.restype = i
+        L.polar_select_gemm_down_workspace_bytes.argtypes = [i, i, i, ctypes.POINTER(ctypes.c_size_t)]
+        L.polar_select_gemm_down_workspace_bytes.restype = i
         L.polar_neuron_union.argtypes = [vp, i, i, i, i, vp, vp, vp]
         L.polar_neuron_union.restype = i
         L.polar_neuron_union_ws.argtypes = [vp, i, i, i, i, vp, vp, vp, ctypes.c_size_t, vp]
@@ -303,6 +307,37 @@ def select_gemm(A: torch.Tensor, W: torch.Tensor, idx: torch.Tensor,
                                  _dev(count, "count", torch.int32), _dev(out, "out", torch.float32),
                                  M, K, N, cap, _dtype_code(A), 1 if relu else 0, _stream())
     _check(rc, "polar_select_gemm")
+    return out
+
+
+def select_gemm_down_workspace_bytes(M: int, Kout: int, cap: int) -> int:
+    """Workspace size polar_select_gemm_down requires."""
+    n = ctypes.c_size_t(0)
+    _check(lib().polar_select_gemm_down_workspace_bytes(M, Kout, cap, ctypes.byref(n)),
+           "polar_select_gemm_down_workspace_bytes")
+    return int(n.value)
+
+
+def select_gemm_down(H: torch.Tensor, W2: torch.Tensor, idx: torch.Tensor,
+                     count: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """h16(H) @ W2[idx]: H float32 [M,cap] (select_gemm's output), W2 [N,Kout] fp16/bf16 (one row per
+    neuron), idx int32 [cap], count int32 [1] on the device (None: all live) -> float32 [M,Kout].
+    A workspace is allocated when none is given."""
+    M, cap = H.shape
+    N, Kout = W2.shape
+    if idx.shape[0] != cap:
+        raise ValueError("idx must have one entry per column of H")
+    if out is None:
+        out = torch.empty((M, Kout), dtype=torch.float32, device=W2.device)
+    if workspace is None:
+        workspace = torch.empty(max(select_gemm_down_workspace_bytes(M, Kout, cap), 16), dtype=torch.uint8,
+                                device=W2.device)
+    rc = lib().polar_select_gemm_down(_dev(H, "H", torch.float32), _dev(W2, "W2"), _dev(idx, "idx", torch.int32),
+                                      _dev(count, "count", torch.int32), _dev(out, "out", torch.float32),
+                                      M, Kout, N, cap, _dtype_code(W2), _dev(workspace, "workspace"),
+                                      workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "polar_select_gemm_down")
     return out
 
 

@@ -11,7 +11,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 LIB_PATH = os.path.join(_PKG, "libpolar.so")
-SOURCES = ["polar_abi.hip", "polar_router.hip", "polar_sha.hip", "polar_sha_gqa.hip", "polar_label.hip", "polar_probe.hip", "polar_gemm.hip"]
+SOURCES = ["polar_abi.hip", "polar_router.hip", "polar_sha.hip", "polar_sha_gqa.hip", "polar_label.hip", "polar_probe.hip", "polar_gemm.hip", "polar_gemm_down.hip"]
 
 # Packed-fp32 instructions are switched off for all device code of this library.
 HIPCC_FLAGS = [

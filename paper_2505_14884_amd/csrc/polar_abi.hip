@@ -162,7 +162,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 1300; }
+int polar_version(void) { return 1400; }
 
 int polar_last_hip_error(void) { return g_last_hip_error; }
 
@@ -377,6 +377,38 @@ int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32
     if (!count_out || (cap > 0 && !idx_out) || ((long long)B * kn > 0 && !topk)) return POLAR_EINVAL;
     return record(launch_neuron_union(topk, B, kn, N, cap, idx_out, count_out,
                                       static_cast<hipStream_t>(stream)));
+}
+
+static int check_down_sizes(int M, int Kout, int N, int cap)
+{
+    if (M < 0 || Kout < 1 || N < 1 || cap < 0) return POLAR_EINVAL;
+    if (Kout % 256 != 0 || M > 64 || (long long)N * Kout > (1ll << 40)) return POLAR_EUNSUPPORTED;
+    return POLAR_OK;
+}
+
+int polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap, size_t *bytes)
+{
+    if (!bytes) return POLAR_EINVAL;
+    const int rc = check_down_sizes(M, Kout, 1, cap);
+    if (rc != POLAR_OK) return rc;
+    *bytes = M == 0 ? 0 : select_gemm_down_workspace_bytes(M, Kout, cap);
+    return POLAR_OK;
+}
+
+int polar_select_gemm_down(const float *H, const void *W2, const int32_t *idx, const int32_t *count,
+                           float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    if (!dtype_ok(dt)) return POLAR_EINVAL;
+    const int rc = check_down_sizes(M, Kout, N, cap);
+    if (rc != POLAR_OK) return rc;
+    if (M == 0) return POLAR_OK;
+    if (!W2 || !Y || !workspace || (cap > 0 && (!H || !idx))) return POLAR_EINVAL;
+    if (((uintptr_t)W2 & 15u) || ((uintptr_t)Y & 15u) || ((uintptr_t)workspace & 15u) || ((uintptr_t)H & 3u))
+        return POLAR_EINVAL;
+    if (workspace_bytes < select_gemm_down_workspace_bytes(M, Kout, cap)) return POLAR_EWORKSPACE;
+    return record(launch_select_gemm_down(H, W2, idx, count, Y, M, Kout, N, cap, dt, workspace,
+                                          static_cast<hipStream_t>(stream)));
 }
 
 int polar_neuron_union_workspace_bytes(int B, int kn, int N, size_t *bytes)

@@ -1,0 +1,335 @@
+// Second factor of the sparsified MLP for gfx950 (Section 3.1: MLP_{S_B}(x) =
+// sigma(x W_{1,S_B}) W_{2,S_B}^T, the sum running over the selected neurons only; Section 4.1 and
+// Appendix "Sparse Kernels": the index is applied inside the kernel, the weights are stored one
+// contiguous row per neuron).
+//
+//   Y[m, c] = sum_{j < live} h16(H[m, j]) * W2[idx[j], c]       H [M,cap] float, W2 [N,Kout]
+//
+// Here the gather runs along the contraction axis: every selected neuron contributes one row of
+// Kout weights, read once and used for M <= 64 multiply-adds per element, so the kernel is bound
+// by HBM like the first factor and is organised around streaming those rows:
+//   * a wave owns 128 output columns and all M rows (MT * 8 accumulator tiles of 16 x 16) and walks
+//     the selected neurons 32 at a time: 8 loads of 16 bytes per lane fetch 32 row pieces of 256
+//     bytes (16 lanes per piece, 4 pieces per load: whole cache lines).  A lane then holds an
+//     8 x 8 block (8 neurons x 8 columns) of 16-bit weights; transposed inside the lane (byte
+//     permutes, no LDS) it is the B operand of 8 matrix-core steps, one per column e of the block:
+//     lane (x, kg) feeds column 8x + e with the neurons 8kg .. 8kg + 7 of the block.
+//   * the activations are the A operand: lane (x, kg) reads H[m = 16t + x, 8 consecutive j] as
+//     floats, zeroes the entries whose id is invalid or beyond the live count and rounds them to
+//     the storage type (the matrix cores take 16-bit operands; a 16-bit model holds them so).
+//   * the waves of a workgroup do not talk to each other while they stream: no LDS tile, no
+//     barrier.  A workgroup is a pair of column blocks times a pair of neuron parities: waves
+//     (c, 0) and (c, 1) take the even and the odd 32-neuron blocks of the workgroup's range and
+//     add their accumulators through LDS at the end.
+//   * the launch is Kout/256 column blocks times NS contraction ranges, NS chosen so that the
+//     grid fills the compute units once; range s covers an NS-th of the live blocks, whatever the
+//     live count is (it stays on the device), and leaves its sums in the workspace; a second
+//     kernel adds the NS sums of every output element in ascending range order and stores Y.
+#include "polar_internal.h"
+
+namespace polar {
+namespace {
+
+#ifndef POLAR_DOWN_RING
+#define POLAR_DOWN_RING 2
+#endif
+constexpr int kDownThreads = 256;
+constexpr int kDownWaveCols = 128;               // output columns per wave
+constexpr int kDownGroupCols = 2 * kDownWaveCols;    // per workgroup (two column blocks x two parities)
+constexpr int kDownBlock = 32;                   // neurons per step (the contraction depth of one MFMA)
+constexpr int kDownMaxIds = 8192;                // ids of a workgroup's range kept in LDS
+constexpr int kDownTargetGroups = 256;           // one workgroup per compute unit
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+// four floats that need only 4-byte alignment (a row of H starts wherever cap puts it)
+typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+
+template <bool BF> __device__ __forceinline__ f32x4 mfma16x16x32(const u32x4 &a, const u32x4 &b, f32x4 c)
+{
+    if (BF)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// bit pattern of x rounded to the storage type (nearest, ties to even)
+template <bool BF> __device__ __forceinline__ unsigned int to_storage(float x)
+{
+    if constexpr (BF)
+        return (unsigned int)__builtin_bit_cast(unsigned short, (__bf16)x);
+    else
+        return (unsigned int)__builtin_bit_cast(unsigned short, (_Float16)x);
+}
+
+// The blocks of 32 neurons are dealt to the NS ranges as evenly as whole blocks allow.
+__device__ __forceinline__ int range_bound(int blocks, int NS, int s) { return (int)((long)blocks * s / NS); }
+
+// grid = (Kout / 256) * NS workgroups; block = 256 threads (4 waves).
+// part holds, per (range, column block of 128), MT * 8 accumulator tiles of 64 lanes x 16 bytes.
+template <bool BF, int MT>
+__global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
+    const float *__restrict__ H, const uint16_t *__restrict__ W2, const int32_t *__restrict__ idx,
+    const int32_t *__restrict__ count_ptr, float *__restrict__ part, int M, int Kout, int N, int cap,
+    int NS)
+{
+    // the ids of the range while streaming, the odd waves' accumulators at the end
+    __shared__ __align__(16) unsigned char smem[2 * MT * 8 * 64 * 16 > kDownMaxIds * 4 ? 2 * MT * 8 * 64 * 16
+                                                                                    : kDownMaxIds * 4];
+    int *sh_id = reinterpret_cast<int *>(smem);
+
+    int count = cap;
+    if (count_ptr) {
+        const int c = *count_ptr;
+        count = c < 0 ? 0 : (c < cap ? c : cap);
+    }
+    const int groups = Kout / kDownGroupCols;
+    const int cg = (int)blockIdx.x % groups, s = (int)blockIdx.x / groups;
+    const int blocks = (count + kDownBlock - 1) / kDownBlock;
+    const int b_begin = range_bound(blocks, NS, s), b_end = range_bound(blocks, NS, s + 1);
+    const int j_begin = b_begin * kDownBlock;
+
+    // the wave index is the same in every lane: kept scalar, so that the loop below and its
+    // branches are scalar too and the compiler's count of outstanding loads stays exact
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int x = lane & 15, kg = lane >> 4;
+    const int cw = wave & 1, parity = wave >> 1;
+    const int col0 = cg * kDownGroupCols + cw * kDownWaveCols;
+
+    // ids of the range, -1 for an id outside [0, N) or a position at or beyond the live count
+    for (int e = tid; e < (b_end - b_begin) * kDownBlock; e += kDownThreads) {
+        const int j = j_begin + e;
+        const int id = j < count ? idx[j] : -1;
+        sh_id[e] = (id >= 0 && id < N) ? id : -1;
+    }
+    __syncthreads();
+
+    f32x4 acc[MT][8];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[t][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // the rows of H this lane feeds (clamped: rows m >= M are computed and never stored)
+    const float *hrow[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        int m = 16 * t + x;
+        m = m < M ? m : M - 1;
+        hrow[t] = H + (size_t)m * cap;
+    }
+    const uint16_t *wcol = W2 + col0 + 8 * x;
+
+    // Ring of two blocks: slot r holds this wave's block b (weights: 8 row pieces; activations: 8
+    // floats per row tile; ids of the lane's 8 neurons).  A block index beyond the range is
+    // clamped for the loads and skipped for the arithmetic.
+    u32x4 wq[POLAR_DOWN_RING][8];
+    f32x4 hq[POLAR_DOWN_RING][MT][2];
+    i32x4 iq[POLAR_DOWN_RING][2];
+    const int last = b_end - 1;
+#ifdef POLAR_DOWN_ABLATE_H
+#define POLAR_DOWN_J0(v) (8 * kg)
+#else
+#define POLAR_DOWN_J0(v) (v)
+#endif
+#ifdef POLAR_DOWN_ABLATE_W
+#define POLAR_DOWN_ID(v) ((v) & 31)
+#else
+#define POLAR_DOWN_ID(v) (v)
+#endif
+#define POLAR_DOWN_FETCH(r, block)                                                                 \
+    {                                                                                              \
+        const int bb = (block) < last ? (block) : last;                                            \
+        const int e0 = (bb - b_begin) * kDownBlock + 8 * kg;      /* this lane's 8 neurons */       \
+        iq[r][0] = *reinterpret_cast<const i32x4 *>(sh_id + e0);                                   \
+        iq[r][1] = *reinterpret_cast<const i32x4 *>(sh_id + e0 + 4);                               \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
+        {                                                                                          \
+            const int id = POLAR_DOWN_ID(iq[r][i >> 2][i & 3]);                                    \
+            wq[r][i] = *reinterpret_cast<const u32x4 *>(wcol + (size_t)(id < 0 ? 0 : id) * Kout);  \
+        }                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+        const int j0 = POLAR_DOWN_J0(j_begin + e0);                                                \
+        if (j_begin + (bb - b_begin + 1) * kDownBlock <= cap) {   /* the same for the whole wave */  \
+            _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
+            {                                                                                      \
+                hq[r][t][0] = *reinterpret_cast<const f32x4u *>(hrow[t] + j0);                     \
+                hq[r][t][1] = *reinterpret_cast<const f32x4u *>(hrow[t] + j0 + 4);                 \
+            }                                                                                      \
+        } else {                                 /* the block that holds the end of the rows: */   \
+            _Pragma("unroll") for (int t = 0; t < MT; ++t)        /* element by element, clamped */ \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i)                                      \
+                    hq[r][t][i >> 2][i & 3] = hrow[t][j0 + i < cap ? j0 + i : cap - 1];            \
+        }                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+    }
+#define POLAR_DOWN_MULTIPLY(r)                                                                     \
+    {                                                                                              \
+        /* B operands: o[e] = column e of the lane's 8 x 8 block, its 8 neurons packed in pairs */  \
+        u32x4 o[8];                                                                                \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e)                                              \
+            _Pragma("unroll") for (int p = 0; p < 4; ++p)                                          \
+        {                                                                                          \
+            const unsigned int lo = wq[r][2 * p][e >> 1], hi = wq[r][2 * p + 1][e >> 1];           \
+            o[e][p] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16)); \
+        }                                                                                          \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
+        {                                                                                          \
+            u32x4 a;                                                                               \
+            _Pragma("unroll") for (int p = 0; p < 4; ++p)                                          \
+            {                                                                                      \
+                const int i0 = 2 * p, i1 = 2 * p + 1;                                              \
+                const float h0 = iq[r][i0 >> 2][i0 & 3] >= 0 ? hq[r][t][i0 >> 2][i0 & 3] : 0.0f;   \
+                const float h1 = iq[r][i1 >> 2][i1 & 3] >= 0 ? hq[r][t][i1 >> 2][i1 & 3] : 0.0f;   \
+                a[p] = to_storage<BF>(h0) | (to_storage<BF>(h1) << 16);                            \
+            }                                                                                      \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) acc[t][e] = mfma16x16x32<BF>(a, o[e], acc[t][e]); \
+        }                                                                                          \
+    }
+
+    int b = b_begin + parity;
+    if (b < b_end) {
+#if POLAR_DOWN_RING == 3
+        POLAR_DOWN_FETCH(0, b)
+        POLAR_DOWN_FETCH(1, b + 2)
+        POLAR_DOWN_FETCH(2, b + 4)
+        for (; b < b_end; b += 6) {
+            POLAR_DOWN_MULTIPLY(0)
+            POLAR_DOWN_FETCH(0, b + 6)
+            if (b + 2 < b_end) POLAR_DOWN_MULTIPLY(1)
+            POLAR_DOWN_FETCH(1, b + 8)
+            if (b + 4 < b_end) POLAR_DOWN_MULTIPLY(2)
+            POLAR_DOWN_FETCH(2, b + 10)
+        }
+#else
+        POLAR_DOWN_FETCH(0, b)
+        POLAR_DOWN_FETCH(1, b + 2)
+        for (; b < b_end; b += 4) {
+            POLAR_DOWN_MULTIPLY(0)
+            POLAR_DOWN_FETCH(0, b + 4)
+            if (b + 2 < b_end) POLAR_DOWN_MULTIPLY(1)
+            POLAR_DOWN_FETCH(1, b + 6)
+        }
+#endif
+    }
+#undef POLAR_DOWN_MULTIPLY
+#undef POLAR_DOWN_FETCH
+
+    // odd-parity waves hand their sums over through LDS; even-parity waves add them (one fixed
+    // order) and store the range's sums
+    __syncthreads();                             // the ids are no longer needed
+    f32x4 *sh_acc = reinterpret_cast<f32x4 *>(smem) + (size_t)cw * MT * 8 * 64 + lane;
+    if (parity == 1) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sh_acc[(t * 8 + e) * 64] = acc[t][e];
+    }
+    __syncthreads();
+    if (parity == 0) {
+        f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
+                     ((size_t)s * (Kout / kDownWaveCols) + (size_t)cg * 2 + cw) * (MT * 8) * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dst[(t * 8 + e) * 64] = acc[t][e] + sh_acc[(t * 8 + e) * 64];
+    }
+}
+
+// grid = (Kout / 128) * MT workgroups of 64 threads: workgroup (column block, row tile t) adds the
+// NS sums of its 16 x 128 outputs in ascending range order.  Accumulator layout: lane (x, kg)
+// holds rows 16t + 4kg + i (i < 4) of column 8x + e for each of its 8 tiles e, so per row it
+// owns 8 consecutive columns: two 16-byte stores.
+template <int MT>
+__global__ __launch_bounds__(64) void select_gemm_down_reduce_kernel(const float *__restrict__ part,
+                                                                    float *__restrict__ Y, int M, int Kout,
+                                                                    int NS)
+{
+    const int cb = (int)blockIdx.x / MT, t = (int)blockIdx.x % MT;
+    const int lane = threadIdx.x, x = lane & 15, kg = lane >> 4;
+    const size_t per_range = (size_t)(Kout / kDownWaveCols) * (MT * 8) * 64;
+    const f32x4 *src = reinterpret_cast<const f32x4 *>(part) + ((size_t)cb * (MT * 8) + t * 8) * 64 + lane;
+    f32x4 sum[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sum[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < NS; ++s) {
+        f32x4 v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = src[(size_t)s * per_range + e * 64];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum[e] += v[e];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = 16 * t + 4 * kg + i;
+        if (m >= M) continue;
+        f32x4 *dst = reinterpret_cast<f32x4 *>(Y + (size_t)m * Kout + cb * kDownWaveCols + 8 * x);
+        dst[0] = (f32x4){sum[0][i], sum[1][i], sum[2][i], sum[3][i]};
+        dst[1] = (f32x4){sum[4][i], sum[5][i], sum[6][i], sum[7][i]};
+    }
+}
+
+int down_mt(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : 4); }
+
+// contraction ranges: enough to fill the compute units once, and never more ids per range than
+// the kernel keeps in LDS
+int down_ranges(int Kout, int cap)
+{
+    const int groups = Kout / kDownGroupCols;
+    int ns = kDownTargetGroups / groups;
+    if (ns < 1) ns = 1;
+    const long blocks = ((long)cap + kDownBlock - 1) / kDownBlock;
+    const long max_blocks = kDownMaxIds / kDownBlock - 1;     // a range holds at most blocks / ns + 1 blocks
+    while (blocks / ns + 1 > max_blocks + 1) ++ns;
+    if (ns > blocks && blocks > 0) ns = (int)blocks;          // no empty ranges beyond the live blocks' count
+    return ns < 1 ? 1 : ns;
+}
+
+}  // namespace
+
+size_t select_gemm_down_workspace_bytes(int M, int Kout, int cap)
+{
+    return (size_t)down_ranges(Kout, cap) * (Kout / kDownWaveCols) * down_mt(M) * 8 * 64 * sizeof(f32x4);
+}
+
+template <bool BF>
+static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H, const uint16_t *W2,
+                                 const int32_t *idx, const int32_t *count, float *Y, float *part, int M,
+                                 int Kout, int N, int cap)
+{
+    const dim3 grid((unsigned)(Kout / kDownGroupCols * NS)), block(kDownThreads);
+    const dim3 rgrid((unsigned)(Kout / kDownWaveCols * mt)), rblock(64);
+    switch (mt) {
+    case 1:
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 1>), grid, block, 0, st, H, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_reduce_kernel<1>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
+        break;
+    case 2:
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 2>), grid, block, 0, st, H, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_reduce_kernel<2>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
+        break;
+    default:
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 4>), grid, block, 0, st, H, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_reduce_kernel<4>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
+        break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t *idx, const int32_t *count,
+                                   float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
+                                   hipStream_t stream)
+{
+    const int mt = down_mt(M), NS = down_ranges(Kout, cap);
+    const uint16_t *W16 = static_cast<const uint16_t *>(W2);
+    float *part = static_cast<float *>(workspace);
+    return dt == POLAR_BF16 ? launch_down_mt<true>(mt, NS, stream, H, W16, idx, count, Y, part, M, Kout, N, cap)
+                            : launch_down_mt<false>(mt, NS, stream, H, W16, idx, count, Y, part, M, Kout, N, cap);
+}
+
+}  // namespace polar

@@ -73,6 +73,11 @@ size_t select_gemm_workspace_bytes(int M);
 hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
                                  float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
                                  void *workspace, size_t workspace_bytes, hipStream_t stream);
+// Second MLP factor: Y = h16(H) * W2[idx,:] (M <= 64, Kout % 256 == 0; the workspace is required).
+size_t select_gemm_down_workspace_bytes(int M, int Kout, int cap);
+hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t *idx, const int32_t *count,
+                                   float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
+                                   hipStream_t stream);
 hipError_t launch_read_probe(const void *src, size_t slabs, size_t slab_bytes, int nontemporal,
                              uint32_t *sink, hipStream_t stream);
 int neuron_union_max_n();

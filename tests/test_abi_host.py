@@ -169,6 +169,30 @@ def test_select_gemm_and_union_argument_errors():
     assert polar.neuron_union_workspace_bytes(4, 1024, 36864) == 2 * 1152 * 4
 
 
+def test_select_gemm_down_argument_errors():
+    L = binding.lib()
+    A16 = ctypes.c_void_p(0x1000)
+    big = 1 << 30
+    d = lambda H=A16, W2=A16, idx=FAKE, Y=A16, M=4, Kout=256, N=64, cap=32, dt=0, ws=A16, wsb=big: \
+        L.polar_select_gemm_down(H, W2, idx, None, Y, M, Kout, N, cap, dt, ws, wsb, None)
+    assert d(M=-1) == EINVAL and d(Kout=0) == EINVAL and d(N=0) == EINVAL and d(cap=-1) == EINVAL
+    assert d(dt=2) == EINVAL
+    assert d(Kout=384) == EUNSUPPORTED and d(M=65) == EUNSUPPORTED
+    assert d(W2=None) == EINVAL and d(Y=None) == EINVAL and d(ws=None) == EINVAL
+    assert d(H=None) == EINVAL and d(idx=None) == EINVAL
+    assert d(H=ctypes.c_void_p(0x1002)) == EINVAL and d(Y=ctypes.c_void_p(0x1008)) == EINVAL
+    assert d(wsb=16) == EWORKSPACE
+    assert d(M=0, H=None, W2=None, idx=None, Y=None, ws=None) == OK
+    n = ctypes.c_size_t(0)
+    q = lambda M, Kout, cap: L.polar_select_gemm_down_workspace_bytes(M, Kout, cap, ctypes.byref(n))
+    assert q(4, 256, 32) == OK and n.value > 0 and n.value % (256 * 16 * 4) == 0
+    assert q(64, 9216, 36864) == OK and n.value == 7 * 64 * 9216 * 4       # 36 column groups x 7 ranges
+    assert q(64, 9216, 400000) == OK and n.value % (64 * 9216 * 4) == 0 and n.value // (64 * 9216 * 4) >= 49
+    assert q(0, 256, 32) == OK and n.value == 0
+    assert q(4, 300, 32) == EUNSUPPORTED and q(65, 256, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
+    assert L.polar_select_gemm_down_workspace_bytes(4, 256, 32, None) == EINVAL
+
+
 def test_workspace_size_is_consistent_with_the_chunking():
     L = binding.lib()
     for (B, Hq, Hkv, S, d, k) in [(4, 8, 8, 256, 64, 4), (32, 32, 32, 1920, 128, 16),

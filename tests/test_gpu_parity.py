@@ -609,6 +609,83 @@ def test_sparse_mlp_first_layer(name, ws):
         assert torch.equal(out[:, :c], again[:, :c])
 
 
+# ----------------------------------------------------------------------------- second MLP factor
+def down_case(M, Kout, N, idx_host, dtype, count=None, seed=0, scale=1.0):
+    g = torch.Generator(device=DEV).manual_seed(2000 + seed)
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+    cap = len(idx_host)
+    # activations like the first factor's output: ReLU of a symmetric value; NaN beyond the live
+    # count (those columns are never written by the first factor and must not be read)
+    H = torch.relu(torch.randn((M, max(cap, 1)), generator=g, device=DEV))[:, :cap].contiguous() * scale
+    live = cap if count is None else max(0, min(count, cap))
+    H[:, live:] = float("nan")
+    W2 = (torch.randn((N, Kout), generator=g, device=DEV) / max(live, 1) ** 0.5).to(tdt)
+    idx = torch.tensor(idx_host, dtype=torch.int32, device=DEV)
+    cnt = None if count is None else torch.tensor([count], dtype=torch.int32, device=DEV)
+    out = torch.full((M, Kout), float("nan"), dtype=torch.float32, device=DEV)
+    nbytes = polar.select_gemm_down_workspace_bytes(M, Kout, cap)
+    workspace = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    polar.select_gemm_down(H, W2, idx, count=cnt, out=out, workspace=workspace)
+    torch.cuda.synchronize()
+    want = orc.select_gemm_down(H[:, :live].cpu().numpy(), host_bits(W2), np.array(idx_host[:live], np.int32), dtype)
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    err = np.abs(got - want).max()
+    assert err <= GEMM_TOL * max(scale, 1.0), err
+    return err
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 33, 64])
+def test_select_gemm_down_shapes(dtype, M):
+    say("\ncase select_gemm_down", dtype, M)
+    rng = np.random.default_rng(100 + M)
+    N = 500
+    for Kout, n in ((256, 77), (512, 300), (1024, 1), (256, 33)):      # ragged blocks of 32, a single neuron
+        idx = rng.permutation(N)[:n].tolist()
+        say("   Kout %d, %d neurons: err %.2e" % (Kout, n, down_case(M, Kout, N, idx, dtype, seed=M + n)))
+
+
+def test_select_gemm_down_ids_counts_and_long_contraction():
+    say("\ncase select_gemm_down ids")
+    idx = [3, -1, 3, 99, 100, 7, 0, 42] * 5                # invalid ids (-1, 100) and repeats
+    down_case(9, 256, 100, idx, "f16")
+    down_case(9, 256, 100, idx, "bf16", count=17)          # device-side live count
+    down_case(9, 256, 100, idx, "bf16", count=1000)        # beyond the capacity: clamped
+    down_case(9, 256, 100, idx, "f16", count=0)            # nothing live: zeros
+    down_case(4, 512, 100, [], "f16")                      # no capacity at all: zeros
+    rng = np.random.default_rng(9)
+    down_case(64, 512, 40000, rng.permutation(40000)[:12000].tolist(), "f16", seed=1)   # many ranges, long sums
+    down_case(33, 256, 20000, rng.permutation(20000)[:9000].tolist(), "bf16", count=8191, seed=2)
+    down_case(64, 256, 300, list(range(299, -1, -1)), "f16", scale=50.0)       # activations that round coarsely
+
+
+def test_sparsified_mlp_both_factors():
+    """Union -> first factor -> second factor on one stream, no host round trip, against the
+    oracle on sampled output columns (OPT-66B FFN shape)."""
+    w = wl.MLP_CONFIGS["M2_opt66b_ffn"]
+    say("\ncase both factors", w)
+    x, W1, topk = wl.make_mlp_inputs(w, DEV)
+    g = torch.Generator(device=DEV).manual_seed(w.seed + 1)
+    W2 = (torch.randn((w.N, w.K), generator=g, device=DEV) / 100.0).to(W1.dtype)
+    idx, count = polar.neuron_union(topk, w.N)
+    hidden = polar.select_gemm(x, W1, idx, count=count, relu=True,
+                               workspace=polar.alloc_select_gemm_workspace(w.B, DEV))
+    y = polar.select_gemm_down(hidden, W2, idx, count=count)
+    again = polar.select_gemm_down(hidden, W2, idx, count=count)
+    torch.cuda.synchronize()
+    c = int(count.item())
+    cols = np.unique(np.linspace(0, w.K - 1, num=48).astype(np.int64))
+    S = idx[:c].long()
+    want = orc.select_gemm_down(hidden[:, :c].cpu().numpy(), host_bits(W2[S][:, torch.from_numpy(cols).to(DEV)]),
+                                np.arange(c, dtype=np.int32), w.dtype)
+    got = y[:, torch.from_numpy(cols).to(DEV)].cpu().numpy()
+    err = np.abs(got - want).max()
+    say("   %d live neurons, max-abs error %.3e on %d sampled columns, |y| up to %.2f" % (c, err, len(cols), np.abs(want).max()))
+    assert err <= GEMM_TOL
+    assert torch.isfinite(y).all() and torch.equal(y, again)
+
+
 def test_read_probe_folds_every_word_of_every_slab():
     """The bandwidth yardstick really reads what it claims: each slab's result is the XOR of its
     words (slabs of whole 16 KiB wave steps, so no clamped tail load repeats a word)."""
