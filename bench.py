@@ -61,6 +61,10 @@ def parse_args():
                     help="workload of --phase select_gemm (see workloads.MLP_CONFIGS)")
     ap.add_argument("--density", type=float, default=0.0,
                     help="--phase select_gemm: override the target union density")
+    ap.add_argument("--mlp-layers", type=int, default=3,
+                    help="--phase select_gemm: copies of the weight matrices the launches rotate through, so that "
+                         "no launch finds its rows in the 256 MB last-level cache left there by the one before "
+                         "(a model streams another layer's weights every time)")
     ap.add_argument("--gemm-form", choices=["wide", "narrow"], default="wide",
                     help="--phase select_gemm: 'wide' passes a workspace (128-neuron tiles, evenly split "
                          "fixed-size launch + reduction), 'narrow' calls the 32-neuron one-launch kernel")
@@ -100,8 +104,13 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
     def union():
         polar.neuron_union(topk, w.N, workspace=union_ws, out=(idx, count))
 
+    layers = max(1, args.mlp_layers)
+    W1s = [W1] + [W1.clone() for _ in range(layers - 1)]
+    turn = [0]
+
     def gemm(i=0):
-        polar.select_gemm(x, W1, idx, count=count, relu=True, out=out, workspace=workspace)
+        turn[0] += 1
+        polar.select_gemm(x, W1s[turn[0] % layers], idx, count=count, relu=True, out=out, workspace=workspace)
 
     union()
     torch.cuda.synchronize()
@@ -110,9 +119,13 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
     all_idx = torch.arange(w.N, dtype=torch.int32, device=dev)
     dense_out = torch.empty((w.B, w.N), dtype=torch.float32, device=dev)
 
-    if args.phase == "select_gemm_only":
+    if args.phase == "select_gemm_only":       # counter runs: both factors, nothing else
+        W2o = [torch.zeros_like(W1) for _ in range(layers)]
+        yo = torch.empty((w.B, w.K), dtype=torch.float32, device=dev)
+        wso = torch.empty(polar.select_gemm_down_workspace_bytes(w.B, w.K, cap), dtype=torch.uint8, device=dev)
         for i in range(args.warmup + args.steps):
             gemm()
+            polar.select_gemm_down(out, W2o[i % layers], idx, count=count, out=yo, workspace=wso)
         torch.cuda.synchronize()
         print(json.dumps({"phase": "select_gemm_only", "workload": w.name,
                           "launches": args.warmup + args.steps,
@@ -142,13 +155,19 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
     union_ms = ev(union, n_ev)
     dense_ms = float("nan") if args.no_dense else ev(
         lambda: polar.select_gemm(x, W1, all_idx, relu=True, out=dense_out, workspace=workspace), max(5, n_ev // 4))
+    # (all rows of one matrix are 680 MB: more than the last-level cache holds, no rotation needed)
     achieved = bytes_sel / (gemm_ms * 1e-3) / 1e9
     # second factor of the sparsified MLP on the same index: Y = h16(hidden) W2[idx,:]
     g2 = torch.Generator(device=dev).manual_seed(w.seed + 1)
     W2 = (torch.randn((w.N, w.K), generator=g2, device=dev) / 100.0).to(W1.dtype)
+    W2s = [W2] + [W2.clone() for _ in range(layers - 1)]
     y = torch.empty((w.B, w.K), dtype=torch.float32, device=dev)
     down_ws = torch.empty(polar.select_gemm_down_workspace_bytes(w.B, w.K, cap), dtype=torch.uint8, device=dev)
-    down = lambda: polar.select_gemm_down(out, W2, idx, count=count, out=y, workspace=down_ws)
+
+    def down():
+        turn[0] += 1
+        polar.select_gemm_down(out, W2s[turn[0] % layers], idx, count=count, out=y, workspace=down_ws)
+
     down_ms = ev(down, n_ev)
     mlp_ms = ev(lambda: (union(), gemm(), down()), n_ev)
     result = {
@@ -160,6 +179,7 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
         "data": "synthetic",
         "config": {"workload": "%s: B=%d K=%d N=%d %s weights, union %d neurons (%.1f %%)"
                                % (w.name, w.B, w.K, w.N, w.dtype, n_sel, 100.0 * n_sel / w.N),
+                   "weight_copies_rotated": layers,
                    "selected_weight_bytes": bytes_sel, "dense_weight_bytes": w.N * w.K * 2},
         "breakdown_us": {"neuron_union": round(union_ms * 1e3, 2), "select_gemm": round(gemm_ms * 1e3, 2),
                          "dense_gemm_all_rows": None if args.no_dense else round(dense_ms * 1e3, 2),
@@ -178,7 +198,7 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                      "avg_us": round(gemm_ms * 1e3, 2),
                      "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),
                      # rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled; profiles/select_gemm_M2_opt66b_ffn.md
-                     "traffic": (224878494 if wide else 214354185) if (w == wl.MLP_CONFIGS.get(w.name)) else None},
+                     "traffic": (239874332 if wide else 214354185) if (w == wl.MLP_CONFIGS.get(w.name)) else None},
     }
     if not args.no_cpu_baseline:
         from oracle import polar_oracle as orc

@@ -426,7 +426,8 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
         {                                                                                          \
             const u32x4 *p = reinterpret_cast<const u32x4 *>(W + (ahead ? nxt[i] : cur[i])) + x;   \
-            wq[j][i] = p[blk];                                                                     \
+            wq[j][i] = __builtin_nontemporal_load(p + blk);   /* read once: leave the caches to   */ \
+                                                              /* the activations and the partials */ \
         }                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                         \
         _Pragma("unroll") for (int i = 0; i < AP; ++i) aq[j][i] = ap[i][blk];                     \

@@ -14,13 +14,18 @@
 //     8 x 8 block (8 neurons x 8 columns) of 16-bit weights; transposed inside the lane (byte
 //     permutes, no LDS) it is the B operand of 8 matrix-core steps, one per column e of the block:
 //     lane (x, kg) feeds column 8x + e with the neurons 8kg .. 8kg + 7 of the block.
-//   * the activations are the A operand: lane (x, kg) reads H[m = 16t + x, 8 consecutive j] as
-//     floats, zeroes the entries whose id is invalid or beyond the live count and rounds them to
-//     the storage type (the matrix cores take 16-bit operands; a 16-bit model holds them so).
+//   * the activations are the A operand.  A first, small kernel rounds them to the storage type
+//     (the matrix cores take 16-bit operands; a 16-bit model holds them so), zeroes the entries
+//     whose id is invalid or beyond the live count, and pads the rows to a multiple of 32: every
+//     column block needs the same values, so doing it once takes the conversions, the masking and
+//     the row-end special case out of the streaming loop, where lane (x, kg) now reads
+//     H16[m = 16t + x, 8 consecutive j] with one aligned 16-byte load.
 //   * the waves of a workgroup do not talk to each other while they stream: no LDS tile, no
-//     barrier.  A workgroup is a pair of column blocks times a pair of neuron parities: waves
-//     (c, 0) and (c, 1) take the even and the odd 32-neuron blocks of the workgroup's range and
-//     add their accumulators through LDS at the end.
+//     barrier.  A workgroup is a pair of column blocks times four neuron parities: wave (c, p)
+//     takes the 32-neuron blocks p, p + 4, ... of the workgroup's range, and the four add their
+//     accumulators through LDS at the end.  Eight waves per compute unit, two per SIMD, are what
+//     keeps the matrix cores and the vector ALU fed: with one wave per SIMD every dependent
+//     instruction waits out its full latency.
 //   * the launch is Kout/256 column blocks times NS contraction ranges, NS chosen so that the
 //     grid fills the compute units once; range s covers an NS-th of the live blocks, whatever the
 //     live count is (it stays on the device), and leaves its sums in the workspace; a second
@@ -30,10 +35,9 @@
 namespace polar {
 namespace {
 
-#ifndef POLAR_DOWN_RING
-#define POLAR_DOWN_RING 2
-#endif
-constexpr int kDownThreads = 256;
+constexpr int kDownParities = 4;                 // waves that share a column block
+constexpr int kDownThreads = 64 * 2 * kDownParities;
+constexpr int kPrepThreads = 256;
 constexpr int kDownWaveCols = 128;               // output columns per wave
 constexpr int kDownGroupCols = 2 * kDownWaveCols;    // per workgroup (two column blocks x two parities)
 constexpr int kDownBlock = 32;                   // neurons per step (the contraction depth of one MFMA)
@@ -45,8 +49,9 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
-// four floats that need only 4-byte alignment (a row of H starts wherever cap puts it)
+// vectors that need only 4-byte alignment (a row of H starts wherever cap puts it)
 typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef int i32x4u __attribute__((ext_vector_type(4), aligned(4)));
 
 template <bool BF> __device__ __forceinline__ f32x4 mfma16x16x32(const u32x4 &a, const u32x4 &b, f32x4 c)
 {
@@ -69,11 +74,60 @@ template <bool BF> __device__ __forceinline__ unsigned int to_storage(float x)
 // The blocks of 32 neurons are dealt to the NS ranges as evenly as whole blocks allow.
 __device__ __forceinline__ int range_bound(int blocks, int NS, int s) { return (int)((long)blocks * s / NS); }
 
-// grid = (Kout / 256) * NS workgroups; block = 256 threads (4 waves).
+// H16[m, j] = the storage-type bit pattern of H[m, j] rounded to nearest even, or 0 where position j
+// is at or beyond the live count or its id lies outside [0, N); rows have room for cap32 (cap
+// rounded up to a multiple of 32) values and are written, zero-padded, up to the live count
+// rounded up likewise.  One thread per (row, 8 positions).
+template <bool BF>
+__global__ __launch_bounds__(kPrepThreads) void select_gemm_down_prepare_kernel(
+    const float *__restrict__ H, const int32_t *__restrict__ idx, const int32_t *__restrict__ count_ptr,
+    uint16_t *__restrict__ H16, int M, int N, int cap)
+{
+    int count = cap;
+    if (count_ptr) {
+        const int c = *count_ptr;
+        count = c < 0 ? 0 : (c < cap ? c : cap);
+    }
+    const int cap32 = (cap + kDownBlock - 1) / kDownBlock * kDownBlock;
+    const int groups = cap32 / 8;
+    const long item = (long)blockIdx.x * kPrepThreads + threadIdx.x;
+    if (item >= (long)M * groups) return;
+    const int m = (int)(item / groups), j0 = (int)(item % groups) * 8;
+    // the streaming kernel reads whole blocks of 32 up to the live count and nothing beyond
+    if (j0 >= (count + kDownBlock - 1) / kDownBlock * kDownBlock) return;
+    unsigned int v[8];
+    if (j0 + 8 <= count) {                       // eight live positions: vector loads
+        const i32x4u id_lo = *reinterpret_cast<const i32x4u *>(idx + j0);
+        const i32x4u id_hi = *reinterpret_cast<const i32x4u *>(idx + j0 + 4);
+        const f32x4u h_lo = *reinterpret_cast<const f32x4u *>(H + (size_t)m * cap + j0);
+        const f32x4u h_hi = *reinterpret_cast<const f32x4u *>(H + (size_t)m * cap + j0 + 4);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int id = i < 4 ? id_lo[i & 3] : id_hi[i & 3];
+            const float h = i < 4 ? h_lo[i & 3] : h_hi[i & 3];
+            v[i] = (id >= 0 && id < N) ? to_storage<BF>(h) : 0u;
+        }
+    } else {                                     // the group that holds the live count's end, and the padding
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = j0 + i;
+            unsigned int bits = 0u;
+            if (j < count) {
+                const int id = idx[j];
+                if (id >= 0 && id < N) bits = to_storage<BF>(H[(size_t)m * cap + j]);
+            }
+            v[i] = bits;
+        }
+    }
+    const u32x4 packed = {v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+    *reinterpret_cast<u32x4 *>(H16 + (size_t)m * cap32 + j0) = packed;
+}
+
+// grid = (Kout / 256) * NS workgroups; block = 512 threads (8 waves).
 // part holds, per (range, column block of 128), MT * 8 accumulator tiles of 64 lanes x 16 bytes.
 template <bool BF, int MT>
 __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
-    const float *__restrict__ H, const uint16_t *__restrict__ W2, const int32_t *__restrict__ idx,
+    const uint16_t *__restrict__ H16, const uint16_t *__restrict__ W2, const int32_t *__restrict__ idx,
     const int32_t *__restrict__ count_ptr, float *__restrict__ part, int M, int Kout, int N, int cap,
     int NS)
 {
@@ -114,130 +168,102 @@ __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[t][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // the rows of H this lane feeds (clamped: rows m >= M are computed and never stored)
-    const float *hrow[MT];
+    // the rows of H16 this lane feeds (clamped: rows m >= M are computed and never stored)
+    const int cap32 = (cap + kDownBlock - 1) / kDownBlock * kDownBlock;
+    unsigned int hrow[MT];                       // element offsets of the rows (M * cap32 < 2^31)
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         int m = 16 * t + x;
         m = m < M ? m : M - 1;
-        hrow[t] = H + (size_t)m * cap;
+        hrow[t] = (unsigned int)m * (unsigned int)cap32;
     }
     const uint16_t *wcol = W2 + col0 + 8 * x;
 
     // Ring of two blocks: slot r holds this wave's block b (weights: 8 row pieces; activations: 8
-    // floats per row tile; ids of the lane's 8 neurons).  A block index beyond the range is
+    // values per row tile; ids of the lane's 8 neurons).  A block index beyond the range is
     // clamped for the loads and skipped for the arithmetic.
-    u32x4 wq[POLAR_DOWN_RING][8];
-    f32x4 hq[POLAR_DOWN_RING][MT][2];
-    i32x4 iq[POLAR_DOWN_RING][2];
+    u32x4 wq[2][8];
+    u32x4 hq[2][MT];
     const int last = b_end - 1;
-#ifdef POLAR_DOWN_ABLATE_H
-#define POLAR_DOWN_J0(v) (8 * kg)
-#else
-#define POLAR_DOWN_J0(v) (v)
-#endif
-#ifdef POLAR_DOWN_ABLATE_W
-#define POLAR_DOWN_ID(v) ((v) & 31)
-#else
-#define POLAR_DOWN_ID(v) (v)
-#endif
 #define POLAR_DOWN_FETCH(r, block)                                                                 \
     {                                                                                              \
         const int bb = (block) < last ? (block) : last;                                            \
         const int e0 = (bb - b_begin) * kDownBlock + 8 * kg;      /* this lane's 8 neurons */       \
-        iq[r][0] = *reinterpret_cast<const i32x4 *>(sh_id + e0);                                   \
-        iq[r][1] = *reinterpret_cast<const i32x4 *>(sh_id + e0 + 4);                               \
+        const i32x4 id_lo = *reinterpret_cast<const i32x4 *>(sh_id + e0);                          \
+        const i32x4 id_hi = *reinterpret_cast<const i32x4 *>(sh_id + e0 + 4);                      \
         __builtin_amdgcn_sched_barrier(0);                                                         \
         _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
         {                                                                                          \
-            const int id = POLAR_DOWN_ID(iq[r][i >> 2][i & 3]);                                    \
+            const int id = i < 4 ? id_lo[i & 3] : id_hi[i & 3];                                    \
             wq[r][i] = *reinterpret_cast<const u32x4 *>(wcol + (size_t)(id < 0 ? 0 : id) * Kout);  \
         }                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                         \
-        const int j0 = POLAR_DOWN_J0(j_begin + e0);                                                \
-        if (j_begin + (bb - b_begin + 1) * kDownBlock <= cap) {   /* the same for the whole wave */  \
-            _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
-            {                                                                                      \
-                hq[r][t][0] = *reinterpret_cast<const f32x4u *>(hrow[t] + j0);                     \
-                hq[r][t][1] = *reinterpret_cast<const f32x4u *>(hrow[t] + j0 + 4);                 \
-            }                                                                                      \
-        } else {                                 /* the block that holds the end of the rows: */   \
-            _Pragma("unroll") for (int t = 0; t < MT; ++t)        /* element by element, clamped */ \
-                _Pragma("unroll") for (int i = 0; i < 8; ++i)                                      \
-                    hq[r][t][i >> 2][i & 3] = hrow[t][j0 + i < cap ? j0 + i : cap - 1];            \
-        }                                                                                          \
+        const int j0 = j_begin + e0;                                                               \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
+            hq[r][t] = *reinterpret_cast<const u32x4 *>(H16 + (hrow[t] + (unsigned int)j0));       \
         __builtin_amdgcn_sched_barrier(0);                                                         \
     }
 #define POLAR_DOWN_MULTIPLY(r)                                                                     \
     {                                                                                              \
-        /* B operands: o[e] = column e of the lane's 8 x 8 block, its 8 neurons packed in pairs */  \
-        u32x4 o[8];                                                                                \
+        /* B operand of column e of the lane's 8 x 8 block: its 8 neurons packed in pairs */        \
         _Pragma("unroll") for (int e = 0; e < 8; ++e)                                              \
-            _Pragma("unroll") for (int p = 0; p < 4; ++p)                                          \
         {                                                                                          \
-            const unsigned int lo = wq[r][2 * p][e >> 1], hi = wq[r][2 * p + 1][e >> 1];           \
-            o[e][p] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16)); \
-        }                                                                                          \
-        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
-        {                                                                                          \
-            u32x4 a;                                                                               \
+            u32x4 o;                                                                               \
             _Pragma("unroll") for (int p = 0; p < 4; ++p)                                          \
             {                                                                                      \
-                const int i0 = 2 * p, i1 = 2 * p + 1;                                              \
-                const float h0 = iq[r][i0 >> 2][i0 & 3] >= 0 ? hq[r][t][i0 >> 2][i0 & 3] : 0.0f;   \
-                const float h1 = iq[r][i1 >> 2][i1 & 3] >= 0 ? hq[r][t][i1 >> 2][i1 & 3] : 0.0f;   \
-                a[p] = to_storage<BF>(h0) | (to_storage<BF>(h1) << 16);                            \
+                const unsigned int lo = wq[r][2 * p][e >> 1], hi = wq[r][2 * p + 1][e >> 1];       \
+                o[p] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16)); \
             }                                                                                      \
-            _Pragma("unroll") for (int e = 0; e < 8; ++e) acc[t][e] = mfma16x16x32<BF>(a, o[e], acc[t][e]); \
+            _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
+                acc[t][e] = mfma16x16x32<BF>(hq[r][t], o, acc[t][e]);                              \
         }                                                                                          \
     }
 
+    constexpr int P = kDownParities;             // this wave takes every P-th block of the range
     int b = b_begin + parity;
     if (b < b_end) {
-#if POLAR_DOWN_RING == 3
         POLAR_DOWN_FETCH(0, b)
-        POLAR_DOWN_FETCH(1, b + 2)
-        POLAR_DOWN_FETCH(2, b + 4)
-        for (; b < b_end; b += 6) {
+        POLAR_DOWN_FETCH(1, b + P)
+        for (; b < b_end; b += 2 * P) {
             POLAR_DOWN_MULTIPLY(0)
-            POLAR_DOWN_FETCH(0, b + 6)
-            if (b + 2 < b_end) POLAR_DOWN_MULTIPLY(1)
-            POLAR_DOWN_FETCH(1, b + 8)
-            if (b + 4 < b_end) POLAR_DOWN_MULTIPLY(2)
-            POLAR_DOWN_FETCH(2, b + 10)
+            POLAR_DOWN_FETCH(0, b + 2 * P)
+            if (b + P < b_end) POLAR_DOWN_MULTIPLY(1)
+            POLAR_DOWN_FETCH(1, b + 3 * P)
         }
-#else
-        POLAR_DOWN_FETCH(0, b)
-        POLAR_DOWN_FETCH(1, b + 2)
-        for (; b < b_end; b += 4) {
-            POLAR_DOWN_MULTIPLY(0)
-            POLAR_DOWN_FETCH(0, b + 4)
-            if (b + 2 < b_end) POLAR_DOWN_MULTIPLY(1)
-            POLAR_DOWN_FETCH(1, b + 6)
-        }
-#endif
     }
 #undef POLAR_DOWN_MULTIPLY
 #undef POLAR_DOWN_FETCH
 
-    // odd-parity waves hand their sums over through LDS; even-parity waves add them (one fixed
-    // order) and store the range's sums
-    __syncthreads();                             // the ids are no longer needed
+    // The waves of a column block add their sums through LDS in a fixed order, a pair at a time
+    // (the buffer holds one wave's accumulators per column block): (p0 + p2) + (p1 + p3);
+    // parity 0 stores the range's sums.
     f32x4 *sh_acc = reinterpret_cast<f32x4 *>(smem) + (size_t)cw * MT * 8 * 64 + lane;
-    if (parity == 1) {
+    auto hand_over = [&](int from, int to) {
+        __syncthreads();                         // the buffer (first: the ids) is no longer read
+        if (parity == from) {
 #pragma unroll
-        for (int t = 0; t < MT; ++t)
+            for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sh_acc[(t * 8 + e) * 64] = acc[t][e];
-    }
-    __syncthreads();
+                for (int e = 0; e < 8; ++e) sh_acc[(t * 8 + e) * 64] = acc[t][e];
+        }
+        __syncthreads();
+        if (parity == to) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[t][e] += sh_acc[(t * 8 + e) * 64];
+        }
+    };
+    hand_over(3, 1);
+    hand_over(2, 0);
+    hand_over(1, 0);
     if (parity == 0) {
         f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
                      ((size_t)s * (Kout / kDownWaveCols) + (size_t)cg * 2 + cw) * (MT * 8) * 64 + lane;
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dst[(t * 8 + e) * 64] = acc[t][e] + sh_acc[(t * 8 + e) * 64];
+            for (int e = 0; e < 8; ++e) dst[(t * 8 + e) * 64] = acc[t][e];
     }
 }
 
@@ -292,29 +318,40 @@ int down_ranges(int Kout, int cap)
 
 }  // namespace
 
-size_t select_gemm_down_workspace_bytes(int M, int Kout, int cap)
+static size_t down_partial_bytes(int M, int Kout, int cap)
 {
     return (size_t)down_ranges(Kout, cap) * (Kout / kDownWaveCols) * down_mt(M) * 8 * 64 * sizeof(f32x4);
 }
 
+// the ranges' sums, then the prepared activations
+size_t select_gemm_down_workspace_bytes(int M, int Kout, int cap)
+{
+    const size_t cap32 = ((size_t)cap + kDownBlock - 1) / kDownBlock * kDownBlock;
+    return down_partial_bytes(M, Kout, cap) + (size_t)M * cap32 * sizeof(uint16_t);
+}
+
 template <bool BF>
 static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H, const uint16_t *W2,
-                                 const int32_t *idx, const int32_t *count, float *Y, float *part, int M,
-                                 int Kout, int N, int cap)
+                                 const int32_t *idx, const int32_t *count, float *Y, float *part,
+                                 uint16_t *H16, int M, int Kout, int N, int cap)
 {
     const dim3 grid((unsigned)(Kout / kDownGroupCols * NS)), block(kDownThreads);
     const dim3 rgrid((unsigned)(Kout / kDownWaveCols * mt)), rblock(64);
+    const long items = (long)M * ((cap + kDownBlock - 1) / kDownBlock * kDownBlock / 8);
+    if (items > 0)
+        hipLaunchKernelGGL((select_gemm_down_prepare_kernel<BF>), dim3((unsigned)((items + kPrepThreads - 1) / kPrepThreads)),
+                           dim3(kPrepThreads), 0, st, H, idx, count, H16, M, N, cap);
     switch (mt) {
     case 1:
-        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 1>), grid, block, 0, st, H, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 1>), grid, block, 0, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
         hipLaunchKernelGGL((select_gemm_down_reduce_kernel<1>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
         break;
     case 2:
-        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 2>), grid, block, 0, st, H, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 2>), grid, block, 0, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
         hipLaunchKernelGGL((select_gemm_down_reduce_kernel<2>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
         break;
     default:
-        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 4>), grid, block, 0, st, H, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 4>), grid, block, 0, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
         hipLaunchKernelGGL((select_gemm_down_reduce_kernel<4>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
         break;
     }
@@ -328,8 +365,9 @@ hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t
     const int mt = down_mt(M), NS = down_ranges(Kout, cap);
     const uint16_t *W16 = static_cast<const uint16_t *>(W2);
     float *part = static_cast<float *>(workspace);
-    return dt == POLAR_BF16 ? launch_down_mt<true>(mt, NS, stream, H, W16, idx, count, Y, part, M, Kout, N, cap)
-                            : launch_down_mt<false>(mt, NS, stream, H, W16, idx, count, Y, part, M, Kout, N, cap);
+    uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) + down_partial_bytes(M, Kout, cap));
+    return dt == POLAR_BF16 ? launch_down_mt<true>(mt, NS, stream, H, W16, idx, count, Y, part, H16, M, Kout, N, cap)
+                            : launch_down_mt<false>(mt, NS, stream, H, W16, idx, count, Y, part, H16, M, Kout, N, cap);
 }
 
 }  // namespace polar

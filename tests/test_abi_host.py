@@ -185,9 +185,10 @@ def test_select_gemm_down_argument_errors():
     assert d(M=0, H=None, W2=None, idx=None, Y=None, ws=None) == OK
     n = ctypes.c_size_t(0)
     q = lambda M, Kout, cap: L.polar_select_gemm_down_workspace_bytes(M, Kout, cap, ctypes.byref(n))
-    assert q(4, 256, 32) == OK and n.value > 0 and n.value % (256 * 16 * 4) == 0
-    assert q(64, 9216, 36864) == OK and n.value == 7 * 64 * 9216 * 4       # 36 column groups x 7 ranges
-    assert q(64, 9216, 400000) == OK and n.value % (64 * 9216 * 4) == 0 and n.value // (64 * 9216 * 4) >= 49
+    # the ranges' sums (ranges x padded rows x Kout floats) and the prepared 16-bit activations
+    assert q(4, 256, 33) == OK and n.value > 0 and (n.value - 4 * 64 * 2) % (16 * 256 * 4) == 0
+    assert q(64, 9216, 36864) == OK and n.value == 7 * 64 * 9216 * 4 + 64 * 36864 * 2      # 36 column groups x 7 ranges
+    assert q(64, 9216, 400000) == OK and (n.value - 64 * 400000 * 2) // (64 * 9216 * 4) >= 49
     assert q(0, 256, 32) == OK and n.value == 0
     assert q(4, 300, 32) == EUNSUPPORTED and q(65, 256, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
     assert L.polar_select_gemm_down_workspace_bytes(4, 256, 32, None) == EINVAL
