@@ -264,9 +264,10 @@ int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const
  *               polar_select_gemm_down_workspace_bytes(M, Kout, cap) bytes (else POLAR_EWORKSPACE);
  *               contents are overwritten; calls that overlap in time need separate workspaces
  *
- * 16-bit operands, float accumulation on the matrix cores, float output.  M <= 64 and Kout a
- * multiple of 256, else POLAR_EUNSUPPORTED.  Two launches; the contraction is cut into ranges
- * whose sums are added in a fixed order, so results are reproducible for given sizes and count.
+ * 16-bit operands, float accumulation on the matrix cores, float output.  Kout a multiple of
+ * 256, else POLAR_EUNSUPPORTED.  Three launches per 64 rows of the batch (M > 64 is processed 64
+ * rows at a time); the contraction is cut into ranges whose sums are added in a fixed order, so
+ * results are reproducible for given sizes and count.
  * Hact and idx may be NULL when cap == 0.
  */
 int polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap, size_t *bytes);

@@ -382,7 +382,8 @@ int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32
 static int check_down_sizes(int M, int Kout, int N, int cap)
 {
     if (M < 0 || Kout < 1 || N < 1 || cap < 0) return POLAR_EINVAL;
-    if (Kout % 256 != 0 || M > 64 || (long long)N * Kout > (1ll << 40)) return POLAR_EUNSUPPORTED;
+    if (Kout % 256 != 0 || (long long)N * Kout > (1ll << 40) || (long long)M * cap >= (1ll << 40))
+        return POLAR_EUNSUPPORTED;
     return POLAR_OK;
 }
 

@@ -43,6 +43,7 @@ constexpr int kDownGroupCols = 2 * kDownWaveCols;    // per workgroup (two colum
 constexpr int kDownBlock = 32;                   // neurons per step (the contraction depth of one MFMA)
 constexpr int kDownMaxIds = 8192;                // ids of a workgroup's range kept in LDS
 constexpr int kDownTargetGroups = 256;           // one workgroup per compute unit
+constexpr int kDownMaxRows = 64;                 // rows of the batch per pass
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -326,6 +327,7 @@ static size_t down_partial_bytes(int M, int Kout, int cap)
 // the ranges' sums, then the prepared activations
 size_t select_gemm_down_workspace_bytes(int M, int Kout, int cap)
 {
+    if (M > kDownMaxRows) M = kDownMaxRows;      // larger batches go through in passes of 64 rows
     const size_t cap32 = ((size_t)cap + kDownBlock - 1) / kDownBlock * kDownBlock;
     return down_partial_bytes(M, Kout, cap) + (size_t)M * cap32 * sizeof(uint16_t);
 }
@@ -362,12 +364,24 @@ hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t
                                    float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
                                    hipStream_t stream)
 {
-    const int mt = down_mt(M), NS = down_ranges(Kout, cap);
     const uint16_t *W16 = static_cast<const uint16_t *>(W2);
-    float *part = static_cast<float *>(workspace);
-    uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) + down_partial_bytes(M, Kout, cap));
-    return dt == POLAR_BF16 ? launch_down_mt<true>(mt, NS, stream, H, W16, idx, count, Y, part, H16, M, Kout, N, cap)
-                            : launch_down_mt<false>(mt, NS, stream, H, W16, idx, count, Y, part, H16, M, Kout, N, cap);
+    // batches beyond 64 rows are processed 64 rows at a time (the gathered rows are re-read; the
+    // passes share the workspace, which the stream's order makes safe)
+    for (int m0 = 0; m0 < M; m0 += kDownMaxRows) {
+        const int rows = M - m0 < kDownMaxRows ? M - m0 : kDownMaxRows;
+        const int mt = down_mt(rows), NS = down_ranges(Kout, cap);
+        float *part = static_cast<float *>(workspace);
+        uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) +
+                                                     down_partial_bytes(rows, Kout, cap));
+        const float *Hp = H + (size_t)m0 * cap;
+        float *Yp = Y + (size_t)m0 * Kout;
+        const hipError_t e =
+            dt == POLAR_BF16
+                ? launch_down_mt<true>(mt, NS, stream, Hp, W16, idx, count, Yp, part, H16, rows, Kout, N, cap)
+                : launch_down_mt<false>(mt, NS, stream, Hp, W16, idx, count, Yp, part, H16, rows, Kout, N, cap);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace polar

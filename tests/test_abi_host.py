@@ -177,7 +177,7 @@ def test_select_gemm_down_argument_errors():
         L.polar_select_gemm_down(H, W2, idx, None, Y, M, Kout, N, cap, dt, ws, wsb, None)
     assert d(M=-1) == EINVAL and d(Kout=0) == EINVAL and d(N=0) == EINVAL and d(cap=-1) == EINVAL
     assert d(dt=2) == EINVAL
-    assert d(Kout=384) == EUNSUPPORTED and d(M=65) == EUNSUPPORTED
+    assert d(Kout=384) == EUNSUPPORTED
     assert d(W2=None) == EINVAL and d(Y=None) == EINVAL and d(ws=None) == EINVAL
     assert d(H=None) == EINVAL and d(idx=None) == EINVAL
     assert d(H=ctypes.c_void_p(0x1002)) == EINVAL and d(Y=ctypes.c_void_p(0x1008)) == EINVAL
@@ -190,7 +190,8 @@ def test_select_gemm_down_argument_errors():
     assert q(64, 9216, 36864) == OK and n.value == 7 * 64 * 9216 * 4 + 64 * 36864 * 2      # 36 column groups x 7 ranges
     assert q(64, 9216, 400000) == OK and (n.value - 64 * 400000 * 2) // (64 * 9216 * 4) >= 49
     assert q(0, 256, 32) == OK and n.value == 0
-    assert q(4, 300, 32) == EUNSUPPORTED and q(65, 256, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
+    assert q(4, 300, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
+    assert q(300, 9216, 36864) == OK and n.value == 7 * 64 * 9216 * 4 + 64 * 36864 * 2      # passes of 64 rows share it
     assert L.polar_select_gemm_down_workspace_bytes(4, 256, 32, None) == EINVAL
 
 

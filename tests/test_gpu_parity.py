@@ -636,7 +636,7 @@ def down_case(M, Kout, N, idx_host, dtype, count=None, seed=0, scale=1.0):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("M", [1, 5, 16, 17, 33, 64])
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 33, 64, 65, 150])
 def test_select_gemm_down_shapes(dtype, M):
     say("\ncase select_gemm_down", dtype, M)
     rng = np.random.default_rng(100 + M)
