@@ -686,6 +686,64 @@ def test_sparsified_mlp_both_factors():
     assert torch.isfinite(y).all() and torch.equal(y, again)
 
 
+def test_hip_graph_replays_of_the_sparsified_mlp_match_eager():
+    """Neuron index -> first factor -> second factor recorded into one HIP graph: the live count
+    never leaves the device, so one recording serves whatever ids the requests predict; every
+    replay, with eager work in between, equals the eager result bit for bit."""
+    B, K, N, kn = 24, 512, 3000, 90
+    say("\ncase sparsified MLP graph", B, K, N, kn)
+    g = torch.Generator(device=DEV).manual_seed(77)
+    x = torch.randn((B, K), generator=g, device=DEV).half()
+    W1 = (torch.randn((N, K), generator=g, device=DEV) / K ** 0.5).half()
+    W2 = (torch.randn((N, K), generator=g, device=DEV) / 30.0).half()
+    topk = torch.randint(0, N, (B, kn), generator=g, device=DEV, dtype=torch.int32)
+    cap = min(N, B * kn)
+    ws_union = torch.empty(max(polar.neuron_union_workspace_bytes(B, kn, N), 4), dtype=torch.uint8, device=DEV)
+    ws_up = polar.alloc_select_gemm_workspace(B, DEV)
+    ws_down = torch.empty(polar.select_gemm_down_workspace_bytes(B, K, cap), dtype=torch.uint8, device=DEV)
+
+    def bufs():
+        return (torch.full((cap,), -1, dtype=torch.int32, device=DEV), torch.zeros(1, dtype=torch.int32, device=DEV),
+                torch.zeros((B, cap), dtype=torch.float32, device=DEV), torch.zeros((B, K), dtype=torch.float32, device=DEV))
+
+    def step(idx, count, hidden, y):
+        polar.neuron_union(topk, N, workspace=ws_union, out=(idx, count))
+        polar.select_gemm(x, W1, idx, count=count, relu=True, out=hidden, workspace=ws_up)
+        polar.select_gemm_down(hidden, W2, idx, count=count, out=y, workspace=ws_down)
+
+    rec = bufs()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture
+        step(*rec)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(*rec)
+    for rep in range(4):
+        # other ids (and with them another live count) and other activations every time
+        hot = max(kn, N // (rep + 2))
+        topk.copy_(torch.randint(0, hot, (B, kn), generator=g, device=DEV, dtype=torch.int32))
+        x.copy_(torch.randn((B, K), generator=g, device=DEV).half())
+        eager = bufs()
+        step(*eager)
+        torch.cuda.synchronize()
+        rec[3].fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        c = int(eager[1].item())
+        assert int(rec[1].item()) == c and torch.equal(rec[0][:c], eager[0][:c]), "replay %d: index" % rep
+        assert torch.equal(rec[2][:, :c], eager[2][:, :c]), "replay %d: first factor" % rep
+        assert torch.equal(rec[3].view(torch.int32), eager[3].view(torch.int32)), "replay %d: second factor" % rep
+    S = orc.neuron_union(topk.cpu().numpy(), N)
+    assert c == len(S)
+    hid = orc.select_gemm(host_bits(x), host_bits(W1), S, "f16", True)
+    assert np.abs(rec[2][:, :c].cpu().numpy() - hid).max() <= GEMM_TOL
+    want = orc.select_gemm_down(rec[2][:, :c].cpu().numpy(), host_bits(W2), S, "f16")
+    assert np.abs(rec[3].cpu().numpy() - want).max() <= GEMM_TOL
+
+
 def test_read_probe_folds_every_word_of_every_slab():
     """The bandwidth yardstick really reads what it claims: each slab's result is the XOR of its
     words (slabs of whole 16 KiB wave steps, so no clamped tail load repeats a word)."""
