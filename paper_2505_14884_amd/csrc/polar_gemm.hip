@@ -255,23 +255,26 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
 // know (it stays on the device): at a 29 % union 332 workgroups land on 256 compute units, one
 // or two each, and the machine waits for the doubly loaded ones; and with every wave owning
 // other rows of the batch, each weight byte drags M/32 activation bytes through L2 and LDS.
-// Here the work is cut the other way round.  A workgroup's tile is 64 neurons; wave w owns 32 of
-// them and all M rows, so the weights are wave-private and the activation block is staged once
-// per workgroup and shared (M/64 activation bytes per weight byte).  The launch has a fixed
-// number G of workgroups; each reads the live count, lays all (tile, K unit) pairs out in one
-// line, tile-major, and takes the g-th of G equal spans of that line, so every compute unit
-// streams the same number of bytes whatever the count is.  A span covers the end of one tile and
-// the start of the next (or, for short K, whole tiles in between): a segment that covers all of
-// a tile's K is finished in place (activation, store to C); any other is stored as raw
-// accumulators in one of the workgroup's two workspace slots (slot 0: the span's first tile,
-// slot 1: its last), and a second kernel adds each tile's segments in ascending workgroup
-// order, applies the activation and stores.  The order of the additions depends only on
-// (count, K, G), so results are reproducible.
-constexpr int kStreamWaves = 2;                  // waves per workgroup
-constexpr int kStreamGrid = 512;                 // workgroups per launch, two per compute unit: all that fit, and
-                                                 // enough to overlap one's LDS and barrier phases with the other's loads
+// Here the work is cut the other way round.  A workgroup's tile is 128 neurons; wave w of its
+// eight owns 16 of them and all M rows, so the weights are wave-private and the activation block
+// is staged once per workgroup and shared (M/128 activation bytes per weight byte: the
+// activations come from L2, and every line of them in flight takes a place among the compute
+// unit's outstanding misses that a weight line from HBM could have).  The launch has a fixed
+// number G of workgroups, one per compute unit; each reads the live count, lays all
+// (tile, K unit) pairs out in one line, tile-major, and takes the g-th of G equal spans of that
+// line, so every compute unit streams the same number of bytes whatever the count is.  A span
+// covers the end of one tile and the start of the next (or, for short K, whole tiles in
+// between): a segment that covers all of a tile's K is finished in place (activation, store to
+// C); any other is stored as raw accumulators in one of the workgroup's two workspace slots
+// (slot 0: the span's first tile, slot 1: its last), and a second kernel adds each tile's
+// segments in ascending workgroup order, applies the activation and stores.  The order of the
+// additions depends only on (count, K, G), so results are reproducible.
+constexpr int kStreamWaves = 8;                  // waves per workgroup
+constexpr int kStreamGrid = 256;                 // workgroups per launch: one per compute unit
 constexpr int kStreamThreads = 64 * kStreamWaves;
-constexpr int kStreamWaveN = 32;                 // neurons per wave
+constexpr int kStreamWaveN = 16;                 // neurons per wave
+constexpr int NH = kStreamWaveN / 16;            // 16-neuron halves per wave
+constexpr int NR = kStreamWaveN / 4;             // row loads per wave and block (4 rows each)
 constexpr int kStreamTileN = kStreamWaveN * kStreamWaves;  // neurons per workgroup tile
 
 // units * G < 2^31 (checked by the host), so 32-bit arithmetic is exact
@@ -371,7 +374,10 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     const int first_tile = u0 / upt;
 
     // activation block: 16 lanes per 256-byte row piece, rows a_row + kARows*i
-    constexpr int kARows = kStreamThreads / 16, AP = 16 * MT / kARows;
+    // (staged by the first kAThreads threads: at most 16 rows per pass, so that MT = 1 has a pass)
+    constexpr int kAThreads = kStreamThreads < 256 ? kStreamThreads : 256;
+    constexpr int kARows = kAThreads / 16, AP = 16 * MT / kARows;
+    const bool stages_a = kAThreads == kStreamThreads || wave < kAThreads / 64;
     const int a_row = tid >> 4;
     const u32x4 *ap[AP];
 #pragma unroll
@@ -403,11 +409,11 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     };
     // row offsets (in elements) of the tile being multiplied and of the tile after it; kept as
     // offsets from W so that every load is known to be a global one
-    size_t cur[8], nxt[8];
+    size_t cur[NR], nxt[NR];
     int tile = first_tile;
     int tile_base = tile * upt, tile_end = tile_base + upt;         // its units
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < NR; ++i) {
         cur[i] = row_offset(0, i);
         nxt[i] = row_offset(1, i);
     }
@@ -416,21 +422,21 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     // that the compiler keeps the order (weights before activations, slot 0 before slot 1): its
     // count of outstanding loads at the loop header is then the same on entry and on the back
     // edge, and nothing is drained there
-    u32x4 wq[kUnitBlocks][8], aq[kUnitBlocks][AP];
+    u32x4 wq[kUnitBlocks][NR], aq[kUnitBlocks][AP];
 #define POLAR_STREAM_FETCH(j, unit)                                                                \
     {                                                                                              \
         const int v = min((unit), u1 - 1);                                                         \
         const bool ahead = v >= tile_end;                                                          \
         const size_t blk = (size_t)((v - (ahead ? tile_end : tile_base)) * kUnitBlocks + (j)) * 16; \
         __builtin_amdgcn_sched_barrier(0);                                                         \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
+        _Pragma("unroll") for (int i = 0; i < NR; ++i)                                             \
         {                                                                                          \
             const u32x4 *p = reinterpret_cast<const u32x4 *>(W + (ahead ? nxt[i] : cur[i])) + x;   \
             wq[j][i] = __builtin_nontemporal_load(p + blk);   /* read once: leave the caches to   */ \
                                                               /* the activations and the partials */ \
         }                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                         \
-        _Pragma("unroll") for (int i = 0; i < AP; ++i) aq[j][i] = ap[i][blk];                     \
+        if (stages_a) _Pragma("unroll") for (int i = 0; i < AP; ++i) aq[j][i] = ap[i][blk];       \
         __builtin_amdgcn_sched_barrier(0);                                                         \
     }
     // block j of unit u: ring slot j goes to LDS, is refilled for unit u + 1, and is multiplied;
@@ -439,14 +445,14 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
 #define POLAR_STREAM_STEP(j)                                                                       \
     {                                                                                              \
         unsigned char *abuf = sh_at[j];                                                            \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
+        _Pragma("unroll") for (int i = 0; i < NR; ++i)                                             \
             *reinterpret_cast<u32x4 *>(wt + lds_w_wr + 4 * i * kRowBytes) = wq[j][i];              \
-        _Pragma("unroll") for (int i = 0; i < AP; ++i)                                             \
+        if (stages_a) _Pragma("unroll") for (int i = 0; i < AP; ++i)                               \
             *reinterpret_cast<u32x4 *>(abuf + lds_a_wr + kARows * i * kRowBytes) = aq[j][i];       \
         POLAR_STREAM_FETCH(j, u + 1)                                                               \
         __syncthreads();                                                                           \
-        u32x4 bq[2][4];                                                                            \
-        _Pragma("unroll") for (int h = 0; h < 2; ++h)                                              \
+        u32x4 bq[NH][4];                                                                           \
+        _Pragma("unroll") for (int h = 0; h < NH; ++h)                                             \
             _Pragma("unroll") for (int s = 0; s < 4; ++s) bq[h][s] =                               \
                 *reinterpret_cast<const u32x4 *>(wt + lds_op + 16 * h * kRowBytes + 16 * s);       \
         _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
@@ -456,8 +462,8 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
                 *reinterpret_cast<const u32x4 *>(abuf + lds_op + 16 * t * kRowBytes + 16 * s);     \
             _Pragma("unroll") for (int s = 0; s < 4; ++s)                                          \
             {                                                                                      \
-                acc[t][0] = mfma16x16x32<BF>(a[s], bq[0][s], acc[t][0]);                           \
-                acc[t][1] = mfma16x16x32<BF>(a[s], bq[1][s], acc[t][1]);                           \
+                _Pragma("unroll") for (int h = 0; h < NH; ++h)                                     \
+                    acc[t][h] = mfma16x16x32<BF>(a[s], bq[h][s], acc[t][h]);                       \
             }                                                                                      \
         }                                                                                          \
     }
@@ -466,9 +472,11 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     POLAR_STREAM_FETCH(1, u)
     while (u < u1) {
         const int seg_begin = u, seg_end = tile_end < u1 ? tile_end : u1;
-        f32x4 acc[MT][2];
+        f32x4 acc[MT][NH];
 #pragma unroll
-        for (int t = 0; t < MT; ++t) acc[t][0] = acc[t][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int h = 0; h < NH; ++h) acc[t][h] = (f32x4){0.f, 0.f, 0.f, 0.f};
         for (; u < seg_end; ++u) {
             POLAR_STREAM_STEP(0)
             POLAR_STREAM_STEP(1)
@@ -478,7 +486,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
             // the whole contraction of this tile: finish in place (accumulator layout: this
             // lane holds rows 16*t + 4*kg + i of column x of each 16-neuron half)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < NH; ++h) {
                 const int col = tile * kStreamTileN + wave * kStreamWaveN + 16 * h + x;
                 if (col >= count) continue;
                 const bool valid = sh_id[(tile - first_tile) * kStreamTileN + wave * kStreamWaveN + 16 * h + x] >= 0;
@@ -498,18 +506,18 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
             // part of it: raw accumulators to the workspace (slot 0: the span's first tile)
             const int slot = tile == first_tile ? 0 : 1;
             f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
-                         (((size_t)span * 2 + slot) * kStreamWaves + wave) * (MT * 2) * 64 + lane;
+                         (((size_t)span * 2 + slot) * kStreamWaves + wave) * (MT * NH) * 64 + lane;
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) dst[(t * 2 + h) * 64] = acc[t][h];
+                for (int h = 0; h < NH; ++h) dst[(t * NH + h) * 64] = acc[t][h];
         }
         if (u < u1) {                            // on to the next tile; fetch the row ids of the one after it
             ++tile;
             tile_base = tile_end;
             tile_end += upt;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < NR; ++i) {
                 cur[i] = nxt[i];
                 nxt[i] = row_offset(tile + 1 - first_tile, i);
             }
@@ -534,10 +542,10 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
     }
     const int nblk = K / (kBlockK * kUnitBlocks);            // units per tile
     const int tiles = (count + kStreamTileN - 1) / kStreamTileN;
-    constexpr int kQuads = (MT * 2 + 3) / 4;
+    constexpr int kQuads = (MT * NH + 3) / 4;
     const int tile = blockIdx.x / (kStreamWaves * kQuads), wave = blockIdx.x / kQuads % kStreamWaves;
     const int e = (blockIdx.x % kQuads) * 4 + (threadIdx.x >> 6);
-    if (tile >= tiles || e >= MT * 2) return;
+    if (tile >= tiles || e >= MT * NH) return;
     const int units = tiles * nblk, lo = tile * nblk, hi = lo + nblk;
     // the workgroup whose span holds unit lo
     int g0 = (int)((unsigned)lo * (unsigned)G / (unsigned)units);
@@ -552,7 +560,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
     const int lane = threadIdx.x & 63, x = lane & 15, kg = lane >> 4;
     const int n0 = tile * kStreamTileN;
     {
-        const int t = e >> 1, h = e & 1;
+        const int t = e / NH, h = e % NH;
         f32x4 sum = (f32x4){0.f, 0.f, 0.f, 0.f};
         // segments in ascending workgroup order (g0 .. g1, empty spans skipped: adding +0.0
         // leaves the sum as it is), loads issued four at a time
@@ -567,7 +575,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
                 if (span_bound(units, G, g + 1) <= b) continue;
                 const int slot = b / nblk == tile ? 0 : 1;
                 v[q] = *(reinterpret_cast<const f32x4 *>(part) +
-                         ((((size_t)g * 2 + slot) * kStreamWaves + wave) * (MT * 2) + e) * 64 + lane);
+                         ((((size_t)g * 2 + slot) * kStreamWaves + wave) * (MT * NH) + e) * 64 + lane);
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) sum += v[q];
@@ -759,7 +767,7 @@ hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, 
 }
 
 // Workspace of the wide-tile form: two slots of raw accumulators per workgroup.
-static size_t stream_slot_bytes(int mt) { return (size_t)2 * (kStreamWaves) * mt * 2 * 64 * sizeof(f32x4); }
+static size_t stream_slot_bytes(int mt) { return (size_t)2 * kStreamWaves * mt * NH * 64 * sizeof(f32x4); }
 static int stream_mt(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : 4); }
 
 size_t select_gemm_workspace_bytes(int M)
@@ -772,7 +780,7 @@ static hipError_t launch_stream_mt(int mt, int G, int tiles, hipStream_t st, con
                                    const uint16_t *W, const int32_t *idx, const int32_t *count, float *C,
                                    float *part, int M, int K, int N, int cap, int relu)
 {
-    const dim3 grid((unsigned)G), rgrid((unsigned)tiles * kStreamWaves * ((mt * 2 + 3) / 4)), block(kStreamThreads), rblock(kGemmThreads);
+    const dim3 grid((unsigned)G), rgrid((unsigned)tiles * kStreamWaves * ((mt * NH + 3) / 4)), block(kStreamThreads), rblock(kGemmThreads);
     switch (mt) {
     case 1:
         hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 1>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);

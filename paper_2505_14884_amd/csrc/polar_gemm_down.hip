@@ -30,6 +30,8 @@
 //     grid fills the compute units once; range s covers an NS-th of the live blocks, whatever the
 //     live count is (it stays on the device), and leaves its sums in the workspace; a second
 //     kernel adds the NS sums of every output element in ascending range order and stores Y.
+#include <atomic>
+
 #include "polar_internal.h"
 
 namespace polar {
@@ -44,6 +46,8 @@ constexpr int kDownBlock = 32;                   // neurons per step (the contra
 constexpr int kDownMaxIds = 8192;                // ids of a workgroup's range kept in LDS
 constexpr int kDownTargetGroups = 256;           // one workgroup per compute unit
 constexpr int kDownMaxRows = 64;                 // rows of the batch per pass
+constexpr int kChunkBlocks = 8;                  // blocks of activations staged in LDS at a time
+constexpr int kChunkPitch = kChunkBlocks * kDownBlock * 2 + 16;   // bytes per row of a chunk, padded
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -132,10 +136,12 @@ __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
     const int32_t *__restrict__ count_ptr, float *__restrict__ part, int M, int Kout, int N, int cap,
     int NS)
 {
-    // the ids of the range while streaming, the odd waves' accumulators at the end
-    __shared__ __align__(16) unsigned char smem[2 * MT * 8 * 64 * 16 > kDownMaxIds * 4 ? 2 * MT * 8 * 64 * 16
-                                                                                    : kDownMaxIds * 4];
-    int *sh_id = reinterpret_cast<int *>(smem);
+    // LDS: two buffers for chunks of the activations (16 * MT rows x 256 positions, padded rows:
+    // conflict-free 16-byte operand reads), which the waves' accumulators reuse at the end, then
+    // the ids of the range
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int kChunkBytes = 16 * MT * kChunkPitch;
+    int *sh_id = reinterpret_cast<int *>(smem + 2 * kChunkBytes);
 
     int count = cap;
     if (count_ptr) {
@@ -169,22 +175,46 @@ __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[t][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // the rows of H16 this lane feeds (clamped: rows m >= M are computed and never stored)
+    // Activations: the workgroup stages them through LDS a chunk of 8 blocks (256 positions) at
+    // a time, whole cache lines, each once; chunk c + 1 is fetched into registers while chunk c is
+    // multiplied.  (Read straight into operand layout, 16 rows x 64 bytes per load, they took as
+    // many places among the compute unit's outstanding misses as the weights did.)  Thread tid
+    // moves the 16-byte pieces tid + 512 i of a chunk: 32 pieces per row.
     const int cap32 = (cap + kDownBlock - 1) / kDownBlock * kDownBlock;
-    unsigned int hrow[MT];                       // element offsets of the rows (M * cap32 < 2^31)
+    constexpr int kPieces = 16 * MT * 32 / kDownThreads;            // per thread: 1, 2 or 4
+    const uint16_t *hsrc[kPieces];
+    int hdst[kPieces];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        int m = 16 * t + x;
-        m = m < M ? m : M - 1;
-        hrow[t] = (unsigned int)m * (unsigned int)cap32;
+    for (int i = 0; i < kPieces; ++i) {
+        const int e = tid + kDownThreads * i;
+        int m = e >> 5;
+        m = m < M ? m : M - 1;                   // rows m >= M are computed and never stored
+        hsrc[i] = H16 + (size_t)m * cap32 + 8 * (e & 31);
+        hdst[i] = (e >> 5) * kChunkPitch + 16 * (e & 31);
     }
+    u32x4 hp[kPieces];
+    // positions of chunk `first_block`, clamped so that every piece lies inside its row
+    auto fetch_chunk = [&](int first_block) {
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) {
+            int pos = first_block * kDownBlock;
+            const int piece = 8 * ((tid + kDownThreads * i) & 31);
+            pos = pos + piece + 8 <= cap32 ? pos : cap32 - 8 - piece;
+            hp[i] = *reinterpret_cast<const u32x4 *>(hsrc[i] + pos);
+        }
+    };
+    auto store_chunk = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i)
+            *reinterpret_cast<u32x4 *>(smem + buf * kChunkBytes + hdst[i]) = hp[i];
+    };
+    const int lds_a = x * kChunkPitch + 16 * kg;                    // + 16 t rows, + 64 bytes per block of the chunk
     const uint16_t *wcol = W2 + col0 + 8 * x;
 
-    // Ring of two blocks: slot r holds this wave's block b (weights: 8 row pieces; activations: 8
-    // values per row tile; ids of the lane's 8 neurons).  A block index beyond the range is
+    // Ring of two blocks: slot r holds this wave's block b (weights: 8 row pieces; the 8 row pieces
+    // of its 32 neurons).  A block index beyond the range is
     // clamped for the loads and skipped for the arithmetic.
     u32x4 wq[2][8];
-    u32x4 hq[2][MT];
     const int last = b_end - 1;
 #define POLAR_DOWN_FETCH(r, block)                                                                 \
     {                                                                                              \
@@ -199,13 +229,12 @@ __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
             wq[r][i] = *reinterpret_cast<const u32x4 *>(wcol + (size_t)(id < 0 ? 0 : id) * Kout);  \
         }                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                         \
-        const int j0 = j_begin + e0;                                                               \
-        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
-            hq[r][t] = *reinterpret_cast<const u32x4 *>(H16 + (hrow[t] + (unsigned int)j0));       \
-        __builtin_amdgcn_sched_barrier(0);                                                         \
     }
-#define POLAR_DOWN_MULTIPLY(r)                                                                     \
+#define POLAR_DOWN_MULTIPLY(r, abase)                                                                   \
     {                                                                                              \
+        u32x4 ha[MT];                            /* A operands: 8 positions of 16 * MT rows */     \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
+            ha[t] = *reinterpret_cast<const u32x4 *>((abase) + lds_a + 16 * t * kChunkPitch);      \
         /* B operand of column e of the lane's 8 x 8 block: its 8 neurons packed in pairs */        \
         _Pragma("unroll") for (int e = 0; e < 8; ++e)                                              \
         {                                                                                          \
@@ -216,21 +245,32 @@ __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
                 o[p] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16)); \
             }                                                                                      \
             _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
-                acc[t][e] = mfma16x16x32<BF>(hq[r][t], o, acc[t][e]);                              \
+                acc[t][e] = mfma16x16x32<BF>(ha[t], o, acc[t][e]);                                 \
         }                                                                                          \
     }
 
+    // A chunk is 2 * P blocks: each wave's two ring slots.  Every wave runs the same number of
+    // chunks (one barrier each); a block beyond the range is skipped for the arithmetic.
     constexpr int P = kDownParities;             // this wave takes every P-th block of the range
-    int b = b_begin + parity;
-    if (b < b_end) {
-        POLAR_DOWN_FETCH(0, b)
-        POLAR_DOWN_FETCH(1, b + P)
-        for (; b < b_end; b += 2 * P) {
-            POLAR_DOWN_MULTIPLY(0)
-            POLAR_DOWN_FETCH(0, b + 2 * P)
-            if (b + P < b_end) POLAR_DOWN_MULTIPLY(1)
-            POLAR_DOWN_FETCH(1, b + 3 * P)
-        }
+    static_assert(kChunkBlocks == 2 * P, "a chunk is one pass of the two-slot ring of every wave");
+    const int chunks = (b_end - b_begin + kChunkBlocks - 1) / kChunkBlocks;
+    if (chunks > 0) {
+        fetch_chunk(b_begin);
+        store_chunk(0);
+        POLAR_DOWN_FETCH(0, b_begin + parity)
+        POLAR_DOWN_FETCH(1, b_begin + parity + P)
+        __syncthreads();
+    }
+    for (int c = 0; c < chunks; ++c) {
+        const int b = b_begin + c * kChunkBlocks + parity;
+        const unsigned char *abuf = smem + (c & 1) * kChunkBytes;
+        if (c + 1 < chunks) fetch_chunk(b_begin + (c + 1) * kChunkBlocks);
+        if (b < b_end) POLAR_DOWN_MULTIPLY(0, abuf + 64 * parity)
+        POLAR_DOWN_FETCH(0, b + 2 * P)
+        if (b + P < b_end) POLAR_DOWN_MULTIPLY(1, abuf + 64 * (parity + P))
+        POLAR_DOWN_FETCH(1, b + 3 * P)
+        if (c + 1 < chunks) store_chunk((c + 1) & 1);
+        __syncthreads();
     }
 #undef POLAR_DOWN_MULTIPLY
 #undef POLAR_DOWN_FETCH
@@ -240,7 +280,7 @@ __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
     // parity 0 stores the range's sums.
     f32x4 *sh_acc = reinterpret_cast<f32x4 *>(smem) + (size_t)cw * MT * 8 * 64 + lane;
     auto hand_over = [&](int from, int to) {
-        __syncthreads();                         // the buffer (first: the ids) is no longer read
+        __syncthreads();                         // the buffer (first: the activations) is no longer read
         if (parity == from) {
 #pragma unroll
             for (int t = 0; t < MT; ++t)
@@ -343,17 +383,29 @@ static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H,
     if (items > 0)
         hipLaunchKernelGGL((select_gemm_down_prepare_kernel<BF>), dim3((unsigned)((items + kPrepThreads - 1) / kPrepThreads)),
                            dim3(kPrepThreads), 0, st, H, idx, count, H16, M, N, cap);
+    // dynamic LDS: two activation chunks and the ids of a range; above 64 KB it has to be granted
+    const size_t lds = (size_t)2 * 16 * mt * kChunkPitch + (size_t)kDownMaxIds * sizeof(int);
+    static std::atomic<bool> granted[2][3];
+    const void *kernels[3] = {reinterpret_cast<const void *>(select_gemm_down_kernel<BF, 1>),
+                              reinterpret_cast<const void *>(select_gemm_down_kernel<BF, 2>),
+                              reinterpret_cast<const void *>(select_gemm_down_kernel<BF, 4>)};
+    const int ki = mt == 1 ? 0 : (mt == 2 ? 1 : 2);
+    if (lds > 48 * 1024 && !granted[BF ? 1 : 0][ki].load(std::memory_order_acquire)) {
+        const hipError_t e = hipFuncSetAttribute(kernels[ki], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        granted[BF ? 1 : 0][ki].store(true, std::memory_order_release);
+    }
     switch (mt) {
     case 1:
-        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 1>), grid, block, 0, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 1>), grid, block, lds, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
         hipLaunchKernelGGL((select_gemm_down_reduce_kernel<1>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
         break;
     case 2:
-        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 2>), grid, block, 0, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 2>), grid, block, lds, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
         hipLaunchKernelGGL((select_gemm_down_reduce_kernel<2>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
         break;
     default:
-        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 4>), grid, block, 0, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
+        hipLaunchKernelGGL((select_gemm_down_kernel<BF, 4>), grid, block, lds, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
         hipLaunchKernelGGL((select_gemm_down_reduce_kernel<4>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
         break;
     }

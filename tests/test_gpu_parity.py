@@ -493,19 +493,19 @@ def test_select_gemm_shapes(dtype, M, ws):
     say("   err %.2e" % gemm_case(M, K, N, idx, dtype, relu=False, seed=M + 1, ws=ws))
 
 
-@pytest.mark.parametrize("G", [1, 2, 3, 5, 7, 11, 19, 20, None])
+@pytest.mark.parametrize("G", [1, 2, 3, 5, 7, 11, 12, None])
 def test_select_gemm_wide_form_spans(G):
-    """The evenly split form cuts 5 tiles x 4 units (pairs of K blocks) into G spans: whole tiles
-    finished in place (G = 1, 5), tiles shared by several workgroups (first / last slot), spans of
+    """The evenly split form cuts 3 tiles x 4 units (pairs of K blocks) into G spans: whole tiles
+    finished in place (G = 1, 3), tiles shared by several workgroups (first / last slot), spans of
     unequal length, and spans left empty when the live count is below the capacity."""
     say("\ncase select_gemm spans G =", G)
     rng = np.random.default_rng(77)
     N, K = 700, 1024
-    idx = rng.permutation(N)[:300].tolist()                # 5 tiles of 64, the last ragged
+    idx = rng.permutation(N)[:300].tolist()                # 3 tiles of 128, the last ragged
     idx[5], idx[200] = -1, N                               # invalid ids give zero columns
     for M, dtype in ((64, "f16"), (20, "bf16"), (3, "f16")):
         gemm_case(M, K, N, idx, dtype, relu=True, seed=3, ws=True, G=G)
-        gemm_case(M, K, N, idx, dtype, relu=False, seed=4, ws=True, G=G, count=130)   # 3 live tiles
+        gemm_case(M, K, N, idx, dtype, relu=False, seed=4, ws=True, G=G, count=130)   # 2 live tiles
         gemm_case(M, K, N, idx, dtype, relu=False, seed=5, ws=True, G=G, count=0)
 
 
@@ -515,7 +515,7 @@ def test_select_gemm_small_workspace_narrows_the_launch():
     idx = rng.permutation(700)[:300].tolist()
     full = polar.select_gemm_workspace_bytes(64)
     assert full > 0 and polar.select_gemm_workspace_bytes(65) == 0
-    one = 2 * 2 * 8 * 64 * 16          # a workgroup's two slots: 2 waves x 8 accumulator tiles x 64 lanes x 16 B
+    one = 2 * 8 * 4 * 64 * 16          # a workgroup's two slots: 8 waves x 4 accumulator tiles x 64 lanes x 16 B
     assert full % one == 0
     for nbytes in (one, 3 * one, one - 16, 0):             # launch of 1 workgroup, of 3, narrow kernel, narrow kernel
         gemm_case(64, 1024, 700, idx, "f16", relu=True, seed=6, ws=True, ws_bytes=nbytes)
