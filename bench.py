@@ -170,6 +170,20 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
 
     down_ms = ev(down, n_ev)
     mlp_ms = ev(lambda: (union(), gemm(), down()), n_ev)
+    # what the bare access pattern reaches: the same gathered rows, read and nothing else
+    probe_sink = torch.empty(2 * ((n_sel + 63) // 64) * 3, dtype=torch.int32, device=dev)
+    live_idx = idx[:n_sel].contiguous()
+
+    def probe(depth):
+        def run():
+            turn[0] += 1
+            polar.probe_gather_read(W1s[turn[0] % layers], live_idx, slices=3, depth=depth, nontemporal=True,
+                                    sink=probe_sink)
+        for _ in range(3):                        # first launches of a kernel are not representative
+            run()
+        torch.cuda.synchronize()
+        return round(bytes_sel / (min(ev(run, max(5, n_ev // 4)) for _ in range(2)) * 1e-3) / 1e9, 1)
+    gather_probe = {"one_block_in_flight": probe(1), "four_blocks_in_flight": probe(4)}
     result = {
         "metric": "selective fused-gather GEMM effective weight HBM GB/s (gathered rows' bytes / step "
                   "time; step = batch neuron union + GEMM with ReLU)",
@@ -197,6 +211,7 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "avg_us": round(gemm_ms * 1e3, 2),
                      "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),
+                     "gathered_read_probe_GBps": gather_probe,
                      # rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled; profiles/select_gemm_M2_opt66b_ffn.md
                      "traffic": (239691081 if wide else 214354185) if (w == wl.MLP_CONFIGS.get(w.name)) else None},
     }

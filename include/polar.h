@@ -317,13 +317,28 @@ int polar_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int cap, in
 int polar_probe_read(const void *src, size_t slabs, size_t slab_bytes, int nontemporal, uint32_t *sink,
                      void *stream);
 
+/*
+ * The same kind of yardstick for the selective GEMMs (not an operation of the paper): reads the
+ * rows W[idx[j], :] (j < n_idx) of a [N, K] 16-bit matrix the way those kernels stream them,
+ * in 256-byte pieces, 4 rows per wave-wide load, and does nothing else.  Workgroup (tile, slice) of
+ * two waves takes 64 consecutive entries of idx and the slice-th of `slices` equal parts of K;
+ * `depth` (1 or 4) 128-value blocks are in flight per wave.  Timing it over n_idx * K * 2 bytes
+ * gives the read bandwidth this access pattern reaches by itself.
+ *   W     in   [N, K] 16-bit, 16-byte aligned; K a multiple of 128 * slices * depth
+ *   idx   in   [n_idx] int32; an id outside [0,N) reads row 0
+ *   sink  out  [2 * ceil(n_idx / 64) * slices] uint32
+ */
+int polar_probe_gather_read(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices, int depth,
+                            int nontemporal, uint32_t *sink, void *stream);
+
 /* Text for a polar_status value; never NULL. */
 const char *polar_strerror(int status);
 /* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */
 int polar_last_hip_error(void);
 /* ABI version: major * 1000 + minor (1100: adds polar_sha_launches and polar_probe_read; group sizes up to 16;
  * 1200: adds polar_select_gemm_ws and polar_select_gemm_workspace_bytes; 1300: adds polar_neuron_union_ws and
- * polar_neuron_union_workspace_bytes; 1400: adds polar_select_gemm_down and its workspace query). */
+ * polar_neuron_union_workspace_bytes; 1400: adds polar_select_gemm_down and its workspace query;
+ * 1500: adds polar_probe_gather_read). */
 int polar_version(void);
 
 #ifdef __cplusplus

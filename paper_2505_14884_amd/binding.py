@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down", "polar_select_gemm_down_workspace_bytes", "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_probe_gather_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down", "polar_select_gemm_down_workspace_bytes", "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.polar_select_gemm_down.restype = i
         L.polar_select_gemm_down_workspace_bytes.argtypes = [i, i, i, ctypes.POINTER(ctypes.c_size_t)]
         L.polar_select_gemm_down_workspace_bytes.restype = i
+        L.polar_probe_gather_read.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp]
+        L.polar_probe_gather_read.restype = i
         L.polar_neuron_union.argtypes = [vp, i, i, i, i, vp, vp, vp]
         L.polar_neuron_union.restype = i
         L.polar_neuron_union_ws.argtypes = [vp, i, i, i, i, vp, vp, vp, ctypes.c_size_t, vp]
@@ -252,6 +254,19 @@ def probe_read(src: torch.Tensor, slab_bytes: int, nontemporal: bool = True,
     rc = lib().polar_probe_read(_dev(src, "src"), slabs, slab_bytes, 1 if nontemporal else 0,
                                 _dev(sink, "sink"), _stream())
     _check(rc, "polar_probe_read")
+    return sink
+
+
+def probe_gather_read(W: torch.Tensor, idx: torch.Tensor, slices: int = 3, depth: int = 1,
+                      nontemporal: bool = True, sink: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Read yardstick for gathered weight rows (see polar_probe_gather_read)."""
+    N, K = W.shape
+    n_idx = idx.shape[0]
+    if sink is None:
+        sink = torch.empty(max(2 * ((n_idx + 63) // 64) * slices, 1), dtype=torch.int32, device=W.device)
+    rc = lib().polar_probe_gather_read(_dev(W, "W"), _dev(idx, "idx", torch.int32), n_idx, N, K, slices, depth,
+                                       1 if nontemporal else 0, _dev(sink, "sink"), _stream())
+    _check(rc, "polar_probe_gather_read")
     return sink
 
 

@@ -162,7 +162,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 1400; }
+int polar_version(void) { return 1500; }
 
 int polar_last_hip_error(void) { return g_last_hip_error; }
 
@@ -385,6 +385,19 @@ static int check_down_sizes(int M, int Kout, int N, int cap)
     if (Kout % 256 != 0 || (long long)N * Kout > (1ll << 40) || (long long)M * cap >= (1ll << 40))
         return POLAR_EUNSUPPORTED;
     return POLAR_OK;
+}
+
+int polar_probe_gather_read(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices, int depth,
+                            int nontemporal, uint32_t *sink, void *stream)
+{
+    if (n_idx < 0 || N < 1 || K < 1 || slices < 1) return POLAR_EINVAL;
+    if (depth != 1 && depth != 4) return POLAR_EINVAL;
+    if (K % (128 * slices * depth) != 0 || (long long)N * K > (1ll << 40)) return POLAR_EUNSUPPORTED;
+    if ((long long)((n_idx + 63) / 64) * slices > (1ll << 30)) return POLAR_EUNSUPPORTED;
+    if (n_idx == 0) return POLAR_OK;
+    if (!W || !idx || !sink || ((uintptr_t)W & 15u)) return POLAR_EINVAL;
+    return record(launch_gather_probe(W, idx, n_idx, N, K, slices, depth, nontemporal, sink,
+                                      static_cast<hipStream_t>(stream)));
 }
 
 int polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap, size_t *bytes)

@@ -80,6 +80,8 @@ hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t
                                    hipStream_t stream);
 hipError_t launch_read_probe(const void *src, size_t slabs, size_t slab_bytes, int nontemporal,
                              uint32_t *sink, hipStream_t stream);
+hipError_t launch_gather_probe(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices,
+                               int depth, int nontemporal, uint32_t *sink, hipStream_t stream);
 int neuron_union_max_n();
 hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                                int32_t *count_out, hipStream_t stream);

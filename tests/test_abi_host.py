@@ -243,6 +243,19 @@ def test_probe_and_launch_query_argument_checks():
     assert polar.sha_launches(4, 8, 8, 256, 96, 4) == 0
 
 
+def test_gather_probe_argument_checks():
+    L = binding.lib()
+    A16 = ctypes.c_void_p(0x1000)
+    g = lambda W=A16, idx=FAKE, n=100, N=64, K=1536, slices=3, depth=1, sink=FAKE: L.polar_probe_gather_read(
+        W, idx, n, N, K, slices, depth, 1, sink, None)
+    assert g(n=-1) == EINVAL and g(N=0) == EINVAL and g(K=0) == EINVAL and g(slices=0) == EINVAL
+    assert g(depth=3) == EINVAL and g(depth=0) == EINVAL and g(depth=2) == EINVAL
+    assert g(K=1500) == EUNSUPPORTED and g(K=1536, slices=5) == EUNSUPPORTED and g(K=1536, depth=4, slices=2) == EUNSUPPORTED
+    assert g(W=None) == EINVAL and g(idx=None) == EINVAL and g(sink=None) == EINVAL
+    assert g(W=ctypes.c_void_p(0x1008)) == EINVAL
+    assert g(n=0, W=None, idx=None, sink=None) == OK
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The benchmark runs on one GPU only and says so before it touches torch or the GPU."""
     import subprocess

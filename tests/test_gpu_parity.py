@@ -848,3 +848,33 @@ def test_router_ties():
     Wz = torch.zeros((8, 6), dtype=torch.float16, device=DEV)
     Wz[0] = torch.tensor([0.0, -0.0, 0.0, -0.0, 0.0, -0.0])
     assert router_case(hz, Wz, 6, "f16").tolist() == [[0, 1, 2, 3, 4, 5]]
+
+
+@pytest.mark.parametrize("depth", [1, 4])
+def test_gather_probe_folds_every_word_of_every_gathered_row(depth):
+    """The gathered-row yardstick really reads what it claims: each wave's result is the XOR of
+    its 32 rows' words in its slice of K (ids out of range read row 0; a ragged last tile repeats
+    its last entry)."""
+    g = torch.Generator(device=DEV).manual_seed(11)
+    N, K, slices = 300, 1536, 3
+    W = torch.randint(-2 ** 15, 2 ** 15 - 1, (N, K), generator=g, device=DEV, dtype=torch.int16)
+    ids = torch.randint(0, N, (150,), generator=g, device=DEV, dtype=torch.int32)
+    ids[7], ids[99] = -1, N
+    for nt in (False, True):
+        sink = polar.probe_gather_read(W, ids, slices=slices, depth=depth, nontemporal=nt)
+        torch.cuda.synchronize()
+        got = sink.cpu().numpy().view(np.uint32)
+        words = W.cpu().numpy().view(np.uint32).reshape(N, K // 2)
+        idh = ids.cpu().numpy().copy()
+        idh[(idh < 0) | (idh >= N)] = 0
+        per = K // 2 // slices
+        for tile in range(3):
+            for sl in range(slices):
+                for wave in range(2):
+                    first = tile * 64 + wave * 32
+                    if first >= len(idh):
+                        continue
+                    rows = [idh[min(first + r, len(idh) - 1)] for r in range(32)]
+                    want = np.bitwise_xor.reduce(words[rows, sl * per:(sl + 1) * per].reshape(-1))
+                    assert got[2 * (tile * slices + sl) + wave] == want, (depth, nt, tile, sl, wave)
+
