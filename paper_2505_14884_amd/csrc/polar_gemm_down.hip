@@ -11,17 +11,19 @@
 //   * a wave owns 128 output columns and all M rows (MT * 8 accumulator tiles of 16 x 16) and walks
 //     the selected neurons 32 at a time: 8 loads of 16 bytes per lane fetch 32 row pieces of 256
 //     bytes (16 lanes per piece, 4 pieces per load: whole cache lines).  A lane then holds an
-//     8 x 8 block (8 neurons x 8 columns) of 16-bit weights; transposed inside the lane (byte
-//     permutes, no LDS) it is the B operand of 8 matrix-core steps, one per column e of the block:
+//     8 x 8 block (8 neurons x 8 columns) of 16-bit weights; transposed inside the lane (shifts
+//     and masks, no LDS) it is the B operand of 8 matrix-core steps, one per column e of the block:
 //     lane (x, kg) feeds column 8x + e with the neurons 8kg .. 8kg + 7 of the block.
 //   * the activations are the A operand.  A first, small kernel rounds them to the storage type
 //     (the matrix cores take 16-bit operands; a 16-bit model holds them so), zeroes the entries
 //     whose id is invalid or beyond the live count, and pads the rows to a multiple of 32: every
 //     column block needs the same values, so doing it once takes the conversions, the masking and
-//     the row-end special case out of the streaming loop, where lane (x, kg) now reads
-//     H16[m = 16t + x, 8 consecutive j] with one aligned 16-byte load.
-//   * the waves of a workgroup do not talk to each other while they stream: no LDS tile, no
-//     barrier.  A workgroup is a pair of column blocks times four neuron parities: wave (c, p)
+//     the row-end special case out of the streaming loop.  The workgroup stages the prepared
+//     values through LDS, a chunk of 8 blocks at a time (whole cache lines, each once; the next
+//     chunk travels in registers while the current one is multiplied), and lane (x, kg) reads
+//     H16[m = 16t + x, 8 consecutive j] with one 16-byte LDS read.
+//   * apart from one barrier per chunk the waves of a workgroup do not talk to each other while
+//     they stream.  A workgroup is a pair of column blocks times four neuron parities: wave (c, p)
 //     takes the 32-neuron blocks p, p + 4, ... of the workgroup's range, and the four add their
 //     accumulators through LDS at the end.  Eight waves per compute unit, two per SIMD, are what
 //     keeps the matrix cores and the vector ALU fed: with one wave per SIMD every dependent
