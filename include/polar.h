@@ -229,8 +229,9 @@ int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const in
  * form built for decode batches: 128-neuron tiles and a fixed-size launch whose workgroups
  * split the (neuron tile, K block) work evenly whatever the live count is, followed by a
  * small kernel that adds the pieces of each tile in a fixed order (two launches; results are
- * reproducible for given sizes, count and workspace size).  For larger M, or with workspace
- * NULL, it runs the kernel of polar_select_gemm.
+ * reproducible for given sizes, count and workspace size).  For larger M, with workspace NULL,
+ * with K not a multiple of 256 or with cap beyond 196608 it runs the kernel of
+ * polar_select_gemm.
  *   workspace        scratch, DEVICE pointer, 16-byte aligned, caller-owned; contents are
  *                    overwritten; calls that overlap in time need separate workspaces
  *   workspace_bytes  its size; polar_select_gemm_workspace_bytes(M) gives the size at which
