@@ -354,7 +354,7 @@ int down_ranges(int Kout, int cap)
     if (ns < 1) ns = 1;
     const long blocks = ((long)cap + kDownBlock - 1) / kDownBlock;
     const long max_blocks = kDownMaxIds / kDownBlock - 1;     // a range holds at most blocks / ns + 1 blocks
-    while (blocks / ns + 1 > max_blocks + 1) ++ns;
+    if (blocks / ns > max_blocks) ns = (int)((blocks + max_blocks - 1) / max_blocks);
     if (ns > blocks && blocks > 0) ns = (int)blocks;          // no empty ranges beyond the live blocks' count
     return ns < 1 ? 1 : ns;
 }
