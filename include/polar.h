@@ -225,7 +225,7 @@ int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const in
 
 /*
  * The same operation with a workspace (Appendix "Sparse Kernels", Algorithm 3; same arguments,
- * same result up to the order of the float additions).  For M <= 64 the library then runs a
+ * same result up to the order of the float additions).  For M <= 128 the library then runs a
  * form built for decode batches: 128-neuron tiles and a fixed-size launch whose workgroups
  * split the (neuron tile, K block) work evenly whatever the live count is, followed by a
  * small kernel that adds the pieces of each tile in a fixed order (two launches; results are
@@ -235,7 +235,7 @@ int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const in
  *   workspace        scratch, DEVICE pointer, 16-byte aligned, caller-owned; contents are
  *                    overwritten; calls that overlap in time need separate workspaces
  *   workspace_bytes  its size; polar_select_gemm_workspace_bytes(M) gives the size at which
- *                    the launch is as wide as the library wants it (0 for M > 64); a smaller
+ *                    the launch is as wide as the library wants it (0 for M > 128); a smaller
  *                    workspace narrows the launch, it is not an error
  */
 int polar_select_gemm_workspace_bytes(int M, size_t *bytes);

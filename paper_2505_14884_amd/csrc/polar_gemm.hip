@@ -11,7 +11,7 @@
 // far below the ~300 flop/byte ridge of the part, but above what the vector ALUs sustain at
 // HBM speed, so the contraction runs on MFMA (v_mfma_f32_16x16x32) while the kernel is
 // organised around streaming the gathered rows.  Two forms: the one-launch kernel described
-// here, and, further down, an evenly split form for M <= 64 that needs a workspace and is faster:
+// here, and, further down, an evenly split form for M <= 128 that needs a workspace and is faster:
 //   * a workgroup owns 32 selected neurons and walks K in blocks of 128 values; per block it
 //     loads its 32 x 256-byte row pieces with fully coalesced 16-byte loads (16 lanes per
 //     piece), parks them in LDS (padded rows, conflict-free 16-byte reads) and every wave
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Evenly split form for M <= 64 with a caller-supplied workspace.
+// Evenly split form for M <= 128 with a caller-supplied workspace.
 //
 // In the kernel above the number of workgroups follows the live count, which the host does not
 // know (it stays on the device): at a 29 % union 332 workgroups land on 256 compute units, one
@@ -374,8 +374,8 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     const int first_tile = u0 / upt;
 
     // activation block: 16 lanes per 256-byte row piece, rows a_row + kARows*i
-    // (staged by the first kAThreads threads: at most 16 rows per pass, so that MT = 1 has a pass)
-    constexpr int kAThreads = kStreamThreads < 256 ? kStreamThreads : 256;
+    // (staged by the first kAThreads threads: all of them unless the block has only 16 rows)
+    constexpr int kAThreads = 16 * MT * 16 < kStreamThreads ? 16 * MT * 16 : kStreamThreads;
     constexpr int kARows = kAThreads / 16, AP = 16 * MT / kARows;
     const bool stages_a = kAThreads == kStreamThreads || wave < kAThreads / 64;
     const int a_row = tid >> 4;
@@ -403,19 +403,19 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     __syncthreads();
     // this wave's 32 weight rows of a tile: 16 lanes per 256-byte row piece, rows kg + 4*i
     const int my_first = wave * kStreamWaveN + kg;
-    auto row_offset = [&](int tile_in_span, int i) -> size_t {
+    auto row_id = [&](int tile_in_span, int i) -> int {
         const int id = sh_id[(tile_in_span % kSpanTiles) * kStreamTileN + my_first + 4 * i];
-        return (size_t)(id < 0 ? 0 : id) * K;
+        return id < 0 ? 0 : id;
     };
-    // row offsets (in elements) of the tile being multiplied and of the tile after it; kept as
-    // offsets from W so that every load is known to be a global one
-    size_t cur[NR], nxt[NR];
+    // rows of the tile being multiplied and of the tile after it (ids: the address is formed at
+    // the load, from W, so that every load is known to be a global one)
+    int cur[NR], nxt[NR];
     int tile = first_tile;
     int tile_base = tile * upt, tile_end = tile_base + upt;         // its units
 #pragma unroll
     for (int i = 0; i < NR; ++i) {
-        cur[i] = row_offset(0, i);
-        nxt[i] = row_offset(1, i);
+        cur[i] = row_id(0, i);
+        nxt[i] = row_id(1, i);
     }
 
     // loads of block j of unit v (clamped to the span's last unit) into ring slot j; fenced so
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         __builtin_amdgcn_sched_barrier(0);                                                         \
         _Pragma("unroll") for (int i = 0; i < NR; ++i)                                             \
         {                                                                                          \
-            const u32x4 *p = reinterpret_cast<const u32x4 *>(W + (ahead ? nxt[i] : cur[i])) + x;   \
+            const u32x4 *p = reinterpret_cast<const u32x4 *>(W + (size_t)(ahead ? nxt[i] : cur[i]) * K) + x; \
             wq[j][i] = __builtin_nontemporal_load(p + blk);   /* read once: leave the caches to   */ \
                                                               /* the activations and the partials */ \
         }                                                                                          \
@@ -519,7 +519,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
 #pragma unroll
             for (int i = 0; i < NR; ++i) {
                 cur[i] = nxt[i];
-                nxt[i] = row_offset(tile + 1 - first_tile, i);
+                nxt[i] = row_id(tile + 1 - first_tile, i);
             }
         }
     }
@@ -768,11 +768,12 @@ hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, 
 
 // Workspace of the wide-tile form: two slots of raw accumulators per workgroup.
 static size_t stream_slot_bytes(int mt) { return (size_t)2 * kStreamWaves * mt * NH * 64 * sizeof(f32x4); }
-static int stream_mt(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : 4); }
+constexpr int kStreamMaxRows = 128;              // rows of the batch the evenly split form takes
+static int stream_mt(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : (M <= 64 ? 4 : 8)); }
 
 size_t select_gemm_workspace_bytes(int M)
 {
-    return M > 64 ? 0 : (size_t)kStreamGrid * stream_slot_bytes(stream_mt(M));
+    return M > kStreamMaxRows ? 0 : (size_t)kStreamGrid * stream_slot_bytes(stream_mt(M));
 }
 
 template <bool BF>
@@ -790,9 +791,13 @@ static hipError_t launch_stream_mt(int mt, int G, int tiles, hipStream_t st, con
         hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 2>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
         hipLaunchKernelGGL((select_gemm_reduce_kernel<2>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
         break;
-    default:
+    case 4:
         hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 4>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
         hipLaunchKernelGGL((select_gemm_reduce_kernel<4>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
+        break;
+    default:
+        hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 8>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
+        hipLaunchKernelGGL((select_gemm_reduce_kernel<8>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
         break;
     }
     return hipGetLastError();
@@ -803,7 +808,7 @@ hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *id
                                  void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
     const char *form = getenv("POLAR_GEMM_FORM");            // "narrow": always the 32-neuron kernel
-    if (!workspace || M > 64 || K % (kBlockK * kUnitBlocks) != 0 || (form && form[0] == 'n'))
+    if (!workspace || M > kStreamMaxRows || K % (kBlockK * kUnitBlocks) != 0 || (form && form[0] == 'n'))
         return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
     const int mt = stream_mt(M);
     const int tiles = (cap + kStreamTileN - 1) / kStreamTileN;

@@ -67,7 +67,7 @@ hipError_t launch_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, 
 hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
                               float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
                               hipStream_t stream);
-// Wide-tile form (M <= 64, workspace of select_gemm_workspace_bytes(M) bytes or less; falls back to
+// Wide-tile form (M <= 128, workspace of select_gemm_workspace_bytes(M) bytes or less; falls back to
 // the form above when the workspace is absent or M is larger).
 size_t select_gemm_workspace_bytes(int M);
 hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,

@@ -453,7 +453,7 @@ def gemm_workgroups(G):
 
 
 def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0, ws=False, G=None, ws_bytes=None):
-    """ws: call the workspace entry point (wide-tile form for M <= 64); G pins its launch width;
+    """ws: call the workspace entry point (wide-tile form for M <= 128); G pins its launch width;
     ws_bytes shrinks the workspace below the recommended size."""
     g = torch.Generator(device=DEV).manual_seed(1000 + seed)
     tdt = torch.float16 if dtype == "f16" else torch.bfloat16
@@ -466,7 +466,7 @@ def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0, ws=False, G=No
     if ws:
         nbytes = polar.select_gemm_workspace_bytes(M) if ws_bytes is None else ws_bytes
         # poisoned: the kernels must write every slot they later read; a zero-size recommendation
-        # (M > 64) still goes through the workspace entry point with a token buffer
+        # (M > 128) still goes through the workspace entry point with a token buffer
         workspace = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=DEV)
     with gemm_workgroups(G):
         polar.select_gemm(A, W, idx, count=cnt, relu=relu, out=out, workspace=workspace)
@@ -483,7 +483,7 @@ def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0, ws=False, G=No
 
 @pytest.mark.parametrize("ws", [False, True])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("M", [1, 5, 17, 33, 64, 65, 130, 256, 300])
+@pytest.mark.parametrize("M", [1, 5, 17, 33, 64, 65, 100, 128, 130, 256, 300])
 def test_select_gemm_shapes(dtype, M, ws):
     say("\ncase select_gemm", dtype, M, "workspace" if ws else "")
     rng = np.random.default_rng(M)
@@ -503,7 +503,7 @@ def test_select_gemm_wide_form_spans(G):
     N, K = 700, 1024
     idx = rng.permutation(N)[:300].tolist()                # 3 tiles of 128, the last ragged
     idx[5], idx[200] = -1, N                               # invalid ids give zero columns
-    for M, dtype in ((64, "f16"), (20, "bf16"), (3, "f16")):
+    for M, dtype in ((64, "f16"), (20, "bf16"), (3, "f16"), (128, "bf16"), (70, "f16")):
         gemm_case(M, K, N, idx, dtype, relu=True, seed=3, ws=True, G=G)
         gemm_case(M, K, N, idx, dtype, relu=False, seed=4, ws=True, G=G, count=130)   # 2 live tiles
         gemm_case(M, K, N, idx, dtype, relu=False, seed=5, ws=True, G=G, count=0)
@@ -514,7 +514,7 @@ def test_select_gemm_small_workspace_narrows_the_launch():
     rng = np.random.default_rng(78)
     idx = rng.permutation(700)[:300].tolist()
     full = polar.select_gemm_workspace_bytes(64)
-    assert full > 0 and polar.select_gemm_workspace_bytes(65) == 0
+    assert full > 0 and polar.select_gemm_workspace_bytes(129) == 0
     one = 2 * 8 * 4 * 64 * 16          # a workgroup's two slots: 8 waves x 4 accumulator tiles x 64 lanes x 16 B
     assert full % one == 0
     for nbytes in (one, 3 * one, one - 16, 0):             # launch of 1 workgroup, of 3, narrow kernel, narrow kernel
