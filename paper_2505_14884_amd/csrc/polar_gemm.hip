@@ -27,7 +27,6 @@
 //     64, 128, 256) and both 16-column halves of the 32 neurons: 2*MT accumulators.
 // The gather costs nothing extra: a row index only changes the base address of a contiguous
 // 2K-byte stream, which is why the weights are stored one contiguous row per neuron.
-#include <atomic>
 #include <cstdlib>
 
 #include "polar_internal.h"
@@ -401,7 +400,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         sh_id[e] = (id >= 0 && id < N) ? id : -1;
     }
     __syncthreads();
-    // this wave's 32 weight rows of a tile: 16 lanes per 256-byte row piece, rows kg + 4*i
+    // this wave's kStreamWaveN weight rows of a tile: 16 lanes per 256-byte row piece, rows kg + 4*i
     const int my_first = wave * kStreamWaveN + kg;
     auto row_id = [&](int tile_in_span, int i) -> int {
         const int id = sh_id[(tile_in_span % kSpanTiles) * kStreamTileN + my_first + 4 * i];
@@ -440,8 +439,8 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         __builtin_amdgcn_sched_barrier(0);                                                         \
     }
     // block j of unit u: ring slot j goes to LDS, is refilled for unit u + 1, and is multiplied;
-    // the wave's B operands (two 16-neuron halves, four k steps) stay in registers while the M
-    // rows go by, 16 at a time
+    // the wave's B operands (NH groups of 16 neurons, four k steps) stay in registers while the
+    // M rows go by, 16 at a time
 #define POLAR_STREAM_STEP(j)                                                                       \
     {                                                                                              \
         unsigned char *abuf = sh_at[j];                                                            \
@@ -484,7 +483,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
 
         if (seg_end - seg_begin == upt) {
             // the whole contraction of this tile: finish in place (accumulator layout: this
-            // lane holds rows 16*t + 4*kg + i of column x of each 16-neuron half)
+            // lane holds rows 16*t + 4*kg + i of column x of each group of 16 neurons)
 #pragma unroll
             for (int h = 0; h < NH; ++h) {
                 const int col = tile * kStreamTileN + wave * kStreamWaveN + 16 * h + x;
@@ -527,9 +526,9 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
 #undef POLAR_STREAM_FETCH
 }
 
-// grid = tiles * waves per tile * ceil(MT * 2 / 4) workgroups: workgroup (tile, w, q) adds four of the
-// MT * 2 accumulator tiles that wave w of the kernel above left for that tile (thread (j, lane)
-// owns entry e = 4 * q + j = t * 2 + h); G is that kernel's grid.
+// grid = tiles * waves per tile * ceil(MT * NH / 4) workgroups: workgroup (tile, w, q) adds four of
+// the MT * NH accumulator tiles that wave w of the kernel above left for that tile (thread
+// (j, lane) owns entry e = 4 * q + j = t * NH + h); G is that kernel's grid.
 template <int MT>
 __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
     const float *__restrict__ part, const int32_t *__restrict__ idx, const int32_t *__restrict__ count_ptr,
@@ -834,24 +833,13 @@ hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *id
 
 int neuron_union_max_n() { return kUnionMaxWords * 32; }
 
-// dynamic LDS of the union kernels: the bitmap and the scan slots
-static hipError_t union_lds(const void *kernel, std::atomic<size_t> &granted, size_t lds)
-{
-    if (lds > 48 * 1024 && lds > granted.load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        granted.store(lds, std::memory_order_release);
-    }
-    return hipSuccess;
-}
-
 hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                                int32_t *count_out, hipStream_t stream)
 {
     const int words = (N + 31) / 32;
     const size_t lds = ((size_t)words + kUnionScanSlots) * sizeof(unsigned int);
-    static std::atomic<size_t> granted{0};
-    const hipError_t e = union_lds(reinterpret_cast<const void *>(neuron_union_kernel), granted, lds);
+    static LdsGrant granted;                     // the bitmap and the scan slots
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(neuron_union_kernel), lds, granted);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(neuron_union_kernel, dim3(1), dim3(kUnionThreads), lds, stream, topk,
                        (long)B * kn, N, cap, idx_out, count_out);
@@ -880,11 +868,11 @@ hipError_t launch_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int
     const size_t per = (size_t)words * sizeof(unsigned int);
     if (workspace && (size_t)builders * per > workspace_bytes) builders = (int)(workspace_bytes / per);
     if (!workspace || builders < 2) return launch_neuron_union(topk, B, kn, N, cap, idx_out, count_out, stream);
-    static std::atomic<size_t> granted_build{0}, granted_emit{0};
-    hipError_t e = union_lds(reinterpret_cast<const void *>(neuron_bitmap_kernel), granted_build, per);
+    static LdsGrant granted_build, granted_emit;
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(neuron_bitmap_kernel), per, granted_build);
     if (e != hipSuccess) return e;
     const size_t lds = ((size_t)words + kUnionScanSlots) * sizeof(unsigned int);
-    e = union_lds(reinterpret_cast<const void *>(neuron_emit_kernel), granted_emit, lds);
+    e = ensure_dynamic_lds(reinterpret_cast<const void *>(neuron_emit_kernel), lds, granted_emit);
     if (e != hipSuccess) return e;
     unsigned int *maps = static_cast<unsigned int *>(workspace);
     hipLaunchKernelGGL(neuron_bitmap_kernel, dim3(builders), dim3(kUnionThreads), per, stream, topk, total, N, maps);

@@ -32,8 +32,6 @@
 //     grid fills the compute units once; range s covers an NS-th of the live blocks, whatever the
 //     live count is (it stays on the device), and leaves its sums in the workspace; a second
 //     kernel adds the NS sums of every output element in ascending range order and stores Y.
-#include <atomic>
-
 #include "polar_internal.h"
 
 namespace polar {
@@ -43,7 +41,7 @@ constexpr int kDownParities = 4;                 // waves that share a column bl
 constexpr int kDownThreads = 64 * 2 * kDownParities;
 constexpr int kPrepThreads = 256;
 constexpr int kDownWaveCols = 128;               // output columns per wave
-constexpr int kDownGroupCols = 2 * kDownWaveCols;    // per workgroup (two column blocks x two parities)
+constexpr int kDownGroupCols = 2 * kDownWaveCols;    // per workgroup (two column blocks x four parities)
 constexpr int kDownBlock = 32;                   // neurons per step (the contraction depth of one MFMA)
 constexpr int kDownMaxIds = 8192;                // ids of a workgroup's range kept in LDS
 constexpr int kDownTargetGroups = 256;           // one workgroup per compute unit
@@ -387,16 +385,12 @@ static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H,
                            dim3(kPrepThreads), 0, st, H, idx, count, H16, M, N, cap);
     // dynamic LDS: two activation chunks and the ids of a range; above 64 KB it has to be granted
     const size_t lds = (size_t)2 * 16 * mt * kChunkPitch + (size_t)kDownMaxIds * sizeof(int);
-    static std::atomic<bool> granted[2][3];
+    static LdsGrant granted[3];                  // one set per instantiation of this launcher
     const void *kernels[3] = {reinterpret_cast<const void *>(select_gemm_down_kernel<BF, 1>),
                               reinterpret_cast<const void *>(select_gemm_down_kernel<BF, 2>),
                               reinterpret_cast<const void *>(select_gemm_down_kernel<BF, 4>)};
     const int ki = mt == 1 ? 0 : (mt == 2 ? 1 : 2);
-    if (lds > 48 * 1024 && !granted[BF ? 1 : 0][ki].load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute(kernels[ki], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        granted[BF ? 1 : 0][ki].store(true, std::memory_order_release);
-    }
+    if (const hipError_t e = ensure_dynamic_lds(kernels[ki], lds, granted[ki]); e != hipSuccess) return e;
     switch (mt) {
     case 1:
         hipLaunchKernelGGL((select_gemm_down_kernel<BF, 1>), grid, block, lds, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);

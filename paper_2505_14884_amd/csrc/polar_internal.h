@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -33,6 +34,26 @@ struct RouterPlan {
     size_t bytes;  // workspace bytes, 256-aligned
 };
 int make_router_plan(int B, int D, int H, RouterPlan *plan);
+
+// Dynamic LDS beyond the default allowance has to be requested per kernel, on the device the
+// launch goes to.  The request is made only when a launch needs more than any earlier launch of
+// the same kernel on that device did, so steady-state calls (and calls recorded into a HIP graph
+// after one warm-up call) issue launches only.  One LdsGrant per kernel, with static storage.
+struct LdsGrant {
+    static constexpr int kDevices = 64;          // devices remembered; beyond that, every call asks
+    std::atomic<size_t> bytes[kDevices];
+};
+inline hipError_t ensure_dynamic_lds(const void *kernel, size_t lds, LdsGrant &grant)
+{
+    if (lds <= 48 * 1024) return hipSuccess;
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    std::atomic<size_t> *slot = dev >= 0 && dev < LdsGrant::kDevices ? &grant.bytes[dev] : nullptr;
+    if (slot && lds <= slot->load(std::memory_order_acquire)) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess && slot) slot->store(lds, std::memory_order_release);
+    return e;
+}
 
 // Kernel launchers.  Arguments were validated by the caller; each returns the hipError_t of
 // its launch.

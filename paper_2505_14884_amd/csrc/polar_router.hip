@@ -27,8 +27,6 @@
 // 16 requests) otherwise.  All paths share the arithmetic contract above.
 #include <stdlib.h>
 
-#include <atomic>
-
 #include "polar_internal.h"
 
 namespace polar {
@@ -182,18 +180,6 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
     rank_and_emit(sh_logit, sh_rank, H, k, kRouterThreads, tid, head_idx + (size_t)b * k);
 }
 
-// Dynamic LDS beyond the default allowance has to be requested per kernel.  The request is made
-// only when a launch needs more than any earlier launch of the same kernel did, so steady-state
-// calls (and calls recorded into a HIP graph after one warm-up call) issue launches only.
-template <class Kern> hipError_t ensure_dynamic_lds(Kern kern, size_t lds, std::atomic<size_t> &granted)
-{
-    if (lds <= 48 * 1024 || lds <= granted.load(std::memory_order_acquire)) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e == hipSuccess) granted.store(lds, std::memory_order_release);
-    return e;
-}
-
 template <bool BF, int VEC>
 hipError_t launch_vec(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H, int k,
                       int32_t *head_idx, float *logits_out, hipStream_t stream)
@@ -209,8 +195,8 @@ hipError_t launch_vec(const uint16_t *hidden, const uint16_t *Wr, int B, int D, 
     const size_t lds = (size_t)Dpad * sizeof(uint16_t) +
                        ((size_t)nslice * H + (size_t)J * H + H) * sizeof(double);
     auto kern = router_topk_kernel<BF, VEC>;
-    static std::atomic<size_t> granted{0};
-    if (hipError_t e = ensure_dynamic_lds(kern, lds, granted); e != hipSuccess) return e;
+    static LdsGrant granted;
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)B), dim3(kRouterThreads), lds, stream, hidden, Wr, D, H,
                        k, nslice, J, Dpad, head_idx, logits_out);
     return hipGetLastError();
@@ -394,8 +380,8 @@ hipError_t launch_split_vec(const uint16_t *hidden, const uint16_t *Wr, int B, i
     const int RH = kTileR * H;
     const size_t lds = ((size_t)kTileR * plan.Dp + (size_t)nslice * RH + (size_t)J * RH) * sizeof(double);
     auto kern = router_partial_kernel<BF, VEC>;
-    static std::atomic<size_t> granted{0};
-    if (hipError_t e = ensure_dynamic_lds(kern, lds, granted); e != hipSuccess) return e;
+    static LdsGrant granted;
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)plan.P, (unsigned)plan.RT), dim3(kSplitThreads), lds, stream,
                        hidden, Wr, B, D, H, plan.Dp, nslice, J, ws);
     hipError_t e = hipGetLastError();
@@ -588,8 +574,8 @@ hipError_t launch_split_mfma_grp(const uint16_t *hidden, const uint16_t *Wr, int
 {
     const size_t lds = mm_lds_bytes(plan.Dp, H);
     auto kern = router_partial_mfma_kernel<BF, GRP>;
-    static std::atomic<size_t> granted{0};
-    if (hipError_t e = ensure_dynamic_lds(kern, lds, granted); e != hipSuccess) return e;
+    static LdsGrant granted;
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)plan.P, (unsigned)plan.RT), dim3(kMmThreads), lds, stream,
                        hidden, Wr, B, D, H, plan.Dp, ws);
     hipError_t e = hipGetLastError();
