@@ -417,20 +417,21 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         nxt[i] = row_id(1, i);
     }
 
-    // loads of block j of unit v (clamped to the span's last unit) into ring slot j; fenced so
+    // loads of block j of unit v into ring slot j (past the span's end: one piece that every
+    // workgroup shares, so that the loop needs no branch and the memory system no traffic); fenced so
     // that the compiler keeps the order (weights before activations, slot 0 before slot 1): its
     // count of outstanding loads at the loop header is then the same on entry and on the back
     // edge, and nothing is drained there
     u32x4 wq[kUnitBlocks][NR], aq[kUnitBlocks][AP];
 #define POLAR_STREAM_FETCH(j, unit)                                                                \
     {                                                                                              \
-        const int v = min((unit), u1 - 1);                                                         \
-        const bool ahead = v >= tile_end;                                                          \
-        const size_t blk = (size_t)((v - (ahead ? tile_end : tile_base)) * kUnitBlocks + (j)) * 16; \
+        const int v = (unit);                                                                      \
+        const bool past = v >= u1, ahead = v >= tile_end;                                          \
+        const size_t blk = past ? 0 : (size_t)((v - (ahead ? tile_end : tile_base)) * kUnitBlocks + (j)) * 16; \
         __builtin_amdgcn_sched_barrier(0);                                                         \
         _Pragma("unroll") for (int i = 0; i < NR; ++i)                                             \
         {                                                                                          \
-            const u32x4 *p = reinterpret_cast<const u32x4 *>(W + (size_t)(ahead ? nxt[i] : cur[i]) * K) + x; \
+            const u32x4 *p = reinterpret_cast<const u32x4 *>(W + (size_t)(past ? 0 : (ahead ? nxt[i] : cur[i])) * K) + x; \
             wq[j][i] = __builtin_nontemporal_load(p + blk);   /* read once: leave the caches to   */ \
                                                               /* the activations and the partials */ \
         }                                                                                          \
@@ -467,6 +468,44 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         }                                                                                          \
     }
 
+    // a finished segment of `tile`: the whole contraction is finished in place, a part of it goes
+    // to the workspace as raw accumulators
+    auto store_segment = [&](const f32x4 (&sum)[MT][NH], int of_tile, bool whole) {
+        if (whole) {
+            // accumulator layout: this lane holds rows 16*t + 4*kg + i of column x of each group
+            // of 16 neurons
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const int col = of_tile * kStreamTileN + wave * kStreamWaveN + 16 * h + x;
+                if (col >= count) continue;
+                const bool valid = sh_id[(of_tile - first_tile) * kStreamTileN + wave * kStreamWaveN + 16 * h + x] >= 0;
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int row = 16 * t + 4 * kg + i;
+                        if (row < M) {
+                            float val = sum[t][h][i];
+                            if (relu) val = val > 0.0f ? val : 0.0f;
+                            C[(size_t)row * cap + col] = valid ? val : 0.0f;
+                        }
+                    }
+            }
+        } else {
+            const int slot = of_tile == first_tile ? 0 : 1;          // slot 0: the span's first tile
+            f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
+                         (((size_t)span * 2 + slot) * kStreamWaves + wave) * (MT * NH) * 64 + lane;
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int h = 0; h < NH; ++h) dst[(t * NH + h) * 64] = sum[t][h];
+        }
+    };
+    constexpr bool kDefer = MT <= 4;             // beyond that the registers are not there
+    f32x4 held[MT][NH];
+    int held_tile = -1;
+    bool held_whole = false;
+
     POLAR_STREAM_FETCH(0, u)
     POLAR_STREAM_FETCH(1, u)
     while (u < u1) {
@@ -481,35 +520,19 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
             POLAR_STREAM_STEP(1)
         }
 
-        if (seg_end - seg_begin == upt) {
-            // the whole contraction of this tile: finish in place (accumulator layout: this
-            // lane holds rows 16*t + 4*kg + i of column x of each group of 16 neurons)
-#pragma unroll
-            for (int h = 0; h < NH; ++h) {
-                const int col = tile * kStreamTileN + wave * kStreamWaveN + 16 * h + x;
-                if (col >= count) continue;
-                const bool valid = sh_id[(tile - first_tile) * kStreamTileN + wave * kStreamWaveN + 16 * h + x] >= 0;
-#pragma unroll
-                for (int t = 0; t < MT; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int row = 16 * t + 4 * kg + i;
-                        if (row < M) {
-                            float val = acc[t][h][i];
-                            if (relu) val = val > 0.0f ? val : 0.0f;
-                            C[(size_t)row * cap + col] = valid ? val : 0.0f;
-                        }
-                    }
-            }
-        } else {
-            // part of it: raw accumulators to the workspace (slot 0: the span's first tile)
-            const int slot = tile == first_tile ? 0 : 1;
-            f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
-                         (((size_t)span * 2 + slot) * kStreamWaves + wave) * (MT * NH) * 64 + lane;
+        // A segment's stores are counted with the loads in flight, and the loads issued after
+        // them cannot be waited for before the stores are acknowledged: the first segment that is
+        // followed by more work is therefore kept in registers and stored when the span is done.
+        const bool whole = seg_end - seg_begin == upt;
+        if (kDefer && u < u1 && held_tile < 0) {
+            held_tile = tile;
+            held_whole = whole;
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int h = 0; h < NH; ++h) dst[(t * NH + h) * 64] = acc[t][h];
+                for (int h = 0; h < NH; ++h) held[t][h] = acc[t][h];
+        } else {
+            store_segment(acc, tile, whole);
         }
         if (u < u1) {                            // on to the next tile; fetch the row ids of the one after it
             ++tile;
@@ -522,6 +545,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
             }
         }
     }
+    if (kDefer && held_tile >= 0) store_segment(held, held_tile, held_whole);
 #undef POLAR_STREAM_STEP
 #undef POLAR_STREAM_FETCH
 }
