@@ -170,6 +170,16 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
 
     down_ms = ev(down, n_ev)
     mlp_ms = ev(lambda: (union(), gemm(), down()), n_ev)
+    # the same two factors through the one-call entry point (hidden activations stay 16-bit in its workspace)
+    mlp_ws = torch.empty(polar.sparse_mlp_workspace_bytes(w.B, w.K, cap), dtype=torch.uint8, device=dev)
+
+    def fused():
+        turn[0] += 1
+        polar.sparse_mlp(x, W1s[turn[0] % layers], W2s[turn[0] % layers], idx, count=count, relu=True, out=y,
+                         workspace=mlp_ws)
+
+    fused_ms = ev(fused, n_ev)
+    mlp1_ms = ev(lambda: (union(), fused()), n_ev)
     # what the bare access pattern reaches: the same gathered rows, read and nothing else
     probe_sink = torch.empty(2 * ((n_sel + 63) // 64) * 3, dtype=torch.int32, device=dev)
     live_idx = idx[:n_sel].contiguous()
@@ -198,6 +208,8 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
         "breakdown_us": {"neuron_union": round(union_ms * 1e3, 2), "select_gemm": round(gemm_ms * 1e3, 2),
                          "dense_gemm_all_rows": None if args.no_dense else round(dense_ms * 1e3, 2),
                          "select_gemm_down": round(down_ms * 1e3, 2),
+                         "sparse_mlp_one_call": round(fused_ms * 1e3, 2),
+                         "union_and_sparse_mlp_one_call": round(mlp1_ms * 1e3, 2),
                          "union_and_both_factors": round(mlp_ms * 1e3, 2)},
         # the second factor streams the same number of weight bytes (one row of W2 per live neuron)
         "second_factor": {"kernel": "select_gemm_down_kernel + select_gemm_down_reduce_kernel", "bound": "hbm",

@@ -277,6 +277,40 @@ int polar_select_gemm_down(const float *Hact, const void *W2, const int32_t *idx
                            size_t workspace_bytes, void *stream);
 
 /*
+ * The sparsified MLP in one call (Section 3.1: MLP_{S_B}(x) = sigma(x W_{1,S_B}) W_{2,S_B}^T over
+ * the batch's union S_B of active neurons; Section 4.1: both factors gather by the same index):
+ *
+ *   Y[m, c] = sum_{j < live} h16( act( sum_k X[m, k] * W1[idx[j], k] ) ) * W2[idx[j], c]
+ *
+ * i.e. polar_select_gemm_ws followed by polar_select_gemm_down, with the hidden activations kept
+ * in the workspace in the 16-bit form the second factor reads (the first factor's reduction
+ * writes them rounded, masked and padded; no float copy, no separate conversion launch).  The
+ * result is bit-identical to that of the two calls made one after the other.
+ *
+ *   X      in   [M, D] dt, row-major.  16-byte aligned.
+ *   W1     in   [N, D] dt: row n holds neuron n's D input weights.  16-byte aligned.
+ *   W2     in   [N, D] dt: row n holds neuron n's D output weights.  16-byte aligned.
+ *   idx    in   [cap] int32 neuron ids; an id outside [0,N) contributes nothing
+ *   count  in   [1] int32, nullable, DEVICE pointer: live entries of idx (clamped to [0, cap]);
+ *               NULL means all cap
+ *   Y      out  [M, D] float, row-major; every element is written (zeros when nothing is live).
+ *               16-byte aligned.
+ *   relu        nonzero: act = max(., 0); zero: identity
+ *   workspace   required scratch, DEVICE pointer, 256-byte aligned, caller-owned, at least
+ *               polar_sparse_mlp_workspace_bytes(M, D, cap) bytes (else POLAR_EWORKSPACE);
+ *               contents are overwritten; calls that overlap in time need separate workspaces
+ *
+ * D a multiple of 256, else POLAR_EUNSUPPORTED.  Four launches per 64 rows of the batch (M > 64
+ * is processed 64 rows at a time); where the first factor's evenly split form cannot run (see
+ * polar_select_gemm_ws) its one-launch kernel and the conversion launch take its place, with
+ * the same result.  X, W1 and idx may be NULL when cap == 0.
+ */
+int polar_sparse_mlp_workspace_bytes(int M, int D, int cap, size_t *bytes);
+int polar_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx, const int32_t *count,
+                     float *Y, int M, int D, int N, int cap, polar_dtype dt, int relu, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/*
  * Batch neuron index (Section 4.1: the predicted activations of all requests are aggregated
  * into one index tensor; Section 3.1: the union set S_B).
  *
@@ -339,7 +373,7 @@ int polar_last_hip_error(void);
 /* ABI version: major * 1000 + minor (1100: adds polar_sha_launches and polar_probe_read; group sizes up to 16;
  * 1200: adds polar_select_gemm_ws and polar_select_gemm_workspace_bytes; 1300: adds polar_neuron_union_ws and
  * polar_neuron_union_workspace_bytes; 1400: adds polar_select_gemm_down and its workspace query;
- * 1500: adds polar_probe_gather_read). */
+ * 1500: adds polar_probe_gather_read; 1600: adds polar_sparse_mlp and its workspace query). */
 int polar_version(void);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_probe_gather_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down", "polar_select_gemm_down_workspace_bytes", "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes", "polar_strerror",
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_probe_gather_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down", "polar_select_gemm_down_workspace_bytes", "polar_sparse_mlp", "polar_sparse_mlp_workspace_bytes", "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes", "polar_strerror",
            "polar_last_hip_error", "polar_version")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -80,6 +80,10 @@ def lib() -> ctypes.CDLL:
         L.polar_select_gemm_down.restype = i
         L.polar_select_gemm_down_workspace_bytes.argtypes = [i, i, i, ctypes.POINTER(ctypes.c_size_t)]
         L.polar_select_gemm_down_workspace_bytes.restype = i
+        L.polar_sparse_mlp.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp, ctypes.c_size_t, vp]
+        L.polar_sparse_mlp.restype = i
+        L.polar_sparse_mlp_workspace_bytes.argtypes = [i, i, i, ctypes.POINTER(ctypes.c_size_t)]
+        L.polar_sparse_mlp_workspace_bytes.restype = i
         L.polar_probe_gather_read.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp]
         L.polar_probe_gather_read.restype = i
         L.polar_neuron_union.argtypes = [vp, i, i, i, i, vp, vp, vp]
@@ -353,6 +357,36 @@ def select_gemm_down(H: torch.Tensor, W2: torch.Tensor, idx: torch.Tensor,
                                       M, Kout, N, cap, _dtype_code(W2), _dev(workspace, "workspace"),
                                       workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "polar_select_gemm_down")
+    return out
+
+
+def sparse_mlp_workspace_bytes(M: int, D: int, cap: int) -> int:
+    """Workspace size polar_sparse_mlp requires."""
+    n = ctypes.c_size_t(0)
+    _check(lib().polar_sparse_mlp_workspace_bytes(M, D, cap, ctypes.byref(n)), "polar_sparse_mlp_workspace_bytes")
+    return int(n.value)
+
+
+def sparse_mlp(X: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, idx: torch.Tensor,
+               count: Optional[torch.Tensor] = None, relu: bool = True, out: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """h16(act(X @ W1[idx].T)) @ W2[idx] in one call: X [M,D], W1 and W2 [N,D] fp16/bf16 (one row per
+    neuron), idx int32 [cap], count int32 [1] on the device (None: all live) -> float32 [M,D].
+    A workspace is allocated when none is given."""
+    M, D = X.shape
+    N = W1.shape[0]
+    if W1.shape != W2.shape or W1.shape[1] != D or W1.dtype != X.dtype or W2.dtype != X.dtype:
+        raise ValueError("X [M,D], W1 [N,D] and W2 [N,D] must agree in D and dtype")
+    cap = idx.shape[0]
+    if out is None:
+        out = torch.empty((M, D), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = torch.empty(max(sparse_mlp_workspace_bytes(M, D, cap), 256), dtype=torch.uint8, device=X.device)
+    rc = lib().polar_sparse_mlp(_dev(X, "X"), _dev(W1, "W1"), _dev(W2, "W2"), _dev(idx, "idx", torch.int32),
+                                _dev(count, "count", torch.int32), _dev(out, "out", torch.float32),
+                                M, D, N, cap, _dtype_code(X), int(bool(relu)), _dev(workspace, "workspace"),
+                                workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "polar_sparse_mlp")
     return out
 
 

@@ -162,7 +162,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 1500; }
+int polar_version(void) { return 1600; }
 
 int polar_last_hip_error(void) { return g_last_hip_error; }
 
@@ -423,6 +423,40 @@ int polar_select_gemm_down(const float *H, const void *W2, const int32_t *idx, c
     if (workspace_bytes < select_gemm_down_workspace_bytes(M, Kout, cap)) return POLAR_EWORKSPACE;
     return record(launch_select_gemm_down(H, W2, idx, count, Y, M, Kout, N, cap, dt, workspace,
                                           static_cast<hipStream_t>(stream)));
+}
+
+static int check_mlp_sizes(int M, int D, int N, int cap)
+{
+    if (M < 0 || D < 1 || N < 1 || cap < 0) return POLAR_EINVAL;
+    if (D % 256 != 0 || (long long)N * D > (1ll << 40) || (long long)M * cap >= (1ll << 40))
+        return POLAR_EUNSUPPORTED;
+    return POLAR_OK;
+}
+
+int polar_sparse_mlp_workspace_bytes(int M, int D, int cap, size_t *bytes)
+{
+    if (!bytes) return POLAR_EINVAL;
+    const int rc = check_mlp_sizes(M, D, 1, cap);
+    if (rc != POLAR_OK) return rc;
+    *bytes = M == 0 ? 0 : sparse_mlp_workspace_bytes(M, D, cap);
+    return POLAR_OK;
+}
+
+int polar_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx, const int32_t *count,
+                     float *Y, int M, int D, int N, int cap, polar_dtype dt, int relu, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    if (!dtype_ok(dt)) return POLAR_EINVAL;
+    const int rc = check_mlp_sizes(M, D, N, cap);
+    if (rc != POLAR_OK) return rc;
+    if (M == 0) return POLAR_OK;
+    if (!W2 || !Y || !workspace || (cap > 0 && (!X || !W1 || !idx))) return POLAR_EINVAL;
+    if (((uintptr_t)X & 15u) || ((uintptr_t)W1 & 15u) || ((uintptr_t)W2 & 15u) || ((uintptr_t)Y & 15u) ||
+        ((uintptr_t)workspace & 255u))
+        return POLAR_EINVAL;
+    if (workspace_bytes < sparse_mlp_workspace_bytes(M, D, cap)) return POLAR_EWORKSPACE;
+    return record(launch_sparse_mlp(X, W1, W2, idx, count, Y, M, D, N, cap, dt, relu, workspace,
+                                    static_cast<hipStream_t>(stream)));
 }
 
 int polar_neuron_union_workspace_bytes(int B, int kn, int N, size_t *bytes)

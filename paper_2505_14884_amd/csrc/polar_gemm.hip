@@ -59,6 +59,12 @@ template <bool BF> __device__ __forceinline__ f32x4 mfma16x16x32(const u32x4 &a,
                                                   __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
+// bit pattern of v rounded to the 16-bit storage type (nearest, ties to even)
+__device__ __forceinline__ uint16_t to_storage(float v, bool bf)
+{
+    return bf ? __builtin_bit_cast(uint16_t, (__bf16)v) : __builtin_bit_cast(uint16_t, (_Float16)v);
+}
+
 // grid = ceil(cap / kTileN) workgroups; block = 256 threads (4 waves).
 // Rows m >= M of the tile are computed on clamped addresses and never stored; columns at or
 // beyond the live count are never stored; an id outside [0, N) yields a zero column.
@@ -292,8 +298,8 @@ constexpr int kSpanWords = (kStreamGrid + 31) / 32;   // words of a bitmap over 
 template <bool BF, int MT>
 __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const int32_t *__restrict__ idx,
-    const int32_t *__restrict__ count_ptr, float *__restrict__ C, float *__restrict__ part, int M,
-    int K, int N, int cap, int relu)
+    const int32_t *__restrict__ count_ptr, float *__restrict__ C, uint16_t *__restrict__ H16,
+    float *__restrict__ part, int M, int K, int N, int cap, int relu)
 {
     __shared__ __align__(16) unsigned char sh_wt[kStreamWaves][kStreamWaveN * kRowBytes];
     __shared__ __align__(16) unsigned char sh_at[2][16 * MT * kRowBytes];
@@ -477,8 +483,24 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
 #pragma unroll
             for (int h = 0; h < NH; ++h) {
                 const int col = of_tile * kStreamTileN + wave * kStreamWaveN + 16 * h + x;
-                if (col >= count) continue;
                 const bool valid = sh_id[(of_tile - first_tile) * kStreamTileN + wave * kStreamWaveN + 16 * h + x] >= 0;
+                if (H16) {                       // rounded to the storage type, rows padded with zeros
+                    if (col >= (count + 31) / 32 * 32) continue;
+                    const size_t pitch = ((size_t)cap + 31) / 32 * 32;
+#pragma unroll
+                    for (int t = 0; t < MT; ++t)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int row = 16 * t + 4 * kg + i;
+                            if (row < M) {
+                                float val = sum[t][h][i];
+                                if (relu) val = val > 0.0f ? val : 0.0f;
+                                H16[(size_t)row * pitch + col] = (col < count && valid) ? to_storage(val, BF) : (uint16_t)0;
+                            }
+                        }
+                    continue;
+                }
+                if (col >= count) continue;
 #pragma unroll
                 for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -556,7 +578,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
 template <int MT>
 __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
     const float *__restrict__ part, const int32_t *__restrict__ idx, const int32_t *__restrict__ count_ptr,
-    float *__restrict__ C, int M, int K, int N, int cap, int relu, int G)
+    float *__restrict__ C, uint16_t *__restrict__ H16, int bf, int M, int K, int N, int cap, int relu, int G)
 {
     int count = cap;
     if (count_ptr) {
@@ -604,16 +626,20 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
             for (int q = 0; q < 4; ++q) sum += v[q];
         }
         const int col = n0 + wave * kStreamWaveN + 16 * h + x;
-        if (col >= count) return;
-        const int id = idx[col];
+        if (col >= (H16 ? (count + 31) / 32 * 32 : count)) return;
+        const int id = col < count ? idx[col] : -1;
         const bool valid = id >= 0 && id < N;
+        const size_t pitch = ((size_t)cap + 31) / 32 * 32;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = 16 * t + 4 * kg + i;
             if (row < M) {
                 float v = sum[i];
                 if (relu) v = v > 0.0f ? v : 0.0f;
-                C[(size_t)row * cap + col] = valid ? v : 0.0f;
+                if (H16)
+                    H16[(size_t)row * pitch + col] = valid ? to_storage(v, bf != 0) : (uint16_t)0;
+                else
+                    C[(size_t)row * cap + col] = valid ? v : 0.0f;
             }
         }
     }
@@ -802,37 +828,32 @@ size_t select_gemm_workspace_bytes(int M)
 template <bool BF>
 static hipError_t launch_stream_mt(int mt, int G, int tiles, hipStream_t st, const uint16_t *A,
                                    const uint16_t *W, const int32_t *idx, const int32_t *count, float *C,
-                                   float *part, int M, int K, int N, int cap, int relu)
+                                   uint16_t *H16, float *part, int M, int K, int N, int cap, int relu)
 {
     const dim3 grid((unsigned)G), rgrid((unsigned)tiles * kStreamWaves * ((mt * NH + 3) / 4)), block(kStreamThreads), rblock(kGemmThreads);
+    const int bf = BF ? 1 : 0;
+#define POLAR_STREAM_LAUNCH(MT_)                                                                                          \
+    hipLaunchKernelGGL((select_gemm_stream_kernel<BF, MT_>), grid, block, 0, st, A, W, idx, count, C, H16, part, M, K, N, \
+                       cap, relu);                                                                                        \
+    hipLaunchKernelGGL((select_gemm_reduce_kernel<MT_>), rgrid, rblock, 0, st, part, idx, count, C, H16, bf, M, K, N, cap, \
+                       relu, G)
     switch (mt) {
-    case 1:
-        hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 1>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
-        hipLaunchKernelGGL((select_gemm_reduce_kernel<1>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
-        break;
-    case 2:
-        hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 2>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
-        hipLaunchKernelGGL((select_gemm_reduce_kernel<2>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
-        break;
-    case 4:
-        hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 4>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
-        hipLaunchKernelGGL((select_gemm_reduce_kernel<4>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
-        break;
-    default:
-        hipLaunchKernelGGL((select_gemm_stream_kernel<BF, 8>), grid, block, 0, st, A, W, idx, count, C, part, M, K, N, cap, relu);
-        hipLaunchKernelGGL((select_gemm_reduce_kernel<8>), rgrid, rblock, 0, st, part, idx, count, C, M, K, N, cap, relu, G);
-        break;
+    case 1: POLAR_STREAM_LAUNCH(1); break;
+    case 2: POLAR_STREAM_LAUNCH(2); break;
+    case 4: POLAR_STREAM_LAUNCH(4); break;
+    default: POLAR_STREAM_LAUNCH(8); break;
     }
+#undef POLAR_STREAM_LAUNCH
     return hipGetLastError();
 }
 
-hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
-                                 float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
-                                 void *workspace, size_t workspace_bytes, hipStream_t stream)
+// Workgroups the evenly split form would launch for these sizes and this much workspace; 0: it
+// cannot run (the caller takes the one-launch kernel).
+static int stream_grid(int M, int K, int cap, bool have_workspace, size_t workspace_bytes)
 {
     const char *form = getenv("POLAR_GEMM_FORM");            // "narrow": always the 32-neuron kernel
-    if (!workspace || M > kStreamMaxRows || K % (kBlockK * kUnitBlocks) != 0 || (form && form[0] == 'n'))
-        return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
+    if (!have_workspace || M > kStreamMaxRows || K % (kBlockK * kUnitBlocks) != 0 || (form && form[0] == 'n'))
+        return 0;
     const int mt = stream_mt(M);
     const int tiles = (cap + kStreamTileN - 1) / kStreamTileN;
     const long units = (long)tiles * (K / (kBlockK * kUnitBlocks));
@@ -845,14 +866,44 @@ hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *id
     if ((size_t)G * stream_slot_bytes(mt) > workspace_bytes) G = (long)(workspace_bytes / stream_slot_bytes(mt));
     // a span of at most units / G + 1 units touches at most tiles / G + 2 tiles, whose row ids
     // the kernel keeps in LDS; the span arithmetic is 32-bit
-    if (G < 1 || tiles / G + 2 > kSpanTiles || units * G >= (1l << 31))
-        return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
+    if (G < 1 || tiles / G + 2 > kSpanTiles || units * G >= (1l << 31)) return 0;
+    return (int)G;
+}
+
+static hipError_t launch_stream(int G, const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                                float *C, uint16_t *H16, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                                void *workspace, hipStream_t stream)
+{
+    const int mt = stream_mt(M), tiles = (cap + kStreamTileN - 1) / kStreamTileN;
     const uint16_t *A16 = static_cast<const uint16_t *>(A);
     const uint16_t *W16 = static_cast<const uint16_t *>(W);
     float *part = static_cast<float *>(workspace);
     return dt == POLAR_BF16
-               ? launch_stream_mt<true>(mt, (int)G, tiles, stream, A16, W16, idx, count, C, part, M, K, N, cap, relu)
-               : launch_stream_mt<false>(mt, (int)G, tiles, stream, A16, W16, idx, count, C, part, M, K, N, cap, relu);
+               ? launch_stream_mt<true>(mt, G, tiles, stream, A16, W16, idx, count, C, H16, part, M, K, N, cap, relu)
+               : launch_stream_mt<false>(mt, G, tiles, stream, A16, W16, idx, count, C, H16, part, M, K, N, cap, relu);
+}
+
+hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                                 float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                                 void *workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const int G = stream_grid(M, K, cap, workspace != nullptr, workspace_bytes);
+    if (G < 1) return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
+    return launch_stream(G, A, W, idx, count, C, nullptr, M, K, N, cap, dt, relu, workspace, stream);
+}
+
+bool select_gemm_h16_applicable(int M, int K, int cap, size_t workspace_bytes)
+{
+    return stream_grid(M, K, cap, true, workspace_bytes) >= 1;
+}
+
+hipError_t launch_select_gemm_h16(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                                  uint16_t *H16, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                                  void *workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const int G = stream_grid(M, K, cap, true, workspace_bytes);
+    if (G < 1) return hipErrorInvalidValue;      // callers ask select_gemm_h16_applicable first
+    return launch_stream(G, A, W, idx, count, nullptr, H16, M, K, N, cap, dt, relu, workspace, stream);
 }
 
 int neuron_union_max_n() { return kUnionMaxWords * 32; }

@@ -379,7 +379,8 @@ static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H,
 {
     const dim3 grid((unsigned)(Kout / kDownGroupCols * NS)), block(kDownThreads);
     const dim3 rgrid((unsigned)(Kout / kDownWaveCols * mt)), rblock(64);
-    const long items = (long)M * ((cap + kDownBlock - 1) / kDownBlock * kDownBlock / 8);
+    // H == nullptr: H16 already holds the prepared activations
+    const long items = H ? (long)M * ((cap + kDownBlock - 1) / kDownBlock * kDownBlock / 8) : 0;
     if (items > 0)
         hipLaunchKernelGGL((select_gemm_down_prepare_kernel<BF>), dim3((unsigned)((items + kPrepThreads - 1) / kPrepThreads)),
                            dim3(kPrepThreads), 0, st, H, idx, count, H16, M, N, cap);
@@ -408,6 +409,20 @@ static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H,
     return hipGetLastError();
 }
 
+// one pass of at most 64 rows; H == nullptr: H16 is already prepared
+static hipError_t down_pass(const float *H, const uint16_t *W16, const int32_t *idx, const int32_t *count,
+                            float *Y, int rows, int Kout, int N, int cap, polar_dtype dt, void *workspace,
+                            hipStream_t stream)
+{
+    const int mt = down_mt(rows), NS = down_ranges(Kout, cap);
+    float *part = static_cast<float *>(workspace);
+    uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) +
+                                                 down_partial_bytes(rows, Kout, cap));
+    return dt == POLAR_BF16
+               ? launch_down_mt<true>(mt, NS, stream, H, W16, idx, count, Y, part, H16, rows, Kout, N, cap)
+               : launch_down_mt<false>(mt, NS, stream, H, W16, idx, count, Y, part, H16, rows, Kout, N, cap);
+}
+
 hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t *idx, const int32_t *count,
                                    float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
                                    hipStream_t stream)
@@ -417,16 +432,64 @@ hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t
     // passes share the workspace, which the stream's order makes safe)
     for (int m0 = 0; m0 < M; m0 += kDownMaxRows) {
         const int rows = M - m0 < kDownMaxRows ? M - m0 : kDownMaxRows;
-        const int mt = down_mt(rows), NS = down_ranges(Kout, cap);
-        float *part = static_cast<float *>(workspace);
-        uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) +
-                                                     down_partial_bytes(rows, Kout, cap));
-        const float *Hp = H + (size_t)m0 * cap;
-        float *Yp = Y + (size_t)m0 * Kout;
-        const hipError_t e =
-            dt == POLAR_BF16
-                ? launch_down_mt<true>(mt, NS, stream, Hp, W16, idx, count, Yp, part, H16, rows, Kout, N, cap)
-                : launch_down_mt<false>(mt, NS, stream, Hp, W16, idx, count, Yp, part, H16, rows, Kout, N, cap);
+        const hipError_t e = down_pass(H + (size_t)m0 * cap, W16, idx, count, Y + (size_t)m0 * Kout, rows, Kout,
+                                       N, cap, dt, workspace, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Workspace of the two-factor call, three regions that do not overlap: the first factor's partial
+// sums, the second factor's workspace (its partial sums, then the 16-bit hidden activations), and
+// room for the hidden activations as floats, used only where the first factor's evenly split form
+// cannot run.  Each region starts on a multiple of 256 bytes.
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+struct MlpRegions {
+    size_t gemm_bytes, down_offset, hidden_offset, total;
+};
+static MlpRegions mlp_regions(int M, int D, int cap)
+{
+    const int rows = M < kDownMaxRows ? M : kDownMaxRows;
+    MlpRegions r;
+    r.gemm_bytes = select_gemm_workspace_bytes(rows);
+    r.down_offset = align256(r.gemm_bytes);
+    r.hidden_offset = r.down_offset + align256(select_gemm_down_workspace_bytes(rows, D, cap));
+    r.total = r.hidden_offset + align256((size_t)rows * cap * sizeof(float));
+    return r;
+}
+
+size_t sparse_mlp_workspace_bytes(int M, int D, int cap) { return mlp_regions(M, D, cap).total; }
+
+hipError_t launch_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx,
+                             const int32_t *count, float *Y, int M, int D, int N, int cap, polar_dtype dt,
+                             int relu, void *workspace, hipStream_t stream)
+{
+    const MlpRegions r = mlp_regions(M, D, cap);
+    unsigned char *base = static_cast<unsigned char *>(workspace);
+    const uint16_t *X16 = static_cast<const uint16_t *>(X);
+    const uint16_t *W216 = static_cast<const uint16_t *>(W2);
+    // 64 rows of the batch at a time, both factors (larger batches re-read the gathered rows)
+    for (int m0 = 0; m0 < M; m0 += kDownMaxRows) {
+        const int rows = M - m0 < kDownMaxRows ? M - m0 : kDownMaxRows;
+        const uint16_t *Xp = X16 + (size_t)m0 * D;
+        float *Yp = Y + (size_t)m0 * D;
+        void *down_ws = base + r.down_offset;
+        hipError_t e = hipSuccess;
+        if (cap > 0 && select_gemm_h16_applicable(rows, D, cap, r.gemm_bytes)) {
+            // the first factor's reduction writes what the second factor's kernel reads
+            uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(down_ws) +
+                                                         down_partial_bytes(rows, D, cap));
+            e = launch_select_gemm_h16(Xp, W1, idx, count, H16, rows, D, N, cap, dt, relu, base, r.gemm_bytes, stream);
+            if (e != hipSuccess) return e;
+            e = down_pass(nullptr, W216, idx, count, Yp, rows, D, N, cap, dt, down_ws, stream);
+        } else {
+            float *hidden = reinterpret_cast<float *>(base + r.hidden_offset);
+            if (cap > 0) {
+                e = launch_select_gemm(Xp, W1, idx, count, hidden, rows, D, N, cap, dt, relu, stream);
+                if (e != hipSuccess) return e;
+            }
+            e = down_pass(hidden, W216, idx, count, Yp, rows, D, N, cap, dt, down_ws, stream);
+        }
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

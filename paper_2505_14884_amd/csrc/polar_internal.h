@@ -94,11 +94,24 @@ size_t select_gemm_workspace_bytes(int M);
 hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
                                  float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
                                  void *workspace, size_t workspace_bytes, hipStream_t stream);
+// The same product with the output rounded to the storage type and laid out as the second factor's
+// kernel reads it (H16 [M][cap rounded up to 32], zero beyond the live count and for invalid ids),
+// for sizes and a workspace with which the evenly split form can run (ask first).
+bool select_gemm_h16_applicable(int M, int K, int cap, size_t workspace_bytes);
+hipError_t launch_select_gemm_h16(const void *A, const void *W, const int32_t *idx, const int32_t *count,
+                                  uint16_t *H16, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                                  void *workspace, size_t workspace_bytes, hipStream_t stream);
 // Second MLP factor: Y = h16(H) * W2[idx,:] (M <= 64, Kout % 256 == 0; the workspace is required).
 size_t select_gemm_down_workspace_bytes(int M, int Kout, int cap);
 hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t *idx, const int32_t *count,
                                    float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
                                    hipStream_t stream);
+// Both factors in one call: Y = h16(act(X W1[idx,:]^T)) W2[idx,:]; the hidden activations stay in
+// the workspace in 16-bit form (M <= any, D % 256 == 0; the workspace is required).
+size_t sparse_mlp_workspace_bytes(int M, int D, int cap);
+hipError_t launch_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx,
+                             const int32_t *count, float *Y, int M, int D, int N, int cap, polar_dtype dt,
+                             int relu, void *workspace, hipStream_t stream);
 hipError_t launch_read_probe(const void *src, size_t slabs, size_t slab_bytes, int nontemporal,
                              uint32_t *sink, hipStream_t stream);
 hipError_t launch_gather_probe(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices,

@@ -196,6 +196,36 @@ def test_select_gemm_down_argument_errors():
     assert L.polar_select_gemm_down_workspace_bytes(4, 256, 32, None) == EINVAL
 
 
+def test_sparse_mlp_argument_errors():
+    L = binding.lib()
+    A16 = ctypes.c_void_p(0x1000)
+    big = 1 << 32
+    m = lambda X=A16, W1=A16, W2=A16, idx=FAKE, Y=A16, M=4, D=256, N=64, cap=32, dt=0, ws=A16, wsb=big: \
+        L.polar_sparse_mlp(X, W1, W2, idx, None, Y, M, D, N, cap, dt, 1, ws, wsb, None)
+    assert m(M=-1) == EINVAL and m(D=0) == EINVAL and m(N=0) == EINVAL and m(cap=-1) == EINVAL
+    assert m(dt=2) == EINVAL
+    assert m(D=384) == EUNSUPPORTED and m(D=128) == EUNSUPPORTED
+    assert m(X=None) == EINVAL and m(W1=None) == EINVAL and m(W2=None) == EINVAL and m(idx=None) == EINVAL
+    assert m(Y=None) == EINVAL and m(ws=None) == EINVAL
+    assert m(X=ctypes.c_void_p(0x1008)) == EINVAL and m(ws=ctypes.c_void_p(0x1010)) == EINVAL   # 16 and 256 bytes
+    assert m(wsb=4096) == EWORKSPACE
+    assert m(M=0, X=None, W1=None, W2=None, idx=None, Y=None, ws=None) == OK
+    n, g, d = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_size_t(0)
+    q = lambda M, D, cap: L.polar_sparse_mlp_workspace_bytes(M, D, cap, ctypes.byref(n))
+    # three regions, each a multiple of 256 bytes: the first factor's workspace, the second factor's,
+    # and the hidden activations of one pass as floats
+    for (M, D, cap) in [(64, 9216, 36864), (4, 256, 33), (300, 1024, 5000)]:
+        rows = min(M, 64)
+        assert q(M, D, cap) == OK
+        assert L.polar_select_gemm_workspace_bytes(rows, ctypes.byref(g)) == OK
+        assert L.polar_select_gemm_down_workspace_bytes(rows, D, cap, ctypes.byref(d)) == OK
+        up = lambda v: (v + 255) // 256 * 256
+        assert n.value == up(g.value) + up(d.value) + up(rows * cap * 4)
+    assert q(0, 256, 32) == OK and n.value == 0
+    assert q(4, 300, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
+    assert L.polar_sparse_mlp_workspace_bytes(4, 256, 32, None) == EINVAL
+
+
 def test_workspace_size_is_consistent_with_the_chunking():
     L = binding.lib()
     for (B, Hq, Hkv, S, d, k) in [(4, 8, 8, 256, 64, 4), (32, 32, 32, 1920, 128, 16),

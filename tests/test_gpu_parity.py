@@ -686,6 +686,80 @@ def test_sparsified_mlp_both_factors():
     assert torch.isfinite(y).all() and torch.equal(y, again)
 
 
+@contextlib.contextmanager
+def gemm_form(form):
+    """Force the first factor's one-launch kernel ("narrow") or leave the choice to the library (None)."""
+    saved = os.environ.get("POLAR_GEMM_FORM")
+    if form is not None:
+        os.environ["POLAR_GEMM_FORM"] = form
+    try:
+        yield
+    finally:
+        if form is not None:
+            if saved is None:
+                del os.environ["POLAR_GEMM_FORM"]
+            else:
+                os.environ["POLAR_GEMM_FORM"] = saved
+
+
+def mlp_case(M, D, N, idx_host, dtype, count=None, relu=True, seed=0, form=None):
+    """polar_sparse_mlp against the two calls it stands for (bit for bit: same kernels, same order
+    of additions) and against the oracle's two definitions applied one after the other.  The
+    hidden activations are rounded to 16 bits between the factors; where the GPU's float sum and
+    the oracle's double sum fall on different sides of a rounding boundary the hidden value differs
+    by one unit in the last place, which the tolerance allows for a few times per output."""
+    g = torch.Generator(device=DEV).manual_seed(4000 + seed)
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+    X = torch.randn((M, D), generator=g, device=DEV).to(tdt)
+    W1 = (torch.randn((N, D), generator=g, device=DEV) / D ** 0.5).to(tdt)
+    W2 = (torch.randn((N, D), generator=g, device=DEV) / 30.0).to(tdt)
+    cap = len(idx_host)
+    idx = torch.tensor(idx_host, dtype=torch.int32, device=DEV)
+    cnt = None if count is None else torch.tensor([count], dtype=torch.int32, device=DEV)
+    nbytes = polar.sparse_mlp_workspace_bytes(M, D, cap)
+    ws = torch.full((max(nbytes, 256) // 4,), float("nan"), dtype=torch.float32, device=DEV)   # poisoned
+    y = torch.full((M, D), float("nan"), dtype=torch.float32, device=DEV)
+    with gemm_form(form):
+        polar.sparse_mlp(X, W1, W2, idx, count=cnt, relu=relu, out=y, workspace=ws)
+        again = polar.sparse_mlp(X, W1, W2, idx, count=cnt, relu=relu, workspace=ws)
+        hidden = torch.full((M, cap), float("nan"), dtype=torch.float32, device=DEV)
+        for m0 in range(0, M if cap > 0 else 0, 64):        # the one call takes 64 rows at a time
+            rows = min(64, M - m0)
+            polar.select_gemm(X[m0:m0 + rows], W1, idx, count=cnt, relu=relu, out=hidden[m0:m0 + rows],
+                              workspace=polar.alloc_select_gemm_workspace(rows, DEV))
+        two = polar.select_gemm_down(hidden, W2, idx, count=cnt)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y).all()
+    assert torch.equal(y, again) and torch.equal(y, two)
+    live = cap if count is None else max(0, min(count, cap))
+    ids = np.array(idx_host[:live], np.int32)
+    H = orc.select_gemm(host_bits(X), host_bits(W1), ids, dtype, relu)
+    want = orc.select_gemm_down(H.astype(np.float32), host_bits(W2), ids, dtype)
+    ulp = 2.0 ** -10 if dtype == "f16" else 2.0 ** -7
+    tol = GEMM_TOL + 4 * ulp * (np.abs(H).max() if H.size else 0.0) * float(W2.abs().max())
+    err = np.abs(y.cpu().numpy() - want).max()
+    say("   M=%d D=%d N=%d cap=%d live=%d %s relu=%s form=%s: max-abs error %.3e (tolerance %.1e)"
+        % (M, D, N, cap, live, dtype, relu, form, err, tol))
+    assert err <= tol
+
+
+def test_sparse_mlp_one_call():
+    """Both factors in one call, hidden activations kept in 16-bit form in the workspace."""
+    say("\ncase sparse_mlp one call")
+    rng = np.random.default_rng(31)
+    mlp_case(64, 512, 4000, sorted(rng.permutation(4000)[:1500].tolist()), "f16")
+    mlp_case(33, 256, 900, rng.permutation(900)[:333].tolist(), "bf16", seed=1)          # ragged rows, odd count
+    mlp_case(1, 1024, 700, sorted(rng.permutation(700)[:129].tolist()), "f16", seed=2)
+    mlp_case(16, 512, 3000, rng.permutation(3000)[:1000].tolist(), "bf16", count=517, seed=3)
+    mlp_case(48, 256, 600, [5, -1, 7, 600, 9] + list(range(100, 300)), "f16", seed=4)     # ids outside [0, N)
+    mlp_case(20, 256, 500, list(range(64)), "f16", count=0, seed=5)                       # nothing live: zeros
+    mlp_case(24, 512, 500, list(range(200)), "f16", relu=False, seed=6)
+    mlp_case(100, 512, 2000, sorted(rng.permutation(2000)[:700].tolist()), "f16", seed=7)   # two passes of rows
+    mlp_case(150, 256, 1000, rng.permutation(1000)[:400].tolist(), "bf16", count=390, seed=8)
+    mlp_case(40, 512, 2000, sorted(rng.permutation(2000)[:900].tolist()), "f16", seed=9, form="narrow")   # one-launch first factor
+    mlp_case(8, 256, 300, [], "f16", seed=10)                                             # cap = 0
+
+
 def test_hip_graph_replays_of_the_sparsified_mlp_match_eager():
     """Neuron index -> first factor -> second factor recorded into one HIP graph: the live count
     never leaves the device, so one recording serves whatever ids the requests predict; every
