@@ -763,7 +763,8 @@ def test_sparse_mlp_one_call():
 def test_hip_graph_replays_of_the_sparsified_mlp_match_eager():
     """Neuron index -> first factor -> second factor recorded into one HIP graph: the live count
     never leaves the device, so one recording serves whatever ids the requests predict; every
-    replay, with eager work in between, equals the eager result bit for bit."""
+    replay, with eager work in between, equals the eager result bit for bit.  A second graph holds
+    the index and the one-call form of both factors."""
     B, K, N, kn = 24, 512, 3000, 90
     say("\ncase sparsified MLP graph", B, K, N, kn)
     g = torch.Generator(device=DEV).manual_seed(77)
@@ -775,6 +776,7 @@ def test_hip_graph_replays_of_the_sparsified_mlp_match_eager():
     ws_union = torch.empty(max(polar.neuron_union_workspace_bytes(B, kn, N), 4), dtype=torch.uint8, device=DEV)
     ws_up = polar.alloc_select_gemm_workspace(B, DEV)
     ws_down = torch.empty(polar.select_gemm_down_workspace_bytes(B, K, cap), dtype=torch.uint8, device=DEV)
+    ws_mlp = torch.empty(polar.sparse_mlp_workspace_bytes(B, K, cap), dtype=torch.uint8, device=DEV)
 
     def bufs():
         return (torch.full((cap,), -1, dtype=torch.int32, device=DEV), torch.zeros(1, dtype=torch.int32, device=DEV),
@@ -785,16 +787,23 @@ def test_hip_graph_replays_of_the_sparsified_mlp_match_eager():
         polar.select_gemm(x, W1, idx, count=count, relu=True, out=hidden, workspace=ws_up)
         polar.select_gemm_down(hidden, W2, idx, count=count, out=y, workspace=ws_down)
 
-    rec = bufs()
+    def one_call_step(idx, count, hidden, y):
+        polar.neuron_union(topk, N, workspace=ws_union, out=(idx, count))
+        polar.sparse_mlp(x, W1, W2, idx, count=count, relu=True, out=y, workspace=ws_mlp)
+
+    rec, rec1 = bufs(), bufs()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):                      # warm-up outside the capture
         step(*rec)
+        one_call_step(*rec1)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
+    graph, graph1 = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         step(*rec)
+    with torch.cuda.graph(graph1):
+        one_call_step(*rec1)
     for rep in range(4):
         # other ids (and with them another live count) and other activations every time
         hot = max(kn, N // (rep + 2))
@@ -804,12 +813,15 @@ def test_hip_graph_replays_of_the_sparsified_mlp_match_eager():
         step(*eager)
         torch.cuda.synchronize()
         rec[3].fill_(float("nan"))
+        rec1[3].fill_(float("nan"))
         graph.replay()
+        graph1.replay()
         torch.cuda.synchronize()
         c = int(eager[1].item())
         assert int(rec[1].item()) == c and torch.equal(rec[0][:c], eager[0][:c]), "replay %d: index" % rep
         assert torch.equal(rec[2][:, :c], eager[2][:, :c]), "replay %d: first factor" % rep
         assert torch.equal(rec[3].view(torch.int32), eager[3].view(torch.int32)), "replay %d: second factor" % rep
+        assert torch.equal(rec1[3].view(torch.int32), eager[3].view(torch.int32)), "replay %d: one call" % rep
     S = orc.neuron_union(topk.cpu().numpy(), N)
     assert c == len(S)
     hid = orc.select_gemm(host_bits(x), host_bits(W1), S, "f16", True)
