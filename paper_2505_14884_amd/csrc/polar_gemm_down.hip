@@ -324,12 +324,21 @@ __global__ __launch_bounds__(64) void select_gemm_down_reduce_kernel(const float
     f32x4 sum[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) sum[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < NS; ++s) {
-        f32x4 v[8];
+    // four ranges' loads in flight at a time (one range per round trip would make the kernel a chain
+    // of NS memory latencies); the additions stay in ascending range order
+    for (int s0 = 0; s0 < NS; s0 += 4) {
+        f32x4 v[4][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = src[(size_t)s * per_range + e * 64];
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sum[e] += v[e];
+            for (int e = 0; e < 8; ++e)
+                v[q][e] = s0 + q < NS ? src[(size_t)(s0 + q) * per_range + e * 64] : (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (s0 + q < NS) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sum[e] += v[q][e];
+            }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
