@@ -94,8 +94,8 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
     L = polar.binding.lib()
     st = lambda: torch.cuda.current_stream().cuda_stream
 
-    workspace = polar.alloc_select_gemm_workspace(w.B, dev) if args.gemm_form == "wide" else None
-    wide = workspace is not None
+    wide = args.gemm_form == "wide"
+    workspace = polar.alloc_select_gemm_workspace(w.B, dev) if wide else None    # None beyond 128 rows
     union_ws = None
     if wide:
         nbytes = polar.neuron_union_workspace_bytes(w.B, topk.shape[1], w.N)
@@ -218,7 +218,7 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                           "avg_us": round(down_ms * 1e3, 2)},
         "dense_over_selective": None if args.no_dense else round(dense_ms / gemm_ms, 3),
         "ideal_N_over_selected": round(w.N / max(n_sel, 1), 3),
-        "roofline": {"kernel": "select_gemm_stream_kernel + select_gemm_reduce_kernel" if wide else "select_gemm_kernel",
+        "roofline": {"kernel": "select_gemm_stream_kernel + select_gemm_reduce_kernel" if workspace is not None else "select_gemm_kernel",
                      "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "avg_us": round(gemm_ms * 1e3, 2),

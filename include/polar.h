@@ -300,10 +300,11 @@ int polar_select_gemm_down(const float *Hact, const void *W2, const int32_t *idx
  *               polar_sparse_mlp_workspace_bytes(M, D, cap) bytes (else POLAR_EWORKSPACE);
  *               contents are overwritten; calls that overlap in time need separate workspaces
  *
- * D a multiple of 256, else POLAR_EUNSUPPORTED.  Four launches per 64 rows of the batch (M > 64
- * is processed 64 rows at a time); where the first factor's evenly split form cannot run (see
- * polar_select_gemm_ws) its one-launch kernel and the conversion launch take its place, with
- * the same result.  X, W1 and idx may be NULL when cap == 0.
+ * D a multiple of 256, else POLAR_EUNSUPPORTED.  Four launches for up to 64 rows; larger batches
+ * go through in passes (the first factor takes up to 128 rows of the batch per pass, the second
+ * 64) that re-read the gathered rows.  Where the first factor's evenly split form cannot run
+ * (see polar_select_gemm_ws) its one-launch kernel and the conversion launch take its place,
+ * with the same result.  X, W1 and idx may be NULL when cap == 0.
  */
 int polar_sparse_mlp_workspace_bytes(int M, int D, int cap, size_t *bytes);
 int polar_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx, const int32_t *count,

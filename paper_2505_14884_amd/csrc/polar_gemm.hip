@@ -820,6 +820,8 @@ static size_t stream_slot_bytes(int mt) { return (size_t)2 * kStreamWaves * mt *
 constexpr int kStreamMaxRows = 128;              // rows of the batch the evenly split form takes
 static int stream_mt(int M) { return M <= 16 ? 1 : (M <= 32 ? 2 : (M <= 64 ? 4 : 8)); }
 
+int select_gemm_ws_max_rows() { return kStreamMaxRows; }
+
 size_t select_gemm_workspace_bytes(int M)
 {
     return M > kStreamMaxRows ? 0 : (size_t)kStreamGrid * stream_slot_bytes(stream_mt(M));

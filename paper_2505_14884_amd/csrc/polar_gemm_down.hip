@@ -420,13 +420,10 @@ static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H,
 
 // one pass of at most 64 rows; H == nullptr: H16 is already prepared
 static hipError_t down_pass(const float *H, const uint16_t *W16, const int32_t *idx, const int32_t *count,
-                            float *Y, int rows, int Kout, int N, int cap, polar_dtype dt, void *workspace,
-                            hipStream_t stream)
+                            float *Y, int rows, int Kout, int N, int cap, polar_dtype dt, float *part,
+                            uint16_t *H16, hipStream_t stream)
 {
     const int mt = down_mt(rows), NS = down_ranges(Kout, cap);
-    float *part = static_cast<float *>(workspace);
-    uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) +
-                                                 down_partial_bytes(rows, Kout, cap));
     return dt == POLAR_BF16
                ? launch_down_mt<true>(mt, NS, stream, H, W16, idx, count, Y, part, H16, rows, Kout, N, cap)
                : launch_down_mt<false>(mt, NS, stream, H, W16, idx, count, Y, part, H16, rows, Kout, N, cap);
@@ -441,29 +438,36 @@ hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t
     // passes share the workspace, which the stream's order makes safe)
     for (int m0 = 0; m0 < M; m0 += kDownMaxRows) {
         const int rows = M - m0 < kDownMaxRows ? M - m0 : kDownMaxRows;
+        float *part = static_cast<float *>(workspace);
+        uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) +
+                                                     down_partial_bytes(rows, Kout, cap));
         const hipError_t e = down_pass(H + (size_t)m0 * cap, W16, idx, count, Y + (size_t)m0 * Kout, rows, Kout,
-                                       N, cap, dt, workspace, stream);
+                                       N, cap, dt, part, H16, stream);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-// Workspace of the two-factor call, three regions that do not overlap: the first factor's partial
-// sums, the second factor's workspace (its partial sums, then the 16-bit hidden activations), and
-// room for the hidden activations as floats, used only where the first factor's evenly split form
-// cannot run.  Each region starts on a multiple of 256 bytes.
+// Workspace of the two-factor call, four regions that do not overlap: the first factor's partial
+// sums, the second factor's partial sums, the 16-bit hidden activations of one pass of the first
+// factor, and room for the hidden activations of 64 rows as floats, used only where the first
+// factor's evenly split form cannot run.  Each region starts on a multiple of 256 bytes.
 static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 struct MlpRegions {
-    size_t gemm_bytes, down_offset, hidden_offset, total;
+    int up_rows;                                 // rows of the batch one pass of the first factor takes
+    size_t gemm_bytes, down_offset, h16_offset, hidden_offset, total;
 };
 static MlpRegions mlp_regions(int M, int D, int cap)
 {
-    const int rows = M < kDownMaxRows ? M : kDownMaxRows;
+    const int down_rows = M < kDownMaxRows ? M : kDownMaxRows;
+    const size_t cap32 = ((size_t)cap + kDownBlock - 1) / kDownBlock * kDownBlock;
     MlpRegions r;
-    r.gemm_bytes = select_gemm_workspace_bytes(rows);
+    r.up_rows = M < select_gemm_ws_max_rows() ? M : select_gemm_ws_max_rows();
+    r.gemm_bytes = select_gemm_workspace_bytes(r.up_rows);
     r.down_offset = align256(r.gemm_bytes);
-    r.hidden_offset = r.down_offset + align256(select_gemm_down_workspace_bytes(rows, D, cap));
-    r.total = r.hidden_offset + align256((size_t)rows * cap * sizeof(float));
+    r.h16_offset = r.down_offset + align256(down_partial_bytes(down_rows, D, cap));
+    r.hidden_offset = r.h16_offset + align256((size_t)r.up_rows * cap32 * sizeof(uint16_t));
+    r.total = r.hidden_offset + align256((size_t)down_rows * cap * sizeof(float));
     return r;
 }
 
@@ -475,31 +479,39 @@ hipError_t launch_sparse_mlp(const void *X, const void *W1, const void *W2, cons
 {
     const MlpRegions r = mlp_regions(M, D, cap);
     unsigned char *base = static_cast<unsigned char *>(workspace);
+    float *part = reinterpret_cast<float *>(base + r.down_offset);
+    uint16_t *H16 = reinterpret_cast<uint16_t *>(base + r.h16_offset);
+    float *hidden = reinterpret_cast<float *>(base + r.hidden_offset);
+    const size_t cap32 = ((size_t)cap + kDownBlock - 1) / kDownBlock * kDownBlock;
     const uint16_t *X16 = static_cast<const uint16_t *>(X);
     const uint16_t *W216 = static_cast<const uint16_t *>(W2);
-    // 64 rows of the batch at a time, both factors (larger batches re-read the gathered rows)
-    for (int m0 = 0; m0 < M; m0 += kDownMaxRows) {
-        const int rows = M - m0 < kDownMaxRows ? M - m0 : kDownMaxRows;
-        const uint16_t *Xp = X16 + (size_t)m0 * D;
-        float *Yp = Y + (size_t)m0 * D;
-        void *down_ws = base + r.down_offset;
-        hipError_t e = hipSuccess;
-        if (cap > 0 && select_gemm_h16_applicable(rows, D, cap, r.gemm_bytes)) {
-            // the first factor's reduction writes what the second factor's kernel reads
-            uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(down_ws) +
-                                                         down_partial_bytes(rows, D, cap));
-            e = launch_select_gemm_h16(Xp, W1, idx, count, H16, rows, D, N, cap, dt, relu, base, r.gemm_bytes, stream);
+    // The first factor takes up to 128 rows of the batch at a time, the second 64 (larger batches
+    // re-read the gathered rows).
+    for (int m0 = 0; m0 < M; m0 += r.up_rows) {
+        const int rows = M - m0 < r.up_rows ? M - m0 : r.up_rows;
+        // its reduction writes what the second factor's kernel reads
+        const bool fused = cap > 0 && select_gemm_h16_applicable(rows, D, cap, r.gemm_bytes);
+        if (fused) {
+            const hipError_t e = launch_select_gemm_h16(X16 + (size_t)m0 * D, W1, idx, count, H16, rows, D, N, cap,
+                                                        dt, relu, base, r.gemm_bytes, stream);
             if (e != hipSuccess) return e;
-            e = down_pass(nullptr, W216, idx, count, Yp, rows, D, N, cap, dt, down_ws, stream);
-        } else {
-            float *hidden = reinterpret_cast<float *>(base + r.hidden_offset);
-            if (cap > 0) {
-                e = launch_select_gemm(Xp, W1, idx, count, hidden, rows, D, N, cap, dt, relu, stream);
-                if (e != hipSuccess) return e;
-            }
-            e = down_pass(hidden, W216, idx, count, Yp, rows, D, N, cap, dt, down_ws, stream);
         }
-        if (e != hipSuccess) return e;
+        for (int r0 = 0; r0 < rows; r0 += kDownMaxRows) {
+            const int drows = rows - r0 < kDownMaxRows ? rows - r0 : kDownMaxRows;
+            float *Yp = Y + (size_t)(m0 + r0) * D;
+            hipError_t e = hipSuccess;
+            if (fused) {
+                e = down_pass(nullptr, W216, idx, count, Yp, drows, D, N, cap, dt, part, H16 + (size_t)r0 * cap32, stream);
+            } else {
+                if (cap > 0) {
+                    e = launch_select_gemm(X16 + (size_t)(m0 + r0) * D, W1, idx, count, hidden, drows, D, N, cap, dt,
+                                           relu, stream);
+                    if (e != hipSuccess) return e;
+                }
+                e = down_pass(hidden, W216, idx, count, Yp, drows, D, N, cap, dt, part, H16, stream);
+            }
+            if (e != hipSuccess) return e;
+        }
     }
     return hipSuccess;
 }

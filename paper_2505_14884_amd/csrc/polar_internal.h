@@ -91,6 +91,7 @@ hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, 
 // Wide-tile form (M <= 128, workspace of select_gemm_workspace_bytes(M) bytes or less; falls back to
 // the form above when the workspace is absent or M is larger).
 size_t select_gemm_workspace_bytes(int M);
+int select_gemm_ws_max_rows();                   // rows of the batch the wide-tile form takes in one pass
 hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
                                  float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
                                  void *workspace, size_t workspace_bytes, hipStream_t stream);
@@ -107,7 +108,7 @@ hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t
                                    float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
                                    hipStream_t stream);
 // Both factors in one call: Y = h16(act(X W1[idx,:]^T)) W2[idx,:]; the hidden activations stay in
-// the workspace in 16-bit form (M <= any, D % 256 == 0; the workspace is required).
+// the workspace in 16-bit form (D % 256 == 0; the workspace is required).
 size_t sparse_mlp_workspace_bytes(int M, int D, int cap);
 hipError_t launch_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx,
                              const int32_t *count, float *Y, int M, int D, int N, int cap, polar_dtype dt,

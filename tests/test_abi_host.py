@@ -212,15 +212,17 @@ def test_sparse_mlp_argument_errors():
     assert m(M=0, X=None, W1=None, W2=None, idx=None, Y=None, ws=None) == OK
     n, g, d = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_size_t(0)
     q = lambda M, D, cap: L.polar_sparse_mlp_workspace_bytes(M, D, cap, ctypes.byref(n))
-    # three regions, each a multiple of 256 bytes: the first factor's workspace, the second factor's,
-    # and the hidden activations of one pass as floats
-    for (M, D, cap) in [(64, 9216, 36864), (4, 256, 33), (300, 1024, 5000)]:
-        rows = min(M, 64)
+    # four regions, each a multiple of 256 bytes: the first factor's workspace (up to 128 rows a pass),
+    # the second factor's partial sums (64 rows a pass), the 16-bit hidden activations of one pass of the
+    # first factor, and the hidden activations of 64 rows as floats (the fallback's)
+    for (M, D, cap) in [(64, 9216, 36864), (4, 256, 33), (100, 512, 700), (300, 1024, 5000)]:
+        up_rows, down_rows, cap32 = min(M, 128), min(M, 64), (cap + 31) // 32 * 32
         assert q(M, D, cap) == OK
-        assert L.polar_select_gemm_workspace_bytes(rows, ctypes.byref(g)) == OK
-        assert L.polar_select_gemm_down_workspace_bytes(rows, D, cap, ctypes.byref(d)) == OK
+        assert L.polar_select_gemm_workspace_bytes(up_rows, ctypes.byref(g)) == OK
+        assert L.polar_select_gemm_down_workspace_bytes(down_rows, D, cap, ctypes.byref(d)) == OK
+        partial = d.value - down_rows * cap32 * 2
         up = lambda v: (v + 255) // 256 * 256
-        assert n.value == up(g.value) + up(d.value) + up(rows * cap * 4)
+        assert n.value == up(g.value) + up(partial) + up(up_rows * cap32 * 2) + up(down_rows * cap * 4)
     assert q(0, 256, 32) == OK and n.value == 0
     assert q(4, 300, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
     assert L.polar_sparse_mlp_workspace_bytes(4, 256, 32, None) == EINVAL
