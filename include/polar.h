@@ -225,18 +225,18 @@ int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const in
 
 /*
  * The same operation with a workspace (Appendix "Sparse Kernels", Algorithm 3; same arguments,
- * same result up to the order of the float additions).  For M <= 128 the library then runs a
- * form built for decode batches: 128-neuron tiles and a fixed-size launch whose workgroups
- * split the (neuron tile, K block) work evenly whatever the live count is, followed by a
- * small kernel that adds the pieces of each tile in a fixed order (two launches; results are
- * reproducible for given sizes, count and workspace size).  For larger M, with workspace NULL,
- * with K not a multiple of 256 or with cap beyond 196608 it runs the kernel of
- * polar_select_gemm.
+ * same result up to the order of the float additions).  The library then runs a form built for
+ * decode batches: 128-neuron tiles and a fixed-size launch whose workgroups split the (neuron
+ * tile, K block) work evenly whatever the live count is, followed by a small kernel that adds
+ * the pieces of each tile in a fixed order (two launches per 128 rows of the batch: M > 128 is
+ * processed 128 rows at a time; results are reproducible for given sizes, count and workspace
+ * size).  With workspace NULL, with K not a multiple of 256 or with cap beyond 196608 it runs
+ * the kernel of polar_select_gemm.
  *   workspace        scratch, DEVICE pointer, 16-byte aligned, caller-owned; contents are
  *                    overwritten; calls that overlap in time need separate workspaces
  *   workspace_bytes  its size; polar_select_gemm_workspace_bytes(M) gives the size at which
- *                    the launch is as wide as the library wants it (0 for M > 128); a smaller
- *                    workspace narrows the launch, it is not an error
+ *                    the launch is as wide as the library wants it (it grows with M up to
+ *                    128 rows); a smaller workspace narrows the launch, it is not an error
  */
 int polar_select_gemm_workspace_bytes(int M, size_t *bytes);
 int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,

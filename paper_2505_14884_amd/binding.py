@@ -290,7 +290,7 @@ def head_norm_topk(attn_out: torch.Tensor, Hkv: int, k: int,
 
 
 def select_gemm_workspace_bytes(M: int) -> int:
-    """Workspace size at which polar_select_gemm_ws launches as wide as it wants (0 for M > 128)."""
+    """Workspace size at which polar_select_gemm_ws launches as wide as it wants."""
     n = ctypes.c_size_t(0)
     _check(lib().polar_select_gemm_workspace_bytes(M, ctypes.byref(n)), "polar_select_gemm_workspace_bytes")
     return int(n.value)

@@ -11,7 +11,7 @@
 // far below the ~300 flop/byte ridge of the part, but above what the vector ALUs sustain at
 // HBM speed, so the contraction runs on MFMA (v_mfma_f32_16x16x32) while the kernel is
 // organised around streaming the gathered rows.  Two forms: the one-launch kernel described
-// here, and, further down, an evenly split form for M <= 128 that needs a workspace and is faster:
+// here, and, further down, an evenly split form that needs a workspace and is faster:
 //   * a workgroup owns 32 selected neurons and walks K in blocks of 128 values; per block it
 //     loads its 32 x 256-byte row pieces with fully coalesced 16-byte loads (16 lanes per
 //     piece), parks them in LDS (padded rows, conflict-free 16-byte reads) and every wave
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Evenly split form for M <= 128 with a caller-supplied workspace.
+// Evenly split form with a caller-supplied workspace (up to 128 rows of the batch per pass).
 //
 // In the kernel above the number of workgroups follows the live count, which the host does not
 // know (it stays on the device): at a 29 % union 332 workgroups land on 256 compute units, one
@@ -824,7 +824,7 @@ int select_gemm_ws_max_rows() { return kStreamMaxRows; }
 
 size_t select_gemm_workspace_bytes(int M)
 {
-    return M > kStreamMaxRows ? 0 : (size_t)kStreamGrid * stream_slot_bytes(stream_mt(M));
+    return (size_t)kStreamGrid * stream_slot_bytes(stream_mt(M < kStreamMaxRows ? M : kStreamMaxRows));
 }
 
 template <bool BF>
@@ -889,9 +889,19 @@ hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *id
                                  float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
                                  void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    const int G = stream_grid(M, K, cap, workspace != nullptr, workspace_bytes);
-    if (G < 1) return launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu, stream);
-    return launch_stream(G, A, W, idx, count, C, nullptr, M, K, N, cap, dt, relu, workspace, stream);
+    // batches beyond 128 rows are processed 128 rows at a time (the gathered rows are re-read; the
+    // passes share the workspace, which the stream's order makes safe)
+    for (int m0 = 0; m0 < M; m0 += kStreamMaxRows) {
+        const int rows = M - m0 < kStreamMaxRows ? M - m0 : kStreamMaxRows;
+        const uint16_t *Ap = static_cast<const uint16_t *>(A) + (size_t)m0 * K;
+        float *Cp = C + (size_t)m0 * cap;
+        const int G = stream_grid(rows, K, cap, workspace != nullptr, workspace_bytes);
+        const hipError_t e =
+            G < 1 ? launch_select_gemm(Ap, W, idx, count, Cp, rows, K, N, cap, dt, relu, stream)
+                  : launch_stream(G, Ap, W, idx, count, Cp, nullptr, rows, K, N, cap, dt, relu, workspace, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 bool select_gemm_h16_applicable(int M, int K, int cap, size_t workspace_bytes)

@@ -88,8 +88,8 @@ hipError_t launch_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, 
 hipError_t launch_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
                               float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
                               hipStream_t stream);
-// Wide-tile form (M <= 128, workspace of select_gemm_workspace_bytes(M) bytes or less; falls back to
-// the form above when the workspace is absent or M is larger).
+// Wide-tile form (workspace of select_gemm_workspace_bytes(M) bytes or less; up to 128 rows of the
+// batch per pass; falls back to the form above when the workspace is absent).
 size_t select_gemm_workspace_bytes(int M);
 int select_gemm_ws_max_rows();                   // rows of the batch the wide-tile form takes in one pass
 hipError_t launch_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,

@@ -465,8 +465,8 @@ def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0, ws=False, G=No
     workspace = None
     if ws:
         nbytes = polar.select_gemm_workspace_bytes(M) if ws_bytes is None else ws_bytes
-        # poisoned: the kernels must write every slot they later read; a zero-size recommendation
-        # (M > 128) still goes through the workspace entry point with a token buffer
+        # poisoned: the kernels must write every slot they later read; a zero-size request still
+        # goes through the workspace entry point, with a token buffer
         workspace = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=DEV)
     with gemm_workgroups(G):
         polar.select_gemm(A, W, idx, count=cnt, relu=relu, out=out, workspace=workspace)
@@ -514,7 +514,7 @@ def test_select_gemm_small_workspace_narrows_the_launch():
     rng = np.random.default_rng(78)
     idx = rng.permutation(700)[:300].tolist()
     full = polar.select_gemm_workspace_bytes(64)
-    assert full > 0 and polar.select_gemm_workspace_bytes(129) == 0
+    assert full > 0 and polar.select_gemm_workspace_bytes(300) == polar.select_gemm_workspace_bytes(128) == 2 * full
     one = 2 * 8 * 4 * 64 * 16          # a workgroup's two slots: 8 waves x 4 accumulator tiles x 64 lanes x 16 B
     assert full % one == 0
     for nbytes in (one, 3 * one, one - 16, 0):             # launch of 1 workgroup, of 3, narrow kernel, narrow kernel
