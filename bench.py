@@ -55,6 +55,8 @@ def parse_args():
     ap.add_argument("--cpu-sample", type=int, default=0,
                     help="requests the oracle is timed on (0: the whole batch, capped so that the "
                          "host copy of their K and V stays under 12 GB)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the timing of the step replayed from a HIP graph")
     ap.add_argument("--kv-layout", choices=["bhsd", "bshd"], default="bhsd",
                     help="cache layout: [B,Hkv,S,d] (default) or the sequence-major [B,S,Hkv,d]")
     ap.add_argument("--mlp-workload", default="M2_opt66b_ffn",
@@ -395,6 +397,33 @@ def main():
         dense_avg, _, _ = event_time(dense_step, max(5, n_ev // 4))
     achieved = bytes_sel / (part_avg * 1e-3) / 1e9
 
+    # The same step recorded into a HIP graph and replayed (Section 5: the paper runs its router
+    # and kernels under CUDA graphs).  A decode step of a model replays one graph that holds all
+    # its layers, so the figure is the time per layer of a graph of kGraphLayers consecutive
+    # steps (each on the next cache copy); a graph of one step is timed too.
+    kGraphLayers = 8
+    graph_avg = graph1_avg = float("nan")
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)                                   # warm-up outside any capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        layers_graph, one_graph = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(layers_graph):
+            for i in range(kGraphLayers):
+                step(i)
+        with torch.cuda.graph(one_graph):
+            step(0)
+        for _ in range(2):
+            layers_graph.replay()
+            one_graph.replay()
+        torch.cuda.synchronize()
+        n_rep = max(3, n_ev // kGraphLayers)
+        graph_avg = event_time(lambda i: layers_graph.replay(), n_rep)[0] / kGraphLayers
+        graph1_avg = event_time(lambda i: one_graph.replay(), n_ev)[0]
+
     # Read-only yardstick over the same K cache with the streaming kernel's launch shape: what this
     # GPU gives a kernel that does nothing but read, with non-temporal and with plain loads.
     slab = w.S * w.d * 2          # bytes of one head's rows; the probe reads contiguous slabs of that size
@@ -437,6 +466,8 @@ def main():
             "router_topk": round(router_avg * 1e3, 2),
             "sha_decode": round(sha_avg * 1e3, 2),
             "streaming_kernel": round(part_avg * 1e3, 2),
+            "step_in_hip_graph_of_8_layers": None if args.no_graph else round(graph_avg * 1e3, 2),
+            "step_in_hip_graph_of_1_layer": None if args.no_graph else round(graph1_avg * 1e3, 2),
             "dense_k_eq_H": None if args.no_dense else round(dense_avg * 1e3, 2),
         },
         "dense_over_selective": None if args.no_dense else round(dense_avg / sha_avg, 3),
