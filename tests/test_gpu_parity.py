@@ -662,7 +662,7 @@ def test_select_gemm_down_ids_counts_and_long_contraction():
 
 def test_sparsified_mlp_both_factors():
     """Union -> first factor -> second factor on one stream, no host round trip, against the
-    oracle on sampled output columns (OPT-66B FFN shape)."""
+    oracle on sampled output columns (OPT-66B FFN shape); the one-call form gives the same bits."""
     w = wl.MLP_CONFIGS["M2_opt66b_ffn"]
     say("\ncase both factors", w)
     x, W1, topk = wl.make_mlp_inputs(w, DEV)
@@ -673,7 +673,9 @@ def test_sparsified_mlp_both_factors():
                                workspace=polar.alloc_select_gemm_workspace(w.B, DEV))
     y = polar.select_gemm_down(hidden, W2, idx, count=count)
     again = polar.select_gemm_down(hidden, W2, idx, count=count)
+    one_call = polar.sparse_mlp(x, W1, W2, idx, count=count, relu=True)
     torch.cuda.synchronize()
+    assert torch.equal(y, one_call), "both factors in one call, at the size the bench times"
     c = int(count.item())
     cols = np.unique(np.linspace(0, w.K - 1, num=48).astype(np.int64))
     S = idx[:c].long()
