@@ -275,36 +275,56 @@ __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
 #undef POLAR_DOWN_MULTIPLY
 #undef POLAR_DOWN_FETCH
 
-    // The waves of a column block add their sums through LDS in a fixed order, a pair at a time
-    // (the buffer holds one wave's accumulators per column block): (p0 + p2) + (p1 + p3);
-    // parity 0 stores the range's sums.
-    f32x4 *sh_acc = reinterpret_cast<f32x4 *>(smem) + (size_t)cw * MT * 8 * 64 + lane;
-    auto hand_over = [&](int from, int to) {
-        __syncthreads();                         // the buffer (first: the activations) is no longer read
-        if (parity == from) {
+    // The four waves of a column block add their sums through LDS, (p0 + p2) + (p1 + p3), in two
+    // rounds: parities 2 and 3 hand theirs to 0 and 1; then 0 and 1 exchange halves (1 gives its
+    // tiles e < 4, 0 its tiles e >= 4), so that each finishes and stores one half of the range's
+    // sums.  (Addition commutes, so both halves carry the sum in the order above.)  A region
+    // holds one wave's accumulators; there are two per column block.
+    constexpr int kRegion = MT * 8 * 64;         // f32x4 entries
+    f32x4 *region0 = reinterpret_cast<f32x4 *>(smem) + (size_t)(cw * 2 + 0) * kRegion + lane;
+    f32x4 *region1 = reinterpret_cast<f32x4 *>(smem) + (size_t)(cw * 2 + 1) * kRegion + lane;
+    __syncthreads();                             // the activation chunks are no longer read
+    if (parity >= 2) {
+        f32x4 *to = parity == 2 ? region0 : region1;
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) sh_acc[(t * 8 + e) * 64] = acc[t][e];
-        }
-        __syncthreads();
-        if (parity == to) {
+            for (int e = 0; e < 8; ++e) to[(t * 8 + e) * 64] = acc[t][e];
+    }
+    __syncthreads();
+    if (parity < 2) {
+        const f32x4 *from = parity == 0 ? region0 : region1;
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[t][e] += sh_acc[(t * 8 + e) * 64];
-        }
-    };
-    hand_over(3, 1);
-    hand_over(2, 0);
-    hand_over(1, 0);
-    if (parity == 0) {
+            for (int e = 0; e < 8; ++e) acc[t][e] += from[(t * 8 + e) * 64];
+    }
+    __syncthreads();                             // both regions have been read
+    if (parity == 1) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) region0[(t * 8 + e) * 64] = acc[t][e];
+    } else if (parity == 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 4; e < 8; ++e) region1[(t * 8 + e) * 64] = acc[t][e];
+    }
+    __syncthreads();
+    if (parity < 2) {
+        const f32x4 *from = parity == 0 ? region0 : region1;
+        const int e0 = parity == 0 ? 0 : 4;      // the half this wave finishes
         f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
                      ((size_t)s * (Kout / kDownWaveCols) + (size_t)cg * 2 + cw) * (MT * 8) * 64 + lane;
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dst[(t * 8 + e) * 64] = acc[t][e];
+            for (int e = 0; e < 4; ++e) {
+                // parity 0: (p0 + p2) + (p1 + p3); parity 1: (p1 + p3) + (p0 + p2), the same sum
+                const f32x4 other = from[(t * 8 + e0 + e) * 64];
+                dst[(t * 8 + e0 + e) * 64] = parity == 0 ? acc[t][e0 + e] + other : other + acc[t][e0 + e];
+            }
     }
 }
 
@@ -394,7 +414,9 @@ static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H,
         hipLaunchKernelGGL((select_gemm_down_prepare_kernel<BF>), dim3((unsigned)((items + kPrepThreads - 1) / kPrepThreads)),
                            dim3(kPrepThreads), 0, st, H, idx, count, H16, M, N, cap);
     // dynamic LDS: two activation chunks and the ids of a range; above 64 KB it has to be granted
-    const size_t lds = (size_t)2 * 16 * mt * kChunkPitch + (size_t)kDownMaxIds * sizeof(int);
+    size_t lds = (size_t)2 * 16 * mt * kChunkPitch + (size_t)kDownMaxIds * sizeof(int);
+    const size_t regions = (size_t)4 * mt * 8 * 64 * sizeof(f32x4);      // the epilogue's exchange buffers
+    if (lds < regions) lds = regions;
     static LdsGrant granted[3];                  // one set per instantiation of this launcher
     const void *kernels[3] = {reinterpret_cast<const void *>(select_gemm_down_kernel<BF, 1>),
                               reinterpret_cast<const void *>(select_gemm_down_kernel<BF, 2>),
