@@ -762,6 +762,24 @@ def test_sparse_mlp_one_call():
     mlp_case(8, 256, 300, [], "f16", seed=10)                                             # cap = 0
 
 
+def test_sparse_mlp_random_shapes():
+    """Seeded random batch sizes, widths, capacities, live counts and id lists (repeats and ids
+    outside [0, N) included) through the one-call form, the two calls and the oracle."""
+    say("\ncase sparse_mlp random shapes")
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        M = int(rng.choice([1, 2, 7, 16, 17, 31, 32, 48, 64, 65, 90, 128, 129, 200]))
+        D = int(rng.choice([256, 512, 768, 1024]))
+        N = int(rng.integers(40, 3000))
+        cap = int(rng.integers(1, min(N, 1200) + 1))
+        ids = rng.integers(-2, N + 2, size=cap)                  # a few invalid ones at either end
+        if case % 3 == 0:
+            ids = np.sort(ids)
+        count = None if case % 4 == 0 else int(rng.integers(0, cap + 40))
+        mlp_case(M, D, N, ids.tolist(), "f16" if case % 2 == 0 else "bf16", count=count, relu=case % 5 != 0,
+                 seed=100 + case)
+
+
 def test_hip_graph_replays_of_the_sparsified_mlp_match_eager():
     """Neuron index -> first factor -> second factor recorded into one HIP graph: the live count
     never leaves the device, so one recording serves whatever ids the requests predict; every
