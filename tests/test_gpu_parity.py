@@ -521,6 +521,20 @@ def test_select_gemm_small_workspace_narrows_the_launch():
         gemm_case(64, 1024, 700, idx, "f16", relu=True, seed=6, ws=True, ws_bytes=nbytes)
 
 
+def test_select_gemm_capacity_at_and_beyond_the_even_split_limit():
+    """The evenly split form keeps the row ids of at most 8 tiles per span in LDS: with 256
+    workgroups that holds up to 1536 tiles (196608 ids).  At the limit every span touches 6 to 8
+    tiles; one tile more and the workspace call runs the one-launch kernel instead, as does the
+    one-call MLP (with the conversion launch)."""
+    say("\ncase select_gemm capacity limit")
+    rng = np.random.default_rng(5)
+    N = 200100
+    for cap in (196608, 196608 + 128):
+        idx = rng.permutation(N)[:cap].tolist()
+        say("   cap", cap, "err %.2e" % gemm_case(3, 256, N, idx, "f16", relu=True, seed=cap % 1000, ws=True))
+    mlp_case(3, 256, N, rng.permutation(N)[:196608 + 128].tolist(), "bf16", count=196700, seed=77)
+
+
 def test_select_gemm_invalid_ids_count_and_long_k():
     say("\ncase select_gemm ids")
     idx = [3, -1, 3, 99, 100, 7, 0, 42] * 5                # invalid ids (-1, 100) and repeats
