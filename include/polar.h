@@ -266,9 +266,10 @@ int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const
  *               contents are overwritten; calls that overlap in time need separate workspaces
  *
  * 16-bit operands, float accumulation on the matrix cores, float output.  Kout a multiple of
- * 256, else POLAR_EUNSUPPORTED.  Three launches per 64 rows of the batch (M > 64 is processed 64
- * rows at a time); the contraction is cut into ranges whose sums are added in a fixed order, so
- * results are reproducible for given sizes and count.
+ * 256, else POLAR_EUNSUPPORTED.  Three launches per 128 rows of the batch (M > 128 is processed
+ * 128 rows at a time; up to 64 rows and 65 to 128 rows run different kernels); the contraction
+ * is cut into ranges whose sums are added in a fixed order, so results are reproducible for
+ * given sizes and count.
  * Hact and idx may be NULL when cap == 0.
  */
 int polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap, size_t *bytes);
@@ -300,11 +301,11 @@ int polar_select_gemm_down(const float *Hact, const void *W2, const int32_t *idx
  *               polar_sparse_mlp_workspace_bytes(M, D, cap) bytes (else POLAR_EWORKSPACE);
  *               contents are overwritten; calls that overlap in time need separate workspaces
  *
- * D a multiple of 256, else POLAR_EUNSUPPORTED.  Four launches for up to 64 rows; larger batches
- * go through in passes (the first factor takes up to 128 rows of the batch per pass, the second
- * 64) that re-read the gathered rows.  Where the first factor's evenly split form cannot run
- * (see polar_select_gemm_ws) its one-launch kernel and the conversion launch take its place,
- * with the same result.  X, W1 and idx may be NULL when cap == 0.
+ * D a multiple of 256, else POLAR_EUNSUPPORTED.  Four launches for up to 128 rows; larger
+ * batches go through 128 rows at a time, re-reading the gathered rows.  Where the first factor's
+ * evenly split form cannot run (see polar_select_gemm_ws) its one-launch kernel and the
+ * conversion launch take its place, with the same result.  X, W1 and idx may be NULL when
+ * cap == 0.
  */
 int polar_sparse_mlp_workspace_bytes(int M, int D, int cap, size_t *bytes);
 int polar_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx, const int32_t *count,

@@ -6,9 +6,10 @@
 //   Y[m, c] = sum_{j < live} h16(H[m, j]) * W2[idx[j], c]       H [M,cap] float, W2 [N,Kout]
 //
 // Here the gather runs along the contraction axis: every selected neuron contributes one row of
-// Kout weights, read once and used for M <= 64 multiply-adds per element, so the kernel is bound
+// Kout weights, read once and used for M <= 128 multiply-adds per element, so the kernel is bound
 // by HBM like the first factor and is organised around streaming those rows:
-//   * a wave owns 128 output columns and all M rows (MT * 8 accumulator tiles of 16 x 16) and walks
+//   * (up to 64 rows; the kernel for 65 to 128 rows is described where it stands) a wave owns 128
+//     output columns and all M rows (MT * 8 accumulator tiles of 16 x 16) and walks
 //     the selected neurons 32 at a time: 8 loads of 16 bytes per lane fetch 32 row pieces of 256
 //     bytes (16 lanes per piece, 4 pieces per load: whole cache lines).  A lane then holds an
 //     8 x 8 block (8 neurons x 8 columns) of 16-bit weights; transposed inside the lane (shifts
@@ -45,7 +46,8 @@ constexpr int kDownGroupCols = 2 * kDownWaveCols;    // per workgroup (two colum
 constexpr int kDownBlock = 32;                   // neurons per step (the contraction depth of one MFMA)
 constexpr int kDownMaxIds = 8192;                // ids of a workgroup's range kept in LDS
 constexpr int kDownTargetGroups = 256;           // one workgroup per compute unit
-constexpr int kDownMaxRows = 64;                 // rows of the batch per pass
+constexpr int kDownMaxRows = 64;                 // rows of the batch the kernel with two column blocks per workgroup takes
+constexpr int kDownPassRows = 128;               // rows of the batch per pass (65 to 128: the row-split kernel)
 constexpr int kChunkBlocks = 8;                  // blocks of activations staged in LDS at a time
 constexpr int kChunkPitch = kChunkBlocks * kDownBlock * 2 + 16;   // bytes per row of a chunk, padded
 
@@ -328,6 +330,212 @@ __global__ __launch_bounds__(kDownThreads) void select_gemm_down_kernel(
     }
 }
 
+// Batches of 65 to 128 rows: the same streaming scheme with the workgroup cut the other way.  A
+// workgroup owns ONE column block of 128; wave (h, p) takes rows 64 h .. 64 h + 63 and the
+// 32-neuron blocks p, p + 4, ... of the range, so the two waves of a parity load the same weight
+// pieces (the second request finds them in the compute unit's cache or in flight) and the gathered
+// rows leave HBM once, not once per 64 rows.  Activations of all 128 rows are staged per chunk
+// (two buffers of 66 KB), which leaves no room for the ids of a whole range: the ids travel with
+// the chunks instead, two chunks ahead (the weight loads of chunk c + 1 are issued during chunk c).
+// grid = (Kout / 128) * NS workgroups; block = 512 threads; part holds, per (range, column block),
+// 64 accumulator tiles (row tile 4 h + t, column tile e).
+constexpr int kSplitRowTiles = 4;                // 16-row tiles per wave
+constexpr int kSplitRows = 2 * 16 * kSplitRowTiles;
+constexpr int kChunkIds = kChunkBlocks * kDownBlock;
+
+template <bool BF>
+__global__ __launch_bounds__(kDownThreads) void select_gemm_down_split_kernel(
+    const uint16_t *__restrict__ H16, const uint16_t *__restrict__ W2, const int32_t *__restrict__ idx,
+    const int32_t *__restrict__ count_ptr, float *__restrict__ part, int M, int Kout, int N, int cap,
+    int NS)
+{
+    constexpr int MT = kSplitRowTiles;
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int kChunkBytes = kSplitRows * kChunkPitch;
+    int *sh_id = reinterpret_cast<int *>(smem + 2 * kChunkBytes);   // two buffers of kChunkIds ids
+
+    int count = cap;
+    if (count_ptr) {
+        const int c = *count_ptr;
+        count = c < 0 ? 0 : (c < cap ? c : cap);
+    }
+    const int groups = Kout / kDownWaveCols;
+    const int cg = (int)blockIdx.x % groups, s = (int)blockIdx.x / groups;
+    const int blocks = (count + kDownBlock - 1) / kDownBlock;
+    const int b_begin = range_bound(blocks, NS, s), b_end = range_bound(blocks, NS, s + 1);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int x = lane & 15, kg = lane >> 4;
+    const int mh = wave & 1, parity = wave >> 1;
+    const int col0 = cg * kDownWaveCols;
+
+    f32x4 acc[MT][8];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[t][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // id of position e of chunk c (first block b_begin + 8 c), -1 for an id outside [0, N) or a
+    // position at or beyond the live count
+    auto chunk_id = [&](int c, int e) -> int {
+        const int j = (b_begin + c * kChunkBlocks) * kDownBlock + e;      // at most count + 3 chunks: fits an int
+        const int id = j < count ? idx[j] : -1;
+        return (id >= 0 && id < N) ? id : -1;
+    };
+    // Activations: a chunk is 128 rows x 256 positions = 4096 pieces of 16 bytes, 8 per thread,
+    // moved in four steps of 2 so that fewer registers are held than in the 64-row kernel.
+    // Thread tid moves piece tid % 32 of the rows tid / 32 + 16 j: one base address and a fixed
+    // stride.  All 128 rows are read whatever M is (the buffer has room for 128; rows m >= M hold
+    // anything, are multiplied and never stored).
+    const int cap32 = (cap + kDownBlock - 1) / kDownBlock * kDownBlock;
+    constexpr int kHalf = 2;                     // pieces per step
+    const int piece = 8 * (tid & 31);
+    const uint16_t *hbase = H16 + (size_t)(tid >> 5) * cap32 + piece;
+    const size_t hstride = (size_t)16 * cap32;
+    unsigned char *sbase = smem + (tid >> 5) * kChunkPitch + 16 * (tid & 31);
+    u32x4 hp[kHalf];
+    auto fetch_half = [&](int first_block, int half) {
+        int pos = first_block * kDownBlock;
+        pos = pos + piece + 8 <= cap32 ? pos : cap32 - 8 - piece;       // every piece inside its row
+#pragma unroll
+        for (int i = 0; i < kHalf; ++i)
+            hp[i] = *reinterpret_cast<const u32x4 *>(hbase + (size_t)(half * kHalf + i) * hstride + pos);
+    };
+    auto store_half = [&](int buf, int half) {
+#pragma unroll
+        for (int i = 0; i < kHalf; ++i)
+            *reinterpret_cast<u32x4 *>(sbase + buf * kChunkBytes + (half * kHalf + i) * 16 * kChunkPitch) = hp[i];
+    };
+    const int lds_a = (64 * mh + x) * kChunkPitch + 16 * kg;        // + 16 t rows, + 64 bytes per block of the chunk
+    const uint16_t *wcol = W2 + col0 + 8 * x;
+
+    // ring of two blocks per wave, as in the 64-row kernel; block `block` lies in chunk `ch`
+    u32x4 wq[2][8];
+    const int last = b_end - 1;
+#define POLAR_SPLIT_FETCH(r, block, ch)                                                            \
+    {                                                                                              \
+        const int bb = (block) < last ? (block) : last;                                            \
+        int e0 = (bb - b_begin - (ch) * kChunkBlocks) * kDownBlock + 8 * kg;                       \
+        e0 = e0 < 0 ? 0 : (e0 > kChunkIds - 8 ? kChunkIds - 8 : e0);  /* a clamped block: any ids */ \
+        const int *ids = sh_id + ((ch) & 1) * kChunkIds + e0;                                      \
+        const i32x4 id_lo = *reinterpret_cast<const i32x4 *>(ids);                                 \
+        const i32x4 id_hi = *reinterpret_cast<const i32x4 *>(ids + 4);                             \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+        _Pragma("unroll") for (int i = 0; i < 8; ++i)                                              \
+        {                                                                                          \
+            const int id = i < 4 ? id_lo[i & 3] : id_hi[i & 3];                                    \
+            wq[r][i] = *reinterpret_cast<const u32x4 *>(wcol + (size_t)(id < 0 ? 0 : id) * Kout);  \
+        }                                                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+    }
+#define POLAR_SPLIT_MULTIPLY(r, abase)                                                             \
+    {                                                                                              \
+        u32x4 ha[MT];                                                                              \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
+            ha[t] = *reinterpret_cast<const u32x4 *>((abase) + lds_a + 16 * t * kChunkPitch);      \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e)                                              \
+        {                                                                                          \
+            u32x4 o;                                                                               \
+            _Pragma("unroll") for (int p = 0; p < 4; ++p)                                          \
+            {                                                                                      \
+                const unsigned int lo = wq[r][2 * p][e >> 1], hi = wq[r][2 * p + 1][e >> 1];       \
+                o[p] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16)); \
+            }                                                                                      \
+            _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
+                acc[t][e] = mfma16x16x32<BF>(ha[t], o, acc[t][e]);                                 \
+        }                                                                                          \
+    }
+
+    constexpr int P = kDownParities;
+    const int chunks = (b_end - b_begin + kChunkBlocks - 1) / kChunkBlocks;
+    if (chunks > 0) {
+        // ids of chunks 0 and 1, activations of chunk 0
+        if (tid < kChunkIds) {
+            sh_id[tid] = chunk_id(0, tid);
+            sh_id[kChunkIds + tid] = chunk_id(1, tid);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            fetch_half(b_begin, q);
+            store_half(0, q);
+        }
+        __syncthreads();
+        POLAR_SPLIT_FETCH(0, b_begin + parity, 0)
+        POLAR_SPLIT_FETCH(1, b_begin + parity + P, 0)
+    }
+    for (int c = 0; c < chunks; ++c) {
+        const int b = b_begin + c * kChunkBlocks + parity;
+        const unsigned char *abuf = smem + (c & 1) * kChunkBytes;
+        const int next_first = b_begin + (c + 1) * kChunkBlocks;
+        const int id_next = tid < kChunkIds ? chunk_id(c + 2, tid) : -1;    // consumed during chunk c + 1
+        fetch_half(next_first, 0);
+        if (b < b_end) POLAR_SPLIT_MULTIPLY(0, abuf + 64 * parity)
+        store_half((c + 1) & 1, 0);
+        fetch_half(next_first, 1);
+        POLAR_SPLIT_FETCH(0, b + 2 * P, c + 1)
+        store_half((c + 1) & 1, 1);
+        fetch_half(next_first, 2);
+        if (b + P < b_end) POLAR_SPLIT_MULTIPLY(1, abuf + 64 * (parity + P))
+        store_half((c + 1) & 1, 2);
+        fetch_half(next_first, 3);
+        POLAR_SPLIT_FETCH(1, b + 3 * P, c + 1)
+        store_half((c + 1) & 1, 3);
+        // buffer c & 1 held the ids of chunk c, last read while chunk c - 1 was multiplied
+        if (tid < kChunkIds) sh_id[(c & 1) * kChunkIds + tid] = id_next;
+        __syncthreads();
+    }
+#undef POLAR_SPLIT_MULTIPLY
+#undef POLAR_SPLIT_FETCH
+
+    // The four waves of a row half add their sums through LDS as in the 64-row kernel:
+    // (p0 + p2) + (p1 + p3), two rounds, parities 0 and 1 each storing one half of the tiles.
+    constexpr int kRegion = MT * 8 * 64;         // f32x4 entries
+    f32x4 *region0 = reinterpret_cast<f32x4 *>(smem) + (size_t)(mh * 2 + 0) * kRegion + lane;
+    f32x4 *region1 = reinterpret_cast<f32x4 *>(smem) + (size_t)(mh * 2 + 1) * kRegion + lane;
+    __syncthreads();                             // chunks and ids are no longer read
+    if (parity >= 2) {
+        f32x4 *to = parity == 2 ? region0 : region1;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) to[(t * 8 + e) * 64] = acc[t][e];
+    }
+    __syncthreads();
+    if (parity < 2) {
+        const f32x4 *from = parity == 0 ? region0 : region1;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[t][e] += from[(t * 8 + e) * 64];
+    }
+    __syncthreads();
+    if (parity == 1) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) region0[(t * 8 + e) * 64] = acc[t][e];
+    } else if (parity == 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 4; e < 8; ++e) region1[(t * 8 + e) * 64] = acc[t][e];
+    }
+    __syncthreads();
+    if (parity < 2) {
+        const f32x4 *from = parity == 0 ? region0 : region1;
+        const int e0 = parity == 0 ? 0 : 4;
+        f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
+                     (((size_t)s * groups + cg) * (2 * MT) + (size_t)mh * MT) * 8 * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const f32x4 other = from[(t * 8 + e0 + e) * 64];
+                dst[(t * 8 + e0 + e) * 64] = parity == 0 ? acc[t][e0 + e] + other : other + acc[t][e0 + e];
+            }
+    }
+}
+
 // grid = (Kout / 128) * MT workgroups of 64 threads: workgroup (column block, row tile t) adds the
 // NS sums of its 16 x 128 outputs in ascending range order.  Accumulator layout: lane (x, kg)
 // holds rows 16t + 4kg + i (i < 4) of column 8x + e for each of its 8 tiles e, so per row it
@@ -386,19 +594,43 @@ int down_ranges(int Kout, int cap)
     return ns < 1 ? 1 : ns;
 }
 
-}  // namespace
-
-static size_t down_partial_bytes(int M, int Kout, int cap)
+// contraction ranges of the row-split kernel (one column block per workgroup; the ids travel
+// with the chunks, so a range may be of any length)
+int down_split_ranges(int Kout, int cap)
 {
-    return (size_t)down_ranges(Kout, cap) * (Kout / kDownWaveCols) * down_mt(M) * 8 * 64 * sizeof(f32x4);
+    const int groups = Kout / kDownWaveCols;
+    int ns = kDownTargetGroups / groups;
+    const long blocks = ((long)cap + kDownBlock - 1) / kDownBlock;
+    if (ns > blocks && blocks > 0) ns = (int)blocks;
+    return ns < 1 ? 1 : ns;
 }
 
-// the ranges' sums, then the prepared activations
+}  // namespace
+
+// partial sums of one pass of `rows` rows
+static size_t down_partial_bytes(int rows, int Kout, int cap)
+{
+    if (rows > kDownMaxRows)
+        return (size_t)down_split_ranges(Kout, cap) * (Kout / kDownWaveCols) * (2 * kSplitRowTiles) * 8 * 64 * sizeof(f32x4);
+    return (size_t)down_ranges(Kout, cap) * (Kout / kDownWaveCols) * down_mt(rows) * 8 * 64 * sizeof(f32x4);
+}
+
+// room for the partial sums of every pass a batch of M rows goes through: passes of 128 rows, a
+// remainder of up to 128
+size_t select_gemm_down_partial_region(int M, int Kout, int cap)
+{
+    const size_t small = down_partial_bytes(M < kDownMaxRows ? M : kDownMaxRows, Kout, cap);
+    const size_t large = M > kDownMaxRows ? down_partial_bytes(kDownPassRows, Kout, cap) : 0;
+    return small > large ? small : large;
+}
+
+// the ranges' sums, then the prepared activations of one pass
 size_t select_gemm_down_workspace_bytes(int M, int Kout, int cap)
 {
-    if (M > kDownMaxRows) M = kDownMaxRows;      // larger batches go through in passes of 64 rows
+    // (the row-split kernel reads 128 rows of them whatever the batch size is)
+    const size_t rows = M <= kDownMaxRows ? M : kDownPassRows;
     const size_t cap32 = ((size_t)cap + kDownBlock - 1) / kDownBlock * kDownBlock;
-    return down_partial_bytes(M, Kout, cap) + (size_t)M * cap32 * sizeof(uint16_t);
+    return select_gemm_down_partial_region(M, Kout, cap) + rows * cap32 * sizeof(uint16_t);
 }
 
 template <bool BF>
@@ -440,11 +672,39 @@ static hipError_t launch_down_mt(int mt, int NS, hipStream_t st, const float *H,
     return hipGetLastError();
 }
 
-// one pass of at most 64 rows; H == nullptr: H16 is already prepared
+template <bool BF>
+static hipError_t launch_down_split(int NS, hipStream_t st, const float *H, const uint16_t *W2, const int32_t *idx,
+                                    const int32_t *count, float *Y, float *part, uint16_t *H16, int M, int Kout,
+                                    int N, int cap)
+{
+    const dim3 grid((unsigned)(Kout / kDownWaveCols * NS)), block(kDownThreads);
+    const dim3 rgrid((unsigned)(Kout / kDownWaveCols * 2 * kSplitRowTiles)), rblock(64);
+    const long items = H ? (long)M * ((cap + kDownBlock - 1) / kDownBlock * kDownBlock / 8) : 0;
+    if (items > 0)
+        hipLaunchKernelGGL((select_gemm_down_prepare_kernel<BF>), dim3((unsigned)((items + kPrepThreads - 1) / kPrepThreads)),
+                           dim3(kPrepThreads), 0, st, H, idx, count, H16, M, N, cap);
+    // dynamic LDS: two activation chunks of 128 rows and two chunks' ids (the epilogue's four
+    // exchange buffers fit inside)
+    const size_t lds = (size_t)2 * kSplitRows * kChunkPitch + (size_t)2 * kChunkIds * sizeof(int);
+    static_assert((size_t)2 * kSplitRows * kChunkPitch >= (size_t)4 * kSplitRowTiles * 8 * 64 * sizeof(f32x4), "exchange buffers");
+    static LdsGrant granted;
+    const void *kernel = reinterpret_cast<const void *>(select_gemm_down_split_kernel<BF>);
+    if (const hipError_t e = ensure_dynamic_lds(kernel, lds, granted); e != hipSuccess) return e;
+    hipLaunchKernelGGL((select_gemm_down_split_kernel<BF>), grid, block, lds, st, H16, W2, idx, count, part, M, Kout, N, cap, NS);
+    hipLaunchKernelGGL((select_gemm_down_reduce_kernel<2 * kSplitRowTiles>), rgrid, rblock, 0, st, part, Y, M, Kout, NS);
+    return hipGetLastError();
+}
+
+// one pass of at most 128 rows; H == nullptr: H16 is already prepared
 static hipError_t down_pass(const float *H, const uint16_t *W16, const int32_t *idx, const int32_t *count,
                             float *Y, int rows, int Kout, int N, int cap, polar_dtype dt, float *part,
                             uint16_t *H16, hipStream_t stream)
 {
+    if (rows > kDownMaxRows) {
+        const int NS = down_split_ranges(Kout, cap);
+        return dt == POLAR_BF16 ? launch_down_split<true>(NS, stream, H, W16, idx, count, Y, part, H16, rows, Kout, N, cap)
+                                : launch_down_split<false>(NS, stream, H, W16, idx, count, Y, part, H16, rows, Kout, N, cap);
+    }
     const int mt = down_mt(rows), NS = down_ranges(Kout, cap);
     return dt == POLAR_BF16
                ? launch_down_mt<true>(mt, NS, stream, H, W16, idx, count, Y, part, H16, rows, Kout, N, cap)
@@ -456,13 +716,13 @@ hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t
                                    hipStream_t stream)
 {
     const uint16_t *W16 = static_cast<const uint16_t *>(W2);
-    // batches beyond 64 rows are processed 64 rows at a time (the gathered rows are re-read; the
+    // batches beyond 128 rows are processed 128 rows at a time (the gathered rows are re-read; the
     // passes share the workspace, which the stream's order makes safe)
-    for (int m0 = 0; m0 < M; m0 += kDownMaxRows) {
-        const int rows = M - m0 < kDownMaxRows ? M - m0 : kDownMaxRows;
-        float *part = static_cast<float *>(workspace);
-        uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) +
-                                                     down_partial_bytes(rows, Kout, cap));
+    float *part = static_cast<float *>(workspace);
+    uint16_t *H16 = reinterpret_cast<uint16_t *>(static_cast<unsigned char *>(workspace) +
+                                                 select_gemm_down_partial_region(M, Kout, cap));
+    for (int m0 = 0; m0 < M; m0 += kDownPassRows) {
+        const int rows = M - m0 < kDownPassRows ? M - m0 : kDownPassRows;
         const hipError_t e = down_pass(H + (size_t)m0 * cap, W16, idx, count, Y + (size_t)m0 * Kout, rows, Kout,
                                        N, cap, dt, part, H16, stream);
         if (e != hipSuccess) return e;
@@ -472,7 +732,7 @@ hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t
 
 // Workspace of the two-factor call, four regions that do not overlap: the first factor's partial
 // sums, the second factor's partial sums, the 16-bit hidden activations of one pass of the first
-// factor, and room for the hidden activations of 64 rows as floats, used only where the first
+// factor, and room for the hidden activations of one pass as floats, used only where the first
 // factor's evenly split form cannot run.  Each region starts on a multiple of 256 bytes.
 static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 struct MlpRegions {
@@ -481,14 +741,14 @@ struct MlpRegions {
 };
 static MlpRegions mlp_regions(int M, int D, int cap)
 {
-    const int down_rows = M < kDownMaxRows ? M : kDownMaxRows;
+    const int down_rows = M < kDownPassRows ? M : kDownPassRows;
     const size_t cap32 = ((size_t)cap + kDownBlock - 1) / kDownBlock * kDownBlock;
     MlpRegions r;
     r.up_rows = M < select_gemm_ws_max_rows() ? M : select_gemm_ws_max_rows();
     r.gemm_bytes = select_gemm_workspace_bytes(r.up_rows);
     r.down_offset = align256(r.gemm_bytes);
-    r.h16_offset = r.down_offset + align256(down_partial_bytes(down_rows, D, cap));
-    r.hidden_offset = r.h16_offset + align256((size_t)r.up_rows * cap32 * sizeof(uint16_t));
+    r.h16_offset = r.down_offset + align256(select_gemm_down_partial_region(M, D, cap));
+    r.hidden_offset = r.h16_offset + align256((size_t)(M <= kDownMaxRows ? M : kDownPassRows) * cap32 * sizeof(uint16_t));
     r.total = r.hidden_offset + align256((size_t)down_rows * cap * sizeof(float));
     return r;
 }
@@ -507,7 +767,7 @@ hipError_t launch_sparse_mlp(const void *X, const void *W1, const void *W2, cons
     const size_t cap32 = ((size_t)cap + kDownBlock - 1) / kDownBlock * kDownBlock;
     const uint16_t *X16 = static_cast<const uint16_t *>(X);
     const uint16_t *W216 = static_cast<const uint16_t *>(W2);
-    // The first factor takes up to 128 rows of the batch at a time, the second 64 (larger batches
+    // Both factors take up to 128 rows of the batch at a time (larger batches
     // re-read the gathered rows).
     for (int m0 = 0; m0 < M; m0 += r.up_rows) {
         const int rows = M - m0 < r.up_rows ? M - m0 : r.up_rows;
@@ -518,8 +778,8 @@ hipError_t launch_sparse_mlp(const void *X, const void *W1, const void *W2, cons
                                                         dt, relu, base, r.gemm_bytes, stream);
             if (e != hipSuccess) return e;
         }
-        for (int r0 = 0; r0 < rows; r0 += kDownMaxRows) {
-            const int drows = rows - r0 < kDownMaxRows ? rows - r0 : kDownMaxRows;
+        for (int r0 = 0; r0 < rows; r0 += kDownPassRows) {
+            const int drows = rows - r0 < kDownPassRows ? rows - r0 : kDownPassRows;
             float *Yp = Y + (size_t)(m0 + r0) * D;
             hipError_t e = hipSuccess;
             if (fused) {

@@ -102,7 +102,8 @@ bool select_gemm_h16_applicable(int M, int K, int cap, size_t workspace_bytes);
 hipError_t launch_select_gemm_h16(const void *A, const void *W, const int32_t *idx, const int32_t *count,
                                   uint16_t *H16, int M, int K, int N, int cap, polar_dtype dt, int relu,
                                   void *workspace, size_t workspace_bytes, hipStream_t stream);
-// Second MLP factor: Y = h16(H) * W2[idx,:] (M <= 64, Kout % 256 == 0; the workspace is required).
+// Second MLP factor: Y = h16(H) * W2[idx,:] (Kout % 256 == 0; the workspace is required; up to 128
+// rows of the batch per pass).
 size_t select_gemm_down_workspace_bytes(int M, int Kout, int cap);
 hipError_t launch_select_gemm_down(const float *H, const void *W2, const int32_t *idx, const int32_t *count,
                                    float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,

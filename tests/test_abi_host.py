@@ -192,7 +192,9 @@ def test_select_gemm_down_argument_errors():
     assert q(64, 9216, 400000) == OK and (n.value - 64 * 400000 * 2) // (64 * 9216 * 4) >= 49
     assert q(0, 256, 32) == OK and n.value == 0
     assert q(4, 300, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
-    assert q(300, 9216, 36864) == OK and n.value == 7 * 64 * 9216 * 4 + 64 * 36864 * 2      # passes of 64 rows share it
+    # beyond 64 rows: passes of up to 128 rows (72 column blocks x 3 ranges) and a remainder share it
+    assert q(300, 9216, 36864) == OK and n.value == max(7 * 64, 3 * 128) * 9216 * 4 + 128 * 36864 * 2
+    assert q(65, 9216, 36864) == OK and n.value == max(7 * 64, 3 * 128) * 9216 * 4 + 128 * 36864 * 2
     assert L.polar_select_gemm_down_workspace_bytes(4, 256, 32, None) == EINVAL
 
 
@@ -213,16 +215,16 @@ def test_sparse_mlp_argument_errors():
     n, g, d = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_size_t(0)
     q = lambda M, D, cap: L.polar_sparse_mlp_workspace_bytes(M, D, cap, ctypes.byref(n))
     # four regions, each a multiple of 256 bytes: the first factor's workspace (up to 128 rows a pass),
-    # the second factor's partial sums (64 rows a pass), the 16-bit hidden activations of one pass of the
-    # first factor, and the hidden activations of 64 rows as floats (the fallback's)
+    # the second factor's partial sums, the 16-bit hidden activations of one pass (128 rows of them
+    # beyond 64 rows), and the hidden activations of one pass as floats (the fallback's)
     for (M, D, cap) in [(64, 9216, 36864), (4, 256, 33), (100, 512, 700), (300, 1024, 5000)]:
-        up_rows, down_rows, cap32 = min(M, 128), min(M, 64), (cap + 31) // 32 * 32
+        rows, h16_rows, cap32 = min(M, 128), (M if M <= 64 else 128), (cap + 31) // 32 * 32
         assert q(M, D, cap) == OK
-        assert L.polar_select_gemm_workspace_bytes(up_rows, ctypes.byref(g)) == OK
-        assert L.polar_select_gemm_down_workspace_bytes(down_rows, D, cap, ctypes.byref(d)) == OK
-        partial = d.value - down_rows * cap32 * 2
+        assert L.polar_select_gemm_workspace_bytes(rows, ctypes.byref(g)) == OK
+        assert L.polar_select_gemm_down_workspace_bytes(M, D, cap, ctypes.byref(d)) == OK
+        partial = d.value - h16_rows * cap32 * 2
         up = lambda v: (v + 255) // 256 * 256
-        assert n.value == up(g.value) + up(partial) + up(up_rows * cap32 * 2) + up(down_rows * cap * 4)
+        assert n.value == up(g.value) + up(partial) + up(h16_rows * cap32 * 2) + up(rows * cap * 4)
     assert q(0, 256, 32) == OK and n.value == 0
     assert q(4, 300, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
     assert L.polar_sparse_mlp_workspace_bytes(4, 256, 32, None) == EINVAL
