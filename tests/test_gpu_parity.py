@@ -624,7 +624,9 @@ def test_sparse_mlp_first_layer(name, ws):
 
 
 # ----------------------------------------------------------------------------- second MLP factor
-def down_case(M, Kout, N, idx_host, dtype, count=None, seed=0, scale=1.0):
+def down_case(M, Kout, N, idx_host, dtype, count=None, seed=0, scale=1.0, sample_cols=None):
+    """sample_cols: compare that many evenly spaced output columns instead of all (large cases:
+    every workgroup's column block is hit, the oracle's work stays small)."""
     g = torch.Generator(device=DEV).manual_seed(2000 + seed)
     tdt = torch.float16 if dtype == "f16" else torch.bfloat16
     cap = len(idx_host)
@@ -641,16 +643,19 @@ def down_case(M, Kout, N, idx_host, dtype, count=None, seed=0, scale=1.0):
     workspace = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=DEV)
     polar.select_gemm_down(H, W2, idx, count=cnt, out=out, workspace=workspace)
     torch.cuda.synchronize()
-    want = orc.select_gemm_down(H[:, :live].cpu().numpy(), host_bits(W2), np.array(idx_host[:live], np.int32), dtype)
     got = out.cpu().numpy()
     assert np.isfinite(got).all()
+    if sample_cols:
+        cols = torch.from_numpy(np.unique(np.linspace(0, Kout - 1, num=sample_cols).astype(np.int64))).to(DEV)
+        W2, got = W2[:, cols].contiguous(), got[:, cols.cpu().numpy()]
+    want = orc.select_gemm_down(H[:, :live].cpu().numpy(), host_bits(W2), np.array(idx_host[:live], np.int32), dtype)
     err = np.abs(got - want).max()
     assert err <= GEMM_TOL * max(scale, 1.0), err
     return err
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("M", [1, 5, 16, 17, 33, 64, 65, 150])
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 33, 64, 65, 100, 127, 128, 129, 150, 200])
 def test_select_gemm_down_shapes(dtype, M):
     say("\ncase select_gemm_down", dtype, M)
     rng = np.random.default_rng(100 + M)
@@ -672,6 +677,14 @@ def test_select_gemm_down_ids_counts_and_long_contraction():
     down_case(64, 512, 40000, rng.permutation(40000)[:12000].tolist(), "f16", seed=1)   # many ranges, long sums
     down_case(33, 256, 20000, rng.permutation(20000)[:9000].tolist(), "bf16", count=8191, seed=2)
     down_case(64, 256, 300, list(range(299, -1, -1)), "f16", scale=50.0)       # activations that round coarsely
+    # the kernel for 65 to 128 rows: ids, counts, ranges of several chunks
+    down_case(70, 256, 100, idx, "f16")
+    down_case(128, 256, 100, idx, "bf16", count=17)
+    down_case(90, 512, 100, idx, "bf16", count=1000)
+    down_case(128, 256, 100, idx, "f16", count=0)
+    down_case(65, 512, 100, [], "f16")
+    down_case(100, 1024, 40000, rng.permutation(40000)[:20000].tolist(), "f16", seed=3, sample_cols=64)
+    down_case(128, 4096, 9000, rng.permutation(9000)[:5000].tolist(), "bf16", count=4999, seed=4, sample_cols=96)
 
 
 def test_sparsified_mlp_both_factors():
