@@ -687,10 +687,12 @@ def test_select_gemm_down_ids_counts_and_long_contraction():
     down_case(128, 4096, 9000, rng.permutation(9000)[:5000].tolist(), "bf16", count=4999, seed=4, sample_cols=96)
 
 
-def test_sparsified_mlp_both_factors():
+@pytest.mark.parametrize("B", [64, 128])
+def test_sparsified_mlp_both_factors(B):
     """Union -> first factor -> second factor on one stream, no host round trip, against the
     oracle on sampled output columns (OPT-66B FFN shape); the one-call form gives the same bits."""
     w = wl.MLP_CONFIGS["M2_opt66b_ffn"]
+    w = wl.MlpWorkload(w.name, B, w.K, w.N, w.density, w.dtype, w.seed)       # 128: the kernels for 65 to 128 rows
     say("\ncase both factors", w)
     x, W1, topk = wl.make_mlp_inputs(w, DEV)
     g = torch.Generator(device=DEV).manual_seed(w.seed + 1)
