@@ -301,7 +301,18 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     const int32_t *__restrict__ count_ptr, float *__restrict__ C, uint16_t *__restrict__ H16,
     float *__restrict__ part, int M, int K, int N, int cap, int relu)
 {
-    __shared__ __align__(16) unsigned char sh_wt[kStreamWaves][kStreamWaveN * kRowBytes];
+    // From 33 rows up (MT = 4, 8) the waves pair up.  Wave 2g + r takes the row half r (TW row
+    // tiles) and the neurons of BOTH waves of pair g (HW = 2 groups of 16): each wave reads half
+    // the activation rows for twice the neurons, which takes a sixth (MT = 4) to a quarter
+    // (MT = 8) off the workgroup's LDS traffic: 51.5 -> 48 us at 64 rows, 80 -> 73 us at 128; at
+    // 32 rows it changes nothing.  A wave still loads and parks its own 16 weight rows; the
+    // pair's tile is then read by both, so it is double-buffered like the activations and
+    // ordered by the same barrier.
+    constexpr bool kSplit = MT >= 4;
+    constexpr int TW = kSplit ? MT / 2 : MT;     // 16-row tiles per wave
+    constexpr int HW = kSplit ? 2 * NH : NH;     // 16-neuron groups per wave
+    constexpr int kTileBytes = kStreamTileN * kRowBytes;
+    __shared__ __align__(16) unsigned char sh_wt[(kSplit ? 2 : 1) * kTileBytes];
     __shared__ __align__(16) unsigned char sh_at[2][16 * MT * kRowBytes];
     __shared__ int sh_id[kSpanTiles * kStreamTileN];
     __shared__ unsigned sh_bits[kPhaseBuckets * kSpanWords];
@@ -391,7 +402,10 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         row = row < M ? row : M - 1;
         ap[i] = reinterpret_cast<const u32x4 *>(A + (size_t)row * K) + x;
     }
-    unsigned char *wt = sh_wt[wave];
+    unsigned char *wt = sh_wt + wave * kStreamWaveN * kRowBytes;                       // where this wave parks its rows
+    const int ncol0 = kSplit ? (wave >> 1) * 2 * kStreamWaveN : wave * kStreamWaveN;   // first neuron it multiplies
+    const int row_tile0 = kSplit ? (wave & 1) * TW : 0;                                // first row tile it multiplies
+    const unsigned char *wop = sh_wt + ncol0 * kRowBytes;                              // its B operands' rows
     const int lds_w_wr = kg * kRowBytes + x * 16;                   // + 4*i rows
     const int lds_a_wr = a_row * kRowBytes + x * 16;                // + kARows*i rows
     const int lds_op = x * kRowBytes + kg * 64;                     // operand reads: + 16*s, + 16 rows per tile
@@ -452,23 +466,23 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     {                                                                                              \
         unsigned char *abuf = sh_at[j];                                                            \
         _Pragma("unroll") for (int i = 0; i < NR; ++i)                                             \
-            *reinterpret_cast<u32x4 *>(wt + lds_w_wr + 4 * i * kRowBytes) = wq[j][i];              \
+            *reinterpret_cast<u32x4 *>(wt + (kSplit ? (j) * kTileBytes : 0) + lds_w_wr + 4 * i * kRowBytes) = wq[j][i]; \
         if (stages_a) _Pragma("unroll") for (int i = 0; i < AP; ++i)                               \
             *reinterpret_cast<u32x4 *>(abuf + lds_a_wr + kARows * i * kRowBytes) = aq[j][i];       \
         POLAR_STREAM_FETCH(j, u + 1)                                                               \
         __syncthreads();                                                                           \
-        u32x4 bq[NH][4];                                                                           \
-        _Pragma("unroll") for (int h = 0; h < NH; ++h)                                             \
-            _Pragma("unroll") for (int s = 0; s < 4; ++s) bq[h][s] =                               \
-                *reinterpret_cast<const u32x4 *>(wt + lds_op + 16 * h * kRowBytes + 16 * s);       \
-        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                             \
+        u32x4 bq[HW][4];                                                                           \
+        _Pragma("unroll") for (int h = 0; h < HW; ++h)                                             \
+            _Pragma("unroll") for (int s = 0; s < 4; ++s) bq[h][s] = *reinterpret_cast<const u32x4 *>( \
+                wop + (kSplit ? (j) * kTileBytes : 0) + lds_op + 16 * h * kRowBytes + 16 * s);     \
+        _Pragma("unroll") for (int t = 0; t < TW; ++t)                                             \
         {                                                                                          \
             u32x4 a[4];                                                                            \
             _Pragma("unroll") for (int s = 0; s < 4; ++s) a[s] =                                   \
-                *reinterpret_cast<const u32x4 *>(abuf + lds_op + 16 * t * kRowBytes + 16 * s);     \
+                *reinterpret_cast<const u32x4 *>(abuf + lds_op + 16 * (row_tile0 + t) * kRowBytes + 16 * s); \
             _Pragma("unroll") for (int s = 0; s < 4; ++s)                                          \
             {                                                                                      \
-                _Pragma("unroll") for (int h = 0; h < NH; ++h)                                     \
+                _Pragma("unroll") for (int h = 0; h < HW; ++h)                                     \
                     acc[t][h] = mfma16x16x32<BF>(a[s], bq[h][s], acc[t][h]);                       \
             }                                                                                      \
         }                                                                                          \
@@ -476,22 +490,22 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
 
     // a finished segment of `tile`: the whole contraction is finished in place, a part of it goes
     // to the workspace as raw accumulators
-    auto store_segment = [&](const f32x4 (&sum)[MT][NH], int of_tile, bool whole) {
+    auto store_segment = [&](const f32x4 (&sum)[TW][HW], int of_tile, bool whole) {
         if (whole) {
             // accumulator layout: this lane holds rows 16*t + 4*kg + i of column x of each group
             // of 16 neurons
 #pragma unroll
-            for (int h = 0; h < NH; ++h) {
-                const int col = of_tile * kStreamTileN + wave * kStreamWaveN + 16 * h + x;
-                const bool valid = sh_id[(of_tile - first_tile) * kStreamTileN + wave * kStreamWaveN + 16 * h + x] >= 0;
+            for (int h = 0; h < HW; ++h) {
+                const int col = of_tile * kStreamTileN + ncol0 + 16 * h + x;
+                const bool valid = sh_id[(of_tile - first_tile) * kStreamTileN + ncol0 + 16 * h + x] >= 0;
                 if (H16) {                       // rounded to the storage type, rows padded with zeros
                     if (col >= (count + 31) / 32 * 32) continue;
                     const size_t pitch = ((size_t)cap + 31) / 32 * 32;
 #pragma unroll
-                    for (int t = 0; t < MT; ++t)
+                    for (int t = 0; t < TW; ++t)
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            const int row = 16 * t + 4 * kg + i;
+                            const int row = 16 * (row_tile0 + t) + 4 * kg + i;
                             if (row < M) {
                                 float val = sum[t][h][i];
                                 if (relu) val = val > 0.0f ? val : 0.0f;
@@ -502,10 +516,10 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
                 }
                 if (col >= count) continue;
 #pragma unroll
-                for (int t = 0; t < MT; ++t)
+                for (int t = 0; t < TW; ++t)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const int row = 16 * t + 4 * kg + i;
+                        const int row = 16 * (row_tile0 + t) + 4 * kg + i;
                         if (row < M) {
                             float val = sum[t][h][i];
                             if (relu) val = val > 0.0f ? val : 0.0f;
@@ -516,15 +530,15 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         } else {
             const int slot = of_tile == first_tile ? 0 : 1;          // slot 0: the span's first tile
             f32x4 *dst = reinterpret_cast<f32x4 *>(part) +
-                         (((size_t)span * 2 + slot) * kStreamWaves + wave) * (MT * NH) * 64 + lane;
+                         (((size_t)span * 2 + slot) * kStreamWaves + wave) * (TW * HW) * 64 + lane;
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+            for (int t = 0; t < TW; ++t)
 #pragma unroll
-                for (int h = 0; h < NH; ++h) dst[(t * NH + h) * 64] = sum[t][h];
+                for (int h = 0; h < HW; ++h) dst[(t * HW + h) * 64] = sum[t][h];
         }
     };
     constexpr bool kDefer = MT <= 4;             // beyond that the registers are not there
-    f32x4 held[MT][NH];
+    f32x4 held[TW][HW];
     int held_tile = -1;
     bool held_whole = false;
 
@@ -532,11 +546,11 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     POLAR_STREAM_FETCH(1, u)
     while (u < u1) {
         const int seg_begin = u, seg_end = tile_end < u1 ? tile_end : u1;
-        f32x4 acc[MT][NH];
+        f32x4 acc[TW][HW];
 #pragma unroll
-        for (int t = 0; t < MT; ++t)
+        for (int t = 0; t < TW; ++t)
 #pragma unroll
-            for (int h = 0; h < NH; ++h) acc[t][h] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            for (int h = 0; h < HW; ++h) acc[t][h] = (f32x4){0.f, 0.f, 0.f, 0.f};
         for (; u < seg_end; ++u) {
             POLAR_STREAM_STEP(0)
             POLAR_STREAM_STEP(1)
@@ -550,9 +564,9 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
             held_tile = tile;
             held_whole = whole;
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+            for (int t = 0; t < TW; ++t)
 #pragma unroll
-                for (int h = 0; h < NH; ++h) held[t][h] = acc[t][h];
+                for (int h = 0; h < HW; ++h) held[t][h] = acc[t][h];
         } else {
             store_segment(acc, tile, whole);
         }
@@ -587,10 +601,12 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
     }
     const int nblk = K / (kBlockK * kUnitBlocks);            // units per tile
     const int tiles = (count + kStreamTileN - 1) / kStreamTileN;
-    constexpr int kQuads = (MT * NH + 3) / 4;
+    constexpr bool kSplit = MT >= 4;              // the streaming kernel's pairing of waves
+    constexpr int TW = kSplit ? MT / 2 : MT, HW = kSplit ? 2 * NH : NH;
+    constexpr int kQuads = (TW * HW + 3) / 4;
     const int tile = blockIdx.x / (kStreamWaves * kQuads), wave = blockIdx.x / kQuads % kStreamWaves;
     const int e = (blockIdx.x % kQuads) * 4 + (threadIdx.x >> 6);
-    if (tile >= tiles || e >= MT * NH) return;
+    if (tile >= tiles || e >= TW * HW) return;
     const int units = tiles * nblk, lo = tile * nblk, hi = lo + nblk;
     // the workgroup whose span holds unit lo
     int g0 = (int)((unsigned)lo * (unsigned)G / (unsigned)units);
@@ -605,7 +621,8 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
     const int lane = threadIdx.x & 63, x = lane & 15, kg = lane >> 4;
     const int n0 = tile * kStreamTileN;
     {
-        const int t = e / NH, h = e % NH;
+        const int t = (kSplit ? (wave & 1) * TW : 0) + e / HW, h = e % HW;
+        const int ncol0 = kSplit ? (wave >> 1) * 2 * kStreamWaveN : wave * kStreamWaveN;
         f32x4 sum = (f32x4){0.f, 0.f, 0.f, 0.f};
         // segments in ascending workgroup order (g0 .. g1, empty spans skipped: adding +0.0
         // leaves the sum as it is), loads issued four at a time
@@ -620,12 +637,12 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
                 if (span_bound(units, G, g + 1) <= b) continue;
                 const int slot = b / nblk == tile ? 0 : 1;
                 v[q] = *(reinterpret_cast<const f32x4 *>(part) +
-                         ((((size_t)g * 2 + slot) * kStreamWaves + wave) * (MT * NH) + e) * 64 + lane);
+                         ((((size_t)g * 2 + slot) * kStreamWaves + wave) * (TW * HW) + e) * 64 + lane);
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) sum += v[q];
         }
-        const int col = n0 + wave * kStreamWaveN + 16 * h + x;
+        const int col = n0 + ncol0 + 16 * h + x;
         if (col >= (H16 ? (count + 31) / 32 * 32 : count)) return;
         const int id = col < count ? idx[col] : -1;
         const bool valid = id >= 0 && id < N;
