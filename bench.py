@@ -227,7 +227,7 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                      "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),
                      "gathered_read_probe_GBps": gather_probe,
                      # rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled; profiles/select_gemm_M2_opt66b_ffn.md
-                     "traffic": (224731157 if wide else 214354185) if (w == wl.MLP_CONFIGS.get(w.name)) else None},
+                     "traffic": (224757984 if wide else 214354185) if (w == wl.MLP_CONFIGS.get(w.name)) else None},
     }
     if not args.no_cpu_baseline:
         from oracle import polar_oracle as orc
