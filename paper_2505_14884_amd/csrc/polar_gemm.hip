@@ -261,7 +261,8 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
 // or two each, and the machine waits for the doubly loaded ones; and with every wave owning
 // other rows of the batch, each weight byte drags M/32 activation bytes through L2 and LDS.
 // Here the work is cut the other way round.  A workgroup's tile is 128 neurons; wave w of its
-// eight owns 16 of them and all M rows, so the weights are wave-private and the activation block
+// eight loads 16 of them and multiplies them with all M rows (from 33 rows up, two waves share
+// their 32 neurons and take half the rows each: see the kernel), and the activation block
 // is staged once per workgroup and shared (M/128 activation bytes per weight byte: the
 // activations come from L2, and every line of them in flight takes a place among the compute
 // unit's outstanding misses that a weight line from HBM could have).  The launch has a fixed
@@ -277,7 +278,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_kernel(
 constexpr int kStreamWaves = 8;                  // waves per workgroup
 constexpr int kStreamGrid = 256;                 // workgroups per launch: one per compute unit
 constexpr int kStreamThreads = 64 * kStreamWaves;
-constexpr int kStreamWaveN = 16;                 // neurons per wave
+constexpr int kStreamWaveN = 16;                 // neurons a wave loads per tile
 constexpr int NH = kStreamWaveN / 16;            // 16-neuron halves per wave
 constexpr int NR = kStreamWaveN / 4;             // row loads per wave and block (4 rows each)
 constexpr int kStreamTileN = kStreamWaveN * kStreamWaves;  // neurons per workgroup tile
