@@ -754,8 +754,8 @@ def mlp_case(M, D, N, idx_host, dtype, count=None, relu=True, seed=0, form=None)
         polar.sparse_mlp(X, W1, W2, idx, count=cnt, relu=relu, out=y, workspace=ws)
         again = polar.sparse_mlp(X, W1, W2, idx, count=cnt, relu=relu, workspace=ws)
         hidden = torch.full((M, cap), float("nan"), dtype=torch.float32, device=DEV)
-        for m0 in range(0, M if cap > 0 else 0, 64):        # the one call takes 64 rows at a time
-            rows = min(64, M - m0)
+        for m0 in range(0, M if cap > 0 else 0, 128):       # as the one call does: 128 rows at a time (the order
+            rows = min(128, M - m0)                          # of the additions depends on the pass's row count)
             polar.select_gemm(X[m0:m0 + rows], W1, idx, count=cnt, relu=relu, out=hidden[m0:m0 + rows],
                               workspace=polar.alloc_select_gemm_workspace(rows, DEV))
         two = polar.select_gemm_down(hidden, W2, idx, count=cnt)
