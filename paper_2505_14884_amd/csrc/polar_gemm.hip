@@ -673,7 +673,7 @@ __global__ __launch_bounds__(kGemmThreads) void select_gemm_reduce_kernel(
 // their bitmaps together before it counts and emits.
 constexpr int kUnionThreads = 1024;
 constexpr int kUnionMaxWords = 16384;            // N <= 524288 neurons (64 KB of LDS)
-constexpr int kUnionBuilders = 32;               // workgroups that build partial bitmaps
+constexpr int kUnionBuilders = 8;                // workgroups that build partial bitmaps (more: the emitters OR more maps)
 constexpr int kUnionMinIdsPerBuilder = 2048;
 constexpr int kUnionScanSlots = 32;               // wave totals of the scan (16 used)
 constexpr int kUnionEmitters = 16;               // workgroups of the split form's last launch (one wave's share each)

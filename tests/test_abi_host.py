@@ -166,7 +166,7 @@ def test_select_gemm_and_union_argument_errors():
     assert L.polar_neuron_union_workspace_bytes(2, 3, 64, None) == EINVAL
     assert L.polar_neuron_union_workspace_bytes(2, 3, 524289, ctypes.byref(n)) == EUNSUPPORTED
     assert polar.neuron_union_workspace_bytes(2, 3, 64) == 0                 # too few ids to split
-    assert polar.neuron_union_workspace_bytes(64, 1843, 36864) == 32 * 1152 * 4
+    assert polar.neuron_union_workspace_bytes(64, 1843, 36864) == 8 * 1152 * 4
     assert polar.neuron_union_workspace_bytes(4, 1024, 36864) == 2 * 1152 * 4
 
 
