@@ -50,7 +50,7 @@ typedef enum {
 
 /* Limits of this build (host-checked, POLAR_EUNSUPPORTED beyond them). */
 #define POLAR_MAX_ROUTER_H 256    /* selection units a router may score */
-#define POLAR_MAX_ROUTER_D 16384  /* router input width (the hidden row is staged in LDS) */
+#define POLAR_MAX_ROUTER_D 16384  /* router input width */
 #define POLAR_MAX_GROUP 16        /* query heads per KV head: any 1..16 at d = 128; 1, 2, 4, 8 at d = 64 */
 
 /*

@@ -33,7 +33,6 @@ namespace polar {
 namespace {
 
 constexpr int kRouterThreads = 1024;
-constexpr int kStageBatch = 8;   // hidden elements a thread stages per batch of loads
 constexpr int kRowBatch = 8;     // rows of Wr a thread loads before consuming any
 
 template <bool BF> __device__ __forceinline__ double widen_one(uint32_t bits16)
@@ -92,40 +91,25 @@ __device__ __forceinline__ void rank_and_emit(const double *sh_logit, int *sh_ra
     if (tid < H && sh_rank[tid] < k) row_out[sh_rank[tid]] = tid;
 }
 
-// dynamic LDS: uint16 hidden[Dpad] | double part[nslice*H] | double part2[J*H] | double logit[H]
+// dynamic LDS: double part[nslice*H] | double part2[J*H] | double logit[H]
 template <bool BF, int VEC>
 __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
     const uint16_t *__restrict__ hidden, const uint16_t *__restrict__ Wr, int D, int H, int k,
-    int nslice, int J, int Dpad, int32_t *__restrict__ head_idx, float *__restrict__ logits_out)
+    int nslice, int J, int32_t *__restrict__ head_idx, float *__restrict__ logits_out)
 {
     typedef typename VecOf<VEC>::type vec_t;
     extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t *sh_hidden = reinterpret_cast<uint16_t *>(smem);
-    double *sh_part = reinterpret_cast<double *>(smem + (size_t)Dpad * sizeof(uint16_t));
+    double *sh_part = reinterpret_cast<double *>(smem);
     double *sh_part2 = sh_part + (size_t)nslice * H;
     double *sh_logit = sh_part2 + (size_t)J * H;
     __shared__ int sh_rank[POLAR_MAX_ROUTER_H];
 
     const int b = blockIdx.x, tid = threadIdx.x;
     const uint16_t *hrow = hidden + (size_t)b * D;
-    // Stage the request's hidden row.  Every load of a batch is issued before any is used:
-    // a dependent round trip to memory costs about a microsecond, so the kernel's time is
-    // the number of such rounds, not its arithmetic.
-    for (int base = 0; base < D; base += kStageBatch * kRouterThreads) {
-        uint16_t v[kStageBatch];
-#pragma unroll
-        for (int u = 0; u < kStageBatch; ++u) {
-            const int i = base + u * kRouterThreads + tid;
-            v[u] = i < D ? hrow[i] : (uint16_t)0;
-        }
-#pragma unroll
-        for (int u = 0; u < kStageBatch; ++u) {
-            const int i = base + u * kRouterThreads + tid;
-            if (i < D) sh_hidden[i] = v[u];
-        }
-    }
-    __syncthreads();
-
+    // The request's hidden row is not staged: a thread needs only the elements of its own rows,
+    // and their loads go out together with the rows' (one round trip to memory, not two with a
+    // barrier in between).  A dependent round trip costs about a microsecond, so the kernel's
+    // time is the number of such rounds, not its arithmetic.
     const int CG = H / VEC;                    // column groups per row of Wr
     if (tid < nslice * CG) {
         const int slice = tid / CG, cg = tid - slice * CG;
@@ -137,15 +121,17 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
         // even rows of the batch into chain a0 and odd rows into a1
         for (int i = slice; i < D; i += kRowBatch * nslice) {
             vec_t wv[kRowBatch];
+            uint16_t hq[kRowBatch];
 #pragma unroll
             for (int u = 0; u < kRowBatch; ++u) {
                 const int row = i + u * nslice;
                 wv[u] = w[(size_t)(row < D ? row : i) * CG];
+                hq[u] = hrow[row < D ? row : i];
             }
 #pragma unroll
             for (int u = 0; u < kRowBatch; ++u) {
                 const int row = i + u * nslice;
-                const double hv = row < D ? widen_one<BF>(sh_hidden[row]) : 0.0;
+                const double hv = row < D ? widen_one<BF>(hq[u]) : 0.0;
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
                     if (u & 1)
@@ -191,14 +177,12 @@ hipError_t launch_vec(const uint16_t *hidden, const uint16_t *Wr, int B, int D, 
     while (J * J < nslice) ++J;                       // about sqrt(nslice) groups
     if (J > kRouterThreads / H) J = kRouterThreads / H;
     if (J < 1) J = 1;
-    const int Dpad = (D + 7) & ~7;                    // keeps the double arrays 16-byte aligned
-    const size_t lds = (size_t)Dpad * sizeof(uint16_t) +
-                       ((size_t)nslice * H + (size_t)J * H + H) * sizeof(double);
+    const size_t lds = ((size_t)nslice * H + (size_t)J * H + H) * sizeof(double);
     auto kern = router_topk_kernel<BF, VEC>;
     static LdsGrant granted;
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, granted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)B), dim3(kRouterThreads), lds, stream, hidden, Wr, D, H,
-                       k, nslice, J, Dpad, head_idx, logits_out);
+                       k, nslice, J, head_idx, logits_out);
     return hipGetLastError();
 }
 
