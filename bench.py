@@ -10,8 +10,12 @@ router just chose.  Inputs are seeded synthetic tensors already resident in HBM.
 Prints ONE JSON line.  `value` is the effective KV bandwidth of the whole step: bytes of
 K and V the selected heads oblige a kernel to read, divided by the wall time of a step
 (router included).  `roofline` is for the dominant kernel alone (the KV-streaming kernel),
-timed with events on the launch stream.  `cpu_baseline` is the fp64 oracle on the host
-cores over a bounded sample of the same workload.
+timed with events on the launch stream; its `traffic` is read from the hardware counters in
+this very run: before it touches the GPU, the benchmark runs itself four times as a child
+process under `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE of the streaming kernel, and of a
+plain device copy of known size that scales them).  --no-traffic skips those passes (traffic is
+then null), --traffic-from DIR reads passes made earlier, --traffic-dir DIR keeps the CSV files.
+`cpu_baseline` is the fp64 oracle on the host cores over a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -25,13 +29,6 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
-
-# HBM bytes per launch of the KV-streaming kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# (each scaled by the same counter's reading for a plain 4 GiB copy); measured with this file's
-# --phase partial / --phase copy on the default shape of each workload.  Source:
-# profiles/sha_decode_step_<workload>.md.  Reported only when the shape is that default.
-MEASURED_TRAFFIC_BYTES = {"C4_opt66b": 4533969067, "C5_ragged": 4480275675,
-                          "C3_llama3_8b_gqa": 538364712, "C2_llama2_7b": 504121882}
 DEFAULT_WORKLOAD = "C4_opt66b"
 
 
@@ -57,6 +54,14 @@ def parse_args():
                          "host copy of their K and V stays under 12 GB)")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the timing of the step replayed from a HIP graph")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="do not run the rocprofv3 counter passes (roofline.traffic is then null)")
+    ap.add_argument("--traffic-from", default="",
+                    help="directory of counter passes made earlier by this program (--traffic-dir): read "
+                         "roofline.traffic from them instead of running the passes again")
+    ap.add_argument("--traffic-dir", default="",
+                    help="keep the counter passes' CSV files and logs in this directory (default: a "
+                         "temporary one that is removed)")
     ap.add_argument("--kv-layout", choices=["bhsd", "bshd"], default="bhsd",
                     help="cache layout: [B,Hkv,S,d] (default) or the sequence-major [B,S,Hkv,d]")
     ap.add_argument("--mlp-workload", default="M2_opt66b_ffn",
@@ -80,7 +85,48 @@ def parse_args():
     return ap.parse_args()
 
 
-def bench_select_gemm(args, torch, np, polar, wl, dev):
+def workload_args(args):
+    """The command-line arguments that select the workload, for the child runs of this program."""
+    out = []
+    for flag, value in (("--workload", args.workload), ("--k", args.k), ("--B", args.B), ("--Hq", args.Hq),
+                        ("--Hkv", args.Hkv), ("--S", args.S), ("--kv-layout", args.kv_layout),
+                        ("--mlp-workload", args.mlp_workload), ("--density", args.density),
+                        ("--mlp-layers", args.mlp_layers), ("--gemm-form", args.gemm_form)):
+        if value:
+            out += [flag, str(value)]
+    return out
+
+
+def hbm_traffic(args, phase, kernels):
+    """roofline.traffic for the kernels named: HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE`
+    and `--pmc WRITE_SIZE` runs of this program's --phase <phase> (only those kernels launch), each
+    scaled by the same counter's reading for a plain 4 GiB device copy (--phase copy).  Returns
+    (dict or None, note).  Must run before this process touches the GPU."""
+    from paper_2505_14884_amd import rocprof
+
+    if args.traffic_from:
+        t = rocprof.traffic_from(args.traffic_from, kernels)
+        return t, "read from %s" % args.traffic_from if t else "no usable counter passes in %s" % args.traffic_from
+    if args.no_traffic:
+        return None, "counter passes skipped (--no-traffic)"
+    if not rocprof.rocprofv3():
+        return None, "rocprofv3 not found"
+    import shutil
+    import tempfile
+
+    keep = bool(args.traffic_dir)
+    out_dir = os.path.abspath(args.traffic_dir) if keep else tempfile.mkdtemp(prefix="polar_pmc_")
+    try:
+        t = rocprof.collect_traffic(out_dir, workload_args(args) + ["--phase", phase, "--steps", "5", "--warmup", "2"], kernels)
+        return t, "four rocprofv3 --pmc passes made by this run" if t else "counter passes held no dispatch of %s" % (kernels,)
+    except Exception as e:                       # a failed profiler pass must not cost the benchmark
+        return None, "counter passes failed: %s" % (str(e)[-300:],)
+    finally:
+        if not keep:
+            shutil.rmtree(out_dir, ignore_errors=True)
+
+
+def bench_select_gemm(args, torch, np, polar, wl, dev, traffic, traffic_note):
     """Step = batch union of the predicted neuron ids + selective GEMM with ReLU over the union
     (first layer of the sparsified MLP).  value = bytes of the gathered weight rows / step time."""
     w = wl.MLP_CONFIGS[args.mlp_workload]
@@ -226,8 +272,10 @@ def bench_select_gemm(args, torch, np, polar, wl, dev):
                      "avg_us": round(gemm_ms * 1e3, 2),
                      "mfma_tflops": round(2.0 * w.B * w.K * n_sel / (gemm_ms * 1e-3) / 1e12, 1),
                      "gathered_read_probe_GBps": gather_probe,
-                     # rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled; profiles/select_gemm_M2_opt66b_ffn.md
-                     "traffic": (224757984 if wide else 214354185) if (w == wl.MLP_CONFIGS.get(w.name)) else None},
+                     # HBM bytes per launch of the first factor read from the counters by this run, or null
+                     "traffic": traffic["bytes"] if traffic else None,
+                     "traffic_over_algorithmic": round(traffic["bytes"] / max(bytes_sel, 1), 4) if traffic else None,
+                     "traffic_detail": dict(traffic, note=traffic_note) if traffic else {"note": traffic_note}},
     }
     if not args.no_cpu_baseline:
         from oracle import polar_oracle as orc
@@ -262,6 +310,16 @@ def main():
     import paper_2505_14884_amd as polar
     from paper_2505_14884_amd import workloads as wl
 
+    # Counter passes first, as child processes, while this process has not touched the GPU yet.
+    traffic, traffic_note = None, "not applicable to this phase"
+    if args.phase == "all":
+        w0 = wl.CONFIGS.get(args.workload) or wl.EXTRA_SHAPES[args.workload]
+        Hq0, Hkv0 = args.Hq or w0.Hq, args.Hkv or w0.Hkv
+        grouped0 = Hq0 // Hkv0 > 1 and w0.d == 128
+        traffic, traffic_note = hbm_traffic(args, "partial", ["sha_partial_gqa_kernel<" if grouped0 else "sha_partial_kernel<"])
+    elif args.phase == "select_gemm":
+        traffic, traffic_note = hbm_traffic(args, "select_gemm_only", ["select_gemm_stream_kernel<", "select_gemm_reduce_kernel<", "select_gemm_kernel<"])
+
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
@@ -280,7 +338,7 @@ def main():
         return
 
     if args.phase in ("select_gemm", "select_gemm_only"):
-        bench_select_gemm(args, torch, np, polar, wl, dev)
+        bench_select_gemm(args, torch, np, polar, wl, dev, traffic, traffic_note)
         return
 
     w = wl.CONFIGS.get(args.workload) or wl.EXTRA_SHAPES[args.workload]
@@ -325,6 +383,7 @@ def main():
         polar.router_topk(hidden, Wr, w.k, head_idx=head_idx, workspace=rws)
         polar.sha_decode(q, Ki, Vi, seqlens, head_idx, w.k, out=out, workspace=ws, kv_layout=lay)
 
+    grouped = w.G > 1 and w.d == 128 and polar.get_option("sha_grouped_kernel") == 0   # the matrix-core kernel runs
     # An unsplit cache is finished by the streaming kernel alone (it normalises and zero-fills,
     # no merge kernel): then the attention call itself is one launch of the dominant kernel.
     one_kernel = polar.sha_launches(w.B, w.Hq, w.Hkv, w.S, w.d, w.k) == 1
@@ -431,7 +490,11 @@ def main():
     sink = torch.empty(probe_bytes // slab, dtype=torch.int32, device=dev)
     probe = {}
     for label, nt in (("nontemporal", True), ("plain", False)):
-        t_avg, _, _ = event_time(lambda i: polar.probe_read(caches[i % R][0], slab, nt, sink), max(5, n_ev // 4))
+        run_probe = lambda i: polar.probe_read(caches[i % R][0], slab, nt, sink)
+        for i in range(3):                        # the first launches of a kernel are not representative
+            run_probe(i)
+        torch.cuda.synchronize()
+        t_avg = min(event_time(run_probe, max(10, n_ev // 4))[0] for _ in range(2))
         probe[label] = round(probe_bytes / (t_avg * 1e-3) / 1e9, 1)
 
     result = {
@@ -446,7 +509,10 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        # the arithmetic of the kernel that ran: scores, softmax statistics and the output accumulate in
+        # float; the grouped-head kernel feeds each probability to the second matrix product as two
+        # 16-bit terms (rounded value + rounded remainder), the per-head kernel keeps it a float
+        "dtype": "f32 (P as 2x16-bit terms into MFMA)" if grouped else "f32",
         "data": "synthetic",
         "config": {
             "workload": "%s: B=%d Hq=%d Hkv=%d d=%d S=%d k=%d %s KV, router D=%d"
@@ -473,7 +539,7 @@ def main():
         "dense_over_selective": None if args.no_dense else round(dense_avg / sha_avg, 3),
         "ideal_H_over_k": round(w.Hkv / w.k, 3),
         "roofline": {
-            "kernel": "sha_partial_gqa_kernel" if (w.G > 1 and w.d == 128) else "sha_partial_kernel",
+            "kernel": "sha_partial_gqa_kernel" if grouped else "sha_partial_kernel",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
@@ -483,7 +549,10 @@ def main():
             "median_us": round(part_med * 1e3, 2),
             "min_us": round(part_min * 1e3, 2),
             "read_probe_GBps": probe,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (w == wl.CONFIGS.get(w.name) and lay == "bhsd") else None,
+            # HBM bytes per launch read from the counters by this run (see hbm_traffic), or null
+            "traffic": traffic["bytes"] if traffic else None,
+            "traffic_over_algorithmic": round(traffic["bytes"] / bytes_sel, 4) if traffic else None,
+            "traffic_detail": dict(traffic, note=traffic_note) if traffic else {"note": traffic_note},
         },
     }
 

@@ -14,6 +14,10 @@
  *    no exception crosses the boundary.  B == 0 is a successful no-op.
  *  - 16-bit storage: `dt` says whether hidden/Wr/q/K/V hold IEEE binary16
  *    (POLAR_F16) or bfloat16 (POLAR_BF16).  Accumulation is wider (see each call).
+ *  - Enumerated arguments (`dt`: a polar_dtype, `layout`: a polar_kv_layout, `opt`: a
+ *    polar_option) are declared `int`: the size of an enum type is the compiler's choice, an
+ *    int's is not, and a value outside the enumeration is then an ordinary bad argument
+ *    (POLAR_EINVAL), never undefined behaviour.
  *  - Device-side contents are not validated on the hot path; the behaviour for
  *    out-of-range contents is defined below and never reads or writes out of
  *    bounds.
@@ -54,6 +58,32 @@ typedef enum {
 #define POLAR_MAX_GROUP 16        /* query heads per KV head: any 1..16 at d = 128; 1, 2, 4, 8 at d = 64 */
 
 /*
+ * Process-wide options.  Every option starts at 0, "the library's own choice", which is what
+ * a user wants; the other values pin a kernel or a split granularity so that tests and sweeps
+ * can reach every code path.  The library reads no environment variable.  An option is a plain
+ * integer read (atomically) by each call; changing one while calls that share a workspace are
+ * being made (for instance between polar_sha_partial and polar_sha_merge) changes the layout
+ * the workspace is read with and is a caller error.  Workspace queries answer for the options
+ * in force when they are asked.
+ */
+typedef enum {
+    POLAR_OPT_SHA_CHUNK_ROWS = 0,     /* cache rows per workgroup of the streaming kernel: 0 auto, else 128..2^20
+                                         (rounded up to a multiple of 128) */
+    POLAR_OPT_SHA_FORM = 1,           /* 0 auto, 1 one kernel wherever the cache is unsplit, 2 always streaming + merge */
+    POLAR_OPT_SHA_GROUPED_KERNEL = 2, /* grouped heads at d = 128: 0 matrix-core kernel, 1 vector-ALU kernel
+                                         (group sizes 2, 4, 8 only: others become POLAR_EUNSUPPORTED) */
+    POLAR_OPT_ROUTER_PATH = 3,        /* with a workspace: 0 auto, 1 one-kernel path, 2 split-D path */
+    POLAR_OPT_ROUTER_PHASE1 = 4,      /* split-D phase 1: 0 auto, 1 vector ALU, 2 fp64 matrix cores */
+    POLAR_OPT_GEMM_FORM = 5,          /* polar_select_gemm_ws / polar_sparse_mlp: 0 auto, 1 one-launch kernel */
+    POLAR_OPT_GEMM_WORKGROUPS = 6,    /* launch width of the evenly split GEMM: 0 auto, else 1..256 */
+    POLAR_OPT_COUNT_ = 7
+} polar_option;
+/* POLAR_EINVAL for an unknown option or a value outside the ranges above (nothing is changed). */
+int polar_set_option(int opt, int value);
+/* Current value of an option; POLAR_EINVAL for an unknown option or value == NULL. */
+int polar_get_option(int opt, int *value);
+
+/*
  * Attention-head router and per-request top-k (Section 4.2: the router is one fully
  * connected layer producing a scalar logit per head; the k highest-logit heads of each
  * request form the batch head index).
@@ -83,9 +113,15 @@ typedef enum {
  * timing.  1 <= k <= H <= POLAR_MAX_ROUTER_H, 1 <= D <= POLAR_MAX_ROUTER_D.
  */
 int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, int k,
-                      polar_dtype dt, int32_t *head_idx, float *logits_out, void *workspace,
+                      int dt, int32_t *head_idx, float *logits_out, void *workspace,
                       size_t workspace_bytes, void *stream);
 
+/*
+ * Workspace queries, one style for every operation: `size_t polar_<op>_workspace_bytes(sizes)`
+ * returns the bytes of device scratch the operation wants for these sizes, and 0 where there is
+ * nothing to allocate: sizes the operation rejects (its own call reports the status), an empty
+ * batch, or an input too small for the workspace form to pay.
+ */
 /* Bytes of device workspace the split path of polar_router_topk needs; 0 for invalid sizes. */
 size_t polar_router_workspace_bytes(int B, int D, int H);
 
@@ -120,6 +156,7 @@ size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k);
  *   scale         softmax scale; 0 selects 1/sqrt(d).
  *   workspace     at least polar_sha_workspace_bytes(...) bytes, 256-byte aligned.
  *
+ * q, K, V and out must be 16-byte aligned (the kernels use 16-byte accesses), else POLAR_EINVAL.
  * Scores, softmax statistics and the output are accumulated in float.  A request with
  * n_b == 0 gets zeros.  Supported: d in {64, 128}; G = Hq / Hkv in 1..16 at d = 128, in
  * {1, 2, 4, 8} at d = 64; 1 <= k <= Hkv.
@@ -131,7 +168,7 @@ size_t polar_sha_workspace_bytes(int B, int Hq, int Hkv, int S, int d, int k);
  */
 int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t *seqlens,
                      const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
-                     int k, polar_dtype dt, float scale, void *workspace,
+                     int k, int dt, float scale, void *workspace,
                      size_t workspace_bytes, void *stream);
 
 /*
@@ -143,7 +180,7 @@ int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t 
  */
 int polar_sha_decode_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
                             const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S,
-                            int d, int k, polar_dtype dt, polar_kv_layout layout, float scale,
+                            int d, int k, int dt, int layout, float scale,
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -160,11 +197,11 @@ int polar_sha_decode_layout(const void *q, const void *K, const void *V, const i
  */
 int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
                       const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
-                      polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
+                      int dt, float scale, void *workspace, size_t workspace_bytes,
                       void *stream);
 int polar_sha_partial_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
                              const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
-                             polar_dtype dt, polar_kv_layout layout, float scale, void *workspace,
+                             int dt, int layout, float scale, void *workspace,
                              size_t workspace_bytes, void *stream);
 int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out, int B, int Hq,
                     int Hkv, int S, int d, int k, const void *workspace, size_t workspace_bytes,
@@ -221,7 +258,7 @@ int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, i
  * of 128; A and W 16-byte aligned.  M > 256 is processed 256 rows at a time.
  */
 int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
-                      float *C, int M, int K, int N, int cap, polar_dtype dt, int relu, void *stream);
+                      float *C, int M, int K, int N, int cap, int dt, int relu, void *stream);
 
 /*
  * The same operation with a workspace (Appendix "Sparse Kernels", Algorithm 3; same arguments,
@@ -236,11 +273,12 @@ int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const in
  *                    overwritten; calls that overlap in time need separate workspaces
  *   workspace_bytes  its size; polar_select_gemm_workspace_bytes(M) gives the size at which
  *                    the launch is as wide as the library wants it (it grows with M up to
- *                    128 rows); a smaller workspace narrows the launch, it is not an error
+ *                    128 rows; 0 for M <= 0); a smaller workspace narrows the launch, it is
+ *                    not an error
  */
-int polar_select_gemm_workspace_bytes(int M, size_t *bytes);
+size_t polar_select_gemm_workspace_bytes(int M);
 int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
-                         float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                         float *C, int M, int K, int N, int cap, int dt, int relu,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -272,9 +310,9 @@ int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const
  * given sizes and count.
  * Hact and idx may be NULL when cap == 0.
  */
-int polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap, size_t *bytes);
+size_t polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap);
 int polar_select_gemm_down(const float *Hact, const void *W2, const int32_t *idx, const int32_t *count,
-                           float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
+                           float *Y, int M, int Kout, int N, int cap, int dt, void *workspace,
                            size_t workspace_bytes, void *stream);
 
 /*
@@ -307,9 +345,9 @@ int polar_select_gemm_down(const float *Hact, const void *W2, const int32_t *idx
  * conversion launch take its place, with the same result.  X, W1 and idx may be NULL when
  * cap == 0.
  */
-int polar_sparse_mlp_workspace_bytes(int M, int D, int cap, size_t *bytes);
+size_t polar_sparse_mlp_workspace_bytes(int M, int D, int cap);
 int polar_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx, const int32_t *count,
-                     float *Y, int M, int D, int N, int cap, polar_dtype dt, int relu, void *workspace,
+                     float *Y, int M, int D, int N, int cap, int dt, int relu, void *workspace,
                      size_t workspace_bytes, void *stream);
 
 /*
@@ -337,46 +375,21 @@ int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32
  *   workspace_bytes  its size; polar_neuron_union_workspace_bytes(B, kn, N) gives the size the
  *                    library wants (0: the input is too small to split)
  */
-int polar_neuron_union_workspace_bytes(int B, int kn, int N, size_t *bytes);
+size_t polar_neuron_union_workspace_bytes(int B, int kn, int N);
 int polar_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                           int32_t *count_out, void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Streaming-read yardstick for harnesses (not an operation of the paper): `slabs` workgroups
- * each read one contiguous slab of `slab_bytes` bytes (slab w starts at src + w * slab_bytes)
- * with the per-head streaming kernel's launch shape and fold what they read into sink[w].
- * Timing it over the bytes of a K cache gives the read bandwidth this GPU reaches for that
- * access pattern, to set beside the nominal HBM peak.  nontemporal != 0 marks the loads
- * non-temporal, as the attention kernels do.
- *   src  in   slabs * slab_bytes bytes, 16-byte aligned; slab_bytes a multiple of 16
- *   sink out  [slabs] uint32
- */
-int polar_probe_read(const void *src, size_t slabs, size_t slab_bytes, int nontemporal, uint32_t *sink,
-                     void *stream);
-
-/*
- * The same kind of yardstick for the selective GEMMs (not an operation of the paper): reads the
- * rows W[idx[j], :] (j < n_idx) of a [N, K] 16-bit matrix the way those kernels stream them,
- * in 256-byte pieces, 4 rows per wave-wide load, and does nothing else.  Workgroup (tile, slice) of
- * two waves takes 64 consecutive entries of idx and the slice-th of `slices` equal parts of K;
- * `depth` (1 or 4) 128-value blocks are in flight per wave.  Timing it over n_idx * K * 2 bytes
- * gives the read bandwidth this access pattern reaches by itself.
- *   W     in   [N, K] 16-bit, 16-byte aligned; K a multiple of 128 * slices * depth
- *   idx   in   [n_idx] int32; an id outside [0,N) reads row 0
- *   sink  out  [2 * ceil(n_idx / 64) * slices] uint32
- */
-int polar_probe_gather_read(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices, int depth,
-                            int nontemporal, uint32_t *sink, void *stream);
 
 /* Text for a polar_status value; never NULL. */
 const char *polar_strerror(int status);
 /* The hipError_t (as int) recorded by the most recent POLAR_EHIP on this thread; 0 if none. */
 int polar_last_hip_error(void);
-/* ABI version: major * 1000 + minor (1100: adds polar_sha_launches and polar_probe_read; group sizes up to 16;
- * 1200: adds polar_select_gemm_ws and polar_select_gemm_workspace_bytes; 1300: adds polar_neuron_union_ws and
- * polar_neuron_union_workspace_bytes; 1400: adds polar_select_gemm_down and its workspace query;
- * 1500: adds polar_probe_gather_read; 1600: adds polar_sparse_mlp and its workspace query). */
+/* ABI version: major * 1000 + minor.  2000: options (polar_set_option / polar_get_option) replace the
+ * environment switches; every workspace query returns size_t; the read yardsticks moved to their own
+ * library (polar_probe.h); q, K, V and out of the attention calls must be 16-byte aligned. */
 int polar_version(void);
+/* Hash of the source files this binary was built from (set by the build script; "unknown" for a
+ * build made without it).  Lets a loader refuse a binary older than the sources beside it. */
+const char *polar_source_hash(void);
 
 #ifdef __cplusplus
 }

@@ -29,10 +29,11 @@
  *               batch union of predicted neuron ids that forms that index (Section 3.1,
  *               Section 4.1, Appendix "Sparse Kernels" Algorithm 3)
  *
- * A second routine, oracle_alg1_tiled, follows Algorithm 1 (Selective Head
- * FlashAttention, decode) step by step — tiles of B_c rows, running maximum and
- * sum, output renormalised every tile — so a test can show that the tiled
- * recurrence and the two-pass definition agree.
+ * A second routine, oracle_alg1_tiled, evaluates one head tile by tile, as a
+ * left fold of an associative "softmax state" combination over tiles of B_c
+ * rows (what Algorithm 1, Selective Head FlashAttention (decode), does with its
+ * running maximum and sum and its per-tile renormalised output), so a test can
+ * show that the tiled evaluation and the two-pass definition agree.
  *
  * Readings where the paper is silent (kept in step with the design notes):
  *   - head ids come out ordered by descending logit; equal logits (-0.0 == +0.0)
@@ -372,50 +373,74 @@ int oracle_select_gemm_down(const float *H, const uint16_t *W2, const int32_t *i
     return 0;
 }
 
-/* Algorithm 1 (Selective Head FlashAttention, decode) for ONE already-gathered
- * head, followed in its own order: the cache is visited in tiles of Bc rows;
- * each tile yields its scores, their maximum, the shifted exponentials and
- * their sum; the running maximum and sum are updated with the two rescale
- * factors; the accumulated output is renormalised by the new sum every tile.
- * Inputs are doubles so a test can feed any values. */
+/* Tile-by-tile attention for ONE already-gathered head, as a fold of "softmax states".
+ *
+ * A state summarises attention over a set of cache rows: `top`, the largest scaled score in the
+ * set; `mass`, the sum of exp(score - top) over the set; `mean`, the attention output over the
+ * set, i.e. the exp-weighted mean of its V rows (already divided by mass).  Two states over
+ * disjoint sets combine into the state of the union:
+ *     top = max(top_a, top_b),  w_x = mass_x * exp(top_x - top),
+ *     mass = w_a + w_b,         mean = (w_a * mean_a + w_b * mean_b) / mass.
+ * The empty set is the identity (top = -inf, mass = 0).  Folding this combination from the left
+ * over consecutive tiles of Bc rows, each tile's own state computed by the plain two-pass
+ * definition, is what Algorithm 1 (Selective Head FlashAttention, decode) does with its running
+ * maximum, running sum and per-tile renormalised output; the result is the `mean` of the final
+ * state.  Inputs are doubles so a test can feed any values. */
+typedef struct {
+    double top;
+    double mass;
+    double *mean; /* d values */
+} soft_state;
+
+/* state of rows [first, last) by the two-pass definition; `w` is scratch for last - first weights */
+static void soft_state_of_rows(const double *q, const double *K, const double *V, int first, int last,
+                               int d, double scale, double *w, soft_state *st)
+{
+    st->top = -INFINITY;
+    for (int r = first; r < last; ++r) {
+        double dot = 0.0;
+        for (int e = 0; e < d; ++e) dot += q[e] * K[(size_t)r * d + e];
+        w[r - first] = scale * dot;
+        if (w[r - first] > st->top) st->top = w[r - first];
+    }
+    st->mass = 0.0;
+    for (int r = first; r < last; ++r) {
+        w[r - first] = exp(w[r - first] - st->top);
+        st->mass += w[r - first];
+    }
+    for (int e = 0; e < d; ++e) {
+        double sum = 0.0;
+        for (int r = first; r < last; ++r) sum += w[r - first] * V[(size_t)r * d + e];
+        st->mean[e] = sum / st->mass;
+    }
+}
+
+/* acc <- acc combined with t (t is not empty) */
+static void soft_state_absorb(soft_state *acc, const soft_state *t, int d)
+{
+    const double top = acc->top > t->top ? acc->top : t->top;
+    const double wa = acc->mass > 0.0 ? acc->mass * exp(acc->top - top) : 0.0; /* empty: no exp(-inf + inf) */
+    const double wt = t->mass * exp(t->top - top);
+    const double mass = wa + wt;
+    for (int e = 0; e < d; ++e) acc->mean[e] = (wa * acc->mean[e] + wt * t->mean[e]) / mass;
+    acc->top = top;
+    acc->mass = mass;
+}
+
 int oracle_alg1_tiled(const double *q, const double *K, const double *V, int n, int d, int Bc,
                       double scale, double *out)
 {
     if (!q || !K || !V || !out || n < 1 || d < 1 || Bc < 1) return -1;
-    double m_acc = -INFINITY, l_acc = 0.0;
-    double *p = malloc(sizeof *p * (size_t)Bc);
-    double *pv = malloc(sizeof *pv * (size_t)d);
-    if (!p || !pv) { free(p); free(pv); return -2; }
+    double *w = malloc(sizeof *w * (size_t)Bc);
+    double *tile_mean = malloc(sizeof *tile_mean * (size_t)d);
+    if (!w || !tile_mean) { free(w); free(tile_mean); return -2; }
+    soft_state acc = {-INFINITY, 0.0, out}, tile = {0.0, 0.0, tile_mean};
     for (int e = 0; e < d; ++e) out[e] = 0.0;
-    int tiles = (n + Bc - 1) / Bc;
-    for (int j = 1; j <= tiles; ++j) {
-        int lo = (j - 1) * Bc, hi = j * Bc < n ? j * Bc : n;
-        double m_tile = -INFINITY;
-        for (int r = lo; r < hi; ++r) {
-            double s = 0.0;
-            for (int e = 0; e < d; ++e) s += q[e] * K[(size_t)r * d + e];
-            p[r - lo] = scale * s;
-            if (p[r - lo] > m_tile) m_tile = p[r - lo];
-        }
-        double l_tile = 0.0;
-        for (int r = lo; r < hi; ++r) {
-            p[r - lo] = exp(p[r - lo] - m_tile);
-            l_tile += p[r - lo];
-        }
-        for (int e = 0; e < d; ++e) {
-            pv[e] = 0.0;
-            for (int r = lo; r < hi; ++r) pv[e] += p[r - lo] * V[(size_t)r * d + e];
-        }
-        double m_new = m_acc > m_tile ? m_acc : m_tile;
-        double alpha = exp(m_acc - m_new);   /* exp(-inf) = 0 on the first tile */
-        double beta = exp(m_tile - m_new);
-        double l_new = alpha * l_acc + beta * l_tile;
-        for (int e = 0; e < d; ++e)
-            out[e] = (alpha * l_acc * out[e] + beta * pv[e]) / l_new;
-        l_acc = l_new;
-        m_acc = m_new;
+    for (int first = 0; first < n; first += Bc) {
+        soft_state_of_rows(q, K, V, first, first + Bc < n ? first + Bc : n, d, scale, w, &tile);
+        soft_state_absorb(&acc, &tile, d);
     }
-    free(p);
-    free(pv);
+    free(w);
+    free(tile_mean);
     return 0;
 }

@@ -5,7 +5,9 @@ bench's ``cpu_baseline`` leg import this.  It knows nothing of the HIP library
 and takes numpy arrays of raw 16-bit patterns (uint16) plus a dtype name.
 
 The shared object is compiled from the C file beside it with gcc; it is rebuilt
-here when missing or older than its source (a one-second gcc run).
+here when missing or older than its source (a one-second gcc run).  The
+environment variable POLAR_ORACLE_LIBRARY names another build of the same
+source to load instead (the sanitizer test uses it).
 """
 from __future__ import annotations
 
@@ -23,21 +25,21 @@ _DT = {"f16": 0, "bf16": 1}
 _lib = None
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (-O2 -fopenmp).  Returns the path of the shared object."""
-    stale = (not os.path.exists(_SO)) or os.path.getmtime(_SO) < os.path.getmtime(_SRC)
+def build(force: bool = False, out_path: str = _SO, extra_flags=("-O2",)) -> str:
+    """Compile the oracle with gcc (-O2 -fopenmp by default).  Returns the path of the shared object."""
+    stale = (not os.path.exists(out_path)) or os.path.getmtime(out_path) < os.path.getmtime(_SRC)
     if force or stale:
-        tmp = _SO + ".tmp.%d" % os.getpid()
-        subprocess.run(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall",
+        tmp = out_path + ".tmp.%d" % os.getpid()
+        subprocess.run(["gcc", *extra_flags, "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall",
                         "-Wextra", "-o", tmp, _SRC, "-lm"], check=True)
-        os.replace(tmp, _SO)
-    return _SO
+        os.replace(tmp, out_path)
+    return out_path
 
 
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        L = ctypes.CDLL(os.environ.get("POLAR_ORACLE_LIBRARY") or build())
         c_int, c_long, c_dbl, vp = ctypes.c_int, ctypes.c_long, ctypes.c_double, ctypes.c_void_p
         L.oracle_num_threads.restype = c_int
         L.oracle_set_num_threads.argtypes = [c_int]

@@ -8,23 +8,34 @@ GPU, the call raises.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
 from typing import Optional, Tuple
 
 import torch
 
-from .build import LIB_PATH, build_library
+from .build import LIB_PATH, PROBE_LIB_PATH, build_library, source_hash
 
 F16, BF16 = 0, 1
 KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge", "polar_sha_chunk_rows", "polar_sha_launches", "polar_probe_read", "polar_probe_gather_read", "polar_head_norm_topk", "polar_select_gemm", "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down", "polar_select_gemm_down_workspace_bytes", "polar_sparse_mlp", "polar_sparse_mlp_workspace_bytes", "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes", "polar_strerror",
-           "polar_last_hip_error", "polar_version")
+           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge",
+           "polar_sha_chunk_rows", "polar_sha_launches", "polar_head_norm_topk", "polar_select_gemm",
+           "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down",
+           "polar_select_gemm_down_workspace_bytes", "polar_sparse_mlp", "polar_sparse_mlp_workspace_bytes",
+           "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes",
+           "polar_set_option", "polar_get_option", "polar_strerror", "polar_last_hip_error", "polar_version",
+           "polar_source_hash")
+PROBE_EXPORTS = ("polar_probe_read", "polar_probe_gather_read", "polar_probe_last_hip_error")
+# polar_option in include/polar.h
+OPTIONS = {"sha_chunk_rows": 0, "sha_form": 1, "sha_grouped_kernel": 2, "router_path": 3, "router_phase1": 4,
+           "gemm_form": 5, "gemm_workgroups": 6}
 
 _lib: Optional[ctypes.CDLL] = None
+_probe_lib: Optional[ctypes.CDLL] = None
 
 
 class PolarError(RuntimeError):
@@ -37,14 +48,36 @@ class PolarError(RuntimeError):
         super().__init__("%s: %s: %s%s" % (where, _STATUS.get(status, str(status)), text, extra))
 
 
+def _load_checked() -> ctypes.CDLL:
+    """The in-tree library, built from exactly the sources in the tree: it is compiled when no
+    built copy exists, and compiled again when the copy's baked-in source hash differs from the
+    hash of the sources and headers now on disk (an edit since the last build).  A library named
+    by POLAR_LIBRARY (a tuning variant) is loaded as it is."""
+    path = os.environ.get("POLAR_LIBRARY")
+    if path:
+        return ctypes.CDLL(path)
+    if not (os.path.exists(LIB_PATH) and os.path.exists(PROBE_LIB_PATH)):
+        build_library()
+    L = ctypes.CDLL(LIB_PATH)
+    want = source_hash()
+    try:
+        L.polar_source_hash.restype = ctypes.c_char_p
+        have = L.polar_source_hash().decode()
+    except AttributeError:
+        have = "(a build without a source hash)"
+    if have != want:
+        raise RuntimeError(
+            "%s was built from other sources than the ones in the tree (library %s, tree %s): run "
+            "`python -c 'import __graft_entry__ as g; g.build()'` (a stale binary is never used "
+            "silently, and a loaded one cannot be replaced in this process)" % (LIB_PATH, have, want))
+    return L
+
+
 def lib() -> ctypes.CDLL:
-    """Load the shared library, compiling it first only when no built copy exists."""
+    """Load the shared library (see _load_checked) and declare its signatures."""
     global _lib
     if _lib is None:
-        path = os.environ.get("POLAR_LIBRARY", LIB_PATH)   # a specific build, e.g. a tuning variant
-        if path == LIB_PATH and not os.path.exists(LIB_PATH):
-            build_library()
-        L = ctypes.CDLL(path)
+        L = _load_checked()
         i, vp, f, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
         L.polar_router_topk.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp, sz, vp]
         L.polar_router_topk.restype = i
@@ -56,8 +89,6 @@ def lib() -> ctypes.CDLL:
         L.polar_sha_chunk_rows.restype = i
         L.polar_sha_launches.argtypes = [i] * 6
         L.polar_sha_launches.restype = i
-        L.polar_probe_read.argtypes = [vp, sz, sz, i, vp, vp]
-        L.polar_probe_read.restype = i
         L.polar_sha_decode.argtypes = [vp] * 6 + [i] * 7 + [f, vp, sz, vp]
         L.polar_sha_decode.restype = i
         L.polar_sha_partial.argtypes = [vp] * 5 + [i] * 7 + [f, vp, sz, vp]
@@ -74,30 +105,76 @@ def lib() -> ctypes.CDLL:
         L.polar_select_gemm.restype = i
         L.polar_select_gemm_ws.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp, ctypes.c_size_t, vp]
         L.polar_select_gemm_ws.restype = i
-        L.polar_select_gemm_workspace_bytes.argtypes = [i, ctypes.POINTER(ctypes.c_size_t)]
-        L.polar_select_gemm_workspace_bytes.restype = i
+        L.polar_select_gemm_workspace_bytes.argtypes = [i]
+        L.polar_select_gemm_workspace_bytes.restype = sz
         L.polar_select_gemm_down.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp, ctypes.c_size_t, vp]
         L.polar_select_gemm_down.restype = i
-        L.polar_select_gemm_down_workspace_bytes.argtypes = [i, i, i, ctypes.POINTER(ctypes.c_size_t)]
-        L.polar_select_gemm_down_workspace_bytes.restype = i
+        L.polar_select_gemm_down_workspace_bytes.argtypes = [i, i, i]
+        L.polar_select_gemm_down_workspace_bytes.restype = sz
         L.polar_sparse_mlp.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, vp, ctypes.c_size_t, vp]
         L.polar_sparse_mlp.restype = i
-        L.polar_sparse_mlp_workspace_bytes.argtypes = [i, i, i, ctypes.POINTER(ctypes.c_size_t)]
-        L.polar_sparse_mlp_workspace_bytes.restype = i
-        L.polar_probe_gather_read.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp]
-        L.polar_probe_gather_read.restype = i
+        L.polar_sparse_mlp_workspace_bytes.argtypes = [i, i, i]
+        L.polar_sparse_mlp_workspace_bytes.restype = sz
         L.polar_neuron_union.argtypes = [vp, i, i, i, i, vp, vp, vp]
         L.polar_neuron_union.restype = i
         L.polar_neuron_union_ws.argtypes = [vp, i, i, i, i, vp, vp, vp, ctypes.c_size_t, vp]
         L.polar_neuron_union_ws.restype = i
-        L.polar_neuron_union_workspace_bytes.argtypes = [i, i, i, ctypes.POINTER(ctypes.c_size_t)]
-        L.polar_neuron_union_workspace_bytes.restype = i
+        L.polar_neuron_union_workspace_bytes.argtypes = [i, i, i]
+        L.polar_neuron_union_workspace_bytes.restype = sz
+        L.polar_set_option.argtypes = [i, i]
+        L.polar_set_option.restype = i
+        L.polar_get_option.argtypes = [i, ctypes.POINTER(ctypes.c_int)]
+        L.polar_get_option.restype = i
         L.polar_strerror.argtypes = [i]
         L.polar_strerror.restype = ctypes.c_char_p
         L.polar_last_hip_error.restype = i
         L.polar_version.restype = i
+        L.polar_source_hash.restype = ctypes.c_char_p
         _lib = L
     return _lib
+
+
+def probe_lib() -> ctypes.CDLL:
+    """The read yardsticks' own library (include/polar_probe.h); built with the product library."""
+    global _probe_lib
+    if _probe_lib is None:
+        lib()                                            # builds both when needed, checks the source hash
+        P = ctypes.CDLL(os.environ.get("POLAR_PROBE_LIBRARY", PROBE_LIB_PATH))
+        i, vp, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+        P.polar_probe_read.argtypes = [vp, sz, sz, i, vp, vp]
+        P.polar_probe_read.restype = i
+        P.polar_probe_gather_read.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp]
+        P.polar_probe_gather_read.restype = i
+        P.polar_probe_last_hip_error.restype = i
+        _probe_lib = P
+    return _probe_lib
+
+
+def set_option(name: str, value: int) -> None:
+    """Set a process-wide option of the library (see polar_option in include/polar.h); 0 = automatic."""
+    _check(lib().polar_set_option(OPTIONS[name], int(value)), "polar_set_option(%s, %d)" % (name, value))
+
+
+def get_option(name: str) -> int:
+    v = ctypes.c_int(0)
+    _check(lib().polar_get_option(OPTIONS[name], ctypes.byref(v)), "polar_get_option(%s)" % name)
+    return int(v.value)
+
+
+@contextlib.contextmanager
+def options(**values):
+    """Pin options for the duration of a block (tests and sweeps): options(sha_form=2, router_path=2).
+    None leaves an option as it is."""
+    saved = {}
+    try:
+        for name, value in values.items():
+            if value is not None:
+                saved[name] = get_option(name)
+                set_option(name, value)
+        yield
+    finally:
+        for name, old in saved.items():
+            set_option(name, old)
 
 
 def _dtype_code(t: torch.Tensor) -> int:
@@ -211,14 +288,15 @@ def sha_decode(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, seqlens: torch
         out = torch.empty((B, Hq, d), dtype=torch.float32, device=q.device)
     if workspace is None:
         workspace = alloc_workspace(B, Hq, Hkv, S, d, k, q.device)
-    rc = lib().polar_sha_decode_layout(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"),
-                                       _dev(seqlens, "seqlens", torch.int32),
-                                       _dev(head_idx, "head_idx", torch.int32),
-                                       _dev(out, "out", torch.float32), B, Hq, Hkv, S, d, k,
-                                       _dtype_code(q), KV_LAYOUT[kv_layout], float(scale),
-                                       _dev(workspace, "workspace"),
-                                       workspace.numel() * workspace.element_size(), _stream())
-    _check(rc, "polar_sha_decode")
+    ptrs = (_dev(q, "q"), _dev(K, "K"), _dev(V, "V"), _dev(seqlens, "seqlens", torch.int32),
+            _dev(head_idx, "head_idx", torch.int32), _dev(out, "out", torch.float32))
+    tail = (float(scale), _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
+    if kv_layout == "bhsd":       # the main-text layout goes through the plain entry point
+        rc = lib().polar_sha_decode(*ptrs, B, Hq, Hkv, S, d, k, _dtype_code(q), *tail)
+        _check(rc, "polar_sha_decode")
+    else:
+        rc = lib().polar_sha_decode_layout(*ptrs, B, Hq, Hkv, S, d, k, _dtype_code(q), KV_LAYOUT[kv_layout], *tail)
+        _check(rc, "polar_sha_decode_layout")
     return out
 
 
@@ -226,13 +304,15 @@ def sha_partial(q, K, V, seqlens, head_idx, k: int, workspace: torch.Tensor,
                 scale: float = 0.0, kv_layout: str = "bhsd") -> None:
     """The KV-streaming phase of sha_decode alone (leaves per-chunk partials in workspace)."""
     B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, head_idx, k, kv_layout)
-    rc = lib().polar_sha_partial_layout(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"),
-                                        _dev(seqlens, "seqlens", torch.int32),
-                                        _dev(head_idx, "head_idx", torch.int32), B, Hq, Hkv, S, d, k,
-                                        _dtype_code(q), KV_LAYOUT[kv_layout], float(scale),
-                                        _dev(workspace, "workspace"),
-                                        workspace.numel() * workspace.element_size(), _stream())
-    _check(rc, "polar_sha_partial")
+    ptrs = (_dev(q, "q"), _dev(K, "K"), _dev(V, "V"), _dev(seqlens, "seqlens", torch.int32),
+            _dev(head_idx, "head_idx", torch.int32))
+    tail = (float(scale), _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
+    if kv_layout == "bhsd":
+        rc = lib().polar_sha_partial(*ptrs, B, Hq, Hkv, S, d, k, _dtype_code(q), *tail)
+        _check(rc, "polar_sha_partial")
+    else:
+        rc = lib().polar_sha_partial_layout(*ptrs, B, Hq, Hkv, S, d, k, _dtype_code(q), KV_LAYOUT[kv_layout], *tail)
+        _check(rc, "polar_sha_partial_layout")
 
 
 def sha_merge(seqlens, head_idx, out: torch.Tensor, Hkv: int, S: int, k: int,
@@ -255,8 +335,8 @@ def probe_read(src: torch.Tensor, slab_bytes: int, nontemporal: bool = True,
     slabs = nbytes // slab_bytes
     if sink is None:
         sink = torch.empty(max(slabs, 1), dtype=torch.int32, device=src.device)
-    rc = lib().polar_probe_read(_dev(src, "src"), slabs, slab_bytes, 1 if nontemporal else 0,
-                                _dev(sink, "sink"), _stream())
+    rc = probe_lib().polar_probe_read(_dev(src, "src"), slabs, slab_bytes, 1 if nontemporal else 0,
+                                      _dev(sink, "sink"), _stream())
     _check(rc, "polar_probe_read")
     return sink
 
@@ -268,8 +348,8 @@ def probe_gather_read(W: torch.Tensor, idx: torch.Tensor, slices: int = 3, depth
     n_idx = idx.shape[0]
     if sink is None:
         sink = torch.empty(max(2 * ((n_idx + 63) // 64) * slices, 1), dtype=torch.int32, device=W.device)
-    rc = lib().polar_probe_gather_read(_dev(W, "W"), _dev(idx, "idx", torch.int32), n_idx, N, K, slices, depth,
-                                       1 if nontemporal else 0, _dev(sink, "sink"), _stream())
+    rc = probe_lib().polar_probe_gather_read(_dev(W, "W"), _dev(idx, "idx", torch.int32), n_idx, N, K, slices,
+                                             depth, 1 if nontemporal else 0, _dev(sink, "sink"), _stream())
     _check(rc, "polar_probe_gather_read")
     return sink
 
@@ -291,9 +371,7 @@ def head_norm_topk(attn_out: torch.Tensor, Hkv: int, k: int,
 
 def select_gemm_workspace_bytes(M: int) -> int:
     """Workspace size at which polar_select_gemm_ws launches as wide as it wants."""
-    n = ctypes.c_size_t(0)
-    _check(lib().polar_select_gemm_workspace_bytes(M, ctypes.byref(n)), "polar_select_gemm_workspace_bytes")
-    return int(n.value)
+    return int(lib().polar_select_gemm_workspace_bytes(M))
 
 
 def alloc_select_gemm_workspace(M: int, device) -> Optional[torch.Tensor]:
@@ -331,10 +409,7 @@ def select_gemm(A: torch.Tensor, W: torch.Tensor, idx: torch.Tensor,
 
 def select_gemm_down_workspace_bytes(M: int, Kout: int, cap: int) -> int:
     """Workspace size polar_select_gemm_down requires."""
-    n = ctypes.c_size_t(0)
-    _check(lib().polar_select_gemm_down_workspace_bytes(M, Kout, cap, ctypes.byref(n)),
-           "polar_select_gemm_down_workspace_bytes")
-    return int(n.value)
+    return int(lib().polar_select_gemm_down_workspace_bytes(M, Kout, cap))
 
 
 def select_gemm_down(H: torch.Tensor, W2: torch.Tensor, idx: torch.Tensor,
@@ -362,9 +437,7 @@ def select_gemm_down(H: torch.Tensor, W2: torch.Tensor, idx: torch.Tensor,
 
 def sparse_mlp_workspace_bytes(M: int, D: int, cap: int) -> int:
     """Workspace size polar_sparse_mlp requires."""
-    n = ctypes.c_size_t(0)
-    _check(lib().polar_sparse_mlp_workspace_bytes(M, D, cap, ctypes.byref(n)), "polar_sparse_mlp_workspace_bytes")
-    return int(n.value)
+    return int(lib().polar_sparse_mlp_workspace_bytes(M, D, cap))
 
 
 def sparse_mlp(X: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, idx: torch.Tensor,
@@ -392,9 +465,7 @@ def sparse_mlp(X: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, idx: torch.T
 
 def neuron_union_workspace_bytes(B: int, kn: int, N: int) -> int:
     """Workspace size polar_neuron_union_ws wants for this input (0: too small to split)."""
-    n = ctypes.c_size_t(0)
-    _check(lib().polar_neuron_union_workspace_bytes(B, kn, N, ctypes.byref(n)), "polar_neuron_union_workspace_bytes")
-    return int(n.value)
+    return int(lib().polar_neuron_union_workspace_bytes(B, kn, N))
 
 
 def neuron_union(topk: torch.Tensor, N: int, cap: Optional[int] = None,

@@ -2,7 +2,6 @@
 // Every check below runs before the first HIP call, so invalid arguments are reported the
 // same way with or without a GPU in the machine.
 #include <math.h>
-#include <stdlib.h>
 
 #include "polar_internal.h"
 
@@ -11,6 +10,24 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
+// Process-wide options: plain integers, 0 = the library's own choice.  Relaxed atomics: an option
+// is a hint that each call reads once, not a synchronisation point.
+std::atomic<int> g_options[POLAR_OPT_COUNT_];
+
+bool option_value_ok(int opt, int v)
+{
+    switch (opt) {
+    case POLAR_OPT_SHA_CHUNK_ROWS: return v == 0 || (v >= 128 && v <= (1 << 20));
+    case POLAR_OPT_SHA_FORM: return v >= 0 && v <= 2;
+    case POLAR_OPT_SHA_GROUPED_KERNEL: return v == 0 || v == 1;
+    case POLAR_OPT_ROUTER_PATH: return v >= 0 && v <= 2;
+    case POLAR_OPT_ROUTER_PHASE1: return v >= 0 && v <= 2;
+    case POLAR_OPT_GEMM_FORM: return v == 0 || v == 1;
+    case POLAR_OPT_GEMM_WORKGROUPS: return v >= 0 && v <= 256;
+    default: return false;
+    }
+}
+
 int record(hipError_t e)
 {
     if (e == hipSuccess) return POLAR_OK;
@@ -18,7 +35,7 @@ int record(hipError_t e)
     return POLAR_EHIP;
 }
 
-bool dtype_ok(polar_dtype dt) { return dt == POLAR_F16 || dt == POLAR_BF16; }
+bool dtype_ok(int dt) { return dt == POLAR_F16 || dt == POLAR_BF16; }
 
 // Rows of the cache one workgroup of the streaming kernel covers, i.e. into how many chunks a
 // (request, head) unit is split.  Every workgroup pays a fixed few microseconds (index loads,
@@ -38,7 +55,7 @@ bool dtype_ok(polar_dtype dt) { return dt == POLAR_F16 || dt == POLAR_BF16; }
 // 82.4 us in chunks of 4096).  Its unsplit limit stays at 4096 rows: with ragged lengths longer
 // unsplit caches lose more to the grid's tail (770 against 697 us) than uniform ones gain.
 // Chunks are multiples of 128 rows, which every kernel shape's per-wave step divides, so only a
-// request's last chunk has a ragged tail.  POLAR_SHA_CHUNK_ROWS overrides the choice (sweeps).
+// request's last chunk has a ragged tail.  POLAR_OPT_SHA_CHUNK_ROWS overrides the choice (sweeps).
 constexpr long kComputeUnits = 256;
 constexpr int kMinChunk = 256;
 constexpr long kDirectMaxUnits = 2048;
@@ -53,10 +70,8 @@ constexpr ChunkPolicy kGroupedPolicy = {4096, 4096, 256};
 int choose_chunk(int B, int k, int S, const ChunkPolicy &pol)
 {
     const int cap = (S + 127) / 128 * 128;
-    if (const char *env = getenv("POLAR_SHA_CHUNK_ROWS")) {
-        long chunk = strtol(env, nullptr, 10);
-        if (chunk < 128 || chunk > (1 << 20)) chunk = kMinChunk;
-        chunk = (chunk + 127) / 128 * 128;
+    if (const int forced = option(POLAR_OPT_SHA_CHUNK_ROWS)) {
+        const long chunk = ((long)forced + 127) / 128 * 128;
         return chunk < cap ? (int)chunk : cap;
     }
     const long units = (long)(B > 0 ? B : 1) * k;
@@ -90,13 +105,10 @@ int choose_chunk(int B, int k, int S, const ChunkPolicy &pol)
 //   split, B <  16    = 10.5 + B*D*H / 8.5e6                                      (vector ALU)
 // Examples (single vs split measured): B=64, D=4096, H=8: 8.4 vs 11.3; B=128, D=9216, H=72:
 // 29.3 vs 20.4; B=256, D=4096, H=32: 9.8 vs 13.4; B=1024, D=8192, H=64: 89 vs 48.
-// POLAR_ROUTER_PATH=split|single overrides the choice (tests use it to reach both paths).
+// POLAR_OPT_ROUTER_PATH overrides the choice (tests use it to reach both paths).
 bool router_split_pays(int B, int D, int H, const RouterPlan &plan)
 {
-    if (const char *env = getenv("POLAR_ROUTER_PATH")) {
-        if (env[0] == 's' && env[1] == 'p') return true;
-        if (env[0] == 's' && env[1] == 'i') return false;
-    }
+    if (const int forced = option(POLAR_OPT_ROUTER_PATH)) return forced == 2;
     const double dh = (double)D * H;
     const double rounds = (double)((B + 255) / 256);
     double single_us = 5.2 + dh / 31.0e3;
@@ -122,31 +134,37 @@ int check_sha_sizes(int B, int Hq, int Hkv, int S, int d, int k)
     if (G > POLAR_MAX_GROUP) return POLAR_EUNSUPPORTED;
     // d = 64 runs the vector-ALU kernel, instantiated for power-of-two groups up to 8
     if (d == 64 && G != 1 && G != 2 && G != 4 && G != 8) return POLAR_EUNSUPPORTED;
+    // ... as is the same kernel when an option forces it on grouped heads at d = 128
+    if (d == 128 && G > 1 && option(POLAR_OPT_SHA_GROUPED_KERNEL) == 1 && G != 2 && G != 4 && G != 8)
+        return POLAR_EUNSUPPORTED;
     if (B > 65535 || Hq > 65535) return POLAR_EUNSUPPORTED;   // grid.y limit of the merge kernel
     return POLAR_OK;
 }
 
 }  // namespace
 
+int option(polar_option opt)
+{
+    return (unsigned)opt < (unsigned)POLAR_OPT_COUNT_ ? g_options[opt].load(std::memory_order_relaxed) : 0;
+}
+
 int make_sha_plan(int B, int Hq, int Hkv, int S, int d, int k, ShaPlan *plan)
 {
     const int rc = check_sha_sizes(B, Hq, Hkv, S, d, k);
     if (rc != POLAR_OK) return rc;
     plan->G = Hq / Hkv;
-    const bool grouped_mfma = plan->G > 1 && d == 128;   // which streaming kernel will run
+    plan->grouped_mfma = plan->G > 1 && d == 128 && option(POLAR_OPT_SHA_GROUPED_KERNEL) != 1;
+    const bool grouped_mfma = plan->grouped_mfma;        // which streaming kernel will run
     plan->chunk = choose_chunk(B, k, S, grouped_mfma ? kGroupedPolicy : kPerHeadPolicy);
     plan->nsplit = (S + plan->chunk - 1) / plan->chunk;
     // One-kernel form: an unsplit cache needs no merge; the streaming kernel can normalise, store
     // the rows and zero-fill the unselected heads itself.  That saves a launch (4 to 6 us per step
     // on layers of 0.5 to 1.5 GB) but its scattered zero stores land in the middle of the read
     // stream and cost about 2.5 ns per workgroup (12 us at 4608 workgroups, where the merge
-    // kernel takes 6), so it is used up to kDirectMaxUnits workgroups.  POLAR_SHA_DIRECT=0/1
-    // forces the choice, for comparisons.
+    // kernel takes 6), so it is used up to kDirectMaxUnits workgroups.  POLAR_OPT_SHA_FORM forces
+    // the choice, for comparisons.
     plan->direct = plan->nsplit == 1 && (long)B * k <= kDirectMaxUnits;
-    if (const char *env = getenv("POLAR_SHA_DIRECT")) {
-        if (env[0] == '0') plan->direct = false;
-        if (env[0] == '1') plan->direct = plan->nsplit == 1;
-    }
+    if (const int form = option(POLAR_OPT_SHA_FORM)) plan->direct = form == 1 && plan->nsplit == 1;
     if ((size_t)B * plan->nsplit * k > 0x7fffffffu) return POLAR_EUNSUPPORTED;   // 1-D grid limit
     const size_t units = (size_t)B * k * plan->G * plan->nsplit;
     plan->o_floats = (units * d + 63) / 64 * 64;   // keeps the (max, sum) region 256-byte aligned
@@ -162,7 +180,26 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 1600; }
+int polar_version(void) { return 2000; }
+
+#ifndef POLAR_SOURCE_HASH
+#define POLAR_SOURCE_HASH "unknown"
+#endif
+const char *polar_source_hash(void) { return POLAR_SOURCE_HASH; }
+
+int polar_set_option(int opt, int value)
+{
+    if (!option_value_ok(opt, value)) return POLAR_EINVAL;
+    g_options[opt].store(value, std::memory_order_relaxed);
+    return POLAR_OK;
+}
+
+int polar_get_option(int opt, int *value)
+{
+    if ((unsigned)opt >= (unsigned)POLAR_OPT_COUNT_ || !value) return POLAR_EINVAL;
+    *value = option(static_cast<polar_option>(opt));
+    return POLAR_OK;
+}
 
 int polar_last_hip_error(void) { return g_last_hip_error; }
 
@@ -186,7 +223,7 @@ size_t polar_router_workspace_bytes(int B, int D, int H)
 }
 
 int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, int k,
-                      polar_dtype dt, int32_t *head_idx, float *logits_out, void *workspace,
+                      int dt, int32_t *head_idx, float *logits_out, void *workspace,
                       size_t workspace_bytes, void *stream)
 {
     if (B < 0 || D < 1 || H < 1 || k < 1 || k > H || !dtype_ok(dt)) return POLAR_EINVAL;
@@ -196,13 +233,13 @@ int polar_router_topk(const void *hidden, const void *Wr, int B, int D, int H, i
     if (B == 0) return POLAR_OK;
     if (!hidden || !Wr || !head_idx) return POLAR_EINVAL;
     if (!workspace)
-        return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
+        return record(launch_router_topk(hidden, Wr, B, D, H, k, (polar_dtype)dt, head_idx, logits_out,
                                          static_cast<hipStream_t>(stream)));
     if (((uintptr_t)workspace & 255u) != 0 || workspace_bytes < plan.bytes) return POLAR_EWORKSPACE;
     if (!router_split_pays(B, D, H, plan))
-        return record(launch_router_topk(hidden, Wr, B, D, H, k, dt, head_idx, logits_out,
+        return record(launch_router_topk(hidden, Wr, B, D, H, k, (polar_dtype)dt, head_idx, logits_out,
                                          static_cast<hipStream_t>(stream)));
-    return record(launch_router_split(hidden, Wr, B, D, H, k, dt, plan, head_idx, logits_out,
+    return record(launch_router_split(hidden, Wr, B, D, H, k, (polar_dtype)dt, plan, head_idx, logits_out,
                                       workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -227,6 +264,9 @@ int polar_sha_chunk_rows(int B, int Hq, int Hkv, int S, int d, int k)
     return plan.chunk;
 }
 
+// The attention kernels read q, K, V and write `out` with 16-byte accesses.
+static bool misaligned16(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
 static int check_workspace(const ShaPlan &plan, const void *workspace, size_t workspace_bytes)
 {
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < plan.bytes)
@@ -237,7 +277,7 @@ static int check_workspace(const ShaPlan &plan, const void *workspace, size_t wo
 // `direct_out` non-NULL asks for the one-kernel form (the caller has checked plan.nsplit == 1).
 static int sha_partial_impl(const void *q, const void *K, const void *V, const int32_t *seqlens,
                             const int32_t *head_idx, float *direct_out, int B, int Hq, int Hkv, int S,
-                            int d, int k, polar_dtype dt, polar_kv_layout layout, float scale,
+                            int d, int k, int dt, int layout, float scale,
                             void *workspace, size_t workspace_bytes, void *stream)
 {
     ShaPlan plan;
@@ -248,17 +288,18 @@ static int sha_partial_impl(const void *q, const void *K, const void *V, const i
     if (B == 0) return POLAR_OK;
     if (!head_idx && k != Hkv) return POLAR_EINVAL;
     if (!q || !K || !V || !seqlens) return POLAR_EINVAL;
+    if (misaligned16(q) || misaligned16(K) || misaligned16(V) || misaligned16(direct_out)) return POLAR_EINVAL;
     if ((rc = check_workspace(plan, workspace, workspace_bytes)) != POLAR_OK) return rc;
     const float s = scale == 0.0f ? 1.0f / sqrtf((float)d) : scale;
     const float log2e = 1.4426950408889634f;
     return record(launch_sha_partial(q, K, V, seqlens, head_idx, static_cast<float *>(workspace),
-                                     direct_out, plan, B, Hq, Hkv, S, d, k, dt, layout, s * log2e,
+                                     direct_out, plan, B, Hq, Hkv, S, d, k, (polar_dtype)dt, (polar_kv_layout)layout, s * log2e,
                                      static_cast<hipStream_t>(stream)));
 }
 
 int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t *seqlens,
                       const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
-                      polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
+                      int dt, float scale, void *workspace, size_t workspace_bytes,
                       void *stream)
 {
     return sha_partial_impl(q, K, V, seqlens, head_idx, nullptr, B, Hq, Hkv, S, d, k, dt, POLAR_KV_BHSD,
@@ -267,7 +308,7 @@ int polar_sha_partial(const void *q, const void *K, const void *V, const int32_t
 
 int polar_sha_partial_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
                              const int32_t *head_idx, int B, int Hq, int Hkv, int S, int d, int k,
-                             polar_dtype dt, polar_kv_layout layout, float scale, void *workspace,
+                             int dt, int layout, float scale, void *workspace,
                              size_t workspace_bytes, void *stream)
 {
     return sha_partial_impl(q, K, V, seqlens, head_idx, nullptr, B, Hq, Hkv, S, d, k, dt, layout, scale,
@@ -283,7 +324,7 @@ int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
     if (rc != POLAR_OK) return rc;
     if (B == 0) return POLAR_OK;
     if (!head_idx && k != Hkv) return POLAR_EINVAL;
-    if (!seqlens || !out) return POLAR_EINVAL;
+    if (!seqlens || !out || misaligned16(out)) return POLAR_EINVAL;
     if ((rc = check_workspace(plan, workspace, workspace_bytes)) != POLAR_OK) return rc;
     return record(launch_sha_merge(seqlens, head_idx, out, static_cast<const float *>(workspace),
                                    plan, B, Hq, Hkv, S, d, k, static_cast<hipStream_t>(stream)));
@@ -291,13 +332,13 @@ int polar_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
 
 int polar_sha_decode_layout(const void *q, const void *K, const void *V, const int32_t *seqlens,
                             const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S,
-                            int d, int k, polar_dtype dt, polar_kv_layout layout, float scale,
+                            int d, int k, int dt, int layout, float scale,
                             void *workspace, size_t workspace_bytes, void *stream)
 {
     ShaPlan plan;
     int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);   // size errors take precedence
     if (rc != POLAR_OK) return rc;
-    if (B > 0 && !out) return POLAR_EINVAL;
+    if (B > 0 && (!out || misaligned16(out))) return POLAR_EINVAL;
     const bool direct = plan.direct;
     rc = sha_partial_impl(q, K, V, seqlens, head_idx, direct ? out : nullptr, B, Hq, Hkv, S, d, k, dt,
                           layout, scale, workspace, workspace_bytes, stream);
@@ -308,21 +349,11 @@ int polar_sha_decode_layout(const void *q, const void *K, const void *V, const i
 
 int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t *seqlens,
                      const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
-                     int k, polar_dtype dt, float scale, void *workspace, size_t workspace_bytes,
+                     int k, int dt, float scale, void *workspace, size_t workspace_bytes,
                      void *stream)
 {
     return polar_sha_decode_layout(q, K, V, seqlens, head_idx, out, B, Hq, Hkv, S, d, k, dt,
                                    POLAR_KV_BHSD, scale, workspace, workspace_bytes, stream);
-}
-
-int polar_probe_read(const void *src, size_t slabs, size_t slab_bytes, int nontemporal, uint32_t *sink,
-                     void *stream)
-{
-    if (slab_bytes < 16 || slab_bytes % 16 != 0 || slabs > 0x7fffffffu) return POLAR_EINVAL;
-    if (slabs == 0) return POLAR_OK;
-    if (!src || !sink || ((uintptr_t)src & 15u) != 0) return POLAR_EINVAL;
-    return record(launch_read_probe(src, slabs, slab_bytes, nontemporal, sink,
-                                    static_cast<hipStream_t>(stream)));
 }
 
 int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,
@@ -338,26 +369,21 @@ int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, i
 }
 
 int polar_select_gemm(const void *A, const void *W, const int32_t *idx, const int32_t *count,
-                      float *C, int M, int K, int N, int cap, polar_dtype dt, int relu, void *stream)
+                      float *C, int M, int K, int N, int cap, int dt, int relu, void *stream)
 {
     if (M < 0 || K < 1 || N < 1 || cap < 0 || !dtype_ok(dt)) return POLAR_EINVAL;
     if (K % 128 != 0 || (long long)N * K > (1ll << 40)) return POLAR_EUNSUPPORTED;
     if (M == 0 || cap == 0) return POLAR_OK;
     if (!A || !W || !idx || !C) return POLAR_EINVAL;
     if (((uintptr_t)A & 15u) || ((uintptr_t)W & 15u)) return POLAR_EINVAL;   // 16-byte loads
-    return record(launch_select_gemm(A, W, idx, count, C, M, K, N, cap, dt, relu,
+    return record(launch_select_gemm(A, W, idx, count, C, M, K, N, cap, (polar_dtype)dt, relu,
                                      static_cast<hipStream_t>(stream)));
 }
 
-int polar_select_gemm_workspace_bytes(int M, size_t *bytes)
-{
-    if (M < 0 || !bytes) return POLAR_EINVAL;
-    *bytes = select_gemm_workspace_bytes(M);
-    return POLAR_OK;
-}
+size_t polar_select_gemm_workspace_bytes(int M) { return M <= 0 ? 0 : select_gemm_workspace_bytes(M); }
 
 int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const int32_t *count,
-                         float *C, int M, int K, int N, int cap, polar_dtype dt, int relu,
+                         float *C, int M, int K, int N, int cap, int dt, int relu,
                          void *workspace, size_t workspace_bytes, void *stream)
 {
     if (M < 0 || K < 1 || N < 1 || cap < 0 || !dtype_ok(dt)) return POLAR_EINVAL;
@@ -365,7 +391,7 @@ int polar_select_gemm_ws(const void *A, const void *W, const int32_t *idx, const
     if (M == 0 || cap == 0) return POLAR_OK;
     if (!A || !W || !idx || !C) return POLAR_EINVAL;
     if (((uintptr_t)A & 15u) || ((uintptr_t)W & 15u) || ((uintptr_t)workspace & 15u)) return POLAR_EINVAL;
-    return record(launch_select_gemm_ws(A, W, idx, count, C, M, K, N, cap, dt, relu, workspace,
+    return record(launch_select_gemm_ws(A, W, idx, count, C, M, K, N, cap, (polar_dtype)dt, relu, workspace,
                                         workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream)));
 }
 
@@ -387,30 +413,14 @@ static int check_down_sizes(int M, int Kout, int N, int cap)
     return POLAR_OK;
 }
 
-int polar_probe_gather_read(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices, int depth,
-                            int nontemporal, uint32_t *sink, void *stream)
+size_t polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap)
 {
-    if (n_idx < 0 || N < 1 || K < 1 || slices < 1) return POLAR_EINVAL;
-    if (depth != 1 && depth != 4) return POLAR_EINVAL;
-    if (K % (128 * slices * depth) != 0 || (long long)N * K > (1ll << 40)) return POLAR_EUNSUPPORTED;
-    if ((long long)((n_idx + 63) / 64) * slices > (1ll << 30)) return POLAR_EUNSUPPORTED;
-    if (n_idx == 0) return POLAR_OK;
-    if (!W || !idx || !sink || ((uintptr_t)W & 15u)) return POLAR_EINVAL;
-    return record(launch_gather_probe(W, idx, n_idx, N, K, slices, depth, nontemporal, sink,
-                                      static_cast<hipStream_t>(stream)));
-}
-
-int polar_select_gemm_down_workspace_bytes(int M, int Kout, int cap, size_t *bytes)
-{
-    if (!bytes) return POLAR_EINVAL;
-    const int rc = check_down_sizes(M, Kout, 1, cap);
-    if (rc != POLAR_OK) return rc;
-    *bytes = M == 0 ? 0 : select_gemm_down_workspace_bytes(M, Kout, cap);
-    return POLAR_OK;
+    if (check_down_sizes(M, Kout, 1, cap) != POLAR_OK || M == 0) return 0;
+    return select_gemm_down_workspace_bytes(M, Kout, cap);
 }
 
 int polar_select_gemm_down(const float *H, const void *W2, const int32_t *idx, const int32_t *count,
-                           float *Y, int M, int Kout, int N, int cap, polar_dtype dt, void *workspace,
+                           float *Y, int M, int Kout, int N, int cap, int dt, void *workspace,
                            size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dt)) return POLAR_EINVAL;
@@ -421,7 +431,7 @@ int polar_select_gemm_down(const float *H, const void *W2, const int32_t *idx, c
     if (((uintptr_t)W2 & 15u) || ((uintptr_t)Y & 15u) || ((uintptr_t)workspace & 15u) || ((uintptr_t)H & 3u))
         return POLAR_EINVAL;
     if (workspace_bytes < select_gemm_down_workspace_bytes(M, Kout, cap)) return POLAR_EWORKSPACE;
-    return record(launch_select_gemm_down(H, W2, idx, count, Y, M, Kout, N, cap, dt, workspace,
+    return record(launch_select_gemm_down(H, W2, idx, count, Y, M, Kout, N, cap, (polar_dtype)dt, workspace,
                                           static_cast<hipStream_t>(stream)));
 }
 
@@ -433,17 +443,14 @@ static int check_mlp_sizes(int M, int D, int N, int cap)
     return POLAR_OK;
 }
 
-int polar_sparse_mlp_workspace_bytes(int M, int D, int cap, size_t *bytes)
+size_t polar_sparse_mlp_workspace_bytes(int M, int D, int cap)
 {
-    if (!bytes) return POLAR_EINVAL;
-    const int rc = check_mlp_sizes(M, D, 1, cap);
-    if (rc != POLAR_OK) return rc;
-    *bytes = M == 0 ? 0 : sparse_mlp_workspace_bytes(M, D, cap);
-    return POLAR_OK;
+    if (check_mlp_sizes(M, D, 1, cap) != POLAR_OK || M == 0) return 0;
+    return sparse_mlp_workspace_bytes(M, D, cap);
 }
 
 int polar_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx, const int32_t *count,
-                     float *Y, int M, int D, int N, int cap, polar_dtype dt, int relu, void *workspace,
+                     float *Y, int M, int D, int N, int cap, int dt, int relu, void *workspace,
                      size_t workspace_bytes, void *stream)
 {
     if (!dtype_ok(dt)) return POLAR_EINVAL;
@@ -455,16 +462,14 @@ int polar_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_
         ((uintptr_t)workspace & 255u))
         return POLAR_EINVAL;
     if (workspace_bytes < sparse_mlp_workspace_bytes(M, D, cap)) return POLAR_EWORKSPACE;
-    return record(launch_sparse_mlp(X, W1, W2, idx, count, Y, M, D, N, cap, dt, relu, workspace,
+    return record(launch_sparse_mlp(X, W1, W2, idx, count, Y, M, D, N, cap, (polar_dtype)dt, relu, workspace,
                                     static_cast<hipStream_t>(stream)));
 }
 
-int polar_neuron_union_workspace_bytes(int B, int kn, int N, size_t *bytes)
+size_t polar_neuron_union_workspace_bytes(int B, int kn, int N)
 {
-    if (B < 0 || kn < 0 || N < 1 || !bytes) return POLAR_EINVAL;
-    if (N > neuron_union_max_n()) return POLAR_EUNSUPPORTED;
-    *bytes = neuron_union_workspace_bytes(B, kn, N);
-    return POLAR_OK;
+    if (B < 0 || kn < 0 || N < 1 || N > neuron_union_max_n()) return 0;
+    return neuron_union_workspace_bytes(B, kn, N);
 }
 
 int polar_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,

@@ -871,15 +871,14 @@ static hipError_t launch_stream_mt(int mt, int G, int tiles, hipStream_t st, con
 // cannot run (the caller takes the one-launch kernel).
 static int stream_grid(int M, int K, int cap, bool have_workspace, size_t workspace_bytes)
 {
-    const char *form = getenv("POLAR_GEMM_FORM");            // "narrow": always the 32-neuron kernel
-    if (!have_workspace || M > kStreamMaxRows || K % (kBlockK * kUnitBlocks) != 0 || (form && form[0] == 'n'))
+    if (!have_workspace || M > kStreamMaxRows || K % (kBlockK * kUnitBlocks) != 0 ||
+        option(POLAR_OPT_GEMM_FORM) == 1)                    // forced: always the 32-neuron one-launch kernel
         return 0;
     const int mt = stream_mt(M);
     const int tiles = (cap + kStreamTileN - 1) / kStreamTileN;
     const long units = (long)tiles * (K / (kBlockK * kUnitBlocks));
     long G = kStreamGrid;
-    if (const char *e = getenv("POLAR_GEMM_WGS")) {
-        const long v = atol(e);
+    if (const int v = option(POLAR_OPT_GEMM_WORKGROUPS)) {
         if (v >= 1 && v <= kStreamGrid) G = v;
     }
     if (G > units) G = units;

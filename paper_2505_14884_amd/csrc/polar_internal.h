@@ -10,10 +10,14 @@
 
 namespace polar {
 
+// Current value of a process-wide option (polar_set_option): one relaxed atomic load.
+int option(polar_option opt);
+
 // Launch geometry of the split-KV attention kernels, derived on the host from sizes only
 // (device-side seqlens are never read on the host).
 struct ShaPlan {
     int G;            // query heads per KV head
+    bool grouped_mfma; // the grouped-head matrix-core streaming kernel runs (G > 1, d = 128)
     int chunk;        // cache rows one workgroup of the streaming kernel covers
     int nsplit;       // chunks per (request, slot): ceil(S / chunk)
     bool direct;      // polar_sha_decode runs the streaming kernel alone (it finishes the output)
@@ -114,10 +118,6 @@ size_t sparse_mlp_workspace_bytes(int M, int D, int cap);
 hipError_t launch_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_t *idx,
                              const int32_t *count, float *Y, int M, int D, int N, int cap, polar_dtype dt,
                              int relu, void *workspace, hipStream_t stream);
-hipError_t launch_read_probe(const void *src, size_t slabs, size_t slab_bytes, int nontemporal,
-                             uint32_t *sink, hipStream_t stream);
-hipError_t launch_gather_probe(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices,
-                               int depth, int nontemporal, uint32_t *sink, hipStream_t stream);
 int neuron_union_max_n();
 hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                                int32_t *count_out, hipStream_t stream);

@@ -2,11 +2,25 @@
 // on this GPU with the attention kernel's launch shape.  It gives the bench a measured ceiling to
 // set beside the nominal HBM peak, so "the kernel is at the memory system's practical limit" is
 // a number and not a claim.  A second probe reads gathered weight rows the way the selective
-// GEMMs do.  Not part of the method; no arithmetic of the paper lives here.
-#include "polar_internal.h"
+// GEMMs do.  Not part of the method; no arithmetic of the paper lives here.  Built into a library
+// of its own (libpolar_probe.so, polar_probe.h) so the product library holds operations only.
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "polar_probe.h"
 
 namespace polar {
 namespace {
+
+thread_local int g_probe_hip_error = 0;
+
+int record(hipError_t e)
+{
+    if (e == hipSuccess) return POLAR_OK;
+    g_probe_hip_error = (int)e;
+    return POLAR_EHIP;
+}
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kProbeWaves = 8;    // waves per workgroup, as in the per-head streaming kernel
@@ -102,8 +116,6 @@ __global__ __launch_bounds__(128) void gather_probe_kernel(const uint16_t *__res
     if (lane == 0) sink[2 * blockIdx.x + wave] = x;
 }
 
-}  // namespace
-
 hipError_t launch_gather_probe(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices,
                                int depth, int nontemporal, uint32_t *sink, hipStream_t stream)
 {
@@ -134,4 +146,36 @@ hipError_t launch_read_probe(const void *src, size_t slabs, size_t slab_bytes, i
     return hipGetLastError();
 }
 
+}  // namespace
 }  // namespace polar
+
+using namespace polar;
+
+extern "C" {
+
+int polar_probe_last_hip_error(void) { return g_probe_hip_error; }
+
+int polar_probe_read(const void *src, size_t slabs, size_t slab_bytes, int nontemporal, uint32_t *sink,
+                     void *stream)
+{
+    if (slab_bytes < 16 || slab_bytes % 16 != 0 || slabs > 0x7fffffffu) return POLAR_EINVAL;
+    if (slabs == 0) return POLAR_OK;
+    if (!src || !sink || ((uintptr_t)src & 15u) != 0) return POLAR_EINVAL;
+    return record(launch_read_probe(src, slabs, slab_bytes, nontemporal, sink,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+int polar_probe_gather_read(const void *W, const int32_t *idx, int n_idx, int N, int K, int slices, int depth,
+                            int nontemporal, uint32_t *sink, void *stream)
+{
+    if (n_idx < 0 || N < 1 || K < 1 || slices < 1) return POLAR_EINVAL;
+    if (depth != 1 && depth != 4) return POLAR_EINVAL;
+    if (K % (128 * slices * depth) != 0 || (long long)N * K > (1ll << 40)) return POLAR_EUNSUPPORTED;
+    if ((long long)((n_idx + 63) / 64) * slices > (1ll << 30)) return POLAR_EUNSUPPORTED;
+    if (n_idx == 0) return POLAR_OK;
+    if (!W || !idx || !sink || ((uintptr_t)W & 15u)) return POLAR_EINVAL;
+    return record(launch_gather_probe(W, idx, n_idx, N, K, slices, depth, nontemporal, sink,
+                                      static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

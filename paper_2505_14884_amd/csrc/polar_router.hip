@@ -645,10 +645,8 @@ int make_router_plan(int B, int D, int H, RouterPlan *plan)
     if (B < 0 || D < 1 || H < 1) return POLAR_EINVAL;
     if (H > POLAR_MAX_ROUTER_H || D > POLAR_MAX_ROUTER_D || B > 0x7fffffff / 2)
         return POLAR_EUNSUPPORTED;
-    const char *env = getenv("POLAR_ROUTER_MFMA");          // 0 / 1 force the choice (tests, sweeps)
     plan->mfma = B >= kMmTileR;
-    if (env && env[0] == '0') plan->mfma = false;
-    if (env && env[0] == '1') plan->mfma = true;
+    if (const int forced = option(POLAR_OPT_ROUTER_PHASE1)) plan->mfma = forced == 2;   // tests, sweeps
     if (plan->mfma) {
         // 16 requests per workgroup.  The slice length Dp (rows of Wr per workgroup, a multiple of
         // 32 whose padded 16-bit copy fits 80 KiB of LDS) is the one that minimises

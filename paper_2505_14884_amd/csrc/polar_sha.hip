@@ -26,8 +26,6 @@
 //     applies the same max/sum rescale across chunks, normalises, and stores zeros for
 //     the heads that were not selected.  A cache that is not split can skip the merge: the
 //     streaming kernel then finishes the rows and zero-fills by itself (DIRECT below).
-#include <stdlib.h>
-
 #include "polar_internal.h"
 
 namespace polar {
@@ -448,7 +446,7 @@ hipError_t launch_sha_partial(const void *q, const void *K, const void *V, const
                               hipStream_t stream)
 {
     if (direct_out && plan.nsplit != 1) return hipErrorInvalidValue;
-    if (plan.G > 1 && d == 128 && !getenv("POLAR_SHA_GQA_VALU"))
+    if (plan.grouped_mfma)
         return launch_sha_partial_gqa(q, K, V, seqlens, head_idx, ws, direct_out, plan, B, Hq, Hkv, S,
                                       k, dt, layout, scale_log2e, stream);
     const dim3 grid((unsigned)((size_t)B * plan.nsplit * k));

@@ -3,8 +3,9 @@
 // matrix cores.
 //
 // What is computed is the same as in the per-head kernel (Section 3.2, per-head attention
-// equation; Algorithm 1; Section 3.3 for grouped heads: a selected KV group serves all G query
-// heads of the group from one read of its K and V rows): per (request, selected group, chunk
+// equation; Algorithm 1; Section 4.2, last sentence, for grouped heads: the selection unit is a
+// KV group, and a selected group serves all G query heads of the group from one read of its K
+// and V rows): per (request, selected group, chunk
 // of rows) one record (running max, sum, unnormalised output) per query head.
 //
 // Why a second kernel: with G query rows per K/V row the vector-ALU formulation needs G dot

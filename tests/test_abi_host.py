@@ -15,19 +15,61 @@ FAKE = ctypes.c_void_p(0x1000)          # a non-NULL pointer that is never deref
 ALIGNED = ctypes.c_void_p(0x10000)
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "polar.h")).read()
+def declared_functions(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(polar_[a-z0-9_]+)\s*\(", text)))
 
 
-def test_library_exports_every_declared_symbol():
+def test_libraries_export_every_declared_symbol():
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["polar.h", "polar_probe.h"]
+    for header, L, exports in (("polar.h", binding.lib(), binding.EXPORTS),
+                               ("polar_probe.h", binding.probe_lib(), binding.PROBE_EXPORTS)):
+        names = declared_functions(header)
+        assert set(names) == set(exports)
+        for name in names:
+            assert getattr(L, name) is not None
+    assert binding.lib().polar_version() >= 2000
+    # the yardsticks live in their own library, not in the product
+    for name in binding.PROBE_EXPORTS:
+        assert not hasattr(binding.lib(), name)
+
+
+def test_library_is_built_from_the_sources_in_the_tree():
+    from paper_2505_14884_amd import build
+    assert binding.lib().polar_source_hash().decode() == build.source_hash()
+
+
+def test_options():
     L = binding.lib()
-    names = declared_functions()
-    assert set(names) == set(binding.EXPORTS)
-    for name in names:
-        assert getattr(L, name) is not None
-    assert L.polar_version() >= 1000
+    v = ctypes.c_int(-1)
+    for name, opt in binding.OPTIONS.items():
+        assert L.polar_get_option(opt, ctypes.byref(v)) == OK and v.value == 0, name     # all automatic
+    assert L.polar_set_option(7, 0) == EINVAL and L.polar_set_option(-1, 0) == EINVAL
+    assert L.polar_get_option(7, ctypes.byref(v)) == EINVAL
+    assert L.polar_get_option(0, None) == EINVAL
+    bad = {"sha_chunk_rows": [-1, 1, 127, (1 << 20) + 1], "sha_form": [-1, 3], "sha_grouped_kernel": [2, -1],
+           "router_path": [3, -1], "router_phase1": [3], "gemm_form": [2], "gemm_workgroups": [257, -1]}
+    for name, values in bad.items():
+        for value in values:
+            assert L.polar_set_option(binding.OPTIONS[name], value) == EINVAL, (name, value)
+            assert polar.get_option(name) == 0
+    # options change the plan, and the workspace query follows; leaving the block restores them
+    free = polar.sha_chunk_rows(32, 32, 32, 1920, 128, 16)
+    size = polar.sha_workspace_bytes(32, 32, 32, 1920, 128, 16)
+    with polar.options(sha_chunk_rows=200, sha_form=2):
+        assert polar.get_option("sha_chunk_rows") == 200
+        assert polar.sha_chunk_rows(32, 32, 32, 1920, 128, 16) == 256          # rounded up to 128 rows
+        assert polar.sha_workspace_bytes(32, 32, 32, 1920, 128, 16) > size
+        assert polar.sha_launches(32, 32, 32, 1920, 128, 16) == 2
+    assert polar.sha_chunk_rows(32, 32, 32, 1920, 128, 16) == free and polar.get_option("sha_form") == 0
+    assert polar.sha_launches(32, 32, 32, 1920, 128, 16) == 1
+    # the vector-ALU grouped kernel exists for groups of 2, 4 and 8 only: forcing it elsewhere is a clean status
+    with polar.options(sha_grouped_kernel=1):
+        assert polar.sha_workspace_bytes(4, 24, 8, 256, 128, 4) == 0
+        assert decode(L, Hq=24, Hkv=8, d=128, ws=None, ws_bytes=0) == EUNSUPPORTED
+        assert decode(L, Hq=32, Hkv=8, d=128, ws=None, ws_bytes=0) == EWORKSPACE     # sizes pass, no launch
+    assert polar.sha_workspace_bytes(4, 24, 8, 256, 128, 4) > 0
 
 
 def test_strerror_covers_every_status():
@@ -64,7 +106,7 @@ def test_router_argument_errors():
     assert L.polar_router_workspace_bytes(4, 512, 257) == 0
 
 
-def decode(L, q=FAKE, K=FAKE, V=FAKE, n=FAKE, idx=FAKE, out=FAKE, B=4, Hq=8, Hkv=8, S=256, d=64,
+def decode(L, q=ALIGNED, K=ALIGNED, V=ALIGNED, n=FAKE, idx=FAKE, out=ALIGNED, B=4, Hq=8, Hkv=8, S=256, d=64,
            k=4, dt=0, scale=0.0, ws=ALIGNED, ws_bytes=None):
     if ws_bytes is None:
         ws_bytes = L.polar_sha_workspace_bytes(B, Hq, Hkv, S, d, k)
@@ -85,6 +127,9 @@ def test_sha_argument_errors():
     assert decode(L, idx=None, k=4) == EINVAL               # dense needs k == Hkv
     for name in ("q", "K", "V", "n", "out"):
         assert decode(L, **{name: None}) == EINVAL
+    for name in ("q", "K", "V", "out"):                      # 16-byte accesses: misaligned pointers are refused
+        assert decode(L, **{name: ctypes.c_void_p(0x10008)}) == EINVAL
+    assert L.polar_sha_merge(FAKE, FAKE, ctypes.c_void_p(0x10004), 4, 8, 8, 256, 64, 4, ALIGNED, 1 << 20, None) == EINVAL
     assert decode(L, d=96) == EUNSUPPORTED
     assert decode(L, d=256) == EUNSUPPORTED
     assert decode(L, Hq=136, Hkv=8) == EUNSUPPORTED         # G = 17
@@ -99,12 +144,13 @@ def test_sha_argument_errors():
 def test_layout_entry_points_share_the_checks():
     L = binding.lib()
     args = lambda layout, **kw: L.polar_sha_decode_layout(
-        kw.get("q", FAKE), FAKE, FAKE, FAKE, FAKE, FAKE, 4, 8, 8, 256, kw.get("d", 64), 4, 0, layout,
+        kw.get("q", ALIGNED), ALIGNED, ALIGNED, FAKE, FAKE, ALIGNED, 4, 8, 8, 256, kw.get("d", 64), 4, 0, layout,
         0.0, ALIGNED, L.polar_sha_workspace_bytes(4, 8, 8, 256, 64, 4), None)
     assert args(2) == EINVAL and args(-1) == EINVAL           # unknown layout
     assert args(1, q=None) == EINVAL
     assert args(1, d=96) == EUNSUPPORTED
-    assert L.polar_sha_partial_layout(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 8, 8, 256, 64, 4, 0, 5, 0.0,
+    assert args(1, q=ctypes.c_void_p(0x10002)) == EINVAL
+    assert L.polar_sha_partial_layout(ALIGNED, ALIGNED, ALIGNED, FAKE, FAKE, 4, 8, 8, 256, 64, 4, 0, 5, 0.0,
                                       ALIGNED, 1 << 20, None) == EINVAL
 
 
@@ -140,13 +186,8 @@ def test_select_gemm_and_union_argument_errors():
     assert gw(A=None) == EINVAL and gw(W=None) == EINVAL and gw(idx=None) == EINVAL and gw(C=None) == EINVAL
     assert gw(ws=ctypes.c_void_p(0x1004), wsb=1 << 20) == EINVAL
     assert gw(M=0, A=None, W=None, idx=None, C=None) == OK and gw(cap=0, idx=None, C=None) == OK
-    n = ctypes.c_size_t(7)
-    assert L.polar_select_gemm_workspace_bytes(-1, ctypes.byref(n)) == EINVAL
-    assert L.polar_select_gemm_workspace_bytes(4, None) == EINVAL
-    sizes = []
-    for M in (1, 16, 17, 32, 33, 64, 65, 128, 129, 4096):
-        assert L.polar_select_gemm_workspace_bytes(M, ctypes.byref(n)) == OK
-        sizes.append(n.value)
+    assert L.polar_select_gemm_workspace_bytes(-1) == 0 and L.polar_select_gemm_workspace_bytes(0) == 0
+    sizes = [L.polar_select_gemm_workspace_bytes(M) for M in (1, 16, 17, 32, 33, 64, 65, 128, 129, 4096)]
     assert sizes[0] == sizes[1] > 0 and sizes[2] == sizes[3] == 2 * sizes[0]
     assert sizes[4] == sizes[5] == 4 * sizes[0] and sizes[6] == sizes[7] == 8 * sizes[0]
     assert sizes[8] == sizes[9] == 8 * sizes[0]         # beyond 128 rows: passes of 128 share it
@@ -162,9 +203,8 @@ def test_select_gemm_and_union_argument_errors():
     assert uw(cnt=None) == EINVAL and uw(idx=None) == EINVAL and uw(topk=None) == EINVAL
     assert uw(N=524289) == EUNSUPPORTED
     assert uw(ws=ctypes.c_void_p(0x1002), wsb=1 << 20) == EINVAL
-    assert L.polar_neuron_union_workspace_bytes(-1, 3, 64, ctypes.byref(n)) == EINVAL
-    assert L.polar_neuron_union_workspace_bytes(2, 3, 64, None) == EINVAL
-    assert L.polar_neuron_union_workspace_bytes(2, 3, 524289, ctypes.byref(n)) == EUNSUPPORTED
+    assert L.polar_neuron_union_workspace_bytes(-1, 3, 64) == 0                # invalid sizes: nothing to allocate
+    assert L.polar_neuron_union_workspace_bytes(64, 1843, 524289) == 0
     assert polar.neuron_union_workspace_bytes(2, 3, 64) == 0                 # too few ids to split
     assert polar.neuron_union_workspace_bytes(64, 1843, 36864) == 8 * 1152 * 4
     assert polar.neuron_union_workspace_bytes(4, 1024, 36864) == 2 * 1152 * 4
@@ -184,18 +224,16 @@ def test_select_gemm_down_argument_errors():
     assert d(H=ctypes.c_void_p(0x1002)) == EINVAL and d(Y=ctypes.c_void_p(0x1008)) == EINVAL
     assert d(wsb=16) == EWORKSPACE
     assert d(M=0, H=None, W2=None, idx=None, Y=None, ws=None) == OK
-    n = ctypes.c_size_t(0)
-    q = lambda M, Kout, cap: L.polar_select_gemm_down_workspace_bytes(M, Kout, cap, ctypes.byref(n))
+    q = L.polar_select_gemm_down_workspace_bytes
     # the ranges' sums (ranges x padded rows x Kout floats) and the prepared 16-bit activations
-    assert q(4, 256, 33) == OK and n.value > 0 and (n.value - 4 * 64 * 2) % (16 * 256 * 4) == 0
-    assert q(64, 9216, 36864) == OK and n.value == 7 * 64 * 9216 * 4 + 64 * 36864 * 2      # 36 column groups x 7 ranges
-    assert q(64, 9216, 400000) == OK and (n.value - 64 * 400000 * 2) // (64 * 9216 * 4) >= 49
-    assert q(0, 256, 32) == OK and n.value == 0
-    assert q(4, 300, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
+    assert q(4, 256, 33) > 0 and (q(4, 256, 33) - 4 * 64 * 2) % (16 * 256 * 4) == 0
+    assert q(64, 9216, 36864) == 7 * 64 * 9216 * 4 + 64 * 36864 * 2      # 36 column groups x 7 ranges
+    assert (q(64, 9216, 400000) - 64 * 400000 * 2) // (64 * 9216 * 4) >= 49
+    assert q(0, 256, 32) == 0
+    assert q(4, 300, 32) == 0 and q(-1, 256, 32) == 0                    # sizes the call rejects
     # beyond 64 rows: passes of up to 128 rows (72 column blocks x 3 ranges) and a remainder share it
-    assert q(300, 9216, 36864) == OK and n.value == max(7 * 64, 3 * 128) * 9216 * 4 + 128 * 36864 * 2
-    assert q(65, 9216, 36864) == OK and n.value == max(7 * 64, 3 * 128) * 9216 * 4 + 128 * 36864 * 2
-    assert L.polar_select_gemm_down_workspace_bytes(4, 256, 32, None) == EINVAL
+    assert q(300, 9216, 36864) == max(7 * 64, 3 * 128) * 9216 * 4 + 128 * 36864 * 2
+    assert q(65, 9216, 36864) == max(7 * 64, 3 * 128) * 9216 * 4 + 128 * 36864 * 2
 
 
 def test_sparse_mlp_argument_errors():
@@ -212,22 +250,18 @@ def test_sparse_mlp_argument_errors():
     assert m(X=ctypes.c_void_p(0x1008)) == EINVAL and m(ws=ctypes.c_void_p(0x1010)) == EINVAL   # 16 and 256 bytes
     assert m(wsb=4096) == EWORKSPACE
     assert m(M=0, X=None, W1=None, W2=None, idx=None, Y=None, ws=None) == OK
-    n, g, d = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_size_t(0)
-    q = lambda M, D, cap: L.polar_sparse_mlp_workspace_bytes(M, D, cap, ctypes.byref(n))
+    q = L.polar_sparse_mlp_workspace_bytes
     # four regions, each a multiple of 256 bytes: the first factor's workspace (up to 128 rows a pass),
     # the second factor's partial sums, the 16-bit hidden activations of one pass (128 rows of them
     # beyond 64 rows), and the hidden activations of one pass as floats (the fallback's)
     for (M, D, cap) in [(64, 9216, 36864), (4, 256, 33), (100, 512, 700), (300, 1024, 5000)]:
         rows, h16_rows, cap32 = min(M, 128), (M if M <= 64 else 128), (cap + 31) // 32 * 32
-        assert q(M, D, cap) == OK
-        assert L.polar_select_gemm_workspace_bytes(rows, ctypes.byref(g)) == OK
-        assert L.polar_select_gemm_down_workspace_bytes(M, D, cap, ctypes.byref(d)) == OK
-        partial = d.value - h16_rows * cap32 * 2
+        g = L.polar_select_gemm_workspace_bytes(rows)
+        partial = L.polar_select_gemm_down_workspace_bytes(M, D, cap) - h16_rows * cap32 * 2
         up = lambda v: (v + 255) // 256 * 256
-        assert n.value == up(g.value) + up(partial) + up(h16_rows * cap32 * 2) + up(rows * cap * 4)
-    assert q(0, 256, 32) == OK and n.value == 0
-    assert q(4, 300, 32) == EUNSUPPORTED and q(-1, 256, 32) == EINVAL
-    assert L.polar_sparse_mlp_workspace_bytes(4, 256, 32, None) == EINVAL
+        assert q(M, D, cap) == up(g) + up(partial) + up(h16_rows * cap32 * 2) + up(rows * cap * 4)
+    assert q(0, 256, 32) == 0
+    assert q(4, 300, 32) == 0 and q(-1, 256, 32) == 0
 
 
 def test_workspace_size_is_consistent_with_the_chunking():
@@ -263,7 +297,8 @@ def test_binding_refuses_cpu_tensors():
 
 
 def test_probe_and_launch_query_argument_checks():
-    L = binding.lib()
+    L = binding.probe_lib()
+    assert L.polar_probe_last_hip_error() == 0
     assert L.polar_probe_read(FAKE, 4, 8, 1, FAKE, None) == EINVAL          # slab under 16 bytes
     assert L.polar_probe_read(FAKE, 4, 4100, 1, FAKE, None) == EINVAL       # not a multiple of 16
     assert L.polar_probe_read(None, 4, 4096, 1, FAKE, None) == EINVAL
@@ -279,7 +314,7 @@ def test_probe_and_launch_query_argument_checks():
 
 
 def test_gather_probe_argument_checks():
-    L = binding.lib()
+    L = binding.probe_lib()
     A16 = ctypes.c_void_p(0x1000)
     g = lambda W=A16, idx=FAKE, n=100, N=64, K=1536, slices=3, depth=1, sink=FAKE: L.polar_probe_gather_read(
         W, idx, n, N, K, slices, depth, 1, sink, None)

@@ -4,9 +4,6 @@ Bar: head_idx bit-exact; attention output max-abs error <= 2e-3 (16-bit inputs, 
 accumulation); skipped heads exactly +0.0.  Inputs are seeded and synthetic, shaped like the
 configurations the bench uses.  Every case prints its name before it touches the GPU.
 """
-import contextlib
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -28,22 +25,32 @@ def host_bits(t):
     return wl.bits_u16(t)
 
 
-def check_against_oracle(w, q, K, V, seqlens, head_idx, out, rows=None):
-    """Compare `out` (GPU, float32 [B,Hq,d]) with the oracle for the requests in `rows`."""
+def check_against_oracle(w, q, K, V, seqlens, head_idx, out, rows=None, max_host_bytes=2 << 30):
+    """Compare `out` (GPU, float32 [B,Hq,d]) with the oracle, element by element, for the requests
+    in `rows` (default: every request).  Large batches go to the host a slice of requests at a
+    time, so that the host copy of K and V stays under max_host_bytes."""
     rows = list(range(w.B)) if rows is None else list(rows)
-    sel = torch.tensor(rows, device=q.device)
-    idx_host = None if head_idx is None else head_idx[sel].cpu().numpy()
-    want = orc.sha_decode(host_bits(q[sel]), host_bits(K[sel]), host_bits(V[sel]),
-                          seqlens[sel].cpu().numpy(), idx_host, w.k, w.dtype)
-    got = out[sel].cpu().numpy().astype(np.float64)
-    assert np.isfinite(got).all()
-    err = np.abs(got - want).max() if got.size else 0.0
-    say("   max-abs error %.3e over %d requests" % (err, len(rows)))
-    assert err <= TOL
-    # heads the oracle leaves at zero must be +0.0 bit for bit
-    zero = (want == 0.0).all(axis=2)
-    assert (out[sel].cpu().numpy().view(np.uint32)[zero] == 0).all()
-    return err
+    per_request = 2 * w.Hkv * w.S * w.d * 2
+    step = max(1, min(len(rows) or 1, max_host_bytes // per_request))
+    worst = 0.0
+    for r0 in range(0, len(rows), step):
+        sel = torch.tensor(rows[r0:r0 + step], device=q.device)
+        idx_host = None if head_idx is None else head_idx[sel].cpu().numpy()
+        want = orc.sha_decode(host_bits(q[sel]), host_bits(K[sel]), host_bits(V[sel]),
+                              seqlens[sel].cpu().numpy(), idx_host, w.k, w.dtype)
+        got32 = out[sel].cpu().numpy()
+        got = got32.astype(np.float64)
+        assert np.isfinite(got).all()
+        err = np.abs(got - want).max() if got.size else 0.0
+        assert err <= TOL, (err, rows[r0:r0 + step])
+        # heads the oracle leaves at zero must be +0.0 bit for bit
+        zero = (want == 0.0).all(axis=2)
+        assert (got32.view(np.uint32)[zero] == 0).all()
+        worst = max(worst, float(err))
+        if len(rows) > step:
+            say("   requests %d..%d: max-abs error %.3e" % (rows[r0], rows[min(r0 + step, len(rows)) - 1], err))
+    say("   max-abs error %.3e over %d requests" % (worst, len(rows)))
+    return worst
 
 
 def poison_unselected(w, q, K, V, head_idx):
@@ -57,27 +64,14 @@ def poison_unselected(w, q, K, V, head_idx):
     q.view(w.B, w.Hkv, w.G, w.d)[~keep] = float("nan")
 
 
-# (pass a workspace?, forced path, forced phase-1 kernel): without a workspace the one-kernel path
-# runs; with one the library picks the faster path for the shape unless POLAR_ROUTER_PATH forces the
-# split-D kernels, whose first phase runs on the vector ALU or (POLAR_ROUTER_MFMA) the matrix cores.
-ROUTER_MODES = [(False, None, None), (True, "split", "0"), (True, "split", "1"), (True, None, None)]
+# (pass a workspace?, router_path option, router_phase1 option): without a workspace the one-kernel
+# path runs; with one the library picks the faster path for the shape unless the option forces the
+# split-D kernels (2), whose first phase runs on the vector ALU (1) or the fp64 matrix cores (2).
+ROUTER_MODES = [(False, None, None), (True, 2, 1), (True, 2, 2), (True, None, None)]
 
 
-@contextlib.contextmanager
-def router_path(path, mfma=None):
-    saved = {}
-    for name, value in (("POLAR_ROUTER_PATH", path), ("POLAR_ROUTER_MFMA", mfma)):
-        if value is not None:
-            saved[name] = os.environ.get(name)
-            os.environ[name] = value
-    try:
-        yield
-    finally:
-        for name, old in saved.items():
-            if old is None:
-                del os.environ[name]
-            else:
-                os.environ[name] = old
+def router_path(path, phase1=None):
+    return polar.options(router_path=path, router_phase1=phase1)
 
 
 def run_router(w):
@@ -128,16 +122,14 @@ def test_config_full_parity(name):
 
 
 @pytest.mark.parametrize("name", ["C4_opt66b", "C5_ragged", "X1_gqa8_s8192"])
-def test_config_full_size_sampled_parity(name):
-    """Full-size launch exactly as the bench times it; the oracle recomputes a sample of
-    requests (shortest, longest and a few others), every other request is checked for
-    finiteness and for exact zeros on skipped heads."""
+def test_config_full_size_whole_batch_parity(name):
+    """Full-size launch exactly as the bench times it (same sizes, same plan, NaN-poisoned
+    padding and unselected heads); the oracle recomputes EVERY request, a slice of the batch at
+    a time, and every element and every skipped head's bit pattern is compared."""
     w = wl.CONFIGS.get(name) or wl.EXTRA_SHAPES[name]
     say("\ncase", name, w)
     head_idx = run_router(w)
-    seqlens = wl.make_seqlens(w, "cpu")
-    rows = sorted({int(seqlens.argmin()), int(seqlens.argmax()), 0, w.B // 3, w.B - 1})
-    out = run_attention(w, head_idx, rows=rows, poison=True)
+    out = run_attention(w, head_idx, poison=True)
     selected = torch.zeros((w.B, w.Hkv), dtype=torch.bool, device=DEV)
     selected[torch.arange(w.B, device=DEV)[:, None], head_idx.long()] = True
     skipped = ~selected.repeat_interleave(w.G, dim=1)
@@ -239,14 +231,9 @@ def test_sequence_major_cache_layout(name, dtype, G, d):
     del dense
 
 
-@contextlib.contextmanager
 def two_kernel_form():
     """Keep the streaming + merge pair even where an unsplit cache would take the one-kernel form."""
-    os.environ["POLAR_SHA_DIRECT"] = "0"
-    try:
-        yield
-    finally:
-        del os.environ["POLAR_SHA_DIRECT"]
+    return polar.options(sha_form=2)
 
 
 @pytest.mark.parametrize("dtype,Hkv,G,d,k,S", [("f16", 8, 1, 128, 3, 250), ("bf16", 6, 4, 128, 2, 256),
@@ -320,14 +307,10 @@ def test_random_shapes_against_the_oracle():
         poison_unselected(w, q, K, V, head_idx)
         Kc, Vc = (K, V) if layout == "bhsd" else (K.permute(0, 2, 1, 3).contiguous(),
                                                   V.permute(0, 2, 1, 3).contiguous())
-        if chunk:
-            os.environ["POLAR_SHA_CHUNK_ROWS"] = str(chunk)
-        try:
+        with polar.options(sha_chunk_rows=chunk or None):
             out = torch.full((B, w.Hq, d), float("nan"), dtype=torch.float32, device=DEV)
             polar.sha_decode(q, Kc, Vc, seqlens, head_idx, k, out=out, kv_layout=layout)
             torch.cuda.synchronize()
-        finally:
-            os.environ.pop("POLAR_SHA_CHUNK_ROWS", None)
         check_against_oracle(w, q, K, V, seqlens, head_idx, out)
 
 
@@ -394,11 +377,15 @@ def test_hip_graph_replays_match_eager():
 
 @pytest.mark.parametrize("name", ["C1_tiny", "C2_llama2_7b", "C3_llama3_8b_gqa"])
 def test_head_importance_labels(name):
-    """Labeller = dense attention + per-group output norm + top-k.  The GPU attention is
-    float, the oracle's is double, so a group whose score is within 1e-5 (relative) of the
-    selection boundary may legitimately fall on either side: labels must agree exactly
-    wherever the oracle's scores are separated by more than that, and every GPU label must be
-    valid under the oracle's scores up to that slack."""
+    """Labeller = dense attention + per-group output norm + top-k (Section 3.2 head-sparsity study,
+    Section 4.2 router targets).  Labels are index work, so the bar is bit-exact:
+    (1) the ranking kernel, fed the GPU's own dense attention output, must give on EVERY row the
+        labels the oracle's score and top-k routines give on those same float bits;
+    (2) end to end (oracle attention in double against GPU attention in float) the labels must be
+        identical on every row whose neighbouring oracle scores among the top k+1 differ by more
+        than the float attention's error can move them; rows with a nearer tie are counted and
+        reported, never accepted on a weaker check (they are covered by (1), and the attention
+        that feeds them by the parity tests above)."""
     w = wl.CONFIGS[name]
     say("\ncase labels", name)
     q, K, V, seqlens = wl.make_attention_inputs(w, DEV)
@@ -406,50 +393,36 @@ def test_head_importance_labels(name):
     norms = torch.empty((w.B, w.Hkv), dtype=torch.float32, device=DEV)
     got = polar.head_norm_topk(dense, w.Hkv, w.k, norms_out=norms).cpu().numpy()
     torch.cuda.synchronize()
+    # (1) same bits in, same labels out: the oracle ranks the GPU's float attention output
+    same_bits = dense.cpu().numpy().astype(np.float64)               # float -> double is exact
+    score_same, norm_same = orc.head_scores(same_bits, w.Hkv)
+    want_same = orc.topk(score_same, w.k)
+    assert np.array_equal(got, want_same), "labels differ from the oracle's on the same attention output"
+    np.testing.assert_allclose(norms.cpu().numpy(), norm_same, rtol=2e-7)
+    # (2) end to end
     want, score = orc.head_importance_labels(host_bits(q), host_bits(K), host_bits(V),
                                              seqlens.cpu().numpy(), w.k, w.dtype)
-    np.testing.assert_allclose(norms.cpu().numpy(), np.sqrt(score), rtol=2e-6)
-    slack = 1e-5
-    exact_rows = 0
-    for b in range(w.B):
-        srt = -np.sort(-score[b])
-        gaps = (srt[:-1] - srt[1:]) / srt[:-1]
-        if gaps[: w.k].min(initial=1.0) > slack:          # no near-tie touches the top-k order
-            assert got[b].tolist() == want[b].tolist(), b
-            exact_rows += 1
-        else:
-            s_got = score[b][got[b]]
-            assert len(set(got[b].tolist())) == w.k
-            assert (np.diff(s_got) <= slack * s_got[:-1]).all()            # descending up to slack
-            assert s_got.min() >= srt[w.k - 1] * (1 - slack)               # nothing better left out
-    say("   %d of %d rows compared exactly" % (exact_rows, w.B))
-    assert exact_rows >= w.B // 2
-    # fed with the same float attention output, the kernel is deterministic and its ranking
-    # matches a double-precision ranking of those very values
-    ss = (dense.double().reshape(w.B, w.Hkv, -1) ** 2).sum(dim=2).cpu().numpy()
-    gap_ok = np.array([(np.diff(-np.sort(-ss[b]))[: w.k] < 0).all() for b in range(w.B)])
-    ref = np.argsort(-ss, axis=1, kind="stable")[:, : w.k]
-    assert np.array_equal(got[gap_ok], ref[gap_ok].astype(np.int32))
+    srt = -np.sort(-score, axis=1)
+    top = srt[:, : min(w.k + 1, w.Hkv)]
+    gaps = (top[:, :-1] - top[:, 1:]) / top[:, :-1]
+    # a float attention output within 2e-6 relative of the double one moves a sum of squares by
+    # at most 4e-6 relative, hence neighbouring scores towards each other by at most 8e-6
+    separated = gaps.min(axis=1, initial=1.0) > 1e-5
+    assert np.array_equal(got[separated], want[separated])
+    differ = int((got != want).any(axis=1).sum())
+    say("   %d of %d rows have every top-(k+1) gap above 1e-5 and match exactly; %d rows hold a nearer tie; "
+        "%d rows differ from the double-precision labels; smallest relative gap %.2e"
+        % (int(separated.sum()), w.B, int((~separated).sum()), differ, gaps.min(initial=1.0)))
+    assert differ <= int((~separated).sum())
 
 
 # ----------------------------------------------------------------------------- selective GEMM
 GEMM_TOL = 1e-4      # float accumulation of K <= 9216 products whose sum is O(1): ~sqrt(K) * 2^-24 * |sum| ~ 1e-5
 
 
-@contextlib.contextmanager
 def gemm_workgroups(G):
     """Pin the launch width of the wide-tile GEMM form (None: the library's own)."""
-    saved = os.environ.get("POLAR_GEMM_WGS")
-    if G is not None:
-        os.environ["POLAR_GEMM_WGS"] = str(G)
-    try:
-        yield
-    finally:
-        if G is not None:
-            if saved is None:
-                del os.environ["POLAR_GEMM_WGS"]
-            else:
-                os.environ["POLAR_GEMM_WGS"] = saved
+    return polar.options(gemm_workgroups=G)
 
 
 def gemm_case(M, K, N, idx_host, dtype, relu, count=None, seed=0, ws=False, G=None, ws_bytes=None):
@@ -717,20 +690,9 @@ def test_sparsified_mlp_both_factors(B):
     assert torch.isfinite(y).all() and torch.equal(y, again)
 
 
-@contextlib.contextmanager
 def gemm_form(form):
     """Force the first factor's one-launch kernel ("narrow") or leave the choice to the library (None)."""
-    saved = os.environ.get("POLAR_GEMM_FORM")
-    if form is not None:
-        os.environ["POLAR_GEMM_FORM"] = form
-    try:
-        yield
-    finally:
-        if form is not None:
-            if saved is None:
-                del os.environ["POLAR_GEMM_FORM"]
-            else:
-                os.environ["POLAR_GEMM_FORM"] = saved
+    return polar.options(gemm_form=1 if form == "narrow" else None)
 
 
 def mlp_case(M, D, N, idx_host, dtype, count=None, relu=True, seed=0, form=None):
@@ -738,7 +700,8 @@ def mlp_case(M, D, N, idx_host, dtype, count=None, relu=True, seed=0, form=None)
     of additions) and against the oracle's two definitions applied one after the other.  The
     hidden activations are rounded to 16 bits between the factors; where the GPU's float sum and
     the oracle's double sum fall on different sides of a rounding boundary the hidden value differs
-    by one unit in the last place, which the tolerance allows for a few times per output."""
+    by one unit in the last place: those cases are counted, and the tolerance is widened by exactly
+    what they can contribute."""
     g = torch.Generator(device=DEV).manual_seed(4000 + seed)
     tdt = torch.float16 if dtype == "f16" else torch.bfloat16
     X = torch.randn((M, D), generator=g, device=DEV).to(tdt)
@@ -766,11 +729,26 @@ def mlp_case(M, D, N, idx_host, dtype, count=None, relu=True, seed=0, form=None)
     ids = np.array(idx_host[:live], np.int32)
     H = orc.select_gemm(host_bits(X), host_bits(W1), ids, dtype, relu)
     want = orc.select_gemm_down(H.astype(np.float32), host_bits(W2), ids, dtype)
-    ulp = 2.0 ** -10 if dtype == "f16" else 2.0 ** -7
-    tol = GEMM_TOL + 4 * ulp * (np.abs(H).max() if H.size else 0.0) * float(W2.abs().max())
+    # Where do the GPU's 16-bit hidden values differ from the oracle's?  `hidden` holds the float
+    # sums the GPU rounds (the two-call form is bit-identical to the one call); round both sides'
+    # values to the storage type on the host and count, per request, the neurons whose 16-bit
+    # value differs and by how much.  Each such neuron moves every output of its row by at most
+    # |difference| * max|W2 row|: that sum, not a guessed multiple of an ulp, widens the bound.
+    got_h16 = hidden[:, :live].to(tdt).float().cpu().numpy().astype(np.float64)
+    want_h16 = torch.from_numpy(H.astype(np.float32)).to(tdt).float().numpy().astype(np.float64)
+    valid = (ids >= 0) & (ids < N)
+    w2max = np.zeros(live)
+    if live:
+        w2max[valid] = W2[torch.from_numpy(ids[valid]).long().to(DEV)].abs().max(dim=1).values.float().cpu().numpy()
+    delta = np.abs(got_h16 - want_h16) * valid[None, :]
+    flips = int((delta > 0).sum())
+    allowance = float((delta * w2max[None, :]).sum(axis=1).max()) if live and M else 0.0
+    tol = GEMM_TOL + allowance
     err = np.abs(y.cpu().numpy() - want).max()
-    say("   M=%d D=%d N=%d cap=%d live=%d %s relu=%s form=%s: max-abs error %.3e (tolerance %.1e)"
-        % (M, D, N, cap, live, dtype, relu, form, err, tol))
+    say("   M=%d D=%d N=%d cap=%d live=%d %s relu=%s form=%s: max-abs error %.3e; %d of %d hidden values round "
+        "differently, worth at most %.2e per output (tolerance %.1e)"
+        % (M, D, N, cap, live, dtype, relu, form, err, flips, M * live, allowance, tol))
+    assert flips <= max(4, (M * live) // 50)           # rounding-boundary cases are rare, not the rule
     assert err <= tol
 
 
