@@ -172,6 +172,26 @@ int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t 
                      size_t workspace_bytes, void *stream);
 
 /*
+ * polar_sha_decode for callers that cannot allocate and have no workspace to pass: code that
+ * runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, checks, kernels and result (bit for bit) as polar_sha_decode, minus the workspace:
+ * the split-KV partial results go to a scratch array of POLAR_STATIC_SCRATCH_BYTES that lives in
+ * the library's own device image (one copy per GPU, held until the process ends).  The call
+ * allocates and frees nothing.  Sizes whose polar_sha_workspace_bytes exceed
+ * POLAR_STATIC_SCRATCH_BYTES are refused with POLAR_EWORKSPACE (use polar_sha_decode with a
+ * workspace of your own).  The scratch needs no clearing (the streaming kernel writes every
+ * record the merge kernel reads) and keeps the previous call's contents.  Every call on one GPU
+ * shares that GPU's array: calls that may overlap in time on one GPU (different streams, or
+ * different threads) race and must be ordered by the caller.  The first call on a GPU looks up
+ * the array's device address (with that GPU current); make it outside any graph capture, like
+ * the first launch of any kernel.
+ */
+#define POLAR_STATIC_SCRATCH_BYTES (32u << 20)
+int polar_sha_decode_static(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                            const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
+                            int k, int dt, float scale, void *stream);
+
+/*
  * polar_sha_decode for either cache layout (Section 3.2, footnote: K, V in R^{B x N x Hkv x d}).
  * Identical to polar_sha_decode except that K and V are laid out as `layout` says; with
  * POLAR_KV_BSHD a selected head's rows are d contiguous values every Hkv*d, so the kernel
@@ -385,7 +405,8 @@ const char *polar_strerror(int status);
 int polar_last_hip_error(void);
 /* ABI version: major * 1000 + minor.  2000: options (polar_set_option / polar_get_option) replace the
  * environment switches; every workspace query returns size_t; the read yardsticks moved to their own
- * library (polar_probe.h); q, K, V and out of the attention calls must be 16-byte aligned. */
+ * library (polar_probe.h); q, K, V and out of the attention calls must be 16-byte aligned.
+ * 2100: adds polar_sha_decode_static. */
 int polar_version(void);
 /* Hash of the source files this binary was built from (set by the build script; "unknown" for a
  * build made without it).  Lets a loader refuse a binary older than the sources beside it. */

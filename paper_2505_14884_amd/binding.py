@@ -22,7 +22,7 @@ KV_LAYOUT = {"bhsd": 0, "bshd": 1}   # [B,Hkv,S,d] (default) / [B,S,Hkv,d]
 _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POLAR_EWORKSPACE",
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
-           "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge",
+           "polar_sha_decode_static", "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge",
            "polar_sha_chunk_rows", "polar_sha_launches", "polar_head_norm_topk", "polar_select_gemm",
            "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down",
            "polar_select_gemm_down_workspace_bytes", "polar_sparse_mlp", "polar_sparse_mlp_workspace_bytes",
@@ -91,6 +91,8 @@ def lib() -> ctypes.CDLL:
         L.polar_sha_launches.restype = i
         L.polar_sha_decode.argtypes = [vp] * 6 + [i] * 7 + [f, vp, sz, vp]
         L.polar_sha_decode.restype = i
+        L.polar_sha_decode_static.argtypes = [vp] * 6 + [i] * 7 + [f, vp]
+        L.polar_sha_decode_static.restype = i
         L.polar_sha_partial.argtypes = [vp] * 5 + [i] * 7 + [f, vp, sz, vp]
         L.polar_sha_partial.restype = i
         L.polar_sha_decode_layout.argtypes = [vp] * 6 + [i] * 8 + [f, vp, sz, vp]
@@ -297,6 +299,21 @@ def sha_decode(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, seqlens: torch
     else:
         rc = lib().polar_sha_decode_layout(*ptrs, B, Hq, Hkv, S, d, k, _dtype_code(q), KV_LAYOUT[kv_layout], *tail)
         _check(rc, "polar_sha_decode_layout")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 32 << 20      # POLAR_STATIC_SCRATCH_BYTES in include/polar.h
+
+
+def sha_decode_static(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, seqlens: torch.Tensor,
+                      head_idx: Optional[torch.Tensor], k: int, out: torch.Tensor, scale: float = 0.0) -> torch.Tensor:
+    """sha_decode through the entry point that allocates nothing: the caller passes `out`, the
+    split-KV scratch is the library's own static device array (sizes beyond it raise)."""
+    B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, head_idx, k)
+    rc = lib().polar_sha_decode_static(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"), _dev(seqlens, "seqlens", torch.int32),
+                                       _dev(head_idx, "head_idx", torch.int32), _dev(out, "out", torch.float32),
+                                       B, Hq, Hkv, S, d, k, _dtype_code(q), float(scale), _stream())
+    _check(rc, "polar_sha_decode_static")
     return out
 
 

@@ -3,10 +3,40 @@
 // same way with or without a GPU in the machine.
 #include <math.h>
 
+#include <mutex>
+
 #include "polar_internal.h"
+
+// Scratch of polar_sha_decode_static: part of the library's device image, one copy per GPU.  In
+// host code this name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[POLAR_STATIC_SCRATCH_BYTES];
 
 namespace polar {
 namespace {
+
+// Device address of `scratch` on the current GPU, looked up once per GPU (each GPU holds its own
+// copy at its own address) and kept for the life of the process.
+hipError_t static_scratch(void **ptr)
+{
+    constexpr int kDevices = 64;
+    static std::atomic<void *> known[kDevices];
+    static std::mutex lookup;
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= kDevices) return hipErrorInvalidDevice;
+    void *p = known[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> guard(lookup);
+        p = known[dev].load(std::memory_order_acquire);
+        if (!p) {
+            if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            known[dev].store(p, std::memory_order_release);
+        }
+    }
+    *ptr = p;
+    return hipSuccess;
+}
 
 thread_local int g_last_hip_error = 0;
 
@@ -180,7 +210,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 2000; }
+int polar_version(void) { return 2100; }
 
 #ifndef POLAR_SOURCE_HASH
 #define POLAR_SOURCE_HASH "unknown"
@@ -354,6 +384,27 @@ int polar_sha_decode(const void *q, const void *K, const void *V, const int32_t 
 {
     return polar_sha_decode_layout(q, K, V, seqlens, head_idx, out, B, Hq, Hkv, S, d, k, dt,
                                    POLAR_KV_BHSD, scale, workspace, workspace_bytes, stream);
+}
+
+int polar_sha_decode_static(const void *q, const void *K, const void *V, const int32_t *seqlens,
+                            const int32_t *head_idx, float *out, int B, int Hq, int Hkv, int S, int d,
+                            int k, int dt, float scale, void *stream)
+{
+    ShaPlan plan;
+    const int rc = make_sha_plan(B, Hq, Hkv, S, d, k, &plan);      // size errors first, as in polar_sha_decode
+    if (rc != POLAR_OK) return rc;
+    if (plan.bytes > POLAR_STATIC_SCRATCH_BYTES) return POLAR_EWORKSPACE;
+    if (B == 0) return polar_sha_decode(q, K, V, seqlens, head_idx, out, B, Hq, Hkv, S, d, k, dt, scale, nullptr, 0, stream);
+    // polar_sha_decode's argument checks, made here so that a bad argument is reported before the
+    // first HIP call (the address lookup below) as everywhere else in the library
+    if (!dtype_ok(dt) || !(scale >= 0.0f) || isinf(scale)) return POLAR_EINVAL;
+    if (!head_idx && k != Hkv) return POLAR_EINVAL;
+    if (!q || !K || !V || !seqlens || !out) return POLAR_EINVAL;
+    if (misaligned16(q) || misaligned16(K) || misaligned16(V) || misaligned16(out)) return POLAR_EINVAL;
+    void *ws = nullptr;
+    if (hipError_t e = static_scratch(&ws); e != hipSuccess) return record(e);
+    return polar_sha_decode(q, K, V, seqlens, head_idx, out, B, Hq, Hkv, S, d, k, dt, scale, ws,
+                            POLAR_STATIC_SCRATCH_BYTES, stream);
 }
 
 int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,

@@ -141,6 +141,27 @@ def test_sha_argument_errors():
     assert decode(L, B=0, q=None, K=None, V=None, n=None, out=None, ws=None) == OK   # empty batch
 
 
+def test_static_scratch_entry_point_argument_errors():
+    """polar_sha_decode_static: polar_sha_decode's checks, plus the size limit of the library's own
+    scratch array, all before any HIP call."""
+    L = binding.lib()
+    f = lambda q=ALIGNED, K=ALIGNED, V=ALIGNED, n=FAKE, idx=FAKE, out=ALIGNED, B=4, Hq=8, Hkv=8, S=256, d=64, k=4, dt=0, \
+        scale=0.0: L.polar_sha_decode_static(q, K, V, n, idx, out, B, Hq, Hkv, S, d, k, dt, scale, None)
+    assert f(k=0) == EINVAL and f(k=9) == EINVAL and f(Hq=12) == EINVAL and f(S=0) == EINVAL and f(B=-1) == EINVAL
+    assert f(dt=5) == EINVAL and f(scale=-1.0) == EINVAL and f(idx=None) == EINVAL
+    for name in ("q", "K", "V", "n", "out"):
+        assert f(**{name: None}) == EINVAL
+    assert f(q=ctypes.c_void_p(0x10008)) == EINVAL and f(out=ctypes.c_void_p(0x10004)) == EINVAL
+    assert f(d=96) == EUNSUPPORTED and f(Hq=136) == EUNSUPPORTED
+    assert f(B=0, q=None, K=None, V=None, n=None, out=None) == OK
+    # 256 requests x 32 heads x 8 chunks x 130 floats of records do not fit 32 MiB; 24 heads do
+    assert polar.sha_workspace_bytes(256, 32, 32, 8192, 128, 32) > binding.STATIC_SCRATCH_BYTES
+    assert f(B=256, Hq=32, Hkv=32, S=8192, d=128, k=32) == EWORKSPACE
+    assert polar.sha_workspace_bytes(256, 32, 32, 8192, 128, 24) <= binding.STATIC_SCRATCH_BYTES
+    text = open(os.path.join(ROOT, "include", "polar.h")).read()
+    assert "#define POLAR_STATIC_SCRATCH_BYTES (32u << 20)" in text and binding.STATIC_SCRATCH_BYTES == 32 << 20
+
+
 def test_layout_entry_points_share_the_checks():
     L = binding.lib()
     args = lambda layout, **kw: L.polar_sha_decode_layout(
