@@ -259,6 +259,28 @@ int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, i
                          int32_t *head_idx, float *norms_out, void *stream);
 
 /*
+ * The same labels straight from the caches (Section 3.2: dense attention, heads ranked by the L2
+ * norm of their output; Section 4.2: the k best are the router's targets): dense decode attention
+ * whose merge step takes the norms and ranks them as its epilogue, so no pass over a stored
+ * output is needed.  Two launches: the streaming kernel of polar_sha_decode (k = Hkv, per-chunk
+ * records) and one merge kernel with one workgroup per request.
+ *
+ *   q, K, V, seqlens, S, d, dt, layout, scale   as for polar_sha_decode_layout (dense: every head)
+ *   labels     out  [B, k_label] int32, as head_idx of polar_head_norm_topk
+ *   norms_out  out  [B, Hkv] float, nullable
+ *   attn_out   out  [B, Hq, d] float, nullable: the dense attention output, bit-identical to
+ *                   polar_sha_decode's (head_idx = NULL); 16-byte aligned
+ *   workspace       at least polar_sha_workspace_bytes(B, Hq, Hkv, S, d, Hkv) bytes, 256-byte aligned
+ *
+ * The norm of a group is taken over the float values attn_out holds (or would hold), squares
+ * and sums in double in a fixed order; ordering and tie rules are those of polar_router_topk.
+ * 1 <= k_label <= Hkv <= POLAR_MAX_ROUTER_H.
+ */
+int polar_head_labels(const void *q, const void *K, const void *V, const int32_t *seqlens, int32_t *labels,
+                      float *norms_out, float *attn_out, int B, int Hq, int Hkv, int S, int d, int k_label, int dt,
+                      int layout, float scale, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Selective (fused-gather) GEMM (Appendix "Sparse Kernels", Algorithm 3; Section 3.1, the
  * first factor sigma(x W_{1,S_B}) of the sparsified MLP; Section 4.1).
  *
@@ -406,7 +428,7 @@ int polar_last_hip_error(void);
 /* ABI version: major * 1000 + minor.  2000: options (polar_set_option / polar_get_option) replace the
  * environment switches; every workspace query returns size_t; the read yardsticks moved to their own
  * library (polar_probe.h); q, K, V and out of the attention calls must be 16-byte aligned.
- * 2100: adds polar_sha_decode_static. */
+ * 2100: adds polar_sha_decode_static.  2200: adds polar_head_labels. */
 int polar_version(void);
 /* Hash of the source files this binary was built from (set by the build script; "unknown" for a
  * build made without it).  Lets a loader refuse a binary older than the sources beside it. */

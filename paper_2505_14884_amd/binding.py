@@ -23,7 +23,7 @@ _STATUS = {0: "POLAR_OK", -1: "POLAR_EINVAL", -2: "POLAR_EUNSUPPORTED", -3: "POL
            -4: "POLAR_EHIP"}
 EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_workspace_bytes", "polar_sha_decode",
            "polar_sha_decode_static", "polar_sha_decode_layout", "polar_sha_partial", "polar_sha_partial_layout", "polar_sha_merge",
-           "polar_sha_chunk_rows", "polar_sha_launches", "polar_head_norm_topk", "polar_select_gemm",
+           "polar_sha_chunk_rows", "polar_sha_launches", "polar_head_norm_topk", "polar_head_labels", "polar_select_gemm",
            "polar_select_gemm_ws", "polar_select_gemm_workspace_bytes", "polar_select_gemm_down",
            "polar_select_gemm_down_workspace_bytes", "polar_sparse_mlp", "polar_sparse_mlp_workspace_bytes",
            "polar_neuron_union", "polar_neuron_union_ws", "polar_neuron_union_workspace_bytes",
@@ -103,6 +103,8 @@ def lib() -> ctypes.CDLL:
         L.polar_sha_merge.restype = i
         L.polar_head_norm_topk.argtypes = [vp, i, i, i, i, i, vp, vp, vp]
         L.polar_head_norm_topk.restype = i
+        L.polar_head_labels.argtypes = [vp] * 7 + [i] * 8 + [f, vp, sz, vp]
+        L.polar_head_labels.restype = i
         L.polar_select_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp]
         L.polar_select_gemm.restype = i
         L.polar_select_gemm_ws.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp, ctypes.c_size_t, vp]
@@ -384,6 +386,27 @@ def head_norm_topk(attn_out: torch.Tensor, Hkv: int, k: int,
                                     _dev(norms_out, "norms_out", torch.float32), _stream())
     _check(rc, "polar_head_norm_topk")
     return head_idx
+
+
+def head_labels(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, seqlens: torch.Tensor, k: int,
+                labels: Optional[torch.Tensor] = None, norms_out: Optional[torch.Tensor] = None,
+                attn_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                scale: float = 0.0, kv_layout: str = "bhsd") -> torch.Tensor:
+    """Head-importance labels straight from the caches: dense decode attention with the norm and the
+    ranking as the merge kernel's epilogue -> int32 [B,k] (the k KV groups with the largest output
+    norm per request, best first).  attn_out (float32 [B,Hq,d]) receives the dense output if given."""
+    B, Hq, Hkv, S, d = _sha_shapes(q, K, V, seqlens, None, 0, kv_layout)
+    if labels is None:
+        labels = torch.empty((B, max(k, 0)), dtype=torch.int32, device=q.device)
+    if workspace is None:
+        workspace = alloc_workspace(B, Hq, Hkv, S, d, Hkv, q.device)
+    rc = lib().polar_head_labels(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"), _dev(seqlens, "seqlens", torch.int32),
+                                 _dev(labels, "labels", torch.int32), _dev(norms_out, "norms_out", torch.float32),
+                                 _dev(attn_out, "attn_out", torch.float32), B, Hq, Hkv, S, d, k, _dtype_code(q),
+                                 KV_LAYOUT[kv_layout], float(scale), _dev(workspace, "workspace"),
+                                 workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "polar_head_labels")
+    return labels
 
 
 def select_gemm_workspace_bytes(M: int) -> int:

@@ -98,4 +98,14 @@ def source_hash() -> str:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import argparse
+
+    ap = argparse.ArgumentParser(description="Build libpolar.so and libpolar_probe.so for gfx950.")
+    ap.add_argument("--define", action="append", default=[], metavar="NAME=VALUE",
+                    help="extra preprocessor definition (tuning and timing-only variants), repeatable")
+    ap.add_argument("--out", default=LIB_PATH, help="path of the product library (default: in-tree); load a "
+                                                    "variant with the environment variable POLAR_LIBRARY")
+    ap.add_argument("--probe-out", default="", help="path of the yardstick library (default: beside --out)")
+    a = ap.parse_args()
+    probe = a.probe_out or (PROBE_LIB_PATH if a.out == LIB_PATH else a.out + ".probe.so")
+    print(build_library(verbose=True, defines=a.define, out_path=a.out, probe_path=probe))

@@ -210,7 +210,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 2100; }
+int polar_version(void) { return 2200; }
 
 #ifndef POLAR_SOURCE_HASH
 #define POLAR_SOURCE_HASH "unknown"
@@ -405,6 +405,25 @@ int polar_sha_decode_static(const void *q, const void *K, const void *V, const i
     if (hipError_t e = static_scratch(&ws); e != hipSuccess) return record(e);
     return polar_sha_decode(q, K, V, seqlens, head_idx, out, B, Hq, Hkv, S, d, k, dt, scale, ws,
                             POLAR_STATIC_SCRATCH_BYTES, stream);
+}
+
+int polar_head_labels(const void *q, const void *K, const void *V, const int32_t *seqlens, int32_t *labels,
+                      float *norms_out, float *attn_out, int B, int Hq, int Hkv, int S, int d, int k_label, int dt,
+                      int layout, float scale, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ShaPlan plan;
+    int rc = make_sha_plan(B, Hq, Hkv, S, d, Hkv, &plan);        // the dense plan: every KV head is a unit
+    if (rc != POLAR_OK) return rc;
+    if (k_label < 1 || k_label > Hkv) return POLAR_EINVAL;
+    if (Hkv > POLAR_MAX_ROUTER_H) return POLAR_EUNSUPPORTED;
+    if (B > 0 && (!labels || misaligned16(attn_out))) return POLAR_EINVAL;
+    // the streaming kernel in its record-writing form (argument checks as in polar_sha_partial) ...
+    rc = sha_partial_impl(q, K, V, seqlens, nullptr, nullptr, B, Hq, Hkv, S, d, Hkv, dt, layout, scale, workspace,
+                          workspace_bytes, stream);
+    if (rc != POLAR_OK || B == 0) return rc;
+    // ... and the merge whose epilogue takes the norms and ranks them
+    return record(launch_sha_merge_label(seqlens, attn_out, labels, norms_out, static_cast<const float *>(workspace),
+                                         plan, B, Hq, Hkv, S, d, k_label, static_cast<hipStream_t>(stream)));
 }
 
 int polar_head_norm_topk(const float *attn_out, int B, int Hq, int Hkv, int d, int k,

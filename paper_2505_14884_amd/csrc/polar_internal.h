@@ -79,6 +79,10 @@ hipError_t launch_sha_partial_gqa(const void *q, const void *K, const void *V, c
 hipError_t launch_sha_merge(const int32_t *seqlens, const int32_t *head_idx, float *out,
                             const float *ws, const ShaPlan &plan, int B, int Hq, int Hkv, int S,
                             int d, int k, hipStream_t stream);
+// Dense run's merge with the labeller's norm and ranking as its epilogue (out and norms_out nullable).
+hipError_t launch_sha_merge_label(const int32_t *seqlens, float *out, int32_t *labels, float *norms_out,
+                                  const float *ws, const ShaPlan &plan, int B, int Hq, int Hkv, int S, int d,
+                                  int k_label, hipStream_t stream);
 hipError_t launch_router_topk(const void *hidden, const void *Wr, int B, int D, int H, int k,
                               polar_dtype dt, int32_t *head_idx, float *logits_out,
                               hipStream_t stream);

@@ -33,7 +33,16 @@ namespace polar {
 namespace {
 
 constexpr int kRouterThreads = 1024;
-constexpr int kRowBatch = 8;     // rows of Wr a thread loads before consuming any
+constexpr int kRowBatch = 8;     // rows of Wr a thread of the split-D kernels loads before consuming any
+
+// Timing-only build switches for the one-launch kernel (results are wrong with any of them set; every
+// access stays in bounds): bit 0 drops the global loads, bit 1 the multiply-adds, bit 2 the two
+// LDS reduction levels and the ranking.  They exist to measure what each part of the kernel's few
+// microseconds costs on the machine; the product is built without them.
+#ifndef POLAR_ROUTER_ABLATE
+#define POLAR_ROUTER_ABLATE 0
+#endif
+constexpr int kAblate = POLAR_ROUTER_ABLATE;
 
 template <bool BF> __device__ __forceinline__ double widen_one(uint32_t bits16)
 {
@@ -91,17 +100,69 @@ __device__ __forceinline__ void rank_and_emit(const double *sh_logit, int *sh_ra
     if (tid < H && sh_rank[tid] < k) row_out[sh_rank[tid]] = tid;
 }
 
-// dynamic LDS: double part[nslice*H] | double part2[J*H] | double logit[H]
-template <bool BF, int VEC>
+__device__ __forceinline__ double shfl_xor_f64(double x, int mask)
+{
+    const int lo = __shfl_xor(__double2loint(x), mask), hi = __shfl_xor(__double2hiint(x), mask);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the slices of one wave, in registers.  Lane = slice_in_wave * CG + cg (CG a power of
+// two), every lane holds VEC column sums.  The slice bits of the lane id are taken in ascending
+// order: while a lane still holds more than one column, the two lanes of a pair split the columns
+// between them (each sends the half it gives up and adds the half it receives to the half it keeps:
+// the lane whose bit is set keeps the upper half), after that they exchange and add the one value
+// left.  Every column is thus added up over the same binary tree of slices (pairs, pairs of pairs,
+// ...), and a + b == b + a bit for bit, so identical columns still give identical sums.  On return
+// x[0 .. n) holds the wave's sums of columns first .. first + n - 1 of the lane's column group.
+template <int VEC>
+__device__ __forceinline__ void wave_slice_sums(double (&x)[VEC], int lane, int cg_bits, int &first, int &n)
+{
+    first = 0;
+    const int steps = 6 - cg_bits;               // slice bits of the lane id (wave-uniform)
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {                // step j works on lane bit cg_bits + j
+        const int held = (VEC >> j) > 1 ? (VEC >> j) : 1;   // columns a lane holds before step j (a constant once unrolled)
+        if (j < steps) {
+            const int s = cg_bits + j;
+            const bool upper = (lane >> s) & 1;
+            if (held > 1) {
+                const int half = held / 2;
+#pragma unroll
+                for (int i = 0; i < VEC / 2; ++i) {
+                    if (i < half) {
+                        const double give = upper ? x[i] : x[i + half];
+                        const double keep = upper ? x[i + half] : x[i];
+                        x[i] = keep + shfl_xor_f64(give, 1 << s);
+                    }
+                }
+                first += upper ? half : 0;
+            } else {
+                x[0] += shfl_xor_f64(x[0], 1 << s);
+            }
+        }
+    }
+    n = (VEC >> steps) > 1 ? (VEC >> steps) : 1;
+}
+
+// RB = rows of Wr a thread loads before it consumes any (even, so that a row's chain, a0 or a1, and
+// with it every sum, is the same for every RB): the host picks the smallest of 4, 8, 16 that covers
+// a thread's rows in one batch, since a batch is a dependent round trip to memory and those round
+// trips, not the arithmetic, are what the kernel's time is made of.
+// WAVE_SUMS (H / VEC a power of two up to 64): the slices of a wave are added in registers
+// (wave_slice_sums), only the 16 waves' sums go through LDS (part2[16][H]) and one thread per head
+// adds them in ascending order.  Otherwise the threads' sums go to LDS and are added in two levels.
+// The two long serial LDS loops of that form cost about 2 us of the kernel's 7 to 9.
+template <bool BF, int VEC, int RB, bool WAVE_SUMS>
 __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
     const uint16_t *__restrict__ hidden, const uint16_t *__restrict__ Wr, int D, int H, int k,
-    int nslice, int J, int32_t *__restrict__ head_idx, float *__restrict__ logits_out)
+    int nslice, int J, int cg_bits, int32_t *__restrict__ head_idx, float *__restrict__ logits_out)
 {
     typedef typename VecOf<VEC>::type vec_t;
     extern __shared__ __align__(16) unsigned char smem[];
+    // dynamic LDS: [part: nslice x H] [part2: J x H] [logit: H]; with WAVE_SUMS only [part2: 16 x H] [logit: H]
     double *sh_part = reinterpret_cast<double *>(smem);
-    double *sh_part2 = sh_part + (size_t)nslice * H;
-    double *sh_logit = sh_part2 + (size_t)J * H;
+    double *sh_part2 = WAVE_SUMS ? sh_part : sh_part + (size_t)nslice * H;
+    double *sh_logit = sh_part2 + (size_t)(WAVE_SUMS ? kRouterThreads / 64 : J) * H;
     __shared__ int sh_rank[POLAR_MAX_ROUTER_H];
 
     const int b = blockIdx.x, tid = threadIdx.x;
@@ -111,25 +172,35 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
     // barrier in between).  A dependent round trip costs about a microsecond, so the kernel's
     // time is the number of such rounds, not its arithmetic.
     const int CG = H / VEC;                    // column groups per row of Wr
+    const int slice = tid / CG, cg = tid - slice * CG;
+    double a0[VEC], a1[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) a0[v] = a1[v] = 0.0;
     if (tid < nslice * CG) {
-        const int slice = tid / CG, cg = tid - slice * CG;
         const vec_t *w = reinterpret_cast<const vec_t *>(Wr) + cg;
-        double a0[VEC], a1[VEC];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) a0[v] = a1[v] = 0.0;
-        // rows slice, slice + nslice, ...: kRowBatch loads in flight, then their multiply-adds,
+        // rows slice, slice + nslice, ...: RB loads in flight, then their multiply-adds,
         // even rows of the batch into chain a0 and odd rows into a1
-        for (int i = slice; i < D; i += kRowBatch * nslice) {
-            vec_t wv[kRowBatch];
-            uint16_t hq[kRowBatch];
+        for (int i = slice; i < D; i += RB * nslice) {
+            vec_t wv[RB];
+            uint16_t hq[RB];
 #pragma unroll
-            for (int u = 0; u < kRowBatch; ++u) {
+            for (int u = 0; u < RB; ++u) {
                 const int row = i + u * nslice;
-                wv[u] = w[(size_t)(row < D ? row : i) * CG];
-                hq[u] = hrow[row < D ? row : i];
+                if (kAblate & 1) {
+                    wv[u] = vec_t{};
+                    hq[u] = (uint16_t)(row + tid);
+                } else {
+                    wv[u] = w[(size_t)(row < D ? row : i) * CG];
+                    hq[u] = hrow[row < D ? row : i];
+                }
+            }
+            if (kAblate & 2) {
+#pragma unroll
+                for (int u = 0; u < RB; ++u) a0[0] += (double)(lane16(wv[u], 0) + hq[u]);
+                continue;
             }
 #pragma unroll
-            for (int u = 0; u < kRowBatch; ++u) {
+            for (int u = 0; u < RB; ++u) {
                 const int row = i + u * nslice;
                 const double hv = row < D ? widen_one<BF>(hq[u]) : 0.0;
 #pragma unroll
@@ -141,29 +212,91 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
                 }
             }
         }
+    }
+    if (kAblate & 4) {
+        if (tid < k) head_idx[(size_t)b * k + tid] = (int)(a0[0] + a1[0]) & 1;
+        return;
+    }
+    if (WAVE_SUMS) {
+        double x[VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) sh_part[(size_t)slice * H + cg * VEC + v] = a0[v] + a1[v];
+        for (int v = 0; v < VEC; ++v) x[v] = a0[v] + a1[v];    // threads without rows hold zeros
+        int first, n;
+        wave_slice_sums<VEC>(x, tid & 63, cg_bits, first, n);
+        // after the splitting steps the columns of a group are spread over its lanes; every lane
+        // stores what it holds (lanes that went through exchange-and-add steps hold equal values
+        // and store the same bits)
+        const int wave = tid >> 6;
+        const int cgw = (tid & 63) & (CG - 1);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+            if (i < n) sh_part2[wave * H + cgw * VEC + first + i] = x[i];
+        __syncthreads();
+        if (tid < H) {
+            double part[kRouterThreads / 64];
+#pragma unroll
+            for (int w = 0; w < kRouterThreads / 64; ++w) part[w] = sh_part2[w * H + tid];   // all loads, then
+            double sum = 0.0;
+#pragma unroll
+            for (int w = 0; w < kRouterThreads / 64; ++w) sum += part[w];                    // the adds in order
+            sh_logit[tid] = sum;
+            sh_rank[tid] = 0;
+            if (logits_out) logits_out[(size_t)b * H + tid] = (float)sum;
+        }
+        __syncthreads();
+    } else {
+        if (tid < nslice * CG) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) sh_part[(size_t)slice * H + cg * VEC + v] = a0[v] + a1[v];
+        }
+        __syncthreads();
+        // level 1: group j adds slices j, j+J, j+2J, ... in ascending order
+        if (tid < J * H) {
+            const int j = tid / H, h = tid - j * H;
+            double sum = 0.0;
+            for (int s = j; s < nslice; s += J) sum += sh_part[(size_t)s * H + h];
+            sh_part2[tid] = sum;
+        }
+        __syncthreads();
+        // level 2: the J group sums in ascending order
+        if (tid < H) {
+            double sum = 0.0;
+            for (int j = 0; j < J; ++j) sum += sh_part2[j * H + tid];
+            sh_logit[tid] = sum;
+            sh_rank[tid] = 0;
+            if (logits_out) logits_out[(size_t)b * H + tid] = (float)sum;
+        }
+        __syncthreads();
     }
-    __syncthreads();
-
-    // level 1: group j adds slices j, j+J, j+2J, ... in ascending order
-    if (tid < J * H) {
-        const int j = tid / H, h = tid - j * H;
-        double sum = 0.0;
-        for (int s = j; s < nslice; s += J) sum += sh_part[(size_t)s * H + h];
-        sh_part2[tid] = sum;
-    }
-    __syncthreads();
-    // level 2: the J group sums in ascending order
-    if (tid < H) {
-        double sum = 0.0;
-        for (int j = 0; j < J; ++j) sum += sh_part2[j * H + tid];
-        sh_logit[tid] = sum;
-        sh_rank[tid] = 0;
-        if (logits_out) logits_out[(size_t)b * H + tid] = (float)sum;
-    }
-    __syncthreads();
     rank_and_emit(sh_logit, sh_rank, H, k, kRouterThreads, tid, head_idx + (size_t)b * k);
+}
+
+template <bool BF, int VEC, int RB, bool WAVE_SUMS>
+hipError_t launch_vec_ws(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H, int k, int nslice, int J,
+                         int cg_bits, size_t lds, int32_t *head_idx, float *logits_out, hipStream_t stream)
+{
+    auto kern = router_topk_kernel<BF, VEC, RB, WAVE_SUMS>;
+    static LdsGrant granted;
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, granted); e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)B), dim3(kRouterThreads), lds, stream, hidden, Wr, D, H,
+                       k, nslice, J, cg_bits, head_idx, logits_out);
+    return hipGetLastError();
+}
+
+template <bool BF, int VEC, int RB>
+hipError_t launch_vec_rb(const uint16_t *hidden, const uint16_t *Wr, int B, int D, int H, int k, int nslice, int J,
+                         size_t lds, int32_t *head_idx, float *logits_out, hipStream_t stream)
+{
+    const int CG = H / VEC;
+    int cg_bits = 0;
+    while ((1 << cg_bits) < CG) ++cg_bits;
+#ifndef POLAR_ROUTER_LDS_SUMS                    // (timing comparisons: build with it to keep the two-level LDS form)
+    if ((1 << cg_bits) == CG && CG <= 64)        // the slices of a wave can be added in registers
+        return launch_vec_ws<BF, VEC, RB, true>(hidden, Wr, B, D, H, k, nslice, J, cg_bits,
+                                                (size_t)(kRouterThreads / 64 + 1) * H * sizeof(double), head_idx,
+                                                logits_out, stream);
+#endif
+    return launch_vec_ws<BF, VEC, RB, false>(hidden, Wr, B, D, H, k, nslice, J, 0, lds, head_idx, logits_out, stream);
 }
 
 template <bool BF, int VEC>
@@ -178,12 +311,12 @@ hipError_t launch_vec(const uint16_t *hidden, const uint16_t *Wr, int B, int D, 
     if (J > kRouterThreads / H) J = kRouterThreads / H;
     if (J < 1) J = 1;
     const size_t lds = ((size_t)nslice * H + (size_t)J * H + H) * sizeof(double);
-    auto kern = router_topk_kernel<BF, VEC>;
-    static LdsGrant granted;
-    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, granted); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)B), dim3(kRouterThreads), lds, stream, hidden, Wr, D, H,
-                       k, nslice, J, head_idx, logits_out);
-    return hipGetLastError();
+    const int rows_per_thread = (D + nslice - 1) / nslice;
+    if (rows_per_thread <= 4)
+        return launch_vec_rb<BF, VEC, 4>(hidden, Wr, B, D, H, k, nslice, J, lds, head_idx, logits_out, stream);
+    if (rows_per_thread <= 8 || VEC < 8)              // 16 rows of 16-byte vectors is what the registers hold
+        return launch_vec_rb<BF, VEC, 8>(hidden, Wr, B, D, H, k, nslice, J, lds, head_idx, logits_out, stream);
+    return launch_vec_rb<BF, VEC, 16>(hidden, Wr, B, D, H, k, nslice, J, lds, head_idx, logits_out, stream);
 }
 
 // ---------------------------------------------------------------------------------------

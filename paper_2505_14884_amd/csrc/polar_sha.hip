@@ -338,6 +338,30 @@ constexpr int kMergeHeads = 8;
 constexpr int kMergeThreads = 256;
 constexpr int kNoSlot = 0x7fffffff;
 
+// Element t of one query head's output from its chunk records unit0 .. unit0 + used - 1: one pass
+// with a running max (the recurrence of Algorithm 1 over chunks), then the division by the sum.
+// The loads of different chunks are independent of the arithmetic, so unrolling puts several
+// records in flight at once.
+template <int D>
+__device__ __forceinline__ float fold_chunks(const float *__restrict__ ws_o, const float *__restrict__ ws_ml,
+                                             size_t unit0, int used, int t)
+{
+    const float2 *ml = reinterpret_cast<const float2 *>(ws_ml) + unit0;
+    const float *oc = ws_o + unit0 * D + t;
+    float mx = kNegBig, acc = 0.0f, lsum = 0.0f;
+#pragma unroll 4
+    for (int c = 0; c < used; ++c) {
+        const float2 rec = ml[c];
+        const float part = oc[(size_t)c * D];
+        const float m_new = fmaxf(mx, rec.x);
+        const float a_old = fast_exp2(mx - m_new), a_new = fast_exp2(rec.x - m_new);
+        lsum = fmaf(a_new, rec.y, lsum * a_old);
+        acc = fmaf(a_new, part, acc * a_old);
+        mx = m_new;
+    }
+    return lsum > 0.0f ? acc / lsum : 0.0f;
+}
+
 template <int D>
 __global__ __launch_bounds__(kMergeThreads) void sha_merge_kernel(
     const int32_t *__restrict__ seqlens, const int32_t *__restrict__ head_idx,
@@ -373,28 +397,82 @@ __global__ __launch_bounds__(kMergeThreads) void sha_merge_kernel(
         if (h > h_last) continue;
         const int slot = slot_of[h / G - g_first];
         float result = 0.0f;
-        if (slot != kNoSlot && used > 0) {
-            const size_t unit0 = (((size_t)b * k + slot) * G + (h % G)) * nsplit;
-            // One pass with a running max (the recurrence of Algorithm 1 over chunks): the
-            // loads of different chunks are independent of the arithmetic, so unrolling puts
-            // several records in flight at once.
-            const float2 *ml = reinterpret_cast<const float2 *>(ws_ml) + unit0;
-            const float *oc = ws_o + unit0 * D + t;
-            float mx = kNegBig, acc = 0.0f, lsum = 0.0f;
-#pragma unroll 4
-            for (int c = 0; c < used; ++c) {
-                const float2 rec = ml[c];
-                const float part = oc[(size_t)c * D];
-                const float m_new = fmaxf(mx, rec.x);
-                const float a_old = fast_exp2(mx - m_new), a_new = fast_exp2(rec.x - m_new);
-                lsum = fmaf(a_new, rec.y, lsum * a_old);
-                acc = fmaf(a_new, part, acc * a_old);
-                mx = m_new;
-            }
-            result = lsum > 0.0f ? acc / lsum : 0.0f;
-        }
+        if (slot != kNoSlot && used > 0)
+            result = fold_chunks<D>(ws_o, ws_ml, (((size_t)b * k + slot) * G + (h % G)) * nsplit, used, t);
         out[((size_t)b * Hq + h) * D + t] = result;
     }
+}
+
+// Merge kernel of the head-importance labeller (Section 3.2: heads ranked by the L2 norm of
+// their attention output; Section 4.2: the k best are the router's training targets): the dense
+// run's merge with the norm and the ranking as its epilogue, so the labels need no pass over the
+// stored output.  grid = B, block = 256: one workgroup folds the chunk records of ALL query heads
+// of its request (dense: slot == KV head), 256 / D heads at a time, exactly as sha_merge_kernel
+// does (same fold, same bits), optionally stores them, and adds the squares of each group's
+// G * D values in double (a float squared is exact in double): the D values of a head through an
+// xor butterfly per wave and a fixed-order sum over the head's waves, the G heads of a group in
+// ascending order (one thread does those few additions, so the order never varies).  The groups are then ranked by that sum of squares with the router's rule
+// (larger first, equal by ascending id, NaN last).
+template <int D>
+__global__ __launch_bounds__(kMergeThreads) void sha_merge_label_kernel(
+    const int32_t *__restrict__ seqlens, const float *__restrict__ ws_o, const float *__restrict__ ws_ml,
+    float *__restrict__ out, int32_t *__restrict__ labels, float *__restrict__ norms_out, int Hq, int Hkv,
+    int S, int G, int chunk, int nsplit, int k_label)
+{
+    constexpr int HEADS_PER_PASS = kMergeThreads / D, WAVES_PER_HEAD = D / 64;
+    __shared__ double sh_ss[POLAR_MAX_ROUTER_H];
+    __shared__ double sh_part[kMergeThreads / 64];
+    __shared__ int sh_rank[POLAR_MAX_ROUTER_H];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int g = tid; g < Hkv; g += kMergeThreads) {
+        sh_ss[g] = 0.0;
+        sh_rank[g] = 0;
+    }
+    int n = seqlens[b];
+    n = n < 0 ? 0 : (n > S ? S : n);
+    const int used = (n + chunk - 1) / chunk;
+    const int t = tid % D;
+    for (int h0 = 0; h0 < Hq; h0 += HEADS_PER_PASS) {
+        const int h = h0 + tid / D;
+        float result = 0.0f;
+        if (h < Hq && used > 0)       // dense: unit0 = ((b * Hkv + h / G) * G + h % G) * nsplit = (b * Hq + h) * nsplit
+            result = fold_chunks<D>(ws_o, ws_ml, ((size_t)b * Hq + h) * nsplit, used, t);
+        if (h < Hq && out) out[((size_t)b * Hq + h) * D + t] = result;
+        double sq = (double)result * (double)result;
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            const int lo = __shfl_xor(__double2loint(sq), m), hi = __shfl_xor(__double2hiint(sq), m);
+            sq += __hiloint2double(hi, lo);
+        }
+        __syncthreads();                       // sh_part of the previous pass has been consumed
+        if (lane == 0) sh_part[wave] = sq;
+        __syncthreads();
+        if (tid == 0)                          // one thread, fixed order: waves of a head, heads ascending
+            for (int i = 0; i < HEADS_PER_PASS && h0 + i < Hq; ++i) {
+                double head_ss = 0.0;
+#pragma unroll
+                for (int w = 0; w < WAVES_PER_HEAD; ++w) head_ss += sh_part[i * WAVES_PER_HEAD + w];
+                sh_ss[(h0 + i) / G] += head_ss;
+            }
+    }
+    __syncthreads();
+    for (int g = tid; g < Hkv; g += kMergeThreads)
+        if (norms_out) norms_out[(size_t)b * Hkv + g] = (float)sqrt(sh_ss[g]);
+    const int parts = kMergeThreads / Hkv;            // >= 1: Hkv <= 256
+    if (tid < parts * Hkv) {
+        const int part = tid / Hkv, g = tid - part * Hkv;
+        const double mine = sh_ss[g];
+        int cnt = 0;
+        for (int j = part; j < Hkv; j += parts) {
+            const double other = sh_ss[j];
+            const bool on = other != other, mn = mine != mine;
+            const bool first = (on || mn) ? ((on && mn) ? j < g : mn) : (other > mine || (other == mine && j < g));
+            cnt += first ? 1 : 0;
+        }
+        if (cnt) atomicAdd(&sh_rank[g], cnt);
+    }
+    __syncthreads();
+    if (tid < Hkv && sh_rank[tid] < k_label) labels[(size_t)b * k_label + sh_rank[tid]] = tid;
 }
 
 template <class DT, int D, bool RMS>
@@ -480,6 +558,22 @@ hipError_t launch_sha_merge(const int32_t *seqlens, const int32_t *head_idx, flo
     else if (d == 64)
         hipLaunchKernelGGL((sha_merge_kernel<64>), grid, dim3(kMergeThreads), 0, stream, seqlens, head_idx,
                            ws_o, ws_ml, out, Hq, Hkv, S, k, plan.G, plan.chunk, plan.nsplit);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_sha_merge_label(const int32_t *seqlens, float *out, int32_t *labels, float *norms_out,
+                                  const float *ws, const ShaPlan &plan, int B, int Hq, int Hkv, int S, int d,
+                                  int k_label, hipStream_t stream)
+{
+    const float *ws_o = ws, *ws_ml = ws + plan.o_floats;
+    if (d == 128)
+        hipLaunchKernelGGL((sha_merge_label_kernel<128>), dim3((unsigned)B), dim3(kMergeThreads), 0, stream, seqlens,
+                           ws_o, ws_ml, out, labels, norms_out, Hq, Hkv, S, plan.G, plan.chunk, plan.nsplit, k_label);
+    else if (d == 64)
+        hipLaunchKernelGGL((sha_merge_label_kernel<64>), dim3((unsigned)B), dim3(kMergeThreads), 0, stream, seqlens,
+                           ws_o, ws_ml, out, labels, norms_out, Hq, Hkv, S, plan.G, plan.chunk, plan.nsplit, k_label);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

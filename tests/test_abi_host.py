@@ -187,6 +187,22 @@ def test_head_norm_topk_argument_errors():
     assert f(B=0, out=None, idx=None) == OK
 
 
+def test_head_labels_argument_errors():
+    L = binding.lib()
+    need = L.polar_sha_workspace_bytes(4, 8, 8, 256, 64, 8)
+    f = lambda q=ALIGNED, K=ALIGNED, V=ALIGNED, n=FAKE, labels=FAKE, out=None, B=4, Hq=8, Hkv=8, S=256, d=64, k=3, dt=0, \
+        layout=0, scale=0.0, ws=ALIGNED, wsb=need: L.polar_head_labels(q, K, V, n, labels, None, out, B, Hq, Hkv, S, d, k,
+                                                                      dt, layout, scale, ws, wsb, None)
+    assert f(k=0) == EINVAL and f(k=9) == EINVAL and f(Hq=12) == EINVAL and f(S=0) == EINVAL and f(B=-1) == EINVAL
+    assert f(dt=2) == EINVAL and f(layout=2) == EINVAL and f(scale=-1.0) == EINVAL
+    assert f(labels=None) == EINVAL and f(out=ctypes.c_void_p(0x10008)) == EINVAL
+    for name in ("q", "K", "V", "n"):
+        assert f(**{name: None}) == EINVAL
+    assert f(d=96) == EUNSUPPORTED and f(Hq=512, Hkv=512, k=4) == EUNSUPPORTED
+    assert f(ws=None) == EWORKSPACE and f(wsb=need - 1) == EWORKSPACE
+    assert f(B=0, q=None, K=None, V=None, n=None, labels=None, ws=None) == OK
+
+
 def test_select_gemm_and_union_argument_errors():
     L = binding.lib()
     A16 = ctypes.c_void_p(0x1000)

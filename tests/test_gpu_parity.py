@@ -399,6 +399,18 @@ def test_head_importance_labels(name):
     want_same = orc.topk(score_same, w.k)
     assert np.array_equal(got, want_same), "labels differ from the oracle's on the same attention output"
     np.testing.assert_allclose(norms.cpu().numpy(), norm_same, rtol=2e-7)
+    # the one-call labeller (norm and ranking as the dense merge's epilogue): the same labels, and
+    # the very attention output polar_sha_decode gives, with poisoned outputs and workspace
+    out2 = torch.full_like(dense, float("nan"))
+    norms2 = torch.full_like(norms, float("nan"))
+    labels2 = torch.full((w.B, w.k), -9, dtype=torch.int32, device=DEV)
+    ws = polar.alloc_workspace(w.B, w.Hq, w.Hkv, w.S, w.d, w.Hkv, DEV).fill_(0xFF)
+    polar.head_labels(q, K, V, seqlens, w.k, labels=labels2, norms_out=norms2, attn_out=out2, workspace=ws)
+    labels3 = polar.head_labels(q, K, V, seqlens, w.k)                 # no output, no norms wanted
+    torch.cuda.synchronize()
+    assert torch.equal(out2.view(torch.int32), dense.view(torch.int32))
+    assert np.array_equal(labels2.cpu().numpy(), want_same) and np.array_equal(labels3.cpu().numpy(), want_same)
+    np.testing.assert_allclose(norms2.cpu().numpy(), norm_same, rtol=2e-7)
     # (2) end to end
     want, score = orc.head_importance_labels(host_bits(q), host_bits(K), host_bits(V),
                                              seqlens.cpu().numpy(), w.k, w.dtype)
@@ -414,6 +426,32 @@ def test_head_importance_labels(name):
         "%d rows differ from the double-precision labels; smallest relative gap %.2e"
         % (int(separated.sum()), w.B, int((~separated).sum()), differ, gaps.min(initial=1.0)))
     assert differ <= int((~separated).sum())
+
+
+@pytest.mark.parametrize("dtype,Hkv,G,d,S,layout", [("f16", 5, 1, 64, 300, "bhsd"), ("bf16", 7, 3, 128, 2600, "bshd"),
+                                                      ("f16", 72, 1, 128, 130, "bhsd"), ("bf16", 4, 8, 64, 9000, "bhsd"),
+                                                      ("f16", 256, 1, 64, 40, "bhsd")])
+def test_head_labels_one_call_edge_shapes(dtype, Hkv, G, d, S, layout):
+    """polar_head_labels on ragged lengths (an empty request included), both layouts, split and
+    unsplit caches, several heads per merge pass: labels equal the oracle's ranking of the very
+    output it stores, which equals polar_sha_decode's dense output bit for bit."""
+    w = wl.ShaWorkload("labels", B=5, Hq=Hkv * G, Hkv=Hkv, d=d, S=S, k=max(1, Hkv // 2), D=64, dtype=dtype,
+                       seq_lo=1, seed=300 + Hkv)
+    say("\ncase one-call labels", w, layout)
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV, poison_padding=True)
+    seqlens[3] = 0
+    Kc, Vc = (K, V) if layout == "bhsd" else (K.permute(0, 2, 1, 3).contiguous(), V.permute(0, 2, 1, 3).contiguous())
+    out = torch.full((w.B, w.Hq, w.d), float("nan"), dtype=torch.float32, device=DEV)
+    norms = torch.full((w.B, w.Hkv), float("nan"), dtype=torch.float32, device=DEV)
+    labels = polar.head_labels(q, Kc, Vc, seqlens, w.k, norms_out=norms, attn_out=out, kv_layout=layout)
+    dense = polar.sha_decode(q, Kc, Vc, seqlens, None, w.Hkv, kv_layout=layout)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), dense.view(torch.int32))
+    score, norm = orc.head_scores(out.cpu().numpy().astype(np.float64), w.Hkv)
+    assert np.array_equal(labels.cpu().numpy(), orc.topk(score, w.k))
+    np.testing.assert_allclose(norms.cpu().numpy(), norm, rtol=2e-7)
+    assert labels[3].cpu().tolist() == list(range(w.k))              # empty request: all norms 0, ids in order
+    check_against_oracle(w.scaled(k=w.Hkv), q, K, V, seqlens, None, out)
 
 
 # ----------------------------------------------------------------------------- selective GEMM
