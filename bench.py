@@ -59,6 +59,9 @@ def parse_args():
     ap.add_argument("--traffic-from", default="",
                     help="directory of counter passes made earlier by this program (--traffic-dir): read "
                          "roofline.traffic from them instead of running the passes again")
+    ap.add_argument("--traffic-dense-pass", action="store_true",
+                    help="with the counter passes, also read FETCH_SIZE of the dense run of the same kernel (k = Hkv), "
+                         "for the selective / dense traffic ratio")
     ap.add_argument("--traffic-dir", default="",
                     help="keep the counter passes' CSV files and logs in this directory (default: a "
                          "temporary one that is removed)")
@@ -87,11 +90,14 @@ def parse_args():
 
 def workload_args(args):
     """The command-line arguments that select the workload, for the child runs of this program."""
+    if args.phase in ("select_gemm", "select_gemm_only"):
+        flags = (("--mlp-workload", args.mlp_workload), ("--B", args.B), ("--density", args.density),
+                 ("--mlp-layers", args.mlp_layers), ("--gemm-form", args.gemm_form))
+    else:
+        flags = (("--workload", args.workload), ("--k", args.k), ("--B", args.B), ("--Hq", args.Hq), ("--Hkv", args.Hkv),
+                 ("--S", args.S), ("--kv-layout", args.kv_layout if args.kv_layout != "bhsd" else ""))
     out = []
-    for flag, value in (("--workload", args.workload), ("--k", args.k), ("--B", args.B), ("--Hq", args.Hq),
-                        ("--Hkv", args.Hkv), ("--S", args.S), ("--kv-layout", args.kv_layout),
-                        ("--mlp-workload", args.mlp_workload), ("--density", args.density),
-                        ("--mlp-layers", args.mlp_layers), ("--gemm-form", args.gemm_form)):
+    for flag, value in flags:
         if value:
             out += [flag, str(value)]
     return out
@@ -105,6 +111,8 @@ def hbm_traffic(args, phase, kernels):
     from paper_2505_14884_amd import rocprof
 
     if args.traffic_from:
+        with open(os.path.join(args.traffic_from, "commands.txt"), "a") as f:
+            f.write("python3 bench.py %s\n" % " ".join(sys.argv[1:]))
         t = rocprof.traffic_from(args.traffic_from, kernels)
         return t, "read from %s" % args.traffic_from if t else "no usable counter passes in %s" % args.traffic_from
     if args.no_traffic:
@@ -117,7 +125,17 @@ def hbm_traffic(args, phase, kernels):
     keep = bool(args.traffic_dir)
     out_dir = os.path.abspath(args.traffic_dir) if keep else tempfile.mkdtemp(prefix="polar_pmc_")
     try:
-        t = rocprof.collect_traffic(out_dir, workload_args(args) + ["--phase", phase, "--steps", "5", "--warmup", "2"], kernels)
+        phase_args = workload_args(args) + ["--phase", phase, "--steps", "5", "--warmup", "2"]
+        dense_args = None
+        if args.traffic_dense_pass and phase == "partial":
+            from paper_2505_14884_amd import workloads as wl
+
+            w0 = wl.CONFIGS.get(args.workload) or wl.EXTRA_SHAPES[args.workload]
+            dense_args = [a for a in phase_args] + ["--k", str(args.Hkv or w0.Hkv)]
+        t = rocprof.collect_traffic(out_dir, phase_args, kernels, dense_args)
+        if keep:
+            with open(os.path.join(out_dir, "commands.txt"), "a") as f:
+                f.write("python3 bench.py %s\n" % " ".join(sys.argv[1:]))
         return t, "four rocprofv3 --pmc passes made by this run" if t else "counter passes held no dispatch of %s" % (kernels,)
     except Exception as e:                       # a failed profiler pass must not cost the benchmark
         return None, "counter passes failed: %s" % (str(e)[-300:],)

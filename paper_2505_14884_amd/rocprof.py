@@ -183,7 +183,11 @@ def collect_traffic(out_dir: str, phase_args: Sequence[str], kernels: Sequence[s
 def _commands(profile_dir: str) -> List[str]:
     path = os.path.join(profile_dir, "commands.txt")
     lines = [ln.strip() for ln in open(path).read().splitlines()] if os.path.exists(path) else []
-    return [ln.replace(os.path.abspath(profile_dir), "<dir>").replace(profile_dir, "<dir>") for ln in lines if ln]
+    lines = [ln.replace(os.path.abspath(profile_dir), "<dir>").replace(profile_dir, "<dir>") for ln in lines if ln]
+    # the run that reads the passes back (--traffic-from) is the traced one: it was started under the profiler
+    return [("rocprofv3 --kernel-trace --stats -f csv -d <dir>/trace -o t -- " + ln + " > <dir>/trace.json")
+            if "--traffic-from" in ln else (ln + " > <dir>/bench.json" if ln.startswith("python3 bench.py") else ln)
+            for ln in lines]
 
 
 def _trace_table(rows: List[dict]) -> List[str]:
@@ -222,10 +226,10 @@ def summarize_attention(profile_dir: str) -> str:
         if js and "roofline" in js:
             r, b = js["roofline"], js["breakdown_us"]
             out.append("bench.py, %s: `%s` avg %.2f us (median %.2f, min %.2f) by events on the launch stream = %.1f GB/s = %.2f %% of 8 TB/s; "
-                       "router %.2f us; step %.2f us = %.1f GB/s (%.2f %%); dense (k = H) / selective %s (ideal %s); read yardstick %s GB/s."
+                       "router %.2f us; step %.2f us = %.1f GB/s (%.2f %%); dense (k = H) / selective %s (ideal %s); read yardstick (GB/s) %s."
                        % (label, r["kernel"], r["avg_us"], r["median_us"], r["min_us"], r["achieved"], 100 * r["frac"], b["router_topk"],
                           js["us_per_layer"], js["value"], js["pct_of_hbm_peak"], js.get("dense_over_selective"), js.get("ideal_H_over_k"),
-                          r.get("read_probe_GBps")))
+                          json.dumps(r.get("read_probe_GBps"))))
             out.append("")
     kern = ((bench or trace or {}).get("roofline") or {}).get("kernel")
     t = traffic_from(profile_dir, [kern + "<"] if kern else ["sha_partial"])
@@ -274,13 +278,35 @@ def summarize_mlp(profile_dir: str) -> str:
     return "\n".join(out) + "\n"
 
 
+def summarize_kernels(labelled_dirs: Sequence[str], match: str, title: str, note: str) -> str:
+    """One table of a kernel's duration across several traced runs (`label=trace_dir` each): used for
+    builds of the library with parts of a kernel switched off."""
+    out = ["# %s" % title, ""]
+    if note:
+        out += [note, ""]
+    out += ["| run | kernel | calls | avg us | min us | max us |", "|---|---|---|---|---|---|"]
+    for item in labelled_dirs:
+        label, _, d = item.partition("=")
+        for r in kernel_stats(d):
+            if match in r["kernel"]:
+                out.append("| %s | `%s` | %d | %.2f | %.2f | %.2f |" % (label, r["kernel"], r["calls"], r["avg_us"], r["min_us"], r["max_us"]))
+    return "\n".join(out) + "\n"
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
-    ap.add_argument("kind", choices=["attention", "mlp"])
-    ap.add_argument("dir")
+    ap.add_argument("kind", choices=["attention", "mlp", "kernels"])
+    ap.add_argument("dir", nargs="+", help="profile directory; for `kernels`: label=trace_dir pairs")
     ap.add_argument("--out", default="")
+    ap.add_argument("--match", default="", help="kernels: substring of the kernel name")
+    ap.add_argument("--title", default="rocprofv3 kernel trace")
+    ap.add_argument("--note", default="", help="kernels: text (or @file) placed under the title: commands, what the runs are")
     a = ap.parse_args(argv)
-    text = summarize_attention(a.dir) if a.kind == "attention" else summarize_mlp(a.dir)
+    if a.kind == "kernels":
+        note = open(a.note[1:]).read().rstrip() if a.note.startswith("@") else a.note
+        text = summarize_kernels(a.dir, a.match, a.title, note)
+    else:
+        text = summarize_attention(a.dir[0]) if a.kind == "attention" else summarize_mlp(a.dir[0])
     if a.out:
         with open(a.out, "w") as f:
             f.write(text)
