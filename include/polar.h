@@ -76,7 +76,8 @@ typedef enum {
     POLAR_OPT_ROUTER_PHASE1 = 4,      /* split-D phase 1: 0 auto, 1 vector ALU, 2 fp64 matrix cores */
     POLAR_OPT_GEMM_FORM = 5,          /* polar_select_gemm_ws / polar_sparse_mlp: 0 auto, 1 one-launch kernel */
     POLAR_OPT_GEMM_WORKGROUPS = 6,    /* launch width of the evenly split GEMM: 0 auto, else 1..256 */
-    POLAR_OPT_COUNT_ = 7
+    POLAR_OPT_UNION_FORM = 7,         /* polar_neuron_union_ws: 0 auto, 1 one-launch kernel, 2 split form (builders + emitters) */
+    POLAR_OPT_COUNT_ = 8
 } polar_option;
 /* POLAR_EINVAL for an unknown option or a value outside the ranges above (nothing is changed). */
 int polar_set_option(int opt, int value);
@@ -401,21 +402,24 @@ int polar_sparse_mlp(const void *X, const void *W1, const void *W2, const int32_
  *   idx_out    out  [cap] int32: the distinct ids in ascending order (first min(count, cap))
  *   count_out  out  [1] int32: number of distinct ids, clamped to cap
  *
- * N <= 524288.  One launch, deterministic.
+ * N <= 524288.  One launch, deterministic, no workspace: from a thousand ids on, sixteen
+ * workgroups each mark all the ids in a bitmap of their own (cheap to repeat) and emit a
+ * sixteenth of the output (the slow part), so no workgroup waits for another.
  */
 int polar_neuron_union(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
                        int32_t *count_out, void *stream);
 
 /*
- * The same index with a workspace (Section 4.1; same arguments, same result): several
- * workgroups each mark their share of the ids in a bitmap of their own, stored to the
- * workspace, and a last launch ORs the bitmaps, counts and emits (two launches,
- * deterministic).  Worth it from a few thousand ids on; for smaller inputs, workspace NULL or a
+ * The same index with a workspace (Section 4.1; same arguments, same result), for very large
+ * inputs: several workgroups each mark their SHARE of the ids in a bitmap of their own, stored
+ * to the workspace, and a last launch ORs the bitmaps, counts and emits (two launches,
+ * deterministic).  Worth its second launch only where marking all ids in every workgroup gets
+ * expensive (from about a hundred thousand ids); for smaller inputs, workspace NULL or a
  * workspace too small for two bitmaps it runs the one-launch kernel of polar_neuron_union.
  *   workspace        scratch, DEVICE pointer, 4-byte aligned, caller-owned; contents are
  *                    overwritten; calls that overlap in time need separate workspaces
  *   workspace_bytes  its size; polar_neuron_union_workspace_bytes(B, kn, N) gives the size the
- *                    library wants (0: the input is too small to split)
+ *                    library wants (0: the one-launch kernel is the faster one for this input)
  */
 size_t polar_neuron_union_workspace_bytes(int B, int kn, int N);
 int polar_neuron_union_ws(const int32_t *topk, int B, int kn, int N, int cap, int32_t *idx_out,
@@ -428,7 +432,7 @@ int polar_last_hip_error(void);
 /* ABI version: major * 1000 + minor.  2000: options (polar_set_option / polar_get_option) replace the
  * environment switches; every workspace query returns size_t; the read yardsticks moved to their own
  * library (polar_probe.h); q, K, V and out of the attention calls must be 16-byte aligned.
- * 2100: adds polar_sha_decode_static.  2200: adds polar_head_labels. */
+ * 2100: adds polar_sha_decode_static.  2200: adds polar_head_labels.  2300: POLAR_OPT_UNION_FORM. */
 int polar_version(void);
 /* Hash of the source files this binary was built from (set by the build script; "unknown" for a
  * build made without it).  Lets a loader refuse a binary older than the sources beside it. */

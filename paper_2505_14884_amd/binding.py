@@ -32,7 +32,7 @@ EXPORTS = ("polar_router_topk", "polar_router_workspace_bytes", "polar_sha_works
 PROBE_EXPORTS = ("polar_probe_read", "polar_probe_gather_read", "polar_probe_last_hip_error")
 # polar_option in include/polar.h
 OPTIONS = {"sha_chunk_rows": 0, "sha_form": 1, "sha_grouped_kernel": 2, "router_path": 3, "router_phase1": 4,
-           "gemm_form": 5, "gemm_workgroups": 6}
+           "gemm_form": 5, "gemm_workgroups": 6, "union_form": 7}
 
 _lib: Optional[ctypes.CDLL] = None
 _probe_lib: Optional[ctypes.CDLL] = None

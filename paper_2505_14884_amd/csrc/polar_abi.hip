@@ -54,6 +54,7 @@ bool option_value_ok(int opt, int v)
     case POLAR_OPT_ROUTER_PHASE1: return v >= 0 && v <= 2;
     case POLAR_OPT_GEMM_FORM: return v == 0 || v == 1;
     case POLAR_OPT_GEMM_WORKGROUPS: return v >= 0 && v <= 256;
+    case POLAR_OPT_UNION_FORM: return v >= 0 && v <= 2;
     default: return false;
     }
 }
@@ -210,7 +211,7 @@ using namespace polar;
 
 extern "C" {
 
-int polar_version(void) { return 2200; }
+int polar_version(void) { return 2300; }
 
 #ifndef POLAR_SOURCE_HASH
 #define POLAR_SOURCE_HASH "unknown"

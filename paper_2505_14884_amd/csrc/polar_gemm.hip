@@ -675,6 +675,7 @@ constexpr int kUnionThreads = 1024;
 constexpr int kUnionMaxWords = 16384;            // N <= 524288 neurons (64 KB of LDS)
 constexpr int kUnionBuilders = 8;                // workgroups that build partial bitmaps (more: the emitters OR more maps)
 constexpr int kUnionMinIdsPerBuilder = 2048;
+constexpr long kUnionSplitFrom = 1l << 14;       // ids from which the split form (builders + emitters) pays
 constexpr int kUnionScanSlots = 32;               // wave totals of the scan (16 used)
 constexpr int kUnionEmitters = 16;               // workgroups of the split form's last launch (one wave's share each)
 
@@ -742,6 +743,10 @@ __device__ __forceinline__ void union_emit(const unsigned int *sh_bits, unsigned
     }
 }
 
+// grid = parts (1 or kUnionEmitters): EVERY workgroup marks all the ids in a bitmap of its own, counts and
+// scans it, and emits its share of the output (the bit loops with their scattered 4-byte stores are the
+// slow part of a one-workgroup union: 12 to 19 us for ten thousand ids; marking is cheap to repeat).  No
+// workgroup depends on another, so this is one launch with no workspace.
 __global__ __launch_bounds__(kUnionThreads) void neuron_union_kernel(
     const int32_t *__restrict__ topk, long total, int N, int cap, int32_t *__restrict__ idx_out,
     int32_t *__restrict__ count_out)
@@ -749,7 +754,7 @@ __global__ __launch_bounds__(kUnionThreads) void neuron_union_kernel(
     extern __shared__ unsigned int sh_bits[];     // words, then the scan slots
     const int words = (N + 31) / 32;
     union_mark(sh_bits, words, topk, 0, total, N);
-    union_emit(sh_bits, sh_bits + words, words, cap, idx_out, count_out, 0, 1);
+    union_emit(sh_bits, sh_bits + words, words, cap, idx_out, count_out, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // grid = builders: workgroup g marks its share of the ids and stores its bitmap to maps[g][words]
@@ -945,14 +950,23 @@ hipError_t launch_neuron_union(const int32_t *topk, int B, int kn, int N, int ca
     static LdsGrant granted;                     // the bitmap and the scan slots
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(neuron_union_kernel), lds, granted);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(neuron_union_kernel, dim3(1), dim3(kUnionThreads), lds, stream, topk,
-                       (long)B * kn, N, cap, idx_out, count_out);
+    // a handful of ids: one workgroup; otherwise kUnionEmitters of them share the emit phase
+    const long total = (long)B * kn;
+    const int parts = total < 1024 ? 1 : kUnionEmitters;
+    hipLaunchKernelGGL(neuron_union_kernel, dim3(parts), dim3(kUnionThreads), lds, stream, topk, total, N, cap, idx_out,
+                       count_out);
     return hipGetLastError();
 }
 
-// builders the split form would use for this input (0: not worth splitting)
+// builders the split form would use for this input (0: the one-launch kernel is the faster one).  In the
+// one-launch kernel every workgroup marks all the ids, total / 1024 LDS atomics per thread at about 6 ids per
+// nanosecond and compute unit; from kUnionSplitFrom ids on, sharing the marking over builders and paying a
+// second launch is faster (replayed from a graph, one launch / split: 8848 ids 5.8 / 7.4 us, 35392 ids 11.7 /
+// 9.4 us, 117952 ids 25.7 / 11.8 us).  POLAR_OPT_UNION_FORM pins the choice.
 static int union_builders(long total)
 {
+    const int form = option(POLAR_OPT_UNION_FORM);
+    if (form == 1 || (form == 0 && total < kUnionSplitFrom)) return 0;
     const long want = total / kUnionMinIdsPerBuilder;
     return want < 2 ? 0 : (int)(want < kUnionBuilders ? want : kUnionBuilders);
 }

@@ -45,11 +45,12 @@ def test_options():
     v = ctypes.c_int(-1)
     for name, opt in binding.OPTIONS.items():
         assert L.polar_get_option(opt, ctypes.byref(v)) == OK and v.value == 0, name     # all automatic
-    assert L.polar_set_option(7, 0) == EINVAL and L.polar_set_option(-1, 0) == EINVAL
-    assert L.polar_get_option(7, ctypes.byref(v)) == EINVAL
+    assert L.polar_set_option(8, 0) == EINVAL and L.polar_set_option(-1, 0) == EINVAL
+    assert L.polar_get_option(8, ctypes.byref(v)) == EINVAL
     assert L.polar_get_option(0, None) == EINVAL
     bad = {"sha_chunk_rows": [-1, 1, 127, (1 << 20) + 1], "sha_form": [-1, 3], "sha_grouped_kernel": [2, -1],
-           "router_path": [3, -1], "router_phase1": [3], "gemm_form": [2], "gemm_workgroups": [257, -1]}
+           "router_path": [3, -1], "router_phase1": [3], "gemm_form": [2], "gemm_workgroups": [257, -1],
+           "union_form": [3, -1]}
     for name, values in bad.items():
         for value in values:
             assert L.polar_set_option(binding.OPTIONS[name], value) == EINVAL, (name, value)
@@ -244,7 +245,12 @@ def test_select_gemm_and_union_argument_errors():
     assert L.polar_neuron_union_workspace_bytes(64, 1843, 524289) == 0
     assert polar.neuron_union_workspace_bytes(2, 3, 64) == 0                 # too few ids to split
     assert polar.neuron_union_workspace_bytes(64, 1843, 36864) == 8 * 1152 * 4
-    assert polar.neuron_union_workspace_bytes(4, 1024, 36864) == 2 * 1152 * 4
+    assert polar.neuron_union_workspace_bytes(4, 1024, 36864) == 0              # 4096 ids: the one-launch kernel is faster
+    assert polar.neuron_union_workspace_bytes(16, 1024, 36864) == 8 * 1152 * 4
+    with polar.options(union_form=2):                                           # pinned: split whenever there are two shares
+        assert polar.neuron_union_workspace_bytes(4, 1024, 36864) == 2 * 1152 * 4
+    with polar.options(union_form=1):
+        assert polar.neuron_union_workspace_bytes(64, 1843, 36864) == 0
 
 
 def test_select_gemm_down_argument_errors():

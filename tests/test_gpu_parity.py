@@ -559,9 +559,16 @@ def test_select_gemm_invalid_ids_count_and_long_k():
         gemm_case(64, 9216, 300, list(range(299, -1, -1)), "bf16", relu=True, ws=ws)
 
 
-@pytest.mark.parametrize("ws", [False, True])
+@pytest.mark.parametrize("ws", [False, True, "split"])
 def test_neuron_union_matches_oracle(ws):
-    say("\ncase neuron union", "workspace" if ws else "")
+    """ws False: the one-launch kernel (sixteen workgroups mark everything and share the emit phase); True: the
+    workspace entry point with the library's choice of form; "split": the split form pinned for every size."""
+    say("\ncase neuron union", ws)
+    with polar.options(union_form=2 if ws == "split" else None):
+        union_cases(bool(ws))
+
+
+def union_cases(ws):
     g = torch.Generator(device="cpu").manual_seed(5)
     for (B, kn, N) in [(1, 1, 1), (7, 12, 50), (64, 1843, 36864), (3, 5, 524288), (16, 100, 33),
                        (5, 1000, 524288), (128, 300, 4097)]:
