@@ -119,6 +119,8 @@ def hbm_traffic(args, phase, kernels):
         return None, "counter passes skipped (--no-traffic)"
     if not rocprof.rocprofv3():
         return None, "rocprofv3 not found"
+    if any(name.startswith(("ROCPROF", "ROCP_")) for name in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
+        return None, "this run is itself under a profiler: counter passes skipped (use --traffic-from)"
     import shutil
     import tempfile
 
