@@ -47,6 +47,36 @@ def test_static_scratch_entry_point_matches_the_workspace_entry_point():
     one_call(second)       # smaller, right after: the array still holds the first call's records
 
 
+def test_static_scratch_entry_point_under_graph_capture():
+    """The callers it is for: a step recorded into a HIP graph with no workspace to hand over.  The
+    first call on the GPU was made above (outside any capture); every replay, with eager work in
+    between, must equal the eager result of the workspace entry point bit for bit."""
+    w = wl.ShaWorkload("static-graph", B=5, Hq=8, Hkv=8, d=128, S=3000, k=3, D=64, dtype="f16", seq_lo=500, seed=73)
+    print("\ncase no-alloc graph", w, flush=True)
+    q, K, V, seqlens = wl.make_attention_inputs(w, DEV)
+    head_idx = wl.random_head_idx(w, DEV)
+    out = torch.zeros((w.B, w.Hq, w.d), dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        polar.sha_decode_static(q, K, V, seqlens, head_idx, w.k, out)        # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        polar.sha_decode_static(q, K, V, seqlens, head_idx, w.k, out)
+    gen = torch.Generator(device=DEV).manual_seed(9)
+    for rep in range(3):
+        q.copy_(torch.randn(q.shape, generator=gen, device=DEV).to(q.dtype))
+        head_idx.copy_(wl.random_head_idx(w, DEV, seed_offset=rep + 1))
+        ref = polar.sha_decode(q, K, V, seqlens, head_idx, w.k)              # eager work in between, own workspace
+        torch.cuda.synchronize()
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int32), ref.view(torch.int32)), "replay %d" % rep
+
+
 def test_static_scratch_entry_point_refuses_what_does_not_fit():
     # 256 requests x 32 heads x 8 chunks of 1024 rows x 130 floats: 34 MB of records
     B, Hq, Hkv, S, d, k = 256, 32, 32, 8192, 128, 32
