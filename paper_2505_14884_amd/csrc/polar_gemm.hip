@@ -292,9 +292,17 @@ __device__ __forceinline__ int span_bound(int units, int G, int g) { return (int
 // tile (its row addresses are fetched a tile ahead), so the memory pipeline is filled once per
 // workgroup, not once per tile.
 constexpr int kUnitBlocks = 2;                   // K blocks per unit = ring slots
+// Timing-only build switches for the streaming kernel below (results are wrong with any of them set; no
+// access leaves its bounds and no wait is left without its signal): bit 0 no matrix instructions (the
+// operands are still read), bit 1 no operand reads from LDS either, bit 2 no workgroup barrier per block,
+// bit 3 no activation loads and stores, bit 4 no weight loads, bit 5 one value per thread stored in place of a
+// segment.  They exist to measure where the kernel's
+// time goes at a given batch size; the product is built without them.
+#ifndef POLAR_STREAM_ABLATE
+#define POLAR_STREAM_ABLATE 0
+#endif
+constexpr int kStreamAblate = POLAR_STREAM_ABLATE;
 constexpr int kSpanTiles = 8;                    // tiles a span may touch (row ids kept in LDS)
-constexpr int kPhaseBuckets = 64;                // K positions the spans are sorted by (one per lane)
-constexpr int kSpanWords = (kStreamGrid + 31) / 32;   // words of a bitmap over the spans
 
 template <bool BF, int MT>
 __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
@@ -316,9 +324,6 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     __shared__ __align__(16) unsigned char sh_wt[(kSplit ? 2 : 1) * kTileBytes];
     __shared__ __align__(16) unsigned char sh_at[2][16 * MT * kRowBytes];
     __shared__ int sh_id[kSpanTiles * kStreamTileN];
-    __shared__ unsigned sh_bits[kPhaseBuckets * kSpanWords];
-    __shared__ int sh_bucket[kPhaseBuckets];
-    __shared__ unsigned short sh_order[kStreamGrid];
 
     int count = cap;
     if (count_ptr) {
@@ -330,61 +335,11 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 15, kg = lane >> 4;
 
-    // Which span this workgroup takes.  Workgroups go to the eight dies in turn (g % 8), each
-    // die has its own L2, and the activations only stay in an L2 if its workgroups want the same
-    // K range at about the same time.  The spans are therefore sorted by the K position they
-    // start at (64 buckets, ties by span number) and die x takes the x-th eighth of that order:
-    // its workgroups walk K side by side.  Every workgroup computes the same order: a span
-    // marks its bit in its bucket's bitmap (order-free), a bucket's size and a span's rank in
-    // its bucket are bit counts.  Any one-to-one assignment gives the same result, since spans
-    // and workspace slots go by span number.
+    // Workgroup g takes span g.  (Sorting the spans by the K position they start at, so that the
+    // workgroups of one die walk K side by side, was built and measured: the activations of up to
+    // 128 rows fit every die's L2 whole, and the sort's own barriers cost more than it gained.)
     const int G = (int)gridDim.x;
-    int span;
-    {
-        constexpr int kMine = (kStreamGrid + kStreamThreads - 1) / kStreamThreads;
-        for (int e = tid; e < kPhaseBuckets * kSpanWords; e += kStreamThreads) sh_bits[e] = 0u;
-        __syncthreads();
-        int bucket[kMine];
-#pragma unroll
-        for (int q = 0; q < kMine; ++q) {
-            const int sp = tid + q * kStreamThreads;
-            bucket[q] = 0;
-            if (sp < G) {
-                bucket[q] = (span_bound(units, G, sp) % upt) * kPhaseBuckets / upt;
-                atomicOr(&sh_bits[bucket[q] * kSpanWords + (sp >> 5)], 1u << (sp & 31));
-            }
-        }
-        __syncthreads();
-        if (wave == 0) {                         // bucket sizes, exclusive scan over the 64 buckets
-            int mine = 0;
-#pragma unroll
-            for (int wd = 0; wd < kSpanWords; ++wd) mine += __popc(sh_bits[lane * kSpanWords + wd]);
-            int incl = mine;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-            }
-            sh_bucket[lane] = incl - mine;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < kMine; ++q) {
-            const int sp = tid + q * kStreamThreads;
-            if (sp < G) {
-                const unsigned *bits = sh_bits + bucket[q] * kSpanWords;
-                int pos = sh_bucket[bucket[q]] + __popc(bits[sp >> 5] & ((1u << (sp & 31)) - 1u));
-                for (int wd = 0; wd < (sp >> 5); ++wd) pos += __popc(bits[wd]);
-                sh_order[pos] = (unsigned short)sp;
-            }
-        }
-        __syncthreads();
-        const int die = (int)blockIdx.x & 7, turn = (int)blockIdx.x >> 3;
-        // dies 0 .. die-1 hold ceil((G - d) / 8) workgroups each
-        int before = 0;
-        for (int d = 0; d < die; ++d) before += (G - d + 7) >> 3;
-        span = __builtin_amdgcn_readfirstlane(sh_order[before + turn]);   // the same in every lane: keep it scalar
-    }
+    const int span = (int)blockIdx.x;
     int u = span_bound(units, G, span);
     const int u0 = u, u1 = span_bound(units, G, span + 1);
     if (u0 >= u1) return;
@@ -394,7 +349,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     // (staged by the first kAThreads threads: all of them unless the block has only 16 rows)
     constexpr int kAThreads = 16 * MT * 16 < kStreamThreads ? 16 * MT * 16 : kStreamThreads;
     constexpr int kARows = kAThreads / 16, AP = 16 * MT / kARows;
-    const bool stages_a = kAThreads == kStreamThreads || wave < kAThreads / 64;
+    const bool stages_a = !(kStreamAblate & 8) && (kAThreads == kStreamThreads || wave < kAThreads / 64);
     const int a_row = tid >> 4;
     const u32x4 *ap[AP];
 #pragma unroll
@@ -438,40 +393,60 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
         nxt[i] = row_id(1, i);
     }
 
-    // loads of block j of unit v into ring slot j (past the span's end: one piece that every
-    // workgroup shares, so that the loop needs no branch and the memory system no traffic); fenced so
-    // that the compiler keeps the order (weights before activations, slot 0 before slot 1): its
-    // count of outstanding loads at the loop header is then the same on entry and on the back
-    // edge, and nothing is drained there
-    u32x4 wq[kUnitBlocks][NR], aq[kUnitBlocks][AP];
-#define POLAR_STREAM_FETCH(j, unit)                                                                \
+    // Loads of block j of unit v (past the span's end: one piece that every workgroup shares, so
+    // that the loop needs no branch and the memory system no traffic).  The weights come from HBM
+    // and are fetched two blocks ahead, into ring slot j; the activations come from L2, need
+    // less lead and are fetched one block ahead, into a single slot: every line in flight takes
+    // one of the compute unit's outstanding misses, and the fewer of them the activations hold,
+    // the more are left for the weights (41.7 -> 39.2 us at 128 rows in a stand-alone model of
+    // this pipeline).  The loads are fenced so that the compiler keeps their order
+    // (activations of the next block before weights of the block after it): the wave's loads
+    // complete in order, so what a step waits for is always the oldest of what is in flight,
+    // and the count of outstanding loads at the loop header is the same on entry and on the
+    // back edge, so nothing is drained there.
+    u32x4 wq[kUnitBlocks][NR], aq[AP];
+    if (kStreamAblate & 16)
+        for (int j = 0; j < kUnitBlocks; ++j)
+            for (int i = 0; i < NR; ++i) wq[j][i] = (u32x4){0u, 0u, 0u, 0u};
+#define POLAR_STREAM_BLOCK_OFFSET(j, unit)                                                         \
+    const int v = (unit);                                                                          \
+    const bool past = v >= u1, ahead = v >= tile_end;                                              \
+    const size_t blk = past ? 0 : (size_t)((v - (ahead ? tile_end : tile_base)) * kUnitBlocks + (j)) * 16;
+#define POLAR_STREAM_FETCH_W(j, unit)                                                              \
     {                                                                                              \
-        const int v = (unit);                                                                      \
-        const bool past = v >= u1, ahead = v >= tile_end;                                          \
-        const size_t blk = past ? 0 : (size_t)((v - (ahead ? tile_end : tile_base)) * kUnitBlocks + (j)) * 16; \
+        POLAR_STREAM_BLOCK_OFFSET(j, unit)                                                         \
         __builtin_amdgcn_sched_barrier(0);                                                         \
         _Pragma("unroll") for (int i = 0; i < NR; ++i)                                             \
         {                                                                                          \
             const u32x4 *p = reinterpret_cast<const u32x4 *>(W + (size_t)(past ? 0 : (ahead ? nxt[i] : cur[i])) * K) + x; \
-            wq[j][i] = __builtin_nontemporal_load(p + blk);   /* read once: leave the caches to   */ \
+            if (!(kStreamAblate & 16))                                                             \
+                wq[j][i] = __builtin_nontemporal_load(p + blk); /* read once: leave the caches to */ \
                                                               /* the activations and the partials */ \
         }                                                                                          \
         __builtin_amdgcn_sched_barrier(0);                                                         \
-        if (stages_a) _Pragma("unroll") for (int i = 0; i < AP; ++i) aq[j][i] = ap[i][blk];       \
+    }
+#define POLAR_STREAM_FETCH_A(j, unit)                                                              \
+    {                                                                                              \
+        POLAR_STREAM_BLOCK_OFFSET(j, unit)                                                         \
+        (void)ahead;                                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+        if (stages_a) _Pragma("unroll") for (int i = 0; i < AP; ++i) aq[i] = ap[i][blk];          \
         __builtin_amdgcn_sched_barrier(0);                                                         \
     }
-    // block j of unit u: ring slot j goes to LDS, is refilled for unit u + 1, and is multiplied;
-    // the wave's B operands (NH groups of 16 neurons, four k steps) stay in registers while the
-    // M rows go by, 16 at a time
+    // block j of unit u: the weights in ring slot j and the activations go to LDS, the loads of
+    // the blocks ahead are issued, and the block is multiplied; the wave's B operands (NH groups
+    // of 16 neurons, four k steps) stay in registers while the M rows go by, 16 at a time
 #define POLAR_STREAM_STEP(j)                                                                       \
     {                                                                                              \
         unsigned char *abuf = sh_at[j];                                                            \
         _Pragma("unroll") for (int i = 0; i < NR; ++i)                                             \
             *reinterpret_cast<u32x4 *>(wt + (kSplit ? (j) * kTileBytes : 0) + lds_w_wr + 4 * i * kRowBytes) = wq[j][i]; \
         if (stages_a) _Pragma("unroll") for (int i = 0; i < AP; ++i)                               \
-            *reinterpret_cast<u32x4 *>(abuf + lds_a_wr + kARows * i * kRowBytes) = aq[j][i];       \
-        POLAR_STREAM_FETCH(j, u + 1)                                                               \
-        __syncthreads();                                                                           \
+            *reinterpret_cast<u32x4 *>(abuf + lds_a_wr + kARows * i * kRowBytes) = aq[i];          \
+        POLAR_STREAM_FETCH_A(1 - (j), u + (j))                                                     \
+        POLAR_STREAM_FETCH_W(j, u + 1)                                                             \
+        if (!(kStreamAblate & 4)) __syncthreads();                                                 \
+        if (!(kStreamAblate & 2)) {                                                                \
         u32x4 bq[HW][4];                                                                           \
         _Pragma("unroll") for (int h = 0; h < HW; ++h)                                             \
             _Pragma("unroll") for (int s = 0; s < 4; ++s) bq[h][s] = *reinterpret_cast<const u32x4 *>( \
@@ -484,14 +459,25 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
             _Pragma("unroll") for (int s = 0; s < 4; ++s)                                          \
             {                                                                                      \
                 _Pragma("unroll") for (int h = 0; h < HW; ++h)                                     \
-                    acc[t][h] = mfma16x16x32<BF>(a[s], bq[h][s], acc[t][h]);                       \
+                    if (kStreamAblate & 1) asm volatile("" ::"v"(a[s]), "v"(bq[h][s]));            \
+                    else acc[t][h] = mfma16x16x32<BF>(a[s], bq[h][s], acc[t][h]);                  \
             }                                                                                      \
+        }                                                                                          \
         }                                                                                          \
     }
 
     // a finished segment of `tile`: the whole contraction is finished in place, a part of it goes
     // to the workspace as raw accumulators
     auto store_segment = [&](const f32x4 (&sum)[TW][HW], int of_tile, bool whole) {
+        if (kStreamAblate & 32) {                // one value per thread, so that the sums stay live
+            float v = 0.0f;
+#pragma unroll
+            for (int t = 0; t < TW; ++t)
+#pragma unroll
+                for (int h = 0; h < HW; ++h) v += sum[t][h][0] + sum[t][h][1] + sum[t][h][2] + sum[t][h][3];
+            part[((size_t)span * 2 + (of_tile == first_tile ? 0 : 1)) * kStreamThreads + tid] = v;
+            return;
+        }
         if (whole) {
             // accumulator layout: this lane holds rows 16*t + 4*kg + i of column x of each group
             // of 16 neurons
@@ -538,13 +524,14 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
                 for (int h = 0; h < HW; ++h) dst[(t * HW + h) * 64] = sum[t][h];
         }
     };
-    constexpr bool kDefer = MT <= 4;             // beyond that the registers are not there
+    constexpr bool kDefer = MT <= 4;             // at 128 rows it fits (254 registers) and gains nothing measurable
     f32x4 held[TW][HW];
     int held_tile = -1;
     bool held_whole = false;
 
-    POLAR_STREAM_FETCH(0, u)
-    POLAR_STREAM_FETCH(1, u)
+    POLAR_STREAM_FETCH_W(0, u)
+    POLAR_STREAM_FETCH_A(0, u)
+    POLAR_STREAM_FETCH_W(1, u)
     while (u < u1) {
         const int seg_begin = u, seg_end = tile_end < u1 ? tile_end : u1;
         f32x4 acc[TW][HW];
@@ -584,7 +571,9 @@ __global__ __launch_bounds__(kStreamThreads) void select_gemm_stream_kernel(
     }
     if (kDefer && held_tile >= 0) store_segment(held, held_tile, held_whole);
 #undef POLAR_STREAM_STEP
-#undef POLAR_STREAM_FETCH
+#undef POLAR_STREAM_FETCH_A
+#undef POLAR_STREAM_FETCH_W
+#undef POLAR_STREAM_BLOCK_OFFSET
 }
 
 // grid = tiles * waves per tile * ceil(MT * NH / 4) workgroups: workgroup (tile, w, q) adds four of
