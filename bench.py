@@ -9,7 +9,9 @@ router just chose.  Inputs are seeded synthetic tensors already resident in HBM.
 
 Prints ONE JSON line.  `value` is the effective KV bandwidth of the whole step: bytes of
 K and V the selected heads oblige a kernel to read, divided by the wall time of a step
-(router included).  `roofline` is for the dominant kernel alone (the KV-streaming kernel),
+(router included).  The K timed steps are replayed from HIP graphs, as a decode loop would
+run them (`config.launch` says how; --no-graph launches them one by one, and that time is
+always reported beside it as `breakdown_us.eager_us_per_layer`).  `roofline` is for the dominant kernel alone (the KV-streaming kernel),
 timed with events on the launch stream; its `traffic` is read from the hardware counters in
 this very run: before it touches the GPU, the benchmark runs itself four times as a child
 process under `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE of the streaming kernel, and of a
@@ -430,17 +432,54 @@ def main():
                           "algorithmic_bytes_per_launch": bytes_sel}))
         return
 
-    # ---- whole-step wall time: W untimed, then exactly K timed steps
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # ---- whole-step wall time: W untimed, then exactly K timed steps.
+    # The steps are replayed from HIP graphs (Section 5: the paper runs its router and kernels
+    # under CUDA graphs; a decode step of a model replays one graph that holds all its layers):
+    # a graph of L consecutive steps, each on the next cache copy (L = 8, or the number of copies
+    # rotated if that is larger, but at most K), replayed K // L times; the K % L steps left over
+    # are launched one by one, on the next copies.  With --no-graph all steps are launched one
+    # by one, which is also timed below (`eager_us_per_layer`): there the time depends on how
+    # fast the host gets its launches out (0 to 20 us of gaps per step between runs of the same
+    # binary).  A graph of one step is timed for the breakdown.
+    L = max(1, min(max(8, R), args.steps))
+    layers_graph = one_graph = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)                                   # warm-up outside any capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        layers_graph, one_graph = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(layers_graph):
+            for i in range(L):
+                step(i)
+        with torch.cuda.graph(one_graph):
+            step(0)
+
+    def run_steps(n):
+        if layers_graph is None:
+            for i in range(n):
+                step(i)
+            return
+        for _ in range(n // L):
+            layers_graph.replay()
+        for i in range(n % L):
+            step(i)
+
+    def wall_time(run, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(n)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    run_steps(args.warmup)
+    ms_per_step = wall_time(run_steps, args.steps)
     value = bytes_sel / (ms_per_step * 1e-3) / 1e9
+    for i in range(min(args.warmup, 5)):
+        step(i)
+    eager_ms = wall_time(lambda n: [step(i) for i in range(n)], args.steps)
 
     def event_time(fn, n):
         """Duration of one launch of fn from events on the launch stream: the average over n
@@ -476,31 +515,11 @@ def main():
         dense_avg, _, _ = event_time(dense_step, max(5, n_ev // 4))
     achieved = bytes_sel / (part_avg * 1e-3) / 1e9
 
-    # The same step recorded into a HIP graph and replayed (Section 5: the paper runs its router
-    # and kernels under CUDA graphs).  A decode step of a model replays one graph that holds all
-    # its layers, so the figure is the time per layer of a graph of kGraphLayers consecutive
-    # steps (each on the next cache copy); a graph of one step is timed too.
-    kGraphLayers = 8
+    # the graphs by events on the stream, for the breakdown
     graph_avg = graph1_avg = float("nan")
-    if not args.no_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            step(0)                                   # warm-up outside any capture
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        layers_graph, one_graph = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
-        with torch.cuda.graph(layers_graph):
-            for i in range(kGraphLayers):
-                step(i)
-        with torch.cuda.graph(one_graph):
-            step(0)
-        for _ in range(2):
-            layers_graph.replay()
-            one_graph.replay()
-        torch.cuda.synchronize()
-        n_rep = max(3, n_ev // kGraphLayers)
-        graph_avg = event_time(lambda i: layers_graph.replay(), n_rep)[0] / kGraphLayers
+    if layers_graph is not None:
+        n_rep = max(3, n_ev // L)
+        graph_avg = event_time(lambda i: layers_graph.replay(), n_rep)[0] / L
         graph1_avg = event_time(lambda i: one_graph.replay(), n_ev)[0]
 
     # Read-only yardstick over the same K cache with the streaming kernel's launch shape: what this
@@ -545,6 +564,9 @@ def main():
             "attention_kernels": "streaming kernel only (unsplit cache)" if one_kernel
                                  else "streaming kernel + merge kernel",
             "kv_copies_rotated": R,
+            "launch": "eager launches" if layers_graph is None else
+                      "HIP graph of %d consecutive steps replayed %d times + %d steps launched one by one"
+                      % (L, args.steps // L, args.steps % L),
         },
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "us_per_layer": round(ms_per_step * 1e3, 2),
@@ -552,7 +574,8 @@ def main():
             "router_topk": round(router_avg * 1e3, 2),
             "sha_decode": round(sha_avg * 1e3, 2),
             "streaming_kernel": round(part_avg * 1e3, 2),
-            "step_in_hip_graph_of_8_layers": None if args.no_graph else round(graph_avg * 1e3, 2),
+            "eager_us_per_layer": round(eager_ms * 1e3, 2),
+            "step_in_hip_graph_of_%d_layers" % L: None if args.no_graph else round(graph_avg * 1e3, 2),
             "step_in_hip_graph_of_1_layer": None if args.no_graph else round(graph1_avg * 1e3, 2),
             "dense_k_eq_H": None if args.no_dense else round(dense_avg * 1e3, 2),
         },

@@ -226,9 +226,11 @@ def summarize_attention(profile_dir: str) -> str:
         if js and "roofline" in js:
             r, b = js["roofline"], js["breakdown_us"]
             out.append("bench.py, %s: `%s` avg %.2f us (median %.2f, min %.2f) by events on the launch stream = %.1f GB/s = %.2f %% of 8 TB/s; "
-                       "router %.2f us; step %.2f us = %.1f GB/s (%.2f %%); dense (k = H) / selective %s (ideal %s); read yardstick (GB/s) %s."
+                       "router %.2f us; step %.2f us = %.1f GB/s (%.2f %%; %s; launched one by one: %s us); dense (k = H) / selective %s "
+                       "(ideal %s); read yardstick (GB/s) %s."
                        % (label, r["kernel"], r["avg_us"], r["median_us"], r["min_us"], r["achieved"], 100 * r["frac"], b["router_topk"],
-                          js["us_per_layer"], js["value"], js["pct_of_hbm_peak"], js.get("dense_over_selective"), js.get("ideal_H_over_k"),
+                          js["us_per_layer"], js["value"], js["pct_of_hbm_peak"], js.get("config", {}).get("launch", "eager launches"),
+                          b.get("eager_us_per_layer"), js.get("dense_over_selective"), js.get("ideal_H_over_k"),
                           json.dumps(r.get("read_probe_GBps"))))
             out.append("")
     kern = ((bench or trace or {}).get("roofline") or {}).get("kernel")

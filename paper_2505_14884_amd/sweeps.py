@@ -42,7 +42,7 @@ def _attention_cells(r):
 def attention(out_path):
     head = ["# Sweeps of the selective decode-attention step on one MI355X (bench.py, event timing)", "",
             "Written by `python -m paper_2505_14884_amd.sweeps attention --out <this file>`.  Every line is one run of",
-            "`python bench.py " + " ".join(COMMON) + " <options>` (50 timed steps after 10 warm-up steps; small shapes rotate over",
+            "`python bench.py " + " ".join(COMMON) + " <options>` (50 timed steps after 10 warm-up steps, replayed from HIP graphs; small shapes rotate over",
             "copies of the cache so repeats cannot be served from the 256 MB memory-side cache).  `step` = router + top-k +",
             "selective attention; `stream` = the KV-streaming kernel alone (for an unsplit cache of up to 2048 units that one",
             "kernel is the whole attention call: `kernels` = 1); % = of 8 TB/s on the selected heads' K+V bytes; `dense` = the",
